@@ -1,0 +1,358 @@
+/*
+ * CPU ORACLE for the DSV two-stage sparse attention path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, double-precision statement of what the path computes, written from the
+ * paper's definitions.  It shares no code, header, table or helper with the HIP library and
+ * must never be linked, imported or called by it; only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg use it.
+ *
+ * What is defined where (paper: "DSV: Exploiting Dynamic Sparsity to Accelerate Large-Scale
+ * Video DiT Training"):
+ *   - low-rank projection Q_lr = Q Wq, K_lr = K Wk ......... Sec. "Low-Rank based Sparsity Prediction"
+ *   - approximate scores Q_lr K_lr^T and per-query top-k .... Sec. "Critical KV Estimation with Kernel Fusion"
+ *   - attention over only the selected (critical) KV ........ Sec. "Sparse Attention with Query Grouping",
+ *                                                             with softmax(QK^T/sqrt(d_k))V from
+ *                                                             Sec. "Various Self-Attention Paradigms"
+ *   - dense attention (the k = L limit and the comparator) .. Sec. "Various Self-Attention Paradigms"
+ *
+ * Readings taken where the paper is silent (listed again in the design notes):
+ *   - one (Wq, Wk) pair per head, applied to that head's Q and K;
+ *   - projected values are rounded (nearest-even) to the storage dtype, scores are exact sums;
+ *   - the k largest scores win, equal scores go to the lower key index, rows are emitted in
+ *     ascending key index; exactly k indices per query, no mask, no forced keys;
+ *   - softmax is normalised over the selected subset only; lse is that subset's log-sum-exp;
+ *   - no gradient flows through the selection or the predictor (the predictor is trained
+ *     outside the main graph), so backward returns dQ, dK, dV only.
+ *
+ * Inputs are float arrays that already hold storage-dtype-rounded values; all arithmetic is
+ * in double.  Loops follow the formulas literally: no blocking, no fusion.  OpenMP is used
+ * only across independent query rows (or keys), never inside a sum.
+ *
+ * Parity pins (tests/test_oracle_*.py): textbook GEMM for the projection, brute-force
+ * lexicographic sort for the selection, dense softmax attention and library autograd at
+ * k = L, closed forms (k = 1, Q = 0, all-equal scores), softmax and gradient identities,
+ * central finite differences.  No function here is unpinned.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define DSV_ORACLE_F32 0
+#define DSV_ORACLE_BF16 1
+
+/* Round a double to a binary format with `prec` significand bits (24: fp32, 8: bf16) and
+ * minimum subnormal exponent `emin_sub` (fp32: -149, bf16: -133), nearest-even, straight
+ * from the double (no intermediate fp32 rounding). */
+static double round_to_format(double x, int prec, int emin_sub)
+{
+    if (x == 0.0 || !isfinite(x)) return x;
+    int e;
+    (void)frexp(x, &e);            /* |x| = m * 2^e with 0.5 <= m < 1 */
+    int ulp_exp = e - prec;        /* weight of the last kept bit */
+    if (ulp_exp < emin_sub) ulp_exp = emin_sub;
+    double q = nearbyint(ldexp(x, -ulp_exp));   /* default rounding mode: nearest-even */
+    return ldexp(q, ulp_exp);
+}
+
+double dsv_oracle_round(double x, int dtype)
+{
+    return dtype == DSV_ORACLE_BF16 ? round_to_format(x, 8, -133) : round_to_format(x, 24, -149);
+}
+
+/* Projection of n token rows: out[i, t] = rnd( sum_c X[i, c] * W[c, t] ).
+ * X [n, d], W [d, r], out [n, r] (float holding the rounded value). */
+void dsv_oracle_project(const float *X, const float *W, int64_t n, int d, int r, int dtype, float *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        for (int t = 0; t < r; ++t) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += (double)X[i * d + c] * (double)W[(int64_t)c * r + t];
+            out[i * r + t] = (float)dsv_oracle_round(acc, dtype);
+        }
+    }
+}
+
+/* Approximate scores of nq query rows against all L keys: S[i, j] = sum_t Qlr[i, t] * Klr[j, t].
+ * No scale and no softmax: the ranking is invariant to both. */
+void dsv_oracle_scores(const float *Qlr, const float *Klr, int64_t nq, int64_t L, int r, double *S)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nq; ++i) {
+        for (int64_t j = 0; j < L; ++j) {
+            double acc = 0.0;
+            for (int t = 0; t < r; ++t) acc += (double)Qlr[i * r + t] * (double)Klr[j * r + t];
+            S[i * L + j] = acc;
+        }
+    }
+}
+
+typedef struct { double s; int32_t j; } scored_key;
+
+/* Total order of the selection: higher score first, equal scores -> lower index first. */
+static int cmp_score_desc_index_asc(const void *a, const void *b)
+{
+    const scored_key *x = (const scored_key *)a, *y = (const scored_key *)b;
+    if (x->s > y->s) return -1;
+    if (x->s < y->s) return 1;
+    return (x->j > y->j) - (x->j < y->j);
+}
+
+static int cmp_int32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* Selection on given score rows: idx[i, :] = the k keys first in the total order above,
+ * written in ascending key index.  S [nq, L] (any real-valued scores), idx [nq, k].
+ * Full sort of every row: the definition, not a streaming algorithm. */
+void dsv_oracle_topk_from_scores(const double *S, int64_t nq, int64_t L, int64_t k, int32_t *idx)
+{
+#pragma omp parallel
+    {
+        scored_key *row = (scored_key *)malloc((size_t)L * sizeof(scored_key));
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t i = 0; i < nq; ++i) {
+            for (int64_t j = 0; j < L; ++j) { row[j].s = S[i * L + j]; row[j].j = (int32_t)j; }
+            qsort(row, (size_t)L, sizeof(scored_key), cmp_score_desc_index_asc);
+            for (int64_t t = 0; t < k; ++t) idx[i * k + t] = row[t].j;
+            qsort(idx + i * k, (size_t)k, sizeof(int32_t), cmp_int32);
+        }
+        free(row);
+    }
+}
+
+/* Stage 1 for nq query rows of one head, end to end: project the given query rows and all L
+ * keys, score, select.  Q [nq, d] (the chosen rows), K [L, d], Wq, Wk [d, r].
+ * Optional outputs (may be NULL): Qlr_out [nq, r], Klr_out [L, r], S_out [nq, L]. */
+void dsv_oracle_lowrank_topk(const float *Q, const float *K, const float *Wq, const float *Wk,
+                             int64_t nq, int64_t L, int d, int r, int64_t k, int dtype,
+                             int32_t *idx, float *Qlr_out, float *Klr_out, double *S_out)
+{
+    float *Qlr = Qlr_out ? Qlr_out : (float *)malloc((size_t)nq * r * sizeof(float));
+    float *Klr = Klr_out ? Klr_out : (float *)malloc((size_t)L * r * sizeof(float));
+    double *S = S_out ? S_out : (double *)malloc((size_t)nq * L * sizeof(double));
+    dsv_oracle_project(Q, Wq, nq, d, r, dtype, Qlr);
+    dsv_oracle_project(K, Wk, L, d, r, dtype, Klr);
+    dsv_oracle_scores(Qlr, Klr, nq, L, r, S);
+    dsv_oracle_topk_from_scores(S, nq, L, k, idx);
+    if (!Qlr_out) free(Qlr);
+    if (!Klr_out) free(Klr);
+    if (!S_out) free(S);
+}
+
+/* Sparse attention forward for nq query rows.  Q [nq, d] (the chosen rows), K, V [L, d],
+ * idx [nq, k] (distinct keys per row, any order).
+ *   s_j = scale * q . k_j          for j in idx[i]
+ *   lse = log sum_j exp(s_j)       (computed as m + log sum exp(s_j - m), m = max_j s_j)
+ *   p_j = exp(s_j - lse),  O_i = sum_j p_j v_j
+ * Outputs: O [nq, d], lse [nq]; P [nq, k] optional (NULL to skip), in idx order. */
+void dsv_oracle_sparse_fwd(const float *Q, const float *K, const float *V, const int32_t *idx,
+                           int64_t nq, int64_t L, int d, int64_t k, double scale,
+                           double *O, double *lse, double *P)
+{
+    (void)L;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc((size_t)k * sizeof(double));
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < nq; ++i) {
+            const int32_t *row = idx + i * k;
+            double m = -INFINITY;
+            for (int64_t t = 0; t < k; ++t) {
+                const float *kj = K + (int64_t)row[t] * d;
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c) acc += (double)Q[i * d + c] * (double)kj[c];
+                s[t] = scale * acc;
+                if (s[t] > m) m = s[t];
+            }
+            double z = 0.0;
+            for (int64_t t = 0; t < k; ++t) z += exp(s[t] - m);
+            double l = m + log(z);
+            lse[i] = l;
+            for (int c = 0; c < d; ++c) O[i * d + c] = 0.0;
+            for (int64_t t = 0; t < k; ++t) {
+                double p = exp(s[t] - l);
+                if (P) P[i * k + t] = p;
+                const float *vj = V + (int64_t)row[t] * d;
+                for (int c = 0; c < d; ++c) O[i * d + c] += p * (double)vj[c];
+            }
+        }
+        free(s);
+    }
+}
+
+/* Contribution of one query row to the gradients, shared by the routines below.
+ *   Delta = dO_i . O_i ;  dP_j = dO_i . v_j ;  dS_j = p_j (dP_j - Delta)
+ * q, dOi, Oi [d]; writes p[t], dS[t] for the k selected keys of this row. */
+static void row_p_and_ds(const float *q, const float *dOi, const double *Oi, double lse_i,
+                         const float *K, const float *V, const int32_t *row, int d, int64_t k,
+                         double scale, double *p, double *dS)
+{
+    double delta = 0.0;
+    for (int c = 0; c < d; ++c) delta += (double)dOi[c] * Oi[c];
+    for (int64_t t = 0; t < k; ++t) {
+        const float *kj = K + (int64_t)row[t] * d;
+        const float *vj = V + (int64_t)row[t] * d;
+        double acc = 0.0, dp = 0.0;
+        for (int c = 0; c < d; ++c) acc += (double)q[c] * (double)kj[c];
+        for (int c = 0; c < d; ++c) dp += (double)dOi[c] * (double)vj[c];
+        p[t] = exp(scale * acc - lse_i);
+        dS[t] = p[t] * (dp - delta);
+    }
+}
+
+/* Sparse attention backward for a whole head (selection held constant).
+ * Q, K, V, dO [L, d]; idx [L, k]; O [L, d] and lse [L] are the oracle's own forward results
+ * in double.  Outputs dQ, dK, dV [L, d]:
+ *   dQ_i = scale * sum_j dS_ij k_j
+ *   dK_j = scale * sum_{i : j in idx[i]} dS_ij q_i
+ *   dV_j =         sum_{i : j in idx[i]} p_ij  dO_i
+ * Keys no query selected receive exact zeros.  Serial over queries: the scatter into dK, dV is
+ * written exactly as the sums above read. */
+void dsv_oracle_sparse_bwd(const float *Q, const float *K, const float *V, const int32_t *idx,
+                           const double *O, const double *lse, const float *dO,
+                           int64_t L, int d, int64_t k, double scale,
+                           double *dQ, double *dK, double *dV)
+{
+    double *p = (double *)malloc((size_t)k * sizeof(double));
+    double *dS = (double *)malloc((size_t)k * sizeof(double));
+    memset(dQ, 0, (size_t)L * d * sizeof(double));
+    memset(dK, 0, (size_t)L * d * sizeof(double));
+    memset(dV, 0, (size_t)L * d * sizeof(double));
+    for (int64_t i = 0; i < L; ++i) {
+        const int32_t *row = idx + i * k;
+        row_p_and_ds(Q + i * d, dO + i * d, O + i * d, lse[i], K, V, row, d, k, scale, p, dS);
+        for (int64_t t = 0; t < k; ++t) {
+            int64_t j = row[t];
+            for (int c = 0; c < d; ++c) {
+                dQ[i * d + c] += scale * dS[t] * (double)K[j * d + c];
+                dK[j * d + c] += scale * dS[t] * (double)Q[i * d + c];
+                dV[j * d + c] += p[t] * (double)dO[i * d + c];
+            }
+        }
+    }
+    free(p);
+    free(dS);
+}
+
+/* dQ for nq chosen query rows only (same formulas).  Q, dO, O [nq, d] and lse [nq] are the
+ * chosen rows; K, V [L, d]; idx [nq, k]. */
+void dsv_oracle_sparse_bwd_dq_rows(const float *Q, const float *K, const float *V, const int32_t *idx,
+                                   const double *O, const double *lse, const float *dO,
+                                   int64_t nq, int d, int64_t k, double scale, double *dQ)
+{
+#pragma omp parallel
+    {
+        double *p = (double *)malloc((size_t)k * sizeof(double));
+        double *dS = (double *)malloc((size_t)k * sizeof(double));
+#pragma omp for schedule(static)
+        for (int64_t i = 0; i < nq; ++i) {
+            const int32_t *row = idx + i * k;
+            row_p_and_ds(Q + i * d, dO + i * d, O + i * d, lse[i], K, V, row, d, k, scale, p, dS);
+            for (int c = 0; c < d; ++c) dQ[i * d + c] = 0.0;
+            for (int64_t t = 0; t < k; ++t)
+                for (int c = 0; c < d; ++c)
+                    dQ[i * d + c] += scale * dS[t] * (double)K[(int64_t)row[t] * d + c];
+        }
+        free(p);
+        free(dS);
+    }
+}
+
+/* dK_j and dV_j for ONE key j, given the n queries that selected it.  For each such query the
+ * caller passes its row data: Qs, dOs, Os [n, d], lses [n], and its index row idxs [n, k]
+ * (every row contains j).  K, V [L, d].  Outputs dKj, dVj [d]. */
+void dsv_oracle_sparse_bwd_dkdv_key(int32_t j, const float *Qs, const float *dOs, const double *Os,
+                                    const double *lses, const int32_t *idxs, int64_t n,
+                                    const float *K, const float *V, int d, int64_t k, double scale,
+                                    double *dKj, double *dVj)
+{
+    double *p = (double *)malloc((size_t)k * sizeof(double));
+    double *dS = (double *)malloc((size_t)k * sizeof(double));
+    for (int c = 0; c < d; ++c) { dKj[c] = 0.0; dVj[c] = 0.0; }
+    for (int64_t a = 0; a < n; ++a) {
+        const int32_t *row = idxs + a * k;
+        row_p_and_ds(Qs + a * d, dOs + a * d, Os + a * d, lses[a], K, V, row, d, k, scale, p, dS);
+        for (int64_t t = 0; t < k; ++t) {
+            if (row[t] != j) continue;
+            for (int c = 0; c < d; ++c) {
+                dKj[c] += scale * dS[t] * (double)Qs[a * d + c];
+                dVj[c] += p[t] * (double)dOs[a * d + c];
+            }
+        }
+    }
+    free(p);
+    free(dS);
+}
+
+/* Dense (full, non-causal) attention of one head, brute force: the L x L probability matrix
+ * is materialised.  Q, K, V [L, d] -> O [L, d], lse [L], P [L, L] (optional). */
+void dsv_oracle_dense_fwd(const float *Q, const float *K, const float *V, int64_t L, int d,
+                          double scale, double *O, double *lse, double *P)
+{
+    double *s = (double *)malloc((size_t)L * sizeof(double));
+    for (int64_t i = 0; i < L; ++i) {
+        double m = -INFINITY;
+        for (int64_t j = 0; j < L; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += (double)Q[i * d + c] * (double)K[j * d + c];
+            s[j] = scale * acc;
+            if (s[j] > m) m = s[j];
+        }
+        double z = 0.0;
+        for (int64_t j = 0; j < L; ++j) z += exp(s[j] - m);
+        lse[i] = m + log(z);
+        for (int c = 0; c < d; ++c) O[i * d + c] = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            double p = exp(s[j] - lse[i]);
+            if (P) P[i * L + j] = p;
+            for (int c = 0; c < d; ++c) O[i * d + c] += p * (double)V[j * d + c];
+        }
+    }
+    free(s);
+}
+
+/* Gradient of dense attention, from the materialised P:  dV = P^T dO;  dP = dO V^T;
+ * dS = P o (dP - rowsum(dO o O));  dQ = scale dS K;  dK = scale dS^T Q. */
+void dsv_oracle_dense_bwd(const float *Q, const float *K, const float *V, const float *dO,
+                          int64_t L, int d, double scale, double *dQ, double *dK, double *dV)
+{
+    double *O = (double *)malloc((size_t)L * d * sizeof(double));
+    double *lse = (double *)malloc((size_t)L * sizeof(double));
+    double *P = (double *)malloc((size_t)L * L * sizeof(double));
+    dsv_oracle_dense_fwd(Q, K, V, L, d, scale, O, lse, P);
+    memset(dQ, 0, (size_t)L * d * sizeof(double));
+    memset(dK, 0, (size_t)L * d * sizeof(double));
+    memset(dV, 0, (size_t)L * d * sizeof(double));
+    for (int64_t i = 0; i < L; ++i) {
+        double delta = 0.0;
+        for (int c = 0; c < d; ++c) delta += (double)dO[i * d + c] * O[i * d + c];
+        for (int64_t j = 0; j < L; ++j) {
+            double dp = 0.0;
+            for (int c = 0; c < d; ++c) dp += (double)dO[i * d + c] * (double)V[j * d + c];
+            double p = P[i * L + j];
+            double ds = p * (dp - delta);
+            for (int c = 0; c < d; ++c) {
+                dQ[i * d + c] += scale * ds * (double)K[j * d + c];
+                dK[j * d + c] += scale * ds * (double)Q[i * d + c];
+                dV[j * d + c] += p * (double)dO[i * d + c];
+            }
+        }
+    }
+    free(O);
+    free(lse);
+    free(P);
+}
+
+int dsv_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
