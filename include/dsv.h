@@ -1,0 +1,140 @@
+/*
+ * dsv.h -- C ABI of libdsv: the two-stage dynamic sparse attention of DSV on one MI355X (gfx950).
+ *
+ * Stage 1 (dsv_lowrank_topk) estimates, for every (head, query), which k keys matter most, from
+ * low-rank projections of Q and K; stage 2 (dsv_sparse_attn_fwd / dsv_sparse_attn_bwd) computes
+ * exact softmax attention, and its gradients, over only those keys.
+ *
+ * Conventions that hold for every entry point
+ *   - Tensor pointers are DEVICE pointers owned by the caller, contiguous, row-major, no strides:
+ *       Q, K, V, O, dO, dQ, dK, dV : [B, H, L, d]   element type dsv_problem.dtype
+ *       Wq, Wk                     : [H, d, r]      same element type (one predictor pair per head)
+ *       lse                        : [B, H, L]      float
+ *       idx                        : ragged int32; the block of (b, h) starts at element
+ *                                    off[b*H+h] = sum over earlier (b', h') of L * k_per_head[h'],
+ *                                    and holds [L, k_h] row-major (dsv_idx_offsets computes off).
+ *     dsv_problem and the arrays it points to (k_per_head) are HOST memory, read during the call.
+ *   - The library allocates and frees no device memory and keeps no state between calls.  Scratch
+ *     comes from the caller: ask dsv_*_workspace() for the size, pass a device buffer of at least
+ *     that many bytes, aligned to 256 bytes.  Its contents are undefined afterwards.
+ *   - Work is enqueued on the caller's HIP stream (hip_stream is a hipStream_t; NULL = the default
+ *     stream) and the call returns once it is enqueued.  Outputs are fully overwritten.
+ *   - Errors come back as a dsv_status; nothing is thrown or aborted across the boundary.  Argument
+ *     errors (null pointer, k_h outside [1, L], unsupported d / r / dtype, workspace too small) are
+ *     found on the host before anything is launched.
+ *   - idx contract: every value in [0, L), values distinct within a row.  dsv_lowrank_topk writes
+ *     rows in ascending key index.  The stage-2 calls accept rows in any order.  Rows that break
+ *     the contract give undefined results (never checked on the device).
+ *   - Supported: d in {64, 128}; r in {16, 32, 64}; dtype F32 or BF16; L >= 1; B*H >= 1.
+ *   - Inputs are assumed finite (no NaN / Inf).
+ *
+ * Paper: "DSV: Exploiting Dynamic Sparsity to Accelerate Large-Scale Video DiT Training".
+ */
+#ifndef DSV_H_
+#define DSV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define DSV_API __attribute__((visibility("default")))
+#else
+#define DSV_API
+#endif
+
+typedef enum { DSV_F32 = 0, DSV_BF16 = 1 } dsv_dtype;
+
+typedef enum {
+    DSV_OK = 0,
+    DSV_EINVAL = -1,        /* bad argument: null pointer, size out of range, k_h not in [1, L] */
+    DSV_EUNSUPPORTED = -2,  /* d, r or dtype outside the supported set */
+    DSV_EWORKSPACE = -3,    /* workspace pointer null / misaligned, or ws_bytes too small */
+    DSV_EHIP = -4           /* a HIP runtime call or a kernel launch reported an error */
+} dsv_status;
+
+/* Problem descriptor shared by all calls (host memory). */
+typedef struct dsv_problem {
+    int32_t B;                  /* batch */
+    int32_t H;                  /* heads held by this GPU */
+    int32_t L;                  /* tokens (the paper's S): queries and keys alike */
+    int32_t d;                  /* head dimension */
+    int32_t r;                  /* predictor rank (the paper's d_lr); ignored by stage 2 */
+    int32_t dtype;              /* dsv_dtype of Q, K, V, Wq, Wk, O, dO, dQ, dK, dV */
+    const int32_t *k_per_head;  /* HOST array [H]: KV kept per query in head h, 1 <= k_h <= L
+                                   (one sparsity level per head: Sec. "Limitations and Future Work") */
+    float scale;                /* softmax scale applied to q.k; the paper uses 1/sqrt(d_k) */
+} dsv_problem;
+
+DSV_API const char *dsv_version(void);
+DSV_API const char *dsv_status_string(dsv_status s);
+
+/* Writes off[0 .. B*H] (HOST int64 array of B*H+1 entries): element offsets of each (b, h) block
+ * of idx; off[B*H] is the total element count.  Returns DSV_EINVAL on a bad descriptor. */
+DSV_API dsv_status dsv_idx_offsets(const dsv_problem *p, int64_t *off);
+
+/* ---- Stage 1: critical-KV estimation ------------------------------------------------------
+ * Sec. "Low-Rank based Sparsity Prediction" (Q_lr = Q Wq, K_lr = K Wk with inner dimension r)
+ * and Sec. "Critical KV Estimation with Kernel Fusion" (top-k of every row of Q_lr K_lr^T,
+ * fused with the product so that the [H, L, L] score tensor is never stored); the two-pass
+ * form -- find each query's threshold, then select against it -- is the one Appendix
+ * "Implementation details" gives for large k.
+ *
+ * For every (b, h, i): idx row = the k_h keys j with the largest score
+ *     s_ij = sum_t Q_lr[i, t] * K_lr[j, t],
+ * Q_lr, K_lr rounded to `dtype`, s accumulated in fp32 on the matrix cores; equal scores go to
+ * the lower key index; the row is written in ascending key index; exactly k_h entries.
+ * Needs workspace (projections and per-query selection state). */
+DSV_API size_t dsv_lowrank_topk_workspace(const dsv_problem *p);
+DSV_API dsv_status dsv_lowrank_topk(const dsv_problem *p, const void *Q, const void *K,
+                            const void *Wq, const void *Wk, int32_t *idx,
+                            void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* ---- Stage 2 forward: attention over the selected KV only -----------------------------------
+ * Sec. "Sparse Attention with Query Grouping" (per-query form, no grouping) with the softmax
+ * attention of Sec. "Various Self-Attention Paradigms":
+ *     s_j = scale * q_i . k_j  for j in idx row (b, h, i);   p = softmax over those j only;
+ *     O_i = sum_j p_j v_j;     lse_i = log sum_j exp(s_j).
+ * O is written in `dtype`, lse in float.  Needs no workspace today (the query returns 0, and a
+ * null workspace is accepted when it does). */
+DSV_API size_t dsv_sparse_attn_fwd_workspace(const dsv_problem *p);
+DSV_API dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, const void *K, const void *V,
+                               const int32_t *idx, void *O, float *lse,
+                               void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* ---- Stage 2 backward ------------------------------------------------------------------------
+ * Gradient of the forward above with the selection held constant (the predictor is trained
+ * outside the main graph: Sec. "Low-Rank based Sparsity Prediction"), given O and lse from
+ * dsv_sparse_attn_fwd and the upstream gradient dO:
+ *     Delta_i = dO_i . O_i;  p_ij = exp(s_ij - lse_i);  dS_ij = p_ij (dO_i . v_j - Delta_i);
+ *     dQ_i = scale sum_j dS_ij k_j;
+ *     dK_j = scale sum_{i: j in row i} dS_ij q_i;   dV_j = sum_{i: j in row i} p_ij dO_i.
+ * Keys no query selected get zeros.  dQ, dK, dV are written in `dtype` (accumulated in fp32). */
+DSV_API size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p);
+DSV_API dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *K, const void *V,
+                               const int32_t *idx, const void *O, const float *lse, const void *dO,
+                               void *dQ, void *dK, void *dV,
+                               void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* ---- Stage-1 internals exported for parity checks ---------------------------------------------
+ * dsv_lowrank_project: only the projection step of stage 1 (Sec. "Low-Rank based Sparsity
+ * Prediction").  Qlr, Klr: [B, H, L, r] in `dtype`, no padding.  No workspace.
+ *
+ * dsv_lowrank_scores_rows: the fp32 scores exactly as the selection kernels compute them (same
+ * matrix-core instruction sequence), for n_rows chosen queries of one (b, h).  Qlr, Klr as written
+ * by dsv_lowrank_project; rows: DEVICE int32 [n_rows], each in [0, L); scores: DEVICE float
+ * [n_rows, L].  No workspace. */
+DSV_API dsv_status dsv_lowrank_project(const dsv_problem *p, const void *Q, const void *K,
+                               const void *Wq, const void *Wk, void *Qlr, void *Klr,
+                               void *hip_stream);
+DSV_API dsv_status dsv_lowrank_scores_rows(const dsv_problem *p, const void *Qlr, const void *Klr,
+                                   int32_t b, int32_t h, const int32_t *rows, int32_t n_rows,
+                                   float *scores, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSV_H_ */

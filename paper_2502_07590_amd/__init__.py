@@ -1,0 +1,22 @@
+"""MI355X-native two-stage dynamic sparse attention (DSV hot path) behind a C ABI.
+
+The Python layer only marshals arguments: every step of the path runs in the HIP kernels of
+libdsv.so.  There is no CPU or PyTorch fallback; a missing library is an error.
+"""
+from .binding import (  # noqa: F401
+    DsvError,
+    Problem,
+    library_path,
+    load_library,
+    version,
+    idx_offsets,
+    lowrank_topk,
+    lowrank_topk_workspace,
+    sparse_attn_fwd,
+    sparse_attn_fwd_workspace,
+    sparse_attn_bwd,
+    sparse_attn_bwd_workspace,
+    lowrank_project,
+    lowrank_scores_rows,
+    EXPORTED_SYMBOLS,
+)

@@ -1,0 +1,204 @@
+"""ctypes binding of libdsv.so: same names as the C entry points, argument marshalling only.
+
+PyTorch supplies device memory (tensor.data_ptr()) and the HIP stream; nothing here computes.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libdsv.so")
+
+DSV_F32, DSV_BF16 = 0, 1
+_DTYPE_CODE = {torch.float32: DSV_F32, torch.bfloat16: DSV_BF16}
+_DTYPE_NAME = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+EXPORTED_SYMBOLS = (
+    "dsv_version", "dsv_status_string", "dsv_idx_offsets",
+    "dsv_lowrank_topk_workspace", "dsv_lowrank_topk",
+    "dsv_sparse_attn_fwd_workspace", "dsv_sparse_attn_fwd",
+    "dsv_sparse_attn_bwd_workspace", "dsv_sparse_attn_bwd",
+    "dsv_lowrank_project", "dsv_lowrank_scores_rows",
+)
+
+
+class DsvError(RuntimeError):
+    pass
+
+
+class _CProblem(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("r", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("k_per_head", ctypes.POINTER(ctypes.c_int32)), ("scale", ctypes.c_float)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libdsv.so from the package directory.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise DsvError(f"{_LIB_PATH} is missing: build it with `python -m paper_2502_07590_amd.build` "
+                       "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+    P = ctypes.POINTER(_CProblem)
+    lib.dsv_version.restype = ctypes.c_char_p
+    lib.dsv_status_string.restype = ctypes.c_char_p
+    lib.dsv_status_string.argtypes = [ctypes.c_int]
+    lib.dsv_idx_offsets.restype = ctypes.c_int
+    lib.dsv_idx_offsets.argtypes = [P, ctypes.POINTER(ctypes.c_int64)]
+    for name in ("dsv_lowrank_topk_workspace", "dsv_sparse_attn_fwd_workspace", "dsv_sparse_attn_bwd_workspace"):
+        getattr(lib, name).restype = sz
+        getattr(lib, name).argtypes = [P]
+    lib.dsv_lowrank_topk.restype = ctypes.c_int
+    lib.dsv_lowrank_topk.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dsv_sparse_attn_fwd.restype = ctypes.c_int
+    lib.dsv_sparse_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dsv_sparse_attn_bwd.restype = ctypes.c_int
+    lib.dsv_sparse_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dsv_lowrank_project.restype = ctypes.c_int
+    lib.dsv_lowrank_project.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
+    lib.dsv_lowrank_scores_rows.restype = ctypes.c_int
+    lib.dsv_lowrank_scores_rows.argtypes = [P, vp, vp, i32, i32, vp, i32, vp, vp]
+    _lib = lib
+    return lib
+
+
+def version() -> str:
+    return load_library().dsv_version().decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        msg = load_library().dsv_status_string(status).decode()
+        raise DsvError(f"{what} failed: {msg} (status {status})")
+
+
+class Problem:
+    """Host-side problem descriptor (mirrors struct dsv_problem)."""
+
+    def __init__(self, B: int, H: int, L: int, d: int, r: int, dtype, k_per_head: Sequence[int], scale: float):
+        if isinstance(dtype, str):
+            dtype = _DTYPE_NAME[dtype]
+        self.B, self.H, self.L, self.d, self.r = int(B), int(H), int(L), int(d), int(r)
+        self.torch_dtype = dtype
+        self.k_per_head = [int(k) for k in k_per_head]
+        self.scale = float(scale)
+        self._k_arr = (ctypes.c_int32 * len(self.k_per_head))(*self.k_per_head)
+        self._c = _CProblem(self.B, self.H, self.L, self.d, self.r, _DTYPE_CODE.get(dtype, -1),
+                            ctypes.cast(self._k_arr, ctypes.POINTER(ctypes.c_int32)), self.scale)
+
+    @property
+    def c(self):
+        return ctypes.byref(self._c)
+
+    @property
+    def nnz(self) -> int:
+        return self.B * self.L * sum(self.k_per_head)
+
+
+def idx_offsets(p: Problem):
+    off = (ctypes.c_int64 * (p.B * p.H + 1))()
+    _check(load_library().dsv_idx_offsets(p.c, off), "dsv_idx_offsets")
+    return list(off)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise DsvError("libdsv takes device tensors")
+    if not t.is_contiguous():
+        raise DsvError("libdsv takes contiguous tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _workspace(nbytes: int, device, workspace):
+    if nbytes == 0:
+        return None, 0
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def lowrank_topk_workspace(p: Problem) -> int:
+    return int(load_library().dsv_lowrank_topk_workspace(p.c))
+
+
+def sparse_attn_fwd_workspace(p: Problem) -> int:
+    return int(load_library().dsv_sparse_attn_fwd_workspace(p.c))
+
+
+def sparse_attn_bwd_workspace(p: Problem) -> int:
+    return int(load_library().dsv_sparse_attn_bwd_workspace(p.c))
+
+
+def lowrank_topk(p: Problem, Q, K, Wq, Wk, idx=None, workspace=None, stream=None):
+    """idx (int32, ragged [sum_h L*k_h]) = per-(head, query) top-k keys of the low-rank scores."""
+    lib = load_library()
+    if idx is None:
+        idx = torch.empty(p.nnz, dtype=torch.int32, device=Q.device)
+    ws, nbytes = _workspace(lowrank_topk_workspace(p), Q.device, workspace)
+    _check(lib.dsv_lowrank_topk(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(idx), _ptr(ws), nbytes,
+                                _stream(stream)), "dsv_lowrank_topk")
+    return idx
+
+
+def sparse_attn_fwd(p: Problem, Q, K, V, idx, O=None, lse=None, workspace=None, stream=None):
+    lib = load_library()
+    if O is None:
+        O = torch.empty_like(Q)
+    if lse is None:
+        lse = torch.empty((p.B, p.H, p.L), dtype=torch.float32, device=Q.device)
+    ws, nbytes = _workspace(sparse_attn_fwd_workspace(p), Q.device, workspace)
+    _check(lib.dsv_sparse_attn_fwd(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(lse), _ptr(ws), nbytes,
+                                   _stream(stream)), "dsv_sparse_attn_fwd")
+    return O, lse
+
+
+def sparse_attn_bwd(p: Problem, Q, K, V, idx, O, lse, dO, dQ=None, dK=None, dV=None, workspace=None, stream=None):
+    lib = load_library()
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    ws, nbytes = _workspace(sparse_attn_bwd_workspace(p), Q.device, workspace)
+    _check(lib.dsv_sparse_attn_bwd(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(lse), _ptr(dO),
+                                   _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws), nbytes, _stream(stream)),
+           "dsv_sparse_attn_bwd")
+    return dQ, dK, dV
+
+
+def lowrank_project(p: Problem, Q, K, Wq, Wk, Qlr=None, Klr=None, stream=None):
+    lib = load_library()
+    shape = (p.B, p.H, p.L, p.r)
+    Qlr = torch.empty(shape, dtype=p.torch_dtype, device=Q.device) if Qlr is None else Qlr
+    Klr = torch.empty(shape, dtype=p.torch_dtype, device=Q.device) if Klr is None else Klr
+    _check(lib.dsv_lowrank_project(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(Qlr), _ptr(Klr),
+                                   _stream(stream)), "dsv_lowrank_project")
+    return Qlr, Klr
+
+
+def lowrank_scores_rows(p: Problem, Qlr, Klr, b: int, h: int, rows, scores=None, stream=None):
+    lib = load_library()
+    n = int(rows.numel())
+    scores = torch.empty((n, p.L), dtype=torch.float32, device=Qlr.device) if scores is None else scores
+    _check(lib.dsv_lowrank_scores_rows(p.c, _ptr(Qlr), _ptr(Klr), int(b), int(h), _ptr(rows), n, _ptr(scores),
+                                       _stream(stream)), "dsv_lowrank_scores_rows")
+    return scores

@@ -1,0 +1,203 @@
+// C ABI of libdsv: argument checks, workspace layout, launch order.  All checks run on the host
+// before anything is enqueued; the library never allocates device memory.
+#include <algorithm>
+#include <vector>
+
+#include "common.h"
+
+namespace dsv {
+namespace {
+
+bool supported_d(int d) { return d == 64 || d == 128; }
+bool supported_r(int r) { return r == 16 || r == 32 || r == 64; }
+bool supported_dtype(int t) { return t == DSV_F32 || t == DSV_BF16; }
+size_t esize(int dtype) { return dtype == DSV_BF16 ? 2 : 4; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+dsv_status check_problem(const dsv_problem *p, bool need_r)
+{
+    if (!p || !p->k_per_head) return DSV_EINVAL;
+    if (p->B < 1 || p->H < 1 || p->L < 1) return DSV_EINVAL;
+    if ((int64_t)p->B * p->H > (1 << 20)) return DSV_EINVAL;
+    if (!supported_dtype(p->dtype) || !supported_d(p->d)) return DSV_EUNSUPPORTED;
+    if (need_r && !supported_r(p->r)) return DSV_EUNSUPPORTED;
+    for (int h = 0; h < p->H; ++h)
+        if (p->k_per_head[h] < 1 || p->k_per_head[h] > p->L) return DSV_EINVAL;
+    return DSV_OK;
+}
+
+// Launch tables: all (b, h) pairs sorted by descending k (stable), cut into groups of kMaxSlots.
+std::vector<HeadTable> make_tables(const dsv_problem &p)
+{
+    const int nbh = p.B * p.H;
+    std::vector<int64_t> off(nbh + 1, 0);
+    for (int bh = 0; bh < nbh; ++bh) off[bh + 1] = off[bh] + (int64_t)p.L * p.k_per_head[bh % p.H];
+    std::vector<int> order(nbh);
+    for (int i = 0; i < nbh; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int a, int b) { return p.k_per_head[a % p.H] > p.k_per_head[b % p.H]; });
+    std::vector<HeadTable> tabs((nbh + kMaxSlots - 1) / kMaxSlots);
+    for (int i = 0; i < nbh; ++i) {
+        HeadTable &t = tabs[i / kMaxSlots];
+        const int s = i % kMaxSlots;
+        t.n = s + 1;
+        t.bh[s] = order[i];
+        t.k[s] = p.k_per_head[order[i] % p.H];
+        t.off[s] = off[order[i]];
+    }
+    return tabs;
+}
+
+struct Stage1Workspace {
+    size_t qlr, klr, prefix, krem, total;
+};
+
+Stage1Workspace stage1_layout(const dsv_problem &p)
+{
+    const size_t tok = (size_t)p.B * p.H * p.L;
+    Stage1Workspace w;
+    size_t o = 0;
+    w.qlr = o; o = align_up(o + tok * p.r * esize(p.dtype), 256);
+    w.klr = o; o = align_up(o + tok * p.r * esize(p.dtype), 256);
+    w.prefix = o; o = align_up(o + tok * 4, 256);
+    w.krem = o; o = align_up(o + tok * 4, 256);
+    w.total = o;
+    return w;
+}
+
+dsv_status check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return DSV_OK;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || have < need) return DSV_EWORKSPACE;
+    return DSV_OK;
+}
+
+}  // namespace
+}  // namespace dsv
+
+using namespace dsv;
+
+extern "C" {
+
+const char *dsv_version(void) { return "dsv 0.1 (gfx950)"; }
+
+const char *dsv_status_string(dsv_status s)
+{
+    switch (s) {
+    case DSV_OK: return "ok";
+    case DSV_EINVAL: return "invalid argument";
+    case DSV_EUNSUPPORTED: return "unsupported head dimension, rank or dtype";
+    case DSV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case DSV_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+dsv_status dsv_idx_offsets(const dsv_problem *p, int64_t *off)
+{
+    if (!p || !p->k_per_head || !off || p->B < 1 || p->H < 1 || p->L < 1) return DSV_EINVAL;
+    for (int h = 0; h < p->H; ++h)
+        if (p->k_per_head[h] < 1 || p->k_per_head[h] > p->L) return DSV_EINVAL;
+    off[0] = 0;
+    for (int bh = 0; bh < p->B * p->H; ++bh) off[bh + 1] = off[bh] + (int64_t)p->L * p->k_per_head[bh % p->H];
+    return DSV_OK;
+}
+
+size_t dsv_lowrank_topk_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, true) != DSV_OK) return 0;
+    return stage1_layout(*p).total;
+}
+
+dsv_status dsv_lowrank_topk(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,
+                            int32_t *idx, void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, true);
+    if (st != DSV_OK) return st;
+    if (!Q || !K || !Wq || !Wk || !idx) return DSV_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(Wq) || !aligned16(Wk) || !aligned16(idx)) return DSV_EINVAL;
+    const Stage1Workspace w = stage1_layout(*p);
+    st = check_workspace(workspace, ws_bytes, w.total);
+    if (st != DSV_OK) return st;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    st = launch_project(*p, Q, K, Wq, Wk, ws + w.qlr, ws + w.klr, stream);
+    if (st != DSV_OK) return st;
+    const std::vector<HeadTable> tabs = make_tables(*p);
+    return launch_select(*p, tabs.data(), (int)tabs.size(), ws + w.qlr, ws + w.klr,
+                         reinterpret_cast<uint32_t *>(ws + w.prefix), reinterpret_cast<int32_t *>(ws + w.krem), idx,
+                         stream);
+}
+
+size_t dsv_sparse_attn_fwd_workspace(const dsv_problem *p)
+{
+    (void)p;
+    return 0;
+}
+
+dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, const void *K, const void *V, const int32_t *idx,
+                               void *O, float *lse, void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    (void)workspace;
+    (void)ws_bytes;
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if (!Q || !K || !V || !idx || !O || !lse) return DSV_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(O) || !aligned16(lse))
+        return DSV_EINVAL;
+    const std::vector<HeadTable> tabs = make_tables(*p);
+    return launch_sparse_fwd(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse,
+                             static_cast<hipStream_t>(hip_stream));
+}
+
+size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, false) != DSV_OK) return 0;
+    const size_t n = (size_t)p->B * p->H * p->L * p->d;
+    return 2 * align_up(n * sizeof(float), 256);
+}
+
+dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *K, const void *V, const int32_t *idx,
+                               const void *O, const float *lse, const void *dO, void *dQ, void *dK, void *dV,
+                               void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if (!Q || !K || !V || !idx || !O || !lse || !dO || !dQ || !dK || !dV) return DSV_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(O) || !aligned16(lse) ||
+        !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
+        return DSV_EINVAL;
+    const size_t need = dsv_sparse_attn_bwd_workspace(p);
+    st = check_workspace(workspace, ws_bytes, need);
+    if (st != DSV_OK) return st;
+    char *ws = static_cast<char *>(workspace);
+    float *dKacc = reinterpret_cast<float *>(ws);
+    float *dVacc = reinterpret_cast<float *>(ws + need / 2);
+    const std::vector<HeadTable> tabs = make_tables(*p);
+    return launch_sparse_bwd(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse, dO, dQ, dK, dV, dKacc, dVacc,
+                             static_cast<hipStream_t>(hip_stream));
+}
+
+dsv_status dsv_lowrank_project(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,
+                               void *Qlr, void *Klr, void *hip_stream)
+{
+    dsv_status st = check_problem(p, true);
+    if (st != DSV_OK) return st;
+    if (!Q || !K || !Wq || !Wk || !Qlr || !Klr) return DSV_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(Wq) || !aligned16(Wk) || !aligned16(Qlr) || !aligned16(Klr))
+        return DSV_EINVAL;
+    return launch_project(*p, Q, K, Wq, Wk, Qlr, Klr, static_cast<hipStream_t>(hip_stream));
+}
+
+dsv_status dsv_lowrank_scores_rows(const dsv_problem *p, const void *Qlr, const void *Klr, int32_t b, int32_t h,
+                                   const int32_t *rows, int32_t n_rows, float *scores, void *hip_stream)
+{
+    dsv_status st = check_problem(p, true);
+    if (st != DSV_OK) return st;
+    if (!Qlr || !Klr || !rows || !scores || n_rows < 1) return DSV_EINVAL;
+    if (b < 0 || b >= p->B || h < 0 || h >= p->H) return DSV_EINVAL;
+    if (!aligned16(Qlr) || !aligned16(Klr)) return DSV_EINVAL;
+    return launch_scores_rows(*p, Qlr, Klr, b * p->H + h, rows, n_rows, scores, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

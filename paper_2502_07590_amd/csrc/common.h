@@ -1,0 +1,174 @@
+// Shared device/host helpers of libdsv (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dsv.h"
+
+namespace dsv {
+
+// bf16 tensors are handled as raw 16-bit patterns.
+typedef uint16_t bf16_t;
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+
+constexpr int kWave = 64;
+constexpr int kMaxSlots = 64;  // (batch, head) pairs described by one kernel launch
+
+// Per-launch table of the (batch, head) pairs a grid works on, passed by value as a kernel
+// argument.  Slots are ordered by descending k so that the heaviest heads are dispatched first.
+struct HeadTable {
+    int32_t n;
+    int32_t bh[kMaxSlots];   // b * H + h
+    int32_t k[kMaxSlots];    // KV kept per query in that head
+    int64_t off[kMaxSlots];  // element offset of the head's [L, k] block inside idx
+};
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// Round-to-nearest-even fp32 -> bf16 for finite inputs.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    // row_ror:8, :4, :2, :1 (rotations inside each group of 16 lanes)
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x128, 0xF, 0xF, false));
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x124, 0xF, 0xF, false));
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x122, 0xF, 0xF, false));
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x121, 0xF, 0xF, false));
+    return x;
+}
+
+__device__ __forceinline__ float row16_max(float x)
+{
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x128, 0xF, 0xF, false)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x124, 0xF, 0xF, false)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x122, 0xF, 0xF, false)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x121, 0xF, 0xF, false)));
+    return x;
+}
+
+// ---- a lane's share of one [d]-row: CH consecutive channels, kept as raw 32-bit words -------
+template <typename T, int CH> struct RowChunk {
+    static constexpr int NW = CH * (int)sizeof(T) / 4;
+    uint32_t w[NW];
+};
+
+template <typename T, int CH>
+__device__ __forceinline__ RowChunk<T, CH> load_chunk(const T *p)
+{
+    RowChunk<T, CH> c;
+    constexpr int NW = RowChunk<T, CH>::NW;
+    if constexpr (NW == 2) {
+        uint2 v = *reinterpret_cast<const uint2 *>(p);
+        c.w[0] = v.x; c.w[1] = v.y;
+    } else {
+        static_assert(NW % 4 == 0, "row chunk must be 8 bytes or a multiple of 16 bytes");
+#pragma unroll
+        for (int i = 0; i < NW / 4; ++i) {
+            uint4 v = reinterpret_cast<const uint4 *>(p)[i];
+            c.w[4 * i + 0] = v.x; c.w[4 * i + 1] = v.y; c.w[4 * i + 2] = v.z; c.w[4 * i + 3] = v.w;
+        }
+    }
+    return c;
+}
+
+template <typename T, int CH>
+__device__ __forceinline__ void unpack_chunk(const RowChunk<T, CH> &c, float (&f)[CH])
+{
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) f[i] = __uint_as_float(c.w[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < CH / 2; ++i) {
+            f[2 * i + 0] = __uint_as_float(c.w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(c.w[i] & 0xFFFF0000u);
+        }
+    }
+}
+
+template <typename T, int CH>
+__device__ __forceinline__ void store_chunk(T *p, const float (&f)[CH])
+{
+    constexpr int NW = RowChunk<T, CH>::NW;
+    uint32_t w[NW];
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) w[i] = __float_as_uint(f[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < CH / 2; ++i)
+            w[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+    }
+    if constexpr (NW == 2) {
+        *reinterpret_cast<uint2 *>(p) = make_uint2(w[0], w[1]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < NW / 4; ++i)
+            reinterpret_cast<uint4 *>(p)[i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
+    }
+}
+
+// Partial dot product of two row chunks (this lane's CH channels), fp32 accumulation.
+template <typename T, int CH>
+__device__ __forceinline__ float dot_chunk(const RowChunk<T, CH> &a, const RowChunk<T, CH> &b)
+{
+    float acc = 0.f;
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) acc = fmaf(__uint_as_float(a.w[i]), __uint_as_float(b.w[i]), acc);
+    } else {
+#pragma unroll
+        for (int i = 0; i < CH / 2; ++i)
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w[i]),
+                                                  __builtin_bit_cast(bf16x2_t, b.w[i]), acc, false);
+    }
+    return acc;
+}
+
+// ---- host side ------------------------------------------------------------------------------
+#define DSV_HIP_CHECK(expr)                         \
+    do {                                            \
+        hipError_t e_ = (expr);                     \
+        if (e_ != hipSuccess) return DSV_EHIP;      \
+    } while (0)
+
+#define DSV_LAUNCH_CHECK()                                  \
+    do {                                                    \
+        if (hipGetLastError() != hipSuccess) return DSV_EHIP; \
+    } while (0)
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Host: entry points of the per-stage translation units (called from api.hip).
+dsv_status launch_project(const dsv_problem &p, const void *Q, const void *K, const void *Wq, const void *Wk,
+                          void *Qlr, void *Klr, hipStream_t st);
+dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void *Klr, int bh,
+                              const int32_t *rows, int n_rows, float *scores, hipStream_t st);
+dsv_status launch_select(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
+                         uint32_t *prefix, int32_t *krem, int32_t *idx, hipStream_t st);
+dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                             const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st);
+dsv_status launch_sparse_bwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                             const void *V, const int32_t *idx, const void *O, const float *lse, const void *dO,
+                             void *dQ, void *dK, void *dV, float *dKacc, float *dVacc, hipStream_t st);
+
+}  // namespace dsv

@@ -1,0 +1,80 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol the header declares,
+and turns bad arguments into error codes on the host before anything touches a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def dsv():
+    import paper_2502_07590_amd as m
+    if not os.path.exists(m.library_path()):
+        from paper_2502_07590_amd.build import build_library
+        build_library()
+    m.load_library()
+    return m
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dsv.h")).read()
+    return sorted(set(re.findall(r"DSV_API[^;(]*?\b(dsv_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(dsv):
+    declared = _declared_symbols()
+    assert len(declared) >= 11
+    lib = ctypes.CDLL(dsv.library_path())
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in include/dsv.h but not exported"
+    assert sorted(dsv.EXPORTED_SYMBOLS) == declared
+
+
+def test_version_and_status_strings(dsv):
+    assert "gfx950" in dsv.version()
+    lib = dsv.load_library()
+    assert lib.dsv_status_string(0) == b"ok"
+    assert all(lib.dsv_status_string(s) not in (b"ok", b"unknown status") for s in (-1, -2, -3, -4))
+
+
+def test_idx_offsets_ragged(dsv):
+    p = dsv.Problem(2, 3, 100, 64, 16, "bf16", [10, 100, 1], 0.1)
+    assert dsv.idx_offsets(p) == [0, 1000, 11000, 11100, 12100, 22100, 22200]
+    assert p.nnz == 22200
+
+
+def test_bad_descriptors_are_rejected_on_the_host(dsv):
+    lib = dsv.load_library()
+    one = ctypes.c_void_p(256)       # a non-null, aligned placeholder: never dereferenced on these paths
+    def topk(p, ws=one, ws_bytes=1 << 40):
+        return lib.dsv_lowrank_topk(p.c, one, one, one, one, one, ws, ws_bytes, None)
+    ok = dict(B=1, H=2, L=64, d=64, r=16, dtype="bf16", k_per_head=[8, 8], scale=0.1)
+    assert topk(dsv.Problem(**{**ok, "k_per_head": [8, 65]})) == -1        # k > L
+    assert topk(dsv.Problem(**{**ok, "k_per_head": [0, 8]})) == -1         # k < 1
+    assert topk(dsv.Problem(**{**ok, "L": 0})) == -1
+    assert topk(dsv.Problem(**{**ok, "d": 80})) == -2
+    assert topk(dsv.Problem(**{**ok, "r": 12})) == -2
+    assert topk(dsv.Problem(**{**ok, "dtype": __import__("torch").float16})) == -2
+    p = dsv.Problem(**ok)
+    need = dsv.lowrank_topk_workspace(p)
+    assert need > 0
+    assert topk(p, ws=one, ws_bytes=need - 1) == -3                         # too small
+    assert topk(p, ws=None) == -3                                           # missing
+    assert topk(p, ws=ctypes.c_void_p(264)) == -3                           # misaligned
+    assert lib.dsv_lowrank_topk(p.c, None, one, one, one, one, one, 1 << 40, None) == -1
+    assert lib.dsv_lowrank_topk(p.c, ctypes.c_void_p(260), one, one, one, one, one, 1 << 40, None) == -1
+    assert lib.dsv_sparse_attn_fwd(p.c, one, one, None, one, one, one, None, 0, None) == -1
+    assert lib.dsv_sparse_attn_bwd(p.c, one, one, one, one, one, one, one, one, one, one, None, 0, None) == -3
+    assert dsv.sparse_attn_bwd_workspace(p) >= 2 * 2 * 64 * 64 * 4
+    assert lib.dsv_lowrank_scores_rows(p.c, one, one, 0, 2, one, 4, one, None) == -1   # head out of range
+
+
+def test_missing_library_is_loud(dsv, monkeypatch):
+    import paper_2502_07590_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_PATH", os.path.join(ROOT, "no_such_dir", "libdsv.so"))
+    with pytest.raises(b.DsvError):
+        b.load_library()
