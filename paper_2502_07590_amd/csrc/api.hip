@@ -65,6 +65,26 @@ Stage1Workspace stage1_layout(const dsv_problem &p)
     return w;
 }
 
+struct BwdLayout {
+    size_t delta, cnt, cnt_bytes, col, idxT, total;
+};
+
+BwdLayout bwd_layout(const dsv_problem &p)
+{
+    const size_t nbh = (size_t)p.B * p.H;
+    const size_t tok = nbh * p.L;
+    size_t nnz = 0;
+    for (size_t bh = 0; bh < nbh; ++bh) nnz += (size_t)p.L * p.k_per_head[bh % p.H];
+    BwdLayout w;
+    size_t o = 0;
+    w.delta = o; o = align_up(o + tok * 4, 256);
+    w.cnt = o; w.cnt_bytes = align_up(tok * 4, 16); o = align_up(o + w.cnt_bytes, 256);
+    w.col = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
+    w.idxT = o; o = align_up(o + nnz * 4, 256);
+    w.total = o;
+    return w;
+}
+
 dsv_status check_workspace(const void *ws, size_t have, size_t need)
 {
     if (need == 0) return DSV_OK;
@@ -153,8 +173,7 @@ dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, const void *
 size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p)
 {
     if (check_problem(p, false) != DSV_OK) return 0;
-    const size_t n = (size_t)p->B * p->H * p->L * p->d;
-    return 2 * align_up(n * sizeof(float), 256);
+    return bwd_layout(*p).total;
 }
 
 dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *K, const void *V, const int32_t *idx,
@@ -167,14 +186,18 @@ dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(O) || !aligned16(lse) ||
         !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
         return DSV_EINVAL;
-    const size_t need = dsv_sparse_attn_bwd_workspace(p);
-    st = check_workspace(workspace, ws_bytes, need);
+    const BwdLayout w = bwd_layout(*p);
+    st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
     char *ws = static_cast<char *>(workspace);
-    float *dKacc = reinterpret_cast<float *>(ws);
-    float *dVacc = reinterpret_cast<float *>(ws + need / 2);
+    BwdWorkspace b;
+    b.delta = reinterpret_cast<float *>(ws + w.delta);
+    b.cnt = reinterpret_cast<int32_t *>(ws + w.cnt);
+    b.cnt_bytes = w.cnt_bytes;
+    b.col = reinterpret_cast<int64_t *>(ws + w.col);
+    b.idxT = reinterpret_cast<int32_t *>(ws + w.idxT);
     const std::vector<HeadTable> tabs = make_tables(*p);
-    return launch_sparse_bwd(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse, dO, dQ, dK, dV, dKacc, dVacc,
+    return launch_sparse_bwd(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, lse, dO, dQ, dK, dV, b,
                              static_cast<hipStream_t>(hip_stream));
 }
 

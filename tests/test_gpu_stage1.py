@@ -43,8 +43,11 @@ def test_project_matches_oracle(dtype, d, r, L):
             g = got[0, h].to(torch.float64).cpu().numpy()
             exact = X.astype(np.float64) @ W.astype(np.float64)
             if dtype == "bf16":
-                ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(exact), 1e-30))) - 7)
-                assert np.all(np.abs(g - ref) <= ulp * 1.0001)          # at most one bf16 ulp apart
+                # one bf16 ulp of the result, plus the fp32 accumulation error of the d-term sum (which
+                # dominates only when the terms cancel to a tiny result)
+                ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.maximum(np.abs(g), np.abs(ref)), 1e-30))) - 7)
+                acc_err = d * 2.0 ** -24 * (np.abs(X).astype(np.float64) @ np.abs(W).astype(np.float64))
+                assert np.all(np.abs(g - ref) <= ulp * 1.0001 + acc_err)
                 assert (g == ref).mean() > 0.98                           # and almost always identical
             else:
                 assert np.all(np.abs(g - exact) <= 1e-5 * np.maximum(1.0, np.abs(exact)))
