@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the DSV sparse-attention hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch that is already resident in HBM:
+    stage 1  dsv_lowrank_topk          (project, threshold search, emit idx)
+    stage 2  dsv_sparse_attn_fwd
+             dsv_sparse_attn_bwd_dq, dsv_idx_transpose, dsv_sparse_attn_bwd_dkdv
+             (the three steps dsv_sparse_attn_bwd runs, called one by one so that each can be timed)
+Workload: the L = 128k configuration of the benchmark list (6 heads = one GPU's head-parallel share
+of 24, d = 128, r = 16, k = 8192 per query, bf16).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-dense] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=2, help="index into the benchmark config list (headline: 2)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention comparator")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="query rows of the oracle sample (0 = auto)")
+    return ap.parse_args()
+
+
+def upload_inputs(cfg, seed, dev, torch, wl, np):
+    td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    shape = (1, cfg.H, cfg.L, cfg.d)
+    g = {n: torch.empty(shape, dtype=td, device=dev) for n in ("Q", "K", "V", "dO")}
+    Wq = torch.empty((cfg.H, cfg.d, cfg.r), dtype=td, device=dev)
+    Wk = torch.empty((cfg.H, cfg.d, cfg.r), dtype=td, device=dev)
+    for h in range(cfg.H):
+        t = wl.head_tensors(cfg, h, seed=seed)
+        for n in g:
+            g[n][0, h].copy_(torch.from_numpy(t[n]).to(td))
+        wq, wk = wl.predictor_weights(cfg, h, seed=seed)
+        Wq[h].copy_(torch.from_numpy(wq).to(td))
+        Wk[h].copy_(torch.from_numpy(wk).to(td))
+    return g, Wq, Wk
+
+
+def cpu_baseline(cfg, ks, seed, n_rows, wl, np):
+    """Time the CPU oracle (as it stands) on n_rows query rows of head 0 through the whole path and
+    scale to the full problem: per-head time = t(project all keys) + (L / n_rows) * t(rows)."""
+    import oracle
+    t = wl.head_tensors(cfg, 0, seed=seed)
+    Wq, Wk = wl.predictor_weights(cfg, 0, seed=seed)
+    k = int(ks[0])
+    rows = np.linspace(0, cfg.L - 1, n_rows).astype(np.int64)
+    t0 = time.perf_counter()
+    Klr = oracle.project(t["K"], Wk, cfg.dtype)
+    t_keys = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    Qlr = oracle.project(t["Q"][rows], Wq, cfg.dtype)
+    S = oracle.scores(Qlr, Klr)
+    idx = oracle.topk_from_scores(S, k)
+    t_s1 = time.perf_counter() - t0
+    del S
+    t0 = time.perf_counter()
+    oracle.sparse_fwd(t["Q"][rows], t["K"], t["V"], idx, cfg.scale)
+    t_fwd = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.sparse_bwd_rows(t["Q"][rows], t["K"], t["V"], idx, t["dO"][rows], cfg.scale)
+    t_bwd = time.perf_counter() - t0           # includes the forward it needs for O and lse
+    per_head = t_keys + (cfg.L / n_rows) * (t_s1 + t_fwd + t_bwd)
+    mean_k_scale = float(np.mean(ks)) / k      # other heads scale with their own k in stage 2 only
+    total = cfg.H * (t_keys + (cfg.L / n_rows) * (t_s1 + (t_fwd + t_bwd) * mean_k_scale))
+    return {"seconds_full_problem_extrapolated": total, "per_head_s": per_head, "sample_s": t_keys + t_s1 + t_fwd + t_bwd,
+            "threads": oracle.max_threads(),
+            "parts_s": {"project_keys": t_keys, "stage1_rows": t_s1, "fwd_rows": t_fwd, "bwd_rows": t_bwd}}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one GPU's head-parallel share at the real sequence length); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2502_07590_amd as dsv
+    import workloads as wl
+
+    dsv.load_library()  # fails loudly if libdsv.so is missing: there is no fallback
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    cfg = wl.get_config(args.config)
+    ks = wl.k_per_head(cfg, seed=args.seed)
+    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, ks.tolist(), cfg.scale)
+    esize = 2 if cfg.dtype == "bf16" else 4
+    nnz = int(cfg.L * ks.astype(np.int64).sum())
+    n_scores = cfg.H * cfg.L * cfg.L
+
+    t_gen = time.perf_counter()
+    g, Wq, Wk = upload_inputs(cfg, args.seed, dev, torch, wl, np)
+    t_gen = time.perf_counter() - t_gen
+
+    # device buffers, allocated once
+    idx = torch.empty(nnz, dtype=torch.int32, device=dev)
+    idx_t = torch.empty(nnz, dtype=torch.int32, device=dev)
+    col_ptr = torch.empty((cfg.H, cfg.L + 1), dtype=torch.int64, device=dev)
+    O = torch.empty_like(g["Q"]); dQ = torch.empty_like(g["Q"]); dK = torch.empty_like(g["Q"]); dV = torch.empty_like(g["Q"])
+    lse = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
+    delta = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
+    ws1 = torch.empty(dsv.lowrank_topk_workspace(p), dtype=torch.uint8, device=dev)
+    wst = torch.empty(dsv.idx_transpose_workspace(p), dtype=torch.uint8, device=dev)
+
+    names = ("lowrank_topk", "sparse_attn_fwd", "sparse_attn_bwd_dq", "idx_transpose", "sparse_attn_bwd_dkdv")
+
+    def step(events=None):
+        calls = (
+            lambda: dsv.lowrank_topk(p, g["Q"], g["K"], Wq, Wk, idx=idx, workspace=ws1),
+            lambda: dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx, O=O, lse=lse),
+            lambda: dsv.sparse_attn_bwd_dq(p, g["Q"], g["K"], g["V"], idx, lse, g["dO"], dQ=dQ, delta=delta),
+            lambda: dsv.idx_transpose(p, idx, idx_t=idx_t, col_ptr=col_ptr, workspace=wst),
+            lambda: dsv.sparse_attn_bwd_dkdv(p, g["Q"], g["K"], g["V"], idx_t, col_ptr, lse, delta, g["dO"], dK=dK, dV=dV),
+        )
+        if events is None:
+            for c in calls:
+                c()
+            return
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
+        ev[0].record()
+        for i, c in enumerate(calls):
+            c()
+            ev[i + 1].record()
+        events.append(ev)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    call_ms = {n: 0.0 for n in names}
+    for ev in events:
+        for i, n in enumerate(names):
+            call_ms[n] += ev[i].elapsed_time(ev[i + 1]) / args.steps
+
+    # ---- derived figures ------------------------------------------------------------------------
+    flops_alg = 4.0 * cfg.H * cfg.L * cfg.d * cfg.r + 2.0 * cfg.r * n_scores + 14.0 * cfg.d * nnz
+    flops_dense_eq = 14.0 * cfg.d * n_scores
+    eff_tflops = flops_dense_eq / (ms_per_step * 1e-3) / 1e12
+    # algorithmic bytes per (query, key) pair of each gather pass: one K row + one V row + the index
+    # (forward, dq); one Q row + one dO row + the index + lse_i + Delta_i (dkdv)
+    pair_bytes = {"sparse_attn_fwd": 2 * cfg.d * esize + 4, "sparse_attn_bwd_dq": 2 * cfg.d * esize + 4,
+                  "sparse_attn_bwd_dkdv": 2 * cfg.d * esize + 12}
+    dominant = max(pair_bytes, key=lambda n: call_ms[n])
+    achieved = pair_bytes[dominant] * nnz / (call_ms[dominant] * 1e-3) / 1e9
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": pair_bytes[dominant] * nnz, "launch_ms": round(call_ms[dominant], 3)}
+
+    out = {
+        "metric": "sparse attention fwd+bwd (stage 1 + stage 2) effective TFLOP/s at L=128k" if args.config == 2
+                  else f"sparse attention fwd+bwd effective TFLOP/s, config {args.config}",
+        "value": round(eff_tflops, 2), "unit": "TFLOP/s (dense-equivalent: 14*d*H*L^2 / step time)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}", "B": 1, "H": cfg.H, "L": cfg.L, "d": cfg.d, "r": cfg.r,
+                   "k_per_head": sorted(set(ks.tolist())), "nnz_pairs": nnz, "scale": cfg.scale, "seed": args.seed},
+        "stage_ms": {n: round(v, 3) for n, v in call_ms.items()},
+        "algorithmic_tflops": round(flops_alg / (ms_per_step * 1e-3) / 1e12, 2),
+        "input_generation_s": round(t_gen, 1),
+        "roofline": roofline,
+    }
+
+    # ---- dense comparator: library flash attention fwd+bwd at the same shape ----------------------
+    if not args.no_dense:
+        try:
+            import torch.nn.functional as F
+            q = g["Q"].clone().requires_grad_(True); k_ = g["K"].clone().requires_grad_(True); v = g["V"].clone().requires_grad_(True)
+            def dense():
+                o = F.scaled_dot_product_attention(q, k_, v, scale=cfg.scale)
+                o.backward(g["dO"])
+                q.grad = k_.grad = v.grad = None
+            dense()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 2
+            e0.record()
+            for _ in range(reps):
+                dense()
+            e1.record()
+            torch.cuda.synchronize()
+            dense_ms = e0.elapsed_time(e1) / reps
+            out["dense"] = {"impl": "torch scaled_dot_product_attention fwd+bwd", "ms": round(dense_ms, 3),
+                            "tflops": round(flops_dense_eq / (dense_ms * 1e-3) / 1e12, 2),
+                            "speedup_sparse_over_dense": round(dense_ms / ms_per_step, 3)}
+            del q, k_, v
+        except Exception as e:  # the comparator is optional context; the sparse path above is the product
+            out["dense"] = {"error": repr(e)[:200]}
+
+    # ---- CPU oracle timed on a bounded sample ------------------------------------------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.max_threads()
+        n_rows = args.cpu_rows or max(threads * 128, 256)
+        cb = cpu_baseline(cfg, ks, args.seed, n_rows, wl, np)
+        out["cpu_baseline"] = {
+            "value": round(flops_dense_eq / cb["seconds_full_problem_extrapolated"] / 1e12, 6),
+            "unit": out["unit"], "cores": cb["threads"], "kind": "oracle",
+            "sample": f"{n_rows} evenly spaced query rows of head 0 through projection, scoring, selection, sparse "
+                      f"forward and backward ({cb['sample_s']:.1f} s measured), scaled by L/{n_rows} per head and by "
+                      f"{cfg.H} heads (extrapolated full problem: {cb['seconds_full_problem_extrapolated']:.0f} s)",
+            "parts_s": {k_: round(v, 3) for k_, v in cb["parts_s"].items()},
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

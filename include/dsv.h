@@ -112,12 +112,42 @@ DSV_API dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, cons
  *     Delta_i = dO_i . O_i;  p_ij = exp(s_ij - lse_i);  dS_ij = p_ij (dO_i . v_j - Delta_i);
  *     dQ_i = scale sum_j dS_ij k_j;
  *     dK_j = scale sum_{i: j in row i} dS_ij q_i;   dV_j = sum_{i: j in row i} p_ij dO_i.
- * Keys no query selected get zeros.  dQ, dK, dV are written in `dtype` (accumulated in fp32). */
+ * Keys no query selected get zeros.  dQ, dK, dV are written in `dtype` (accumulated in fp32).
+ * O is accepted for interface symmetry and not read: Delta is formed from the per-pair terms in
+ * fp32 rather than from the storage-rounded O.  The workspace holds Delta, the transposed index
+ * (as large as idx) and its column pointers. */
 DSV_API size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p);
 DSV_API dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *K, const void *V,
                                const int32_t *idx, const void *O, const float *lse, const void *dO,
                                void *dQ, void *dK, void *dV,
                                void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* ---- The three steps of the backward, callable one by one -------------------------------------
+ * dsv_sparse_attn_bwd runs exactly these, in this order, with delta / idx_t / col_ptr placed in
+ * its workspace.  They are exported so that a caller can keep the transposed index across
+ * calls that share idx, and so that each step can be timed on its own.
+ *
+ * dsv_sparse_attn_bwd_dq: query-major sweep.  Writes dQ [B, H, L, d] (`dtype`) and
+ *   delta [B, H, L] (float) = Delta_i = sum_j p_ij (dO_i . v_j), which equals dO_i . O_i.  No workspace.
+ *
+ * dsv_idx_transpose: for every (b, h) and key j, the list of queries i whose idx row holds j.
+ *   idx_t: int32, same ragged layout and size as idx (per head, the lists of key 0, 1, ... back to
+ *   back); col_ptr: int64 [B*H, L+1], list of key j of head bh = idx_t[off[bh] + col_ptr[bh][j] ..
+ *   off[bh] + col_ptr[bh][j+1]).  The order of the queries inside a list is unspecified.
+ *   Workspace: one int32 counter per (b, h, key).
+ *
+ * dsv_sparse_attn_bwd_dkdv: key-major sweep over idx_t.  Writes dK, dV [B, H, L, d] (`dtype`);
+ *   keys with an empty list get zeros.  No workspace. */
+DSV_API dsv_status dsv_sparse_attn_bwd_dq(const dsv_problem *p, const void *Q, const void *K, const void *V,
+                                          const int32_t *idx, const float *lse, const void *dO,
+                                          void *dQ, float *delta, void *hip_stream);
+DSV_API size_t dsv_idx_transpose_workspace(const dsv_problem *p);
+DSV_API dsv_status dsv_idx_transpose(const dsv_problem *p, const int32_t *idx, int32_t *idx_t, int64_t *col_ptr,
+                                     void *workspace, size_t ws_bytes, void *hip_stream);
+DSV_API dsv_status dsv_sparse_attn_bwd_dkdv(const dsv_problem *p, const void *Q, const void *K, const void *V,
+                                            const int32_t *idx_t, const int64_t *col_ptr, const float *lse,
+                                            const float *delta, const void *dO, void *dK, void *dV,
+                                            void *hip_stream);
 
 /* ---- Stage-1 internals exported for parity checks ---------------------------------------------
  * dsv_lowrank_project: only the projection step of stage 1 (Sec. "Low-Rank based Sparsity

@@ -204,25 +204,24 @@ static void row_p_and_ds(const float *q, const float *dOi, const double *Oi, dou
     }
 }
 
-/* Sparse attention backward for a whole head (selection held constant).
- * Q, K, V, dO [L, d]; idx [L, k]; O [L, d] and lse [L] are the oracle's own forward results
- * in double.  Outputs dQ, dK, dV [L, d]:
+/* Sparse attention backward (selection held constant) for nq query rows of one head: their dQ,
+ * and their contributions to dK and dV.  With nq = L and all rows given this is the whole head.
+ * Q, dO, O [nq, d], lse [nq], idx [nq, k] are the rows' data (O, lse: the oracle's own forward
+ * results in double); K, V [L, d].  Outputs: dQ [nq, d] (overwritten); dK, dV [L, d] are
+ * ACCUMULATED INTO (the caller zeroes them), so that keys no query selected stay exactly zero:
  *   dQ_i = scale * sum_j dS_ij k_j
  *   dK_j = scale * sum_{i : j in idx[i]} dS_ij q_i
  *   dV_j =         sum_{i : j in idx[i]} p_ij  dO_i
- * Keys no query selected receive exact zeros.  Serial over queries: the scatter into dK, dV is
- * written exactly as the sums above read. */
-void dsv_oracle_sparse_bwd(const float *Q, const float *K, const float *V, const int32_t *idx,
-                           const double *O, const double *lse, const float *dO,
-                           int64_t L, int d, int64_t k, double scale,
-                           double *dQ, double *dK, double *dV)
+ * Serial over queries: the scatter into dK, dV is written exactly as the sums above read. */
+void dsv_oracle_sparse_bwd_rows(const float *Q, const float *K, const float *V, const int32_t *idx,
+                                const double *O, const double *lse, const float *dO,
+                                int64_t nq, int d, int64_t k, double scale,
+                                double *dQ, double *dK, double *dV)
 {
     double *p = (double *)malloc((size_t)k * sizeof(double));
     double *dS = (double *)malloc((size_t)k * sizeof(double));
-    memset(dQ, 0, (size_t)L * d * sizeof(double));
-    memset(dK, 0, (size_t)L * d * sizeof(double));
-    memset(dV, 0, (size_t)L * d * sizeof(double));
-    for (int64_t i = 0; i < L; ++i) {
+    memset(dQ, 0, (size_t)nq * d * sizeof(double));
+    for (int64_t i = 0; i < nq; ++i) {
         const int32_t *row = idx + i * k;
         row_p_and_ds(Q + i * d, dO + i * d, O + i * d, lse[i], K, V, row, d, k, scale, p, dS);
         for (int64_t t = 0; t < k; ++t) {
@@ -236,6 +235,17 @@ void dsv_oracle_sparse_bwd(const float *Q, const float *K, const float *V, const
     }
     free(p);
     free(dS);
+}
+
+/* Whole head: Q, K, V, dO, O [L, d], idx [L, k], lse [L] -> dQ, dK, dV [L, d]. */
+void dsv_oracle_sparse_bwd(const float *Q, const float *K, const float *V, const int32_t *idx,
+                           const double *O, const double *lse, const float *dO,
+                           int64_t L, int d, int64_t k, double scale,
+                           double *dQ, double *dK, double *dV)
+{
+    memset(dK, 0, (size_t)L * d * sizeof(double));
+    memset(dV, 0, (size_t)L * d * sizeof(double));
+    dsv_oracle_sparse_bwd_rows(Q, K, V, idx, O, lse, dO, L, d, k, scale, dQ, dK, dV);
 }
 
 /* dQ for nq chosen query rows only (same formulas).  Q, dO, O [nq, d] and lse [nq] are the

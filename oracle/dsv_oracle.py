@@ -19,7 +19,7 @@ _LIB = os.path.join(_HERE, "libdsv_oracle.so")
 DTYPES = {"f32": 0, "bf16": 1}
 
 __all__ = ["build", "lib", "round_value", "project", "scores", "topk_from_scores", "lowrank_topk",
-           "sparse_fwd", "sparse_bwd", "sparse_bwd_dq_rows", "sparse_bwd_dkdv_key",
+           "sparse_fwd", "sparse_bwd", "sparse_bwd_rows", "sparse_bwd_dq_rows", "sparse_bwd_dkdv_key",
            "dense_fwd", "dense_bwd", "max_threads", "DTYPES"]
 
 
@@ -151,6 +151,20 @@ def sparse_bwd(Q, K, V, idx, dO, scale: float):
     dQ = np.empty((L, d)); dK = np.empty((L, d)); dV = np.empty((L, d))
     lib().dsv_oracle_sparse_bwd(_p(Q), _p(K), _p(V), _p(idx), _p(O), _p(lse), _p(dO), _i64(L), _int(d),
                                 _i64(k), _dbl(scale), _p(dQ), _p(dK), _p(dV))
+    return dQ, dK, dV
+
+
+def sparse_bwd_rows(Q_rows, K, V, idx_rows, dO_rows, scale: float):
+    """Backward of the given query rows: (dQ [nq, d], dK [L, d], dV [L, d]) where dK, dV hold only
+    these rows' contributions (all of a head's rows give the whole-head gradients)."""
+    Q_rows, K, V, dO_rows, idx_rows = _f32(Q_rows), _f32(K), _f32(V), _f32(dO_rows), _i32(idx_rows)
+    nq, d = Q_rows.shape
+    L = K.shape[0]
+    k = idx_rows.shape[1]
+    O, lse = sparse_fwd(Q_rows, K, V, idx_rows, scale)
+    dQ = np.empty((nq, d)); dK = np.zeros((L, d)); dV = np.zeros((L, d))
+    lib().dsv_oracle_sparse_bwd_rows(_p(Q_rows), _p(K), _p(V), _p(idx_rows), _p(O), _p(lse), _p(dO_rows),
+                                     _i64(nq), _int(d), _i64(k), _dbl(scale), _p(dQ), _p(dK), _p(dV))
     return dQ, dK, dV
 
 

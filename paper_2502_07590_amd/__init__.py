@@ -16,6 +16,10 @@ from .binding import (  # noqa: F401
     sparse_attn_fwd_workspace,
     sparse_attn_bwd,
     sparse_attn_bwd_workspace,
+    sparse_attn_bwd_dq,
+    idx_transpose,
+    idx_transpose_workspace,
+    sparse_attn_bwd_dkdv,
     lowrank_project,
     lowrank_scores_rows,
     EXPORTED_SYMBOLS,

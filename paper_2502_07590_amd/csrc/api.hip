@@ -66,7 +66,7 @@ Stage1Workspace stage1_layout(const dsv_problem &p)
 }
 
 struct BwdLayout {
-    size_t delta, cnt, cnt_bytes, col, idxT, total;
+    size_t delta, cnt, cnt_bytes256, col, idxT, total;
 };
 
 BwdLayout bwd_layout(const dsv_problem &p)
@@ -78,7 +78,7 @@ BwdLayout bwd_layout(const dsv_problem &p)
     BwdLayout w;
     size_t o = 0;
     w.delta = o; o = align_up(o + tok * 4, 256);
-    w.cnt = o; w.cnt_bytes = align_up(tok * 4, 16); o = align_up(o + w.cnt_bytes, 256);
+    w.cnt = o; w.cnt_bytes256 = align_up(tok * 4, 256); o += w.cnt_bytes256;
     w.col = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
     w.idxT = o; o = align_up(o + nnz * 4, 256);
     w.total = o;
@@ -176,29 +176,78 @@ size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p)
     return bwd_layout(*p).total;
 }
 
+dsv_status dsv_sparse_attn_bwd_dq(const dsv_problem *p, const void *Q, const void *K, const void *V,
+                                  const int32_t *idx, const float *lse, const void *dO, void *dQ, float *delta,
+                                  void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if (!Q || !K || !V || !idx || !lse || !dO || !dQ || !delta) return DSV_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(lse) || !aligned16(dO) ||
+        !aligned16(dQ) || !aligned16(delta))
+        return DSV_EINVAL;
+    const std::vector<HeadTable> tabs = make_tables(*p);
+    return launch_bwd_dq(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, lse, dO, dQ, delta,
+                         static_cast<hipStream_t>(hip_stream));
+}
+
+size_t dsv_idx_transpose_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, false) != DSV_OK) return 0;
+    return align_up((size_t)p->B * p->H * p->L * 4, 256);
+}
+
+dsv_status dsv_idx_transpose(const dsv_problem *p, const int32_t *idx, int32_t *idx_t, int64_t *col_ptr,
+                             void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if (!idx || !idx_t || !col_ptr) return DSV_EINVAL;
+    if (!aligned16(idx) || !aligned16(idx_t) || !aligned16(col_ptr)) return DSV_EINVAL;
+    const size_t need = dsv_idx_transpose_workspace(p);
+    st = check_workspace(workspace, ws_bytes, need);
+    if (st != DSV_OK) return st;
+    const std::vector<HeadTable> tabs = make_tables(*p);
+    return launch_idx_transpose(*p, tabs.data(), (int)tabs.size(), idx, idx_t, col_ptr,
+                                static_cast<int32_t *>(workspace), align_up((size_t)p->B * p->H * p->L * 4, 16),
+                                static_cast<hipStream_t>(hip_stream));
+}
+
+dsv_status dsv_sparse_attn_bwd_dkdv(const dsv_problem *p, const void *Q, const void *K, const void *V,
+                                    const int32_t *idx_t, const int64_t *col_ptr, const float *lse, const float *delta,
+                                    const void *dO, void *dK, void *dV, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if (!Q || !K || !V || !idx_t || !col_ptr || !lse || !delta || !dO || !dK || !dV) return DSV_EINVAL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx_t) || !aligned16(col_ptr) ||
+        !aligned16(lse) || !aligned16(delta) || !aligned16(dO) || !aligned16(dK) || !aligned16(dV))
+        return DSV_EINVAL;
+    const std::vector<HeadTable> tabs = make_tables(*p);
+    return launch_bwd_dkdv(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx_t, col_ptr, lse, delta, dO, dK, dV,
+                           static_cast<hipStream_t>(hip_stream));
+}
+
 dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *K, const void *V, const int32_t *idx,
                                const void *O, const float *lse, const void *dO, void *dQ, void *dK, void *dV,
                                void *workspace, size_t ws_bytes, void *hip_stream)
 {
     dsv_status st = check_problem(p, false);
     if (st != DSV_OK) return st;
-    if (!Q || !K || !V || !idx || !O || !lse || !dO || !dQ || !dK || !dV) return DSV_EINVAL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(O) || !aligned16(lse) ||
-        !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
-        return DSV_EINVAL;
+    if (!O || !dQ || !dK || !dV) return DSV_EINVAL;
+    if (!aligned16(O)) return DSV_EINVAL;
     const BwdLayout w = bwd_layout(*p);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
     char *ws = static_cast<char *>(workspace);
-    BwdWorkspace b;
-    b.delta = reinterpret_cast<float *>(ws + w.delta);
-    b.cnt = reinterpret_cast<int32_t *>(ws + w.cnt);
-    b.cnt_bytes = w.cnt_bytes;
-    b.col = reinterpret_cast<int64_t *>(ws + w.col);
-    b.idxT = reinterpret_cast<int32_t *>(ws + w.idxT);
-    const std::vector<HeadTable> tabs = make_tables(*p);
-    return launch_sparse_bwd(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, lse, dO, dQ, dK, dV, b,
-                             static_cast<hipStream_t>(hip_stream));
+    float *delta = reinterpret_cast<float *>(ws + w.delta);
+    int64_t *col = reinterpret_cast<int64_t *>(ws + w.col);
+    int32_t *idx_t = reinterpret_cast<int32_t *>(ws + w.idxT);
+    st = dsv_sparse_attn_bwd_dq(p, Q, K, V, idx, lse, dO, dQ, delta, hip_stream);
+    if (st != DSV_OK) return st;
+    st = dsv_idx_transpose(p, idx, idx_t, col, ws + w.cnt, w.cnt_bytes256, hip_stream);
+    if (st != DSV_OK) return st;
+    return dsv_sparse_attn_bwd_dkdv(p, Q, K, V, idx_t, col, lse, delta, dO, dK, dV, hip_stream);
 }
 
 dsv_status dsv_lowrank_project(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,

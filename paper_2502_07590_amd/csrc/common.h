@@ -167,16 +167,14 @@ dsv_status launch_select(const dsv_problem &p, const HeadTable *tabs, int n_tabs
                          uint32_t *prefix, int32_t *krem, int32_t *idx, hipStream_t st);
 dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                              const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st);
-// Device scratch of the backward (carved from the caller's workspace by api.hip).
-struct BwdWorkspace {
-    float *delta;      // [B*H, L]    Delta_i of every query row
-    int32_t *cnt;      // [B*H, L]    per-key counters, then fill cursors
-    size_t cnt_bytes;  //             size of cnt rounded up to 16 bytes
-    int64_t *col;      // [B*H, L+1]  start of every key's list inside its head's block of idxT
-    int32_t *idxT;     // same ragged layout as idx: per head, the key-major lists back to back
-};
-dsv_status launch_sparse_bwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
-                             const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ, void *dK,
-                             void *dV, const BwdWorkspace &w, hipStream_t st);
+dsv_status launch_bwd_dq(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                         const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ, float *delta,
+                         hipStream_t st);
+dsv_status launch_bwd_dkdv(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                           const void *V, const int32_t *idxT, const int64_t *col, const float *lse, const float *delta,
+                           const void *dO, void *dK, void *dV, hipStream_t st);
+// cnt: [B*H, L] int32 scratch (cnt_bytes = its size rounded up to 16); col: [B*H, L+1] int64.
+dsv_status launch_idx_transpose(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
+                                int32_t *idxT, int64_t *col, int32_t *cnt, size_t cnt_bytes, hipStream_t st);
 
 }  // namespace dsv

@@ -355,51 +355,80 @@ dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_
 }
 
 template <typename T, int D>
-static dsv_status bwd_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
-                        const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ, void *dK,
-                        void *dV, const BwdWorkspace &w, hipStream_t st)
+static dsv_status bwd_dq_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                           const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ,
+                           float *delta, hipStream_t st)
 {
-    const int nbh = p.B * p.H;
-    const int64_t ncnt4 = (int64_t)(w.cnt_bytes / 16);
-    const int zero_blocks = (int)std::min<int64_t>((ncnt4 + 255) / 256, 4096);
-    hipLaunchKernelGGL(fill_zero_i32_kernel, dim3(zero_blocks), dim3(256), 0, st, (int4 *)w.cnt, ncnt4);
-    DSV_LAUNCH_CHECK();
-    const int row_blocks = std::min(p.L, 8192);
     for (int t = 0; t < n_tabs; ++t) {
         dim3 qgrid((p.L + 15) / 16, tabs[t].n);
         hipLaunchKernelGGL((sparse_bwd_dq_kernel<T, D>), qgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
-                           (const T *)V, idx, lse, (const T *)dO, (T *)dQ, w.delta, p.L, p.scale, tabs[t]);
-        hipLaunchKernelGGL(tindex_count_kernel, dim3(row_blocks, tabs[t].n), dim3(256), 0, st, idx, p.L, tabs[t], w.cnt);
-        DSV_LAUNCH_CHECK();
-    }
-    hipLaunchKernelGGL(tindex_scan_kernel, dim3(nbh), dim3(1024), 0, st, w.cnt, w.col, p.L);
-    DSV_LAUNCH_CHECK();
-    for (int t = 0; t < n_tabs; ++t) {
-        hipLaunchKernelGGL(tindex_fill_kernel, dim3(row_blocks, tabs[t].n), dim3(256), 0, st, idx, p.L, tabs[t], w.cnt,
-                           w.col, w.idxT);
-        dim3 kgrid((p.L + 15) / 16, tabs[t].n);
-        hipLaunchKernelGGL((sparse_bwd_dkdv_kernel<T, D>), kgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
-                           (const T *)V, w.idxT, w.col, lse, w.delta, (const T *)dO, (T *)dK, (T *)dV, p.L, p.scale,
-                           tabs[t]);
+                           (const T *)V, idx, lse, (const T *)dO, (T *)dQ, delta, p.L, p.scale, tabs[t]);
         DSV_LAUNCH_CHECK();
     }
     return DSV_OK;
 }
 
-dsv_status launch_sparse_bwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
-                             const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ, void *dK,
-                             void *dV, const BwdWorkspace &w, hipStream_t st)
+template <typename T, int D>
+static dsv_status bwd_dkdv_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                             const void *V, const int32_t *idxT, const int64_t *col, const float *lse,
+                             const float *delta, const void *dO, void *dK, void *dV, hipStream_t st)
 {
-#define DSV_CASE(TT, DD) return bwd_t<TT, DD>(p, tabs, n_tabs, Q, K, V, idx, lse, dO, dQ, dK, dV, w, st)
-    if (p.dtype == DSV_BF16) {
-        if (p.d == 64) DSV_CASE(bf16_t, 64);
-        if (p.d == 128) DSV_CASE(bf16_t, 128);
-    } else if (p.dtype == DSV_F32) {
-        if (p.d == 64) DSV_CASE(float, 64);
-        if (p.d == 128) DSV_CASE(float, 128);
+    for (int t = 0; t < n_tabs; ++t) {
+        dim3 kgrid((p.L + 15) / 16, tabs[t].n);
+        hipLaunchKernelGGL((sparse_bwd_dkdv_kernel<T, D>), kgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
+                           (const T *)V, idxT, col, lse, delta, (const T *)dO, (T *)dK, (T *)dV, p.L, p.scale, tabs[t]);
+        DSV_LAUNCH_CHECK();
     }
-#undef DSV_CASE
-    return DSV_EUNSUPPORTED;
+    return DSV_OK;
+}
+
+#define DSV_DISPATCH_TD(FN, ...)                                        \
+    do {                                                                \
+        if (p.dtype == DSV_BF16) {                                      \
+            if (p.d == 64) return FN<bf16_t, 64>(__VA_ARGS__);          \
+            if (p.d == 128) return FN<bf16_t, 128>(__VA_ARGS__);        \
+        } else if (p.dtype == DSV_F32) {                                \
+            if (p.d == 64) return FN<float, 64>(__VA_ARGS__);           \
+            if (p.d == 128) return FN<float, 128>(__VA_ARGS__);         \
+        }                                                               \
+        return DSV_EUNSUPPORTED;                                        \
+    } while (0)
+
+dsv_status launch_bwd_dq(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                         const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ, float *delta,
+                         hipStream_t st)
+{
+    DSV_DISPATCH_TD(bwd_dq_t, p, tabs, n_tabs, Q, K, V, idx, lse, dO, dQ, delta, st);
+}
+
+dsv_status launch_bwd_dkdv(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                           const void *V, const int32_t *idxT, const int64_t *col, const float *lse, const float *delta,
+                           const void *dO, void *dK, void *dV, hipStream_t st)
+{
+    DSV_DISPATCH_TD(bwd_dkdv_t, p, tabs, n_tabs, Q, K, V, idxT, col, lse, delta, dO, dK, dV, st);
+}
+
+dsv_status launch_idx_transpose(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
+                                int32_t *idxT, int64_t *col, int32_t *cnt, size_t cnt_bytes, hipStream_t st)
+{
+    const int nbh = p.B * p.H;
+    const int64_t ncnt4 = (int64_t)(cnt_bytes / 16);
+    const int zero_blocks = (int)std::min<int64_t>((ncnt4 + 255) / 256, 4096);
+    hipLaunchKernelGGL(fill_zero_i32_kernel, dim3(zero_blocks), dim3(256), 0, st, (int4 *)cnt, ncnt4);
+    DSV_LAUNCH_CHECK();
+    const int row_blocks = std::min(p.L, 8192);
+    for (int t = 0; t < n_tabs; ++t) {
+        hipLaunchKernelGGL(tindex_count_kernel, dim3(row_blocks, tabs[t].n), dim3(256), 0, st, idx, p.L, tabs[t], cnt);
+        DSV_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(tindex_scan_kernel, dim3(nbh), dim3(1024), 0, st, cnt, col, p.L);
+    DSV_LAUNCH_CHECK();
+    for (int t = 0; t < n_tabs; ++t) {
+        hipLaunchKernelGGL(tindex_fill_kernel, dim3(row_blocks, tabs[t].n), dim3(256), 0, st, idx, p.L, tabs[t], cnt, col,
+                           idxT);
+        DSV_LAUNCH_CHECK();
+    }
+    return DSV_OK;
 }
 
 }  // namespace dsv

@@ -188,6 +188,12 @@ def test_row_and_key_sampled_backward_agree_with_the_whole_head():
     dQ, dK, dV = oracle.sparse_bwd(Q, K, V, idx, dO, 0.2)
     rows = np.array([0, 41, 79])
     assert np.allclose(oracle.sparse_bwd_dq_rows(Q[rows], K, V, idx[rows], dO[rows], 0.2), dQ[rows], rtol=0, atol=1e-14)
+    # two halves of the rows: their dK / dV contributions add up to the whole head's
+    a, b = np.arange(0, 37), np.arange(37, L)
+    dQa, dKa, dVa = oracle.sparse_bwd_rows(Q[a], K, V, idx[a], dO[a], 0.2)
+    dQb, dKb, dVb = oracle.sparse_bwd_rows(Q[b], K, V, idx[b], dO[b], 0.2)
+    assert np.allclose(np.concatenate([dQa, dQb]), dQ, rtol=0, atol=1e-14)
+    assert np.allclose(dKa + dKb, dK, rtol=0, atol=1e-13) and np.allclose(dVa + dVb, dV, rtol=0, atol=1e-13)
     for j in (0, 7, 79):
         sel = np.nonzero((idx == j).any(axis=1))[0]
         dKj, dVj = oracle.sparse_bwd_dkdv_key(j, Q[sel], dO[sel], idx[sel], K, V, 0.2)
