@@ -2,10 +2,11 @@
 """Benchmark of the DSV sparse-attention hot path on one MI355X.
 
 One step = one pass of the whole path over one synthetic batch that is already resident in HBM:
-    stage 1  dsv_lowrank_topk          (project, threshold search, emit idx)
+    stage 1  dsv_lowrank_topk_t        (project, threshold search, emit idx and its transpose)
     stage 2  dsv_sparse_attn_fwd
-             dsv_sparse_attn_bwd_dq, dsv_idx_transpose, dsv_sparse_attn_bwd_dkdv
-             (the three steps dsv_sparse_attn_bwd runs, called one by one so that each can be timed)
+             dsv_sparse_attn_bwd_dq, dsv_sparse_attn_bwd_dkdv
+             (the steps dsv_sparse_attn_bwd runs, called one by one so that each can be timed; the
+             transposed index comes from stage 1 instead of dsv_idx_transpose)
 Workload: the L = 128k configuration of the benchmark list (6 heads = one GPU's head-parallel share
 of 24, d = 128, r = 16, k = 8192 per query, bf16).  Prints ONE JSON line.
 
@@ -122,17 +123,15 @@ def main():
     O = torch.empty_like(g["Q"]); dQ = torch.empty_like(g["Q"]); dK = torch.empty_like(g["Q"]); dV = torch.empty_like(g["Q"])
     lse = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
     delta = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
-    ws1 = torch.empty(dsv.lowrank_topk_workspace(p), dtype=torch.uint8, device=dev)
-    wst = torch.empty(dsv.idx_transpose_workspace(p), dtype=torch.uint8, device=dev)
+    ws1 = torch.empty(dsv.lowrank_topk_t_workspace(p), dtype=torch.uint8, device=dev)
 
-    names = ("lowrank_topk", "sparse_attn_fwd", "sparse_attn_bwd_dq", "idx_transpose", "sparse_attn_bwd_dkdv")
+    names = ("lowrank_topk_t", "sparse_attn_fwd", "sparse_attn_bwd_dq", "sparse_attn_bwd_dkdv")
 
     def step(events=None):
         calls = (
-            lambda: dsv.lowrank_topk(p, g["Q"], g["K"], Wq, Wk, idx=idx, workspace=ws1),
+            lambda: dsv.lowrank_topk_t(p, g["Q"], g["K"], Wq, Wk, idx=idx, idx_t=idx_t, col_ptr=col_ptr, workspace=ws1),
             lambda: dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx, O=O, lse=lse),
             lambda: dsv.sparse_attn_bwd_dq(p, g["Q"], g["K"], g["V"], idx, lse, g["dO"], dQ=dQ, delta=delta),
-            lambda: dsv.idx_transpose(p, idx, idx_t=idx_t, col_ptr=col_ptr, workspace=wst),
             lambda: dsv.sparse_attn_bwd_dkdv(p, g["Q"], g["K"], g["V"], idx_t, col_ptr, lse, delta, g["dO"], dK=dK, dV=dV),
         )
         if events is None:

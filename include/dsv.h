@@ -93,6 +93,16 @@ DSV_API dsv_status dsv_lowrank_topk(const dsv_problem *p, const void *Q, const v
                             const void *Wq, const void *Wk, int32_t *idx,
                             void *workspace, size_t ws_bytes, void *hip_stream);
 
+/* Same selection, and in addition its transpose: idx_t / col_ptr in the layout dsv_idx_transpose
+ * documents below, with every key's query list in ASCENDING query order.  The key-major lists are
+ * emitted by re-evaluating the selection predicate key tile by key tile (two more sweeps over the
+ * scores), which is much cheaper than sorting the emitted pairs by key, and is what lets the
+ * backward's dkdv step run without building the lists itself. */
+DSV_API size_t dsv_lowrank_topk_t_workspace(const dsv_problem *p);
+DSV_API dsv_status dsv_lowrank_topk_t(const dsv_problem *p, const void *Q, const void *K,
+                                      const void *Wq, const void *Wk, int32_t *idx, int32_t *idx_t,
+                                      int64_t *col_ptr, void *workspace, size_t ws_bytes, void *hip_stream);
+
 /* ---- Stage 2 forward: attention over the selected KV only -----------------------------------
  * Sec. "Sparse Attention with Query Grouping" (per-query form, no grouping) with the softmax
  * attention of Sec. "Various Self-Attention Paradigms":

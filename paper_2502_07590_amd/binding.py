@@ -19,7 +19,7 @@ _DTYPE_NAME = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 EXPORTED_SYMBOLS = (
     "dsv_version", "dsv_status_string", "dsv_idx_offsets",
-    "dsv_lowrank_topk_workspace", "dsv_lowrank_topk",
+    "dsv_lowrank_topk_workspace", "dsv_lowrank_topk", "dsv_lowrank_topk_t_workspace", "dsv_lowrank_topk_t",
     "dsv_sparse_attn_fwd_workspace", "dsv_sparse_attn_fwd",
     "dsv_sparse_attn_bwd_workspace", "dsv_sparse_attn_bwd",
     "dsv_sparse_attn_bwd_dq", "dsv_idx_transpose_workspace", "dsv_idx_transpose", "dsv_sparse_attn_bwd_dkdv",
@@ -61,11 +61,13 @@ def load_library():
     lib.dsv_idx_offsets.restype = ctypes.c_int
     lib.dsv_idx_offsets.argtypes = [P, ctypes.POINTER(ctypes.c_int64)]
     for name in ("dsv_lowrank_topk_workspace", "dsv_sparse_attn_fwd_workspace", "dsv_sparse_attn_bwd_workspace",
-                 "dsv_idx_transpose_workspace"):
+                 "dsv_idx_transpose_workspace", "dsv_lowrank_topk_t_workspace"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [P]
     lib.dsv_lowrank_topk.restype = ctypes.c_int
     lib.dsv_lowrank_topk.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dsv_lowrank_topk_t.restype = ctypes.c_int
+    lib.dsv_lowrank_topk_t.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_fwd.restype = ctypes.c_int
     lib.dsv_sparse_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_bwd.restype = ctypes.c_int
@@ -167,6 +169,22 @@ def lowrank_topk(p: Problem, Q, K, Wq, Wk, idx=None, workspace=None, stream=None
     _check(lib.dsv_lowrank_topk(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(idx), _ptr(ws), nbytes,
                                 _stream(stream)), "dsv_lowrank_topk")
     return idx
+
+
+def lowrank_topk_t_workspace(p: Problem) -> int:
+    return int(load_library().dsv_lowrank_topk_t_workspace(p.c))
+
+
+def lowrank_topk_t(p: Problem, Q, K, Wq, Wk, idx=None, idx_t=None, col_ptr=None, workspace=None, stream=None):
+    """Stage 1 plus the transposed index: (idx, idx_t, col_ptr)."""
+    lib = load_library()
+    idx = torch.empty(p.nnz, dtype=torch.int32, device=Q.device) if idx is None else idx
+    idx_t = torch.empty(p.nnz, dtype=torch.int32, device=Q.device) if idx_t is None else idx_t
+    col_ptr = torch.empty((p.B * p.H, p.L + 1), dtype=torch.int64, device=Q.device) if col_ptr is None else col_ptr
+    ws, nbytes = _workspace(lowrank_topk_t_workspace(p), Q.device, workspace)
+    _check(lib.dsv_lowrank_topk_t(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(idx), _ptr(idx_t), _ptr(col_ptr),
+                                  _ptr(ws), nbytes, _stream(stream)), "dsv_lowrank_topk_t")
+    return idx, idx_t, col_ptr
 
 
 def sparse_attn_fwd(p: Problem, Q, K, V, idx, O=None, lse=None, workspace=None, stream=None):

@@ -49,10 +49,11 @@ std::vector<HeadTable> make_tables(const dsv_problem &p)
 }
 
 struct Stage1Workspace {
-    size_t qlr, klr, prefix, krem, total;
+    size_t qlr, klr, prefix, krem, jcut, cnt, total;
 };
 
-Stage1Workspace stage1_layout(const dsv_problem &p)
+// transposed: also room for jcut and the per-key list lengths of the key-major emission
+Stage1Workspace stage1_layout(const dsv_problem &p, bool transposed)
 {
     const size_t tok = (size_t)p.B * p.H * p.L;
     Stage1Workspace w;
@@ -61,6 +62,8 @@ Stage1Workspace stage1_layout(const dsv_problem &p)
     w.klr = o; o = align_up(o + tok * p.r * esize(p.dtype), 256);
     w.prefix = o; o = align_up(o + tok * 4, 256);
     w.krem = o; o = align_up(o + tok * 4, 256);
+    w.jcut = o; if (transposed) o = align_up(o + tok * 4, 256);
+    w.cnt = o; if (transposed) o = align_up(o + tok * 4, 256);
     w.total = o;
     return w;
 }
@@ -123,30 +126,57 @@ dsv_status dsv_idx_offsets(const dsv_problem *p, int64_t *off)
     return DSV_OK;
 }
 
-size_t dsv_lowrank_topk_workspace(const dsv_problem *p)
-{
-    if (check_problem(p, true) != DSV_OK) return 0;
-    return stage1_layout(*p).total;
-}
-
-dsv_status dsv_lowrank_topk(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,
-                            int32_t *idx, void *workspace, size_t ws_bytes, void *hip_stream)
+static dsv_status lowrank_topk_impl(const dsv_problem *p, const void *Q, const void *K, const void *Wq,
+                                    const void *Wk, int32_t *idx, int32_t *idx_t, int64_t *col_ptr, bool transposed,
+                                    void *workspace, size_t ws_bytes, void *hip_stream)
 {
     dsv_status st = check_problem(p, true);
     if (st != DSV_OK) return st;
     if (!Q || !K || !Wq || !Wk || !idx) return DSV_EINVAL;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(Wq) || !aligned16(Wk) || !aligned16(idx)) return DSV_EINVAL;
-    const Stage1Workspace w = stage1_layout(*p);
+    if (transposed && (!idx_t || !col_ptr || !aligned16(idx_t) || !aligned16(col_ptr))) return DSV_EINVAL;
+    const Stage1Workspace w = stage1_layout(*p, transposed);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
     char *ws = static_cast<char *>(workspace);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     st = launch_project(*p, Q, K, Wq, Wk, ws + w.qlr, ws + w.klr, stream);
     if (st != DSV_OK) return st;
+    SelectBuffers b;
+    b.prefix = reinterpret_cast<uint32_t *>(ws + w.prefix);
+    b.krem = reinterpret_cast<int32_t *>(ws + w.krem);
+    b.idx = idx;
+    b.jcut = transposed ? reinterpret_cast<int32_t *>(ws + w.jcut) : nullptr;
+    b.cnt = transposed ? reinterpret_cast<int32_t *>(ws + w.cnt) : nullptr;
+    b.col = transposed ? col_ptr : nullptr;
+    b.idx_t = transposed ? idx_t : nullptr;
     const std::vector<HeadTable> tabs = make_tables(*p);
-    return launch_select(*p, tabs.data(), (int)tabs.size(), ws + w.qlr, ws + w.klr,
-                         reinterpret_cast<uint32_t *>(ws + w.prefix), reinterpret_cast<int32_t *>(ws + w.krem), idx,
-                         stream);
+    return launch_select(*p, tabs.data(), (int)tabs.size(), ws + w.qlr, ws + w.klr, b, stream);
+}
+
+size_t dsv_lowrank_topk_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, true) != DSV_OK) return 0;
+    return stage1_layout(*p, false).total;
+}
+
+dsv_status dsv_lowrank_topk(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,
+                            int32_t *idx, void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    return lowrank_topk_impl(p, Q, K, Wq, Wk, idx, nullptr, nullptr, false, workspace, ws_bytes, hip_stream);
+}
+
+size_t dsv_lowrank_topk_t_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, true) != DSV_OK) return 0;
+    return stage1_layout(*p, true).total;
+}
+
+dsv_status dsv_lowrank_topk_t(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,
+                              int32_t *idx, int32_t *idx_t, int64_t *col_ptr, void *workspace, size_t ws_bytes,
+                              void *hip_stream)
+{
+    return lowrank_topk_impl(p, Q, K, Wq, Wk, idx, idx_t, col_ptr, true, workspace, ws_bytes, hip_stream);
 }
 
 size_t dsv_sparse_attn_fwd_workspace(const dsv_problem *p)

@@ -163,8 +163,19 @@ dsv_status launch_project(const dsv_problem &p, const void *Q, const void *K, co
                           void *Qlr, void *Klr, hipStream_t st);
 dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void *Klr, int bh,
                               const int32_t *rows, int n_rows, float *scores, hipStream_t st);
+// Device buffers of the selection.  idx_t == nullptr skips the key-major emission (then jcut, cnt,
+// col may be null as well).
+struct SelectBuffers {
+    uint32_t *prefix;  // [B*H, L]   order-preserving key of each query's threshold score
+    int32_t *krem;     // [B*H, L]   number of keys equal to the threshold that belong to the top-k
+    int32_t *idx;      // out: ragged query-major index
+    int32_t *jcut;     // [B*H, L]   index of the last tie taken
+    int32_t *cnt;      // [B*H, L]   list length of every key
+    int64_t *col;      // out: [B*H, L+1]
+    int32_t *idx_t;    // out: ragged key-major index
+};
 dsv_status launch_select(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
-                         uint32_t *prefix, int32_t *krem, int32_t *idx, hipStream_t st);
+                         const SelectBuffers &b, hipStream_t st);
 dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                              const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st);
 dsv_status launch_bwd_dq(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,

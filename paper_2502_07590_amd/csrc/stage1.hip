@@ -191,11 +191,15 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
 // selected when its score is above the query's threshold, or equal to it while fewer than k_rem
 // equal keys have been taken (lowest index first).  Lanes l and l+32 (same query) merge their 16
 // predicate bits into one 32-bit mask in key order; each lane then writes its own selected keys at
-// cursor + rank, so every row comes out in ascending key index.
+// cursor + rank, so every row comes out in ascending key index.  jcut[query] receives the index of
+// the last tie taken (the k-th key itself is one, so there always is one), so that
+//   selected(i, j)  <=>  s_ij > tau_i  or  (s_ij == tau_i and j <= jcut_i)
+// is a pure function of the pair, which the key-major emission below re-evaluates.
 template <typename T, int R>
 __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
                                                   HeadTable tab, const uint32_t *__restrict__ prefix,
-                                                  const int32_t *__restrict__ krem, int32_t *__restrict__ idx)
+                                                  const int32_t *__restrict__ krem, int32_t *__restrict__ idx,
+                                                  int32_t *__restrict__ jcut)
 {
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
 
     const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
     const uint32_t mine_pos = 0x0F0F0F0Fu << (4 * half);
-    int cursor = 0, ties_taken = 0;
+    int cursor = 0, ties_taken = 0, last_tie = -1;
     const int ntiles = (L + 31) >> 5;
     for (int tile = 0; tile < ntiles; ++tile) {
         const int j0 = tile * 32;
@@ -236,6 +240,7 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
             const int room = ties_wanted - ties_taken;
             while (__popc(meq) > room) meq &= ~(0x80000000u >> __clz(meq));  // drop the highest index
             ties_taken += __popc(meq);
+            if (meq) last_tie = j0 + 31 - __clz(meq);
         }
         const uint32_t sel = mgt | meq;
         uint32_t mine = sel & mine_pos;
@@ -247,6 +252,99 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
         }
         cursor += __popc(sel);
     }
+    if (jcut && live && half == 0) jcut[(int64_t)bh * L + qi] = last_tie;
+}
+
+// ------------------------------------------------------------------------------------ key-major emit
+// The transposed index: for every key j, the ascending list of queries that selected it.  One wave
+// owns 32 keys of one head and walks the QUERY tiles in ascending order, recomputing each 32x32
+// tile with the same operand roles as every other pass (identical score bits) and re-evaluating
+// selected(i, j) from tau_i and jcut_i.  For accumulator v the wave-wide ballot is, in its low half,
+// the query mask of key tile_pos(v) and, in its high half, that of key tile_pos(v)+4.
+//   WRITE = false: count list lengths  -> cnt[bh, j]
+//   WRITE = true : lists start at col[bh, j] (exclusive scan of the counts); lanes with a set bit
+//                  write their query index at position + rank.
+template <typename T, int R, bool WRITE>
+__global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
+                                                    HeadTable tab, const uint32_t *__restrict__ prefix,
+                                                    const int32_t *__restrict__ jcut, int32_t *__restrict__ cnt,
+                                                    const int64_t *__restrict__ col, int32_t *__restrict__ idxT)
+{
+    const int slot = blockIdx.y;
+    const int bh = tab.bh[slot];
+    const int j0 = blockIdx.x * 32;
+    const T *Qb = Qlr + (int64_t)bh * L * R;
+    const T *Kb = Klr + (int64_t)bh * L * R;
+    const uint32_t *pre_b = prefix + (int64_t)bh * L;
+    const int32_t *jcut_b = jcut + (int64_t)bh * L;
+    const int lane = threadIdx.x;
+    const int n = lane & 31, half = lane >> 5;
+    const uint32_t below = (1u << n) - 1u;  // lanes of my half with a lower query index
+
+    const Frag<T, R> kf = load_frag<T, R>(Kb, j0, L, lane);
+    int32_t *out = WRITE ? idxT + tab.off[slot] : nullptr;
+    int64_t pos[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int j = j0 + tile_pos(v) + 4 * half;
+        pos[v] = (WRITE && j < L) ? col[(int64_t)bh * (L + 1) + j] : 0;
+    }
+    const int ntiles = (L + 31) >> 5;
+    for (int qt = 0; qt < ntiles; ++qt) {
+        const int q0 = qt * 32;
+        const bool live = q0 + n < L;
+        const int qi = min(q0 + n, L - 1);
+        const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
+        const float tau = key_score(pre_b[qi]);
+        const int jc = jcut_b[qi];
+        const floatx16_t acc = score_tile<T, R>(kf, qf);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int j = j0 + tile_pos(v) + 4 * half;
+            const bool pred = live && j < L && (acc[v] > tau || (acc[v] == tau && j <= jc));
+            const uint64_t m = __ballot(pred);
+            const uint32_t mh = half ? (uint32_t)(m >> 32) : (uint32_t)m;
+            if (WRITE) {
+                if (pred) out[pos[v] + __popc(mh & below)] = q0 + n;
+            }
+            pos[v] += __popc(mh);
+        }
+    }
+    if (!WRITE && n == 0) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int j = j0 + tile_pos(v) + 4 * half;
+            if (j < L) cnt[(int64_t)bh * L + j] = (int32_t)pos[v];
+        }
+    }
+}
+
+// One block per (b, h): exclusive scan of cnt [L] into col [L+1] (int64).
+__global__ __launch_bounds__(1024) void list_scan_kernel(const int32_t *__restrict__ cnt, int64_t *__restrict__ col,
+                                                         int L)
+{
+    __shared__ int64_t part[1024];
+    const int bh = blockIdx.x;
+    const int32_t *c = cnt + (int64_t)bh * L;
+    int64_t *o = col + (int64_t)bh * (L + 1);
+    const int per = (L + 1023) / 1024;
+    const int lo = min((int)threadIdx.x * per, L), hi = min(lo + per, L);
+    int64_t sum = 0;
+    for (int j = lo; j < hi; ++j) sum += c[j];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int step = 1; step < 1024; step <<= 1) {
+        const int64_t add = threadIdx.x >= (unsigned)step ? part[threadIdx.x - step] : 0;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    int64_t run = part[threadIdx.x] - sum;
+    for (int j = lo; j < hi; ++j) {
+        o[j] = run;
+        run += c[j];
+    }
+    if (threadIdx.x == 1023) o[L] = part[1023];
 }
 
 // ------------------------------------------------------------------------------------ debug scores
@@ -342,27 +440,43 @@ dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void 
 
 template <typename T, int R>
 static dsv_status select_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
-                           uint32_t *prefix, int32_t *krem, int32_t *idx, hipStream_t st)
+                           const SelectBuffers &b, hipStream_t st)
 {
     const T *Ql = (const T *)Qlr;
     const T *Kl = (const T *)Klr;
     const int qtiles = (p.L + 31) / 32;
     for (int t = 0; t < n_tabs; ++t) {
         dim3 grid(qtiles, tabs[t].n);
-        hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], prefix, krem);
-        hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], prefix, krem);
-        hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], prefix, krem);
-        hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], prefix, krem);
-        hipLaunchKernelGGL((emit_kernel<T, R>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], prefix, krem, idx);
+        hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+        hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+        hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+        hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+        hipLaunchKernelGGL((emit_kernel<T, R>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem, b.idx,
+                           b.jcut);
         DSV_LAUNCH_CHECK();
+        if (b.idx_t) {
+            hipLaunchKernelGGL((emit_t_kernel<T, R, false>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], b.prefix,
+                               b.jcut, b.cnt, (const int64_t *)nullptr, (int32_t *)nullptr);
+            DSV_LAUNCH_CHECK();
+        }
+    }
+    if (b.idx_t) {
+        hipLaunchKernelGGL(list_scan_kernel, dim3(p.B * p.H), dim3(1024), 0, st, b.cnt, b.col, p.L);
+        DSV_LAUNCH_CHECK();
+        for (int t = 0; t < n_tabs; ++t) {
+            dim3 grid(qtiles, tabs[t].n);
+            hipLaunchKernelGGL((emit_t_kernel<T, R, true>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], b.prefix,
+                               b.jcut, (int32_t *)nullptr, b.col, b.idx_t);
+            DSV_LAUNCH_CHECK();
+        }
     }
     return DSV_OK;
 }
 
 dsv_status launch_select(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
-                         uint32_t *prefix, int32_t *krem, int32_t *idx, hipStream_t st)
+                         const SelectBuffers &b, hipStream_t st)
 {
-#define DSV_CASE(TT, RR) return select_t<TT, RR>(p, tabs, n_tabs, Qlr, Klr, prefix, krem, idx, st)
+#define DSV_CASE(TT, RR) return select_t<TT, RR>(p, tabs, n_tabs, Qlr, Klr, b, st)
     if (p.dtype == DSV_BF16) {
         if (p.r == 16) DSV_CASE(bf16_t, 16);
         if (p.r == 32) DSV_CASE(bf16_t, 32);

@@ -128,3 +128,51 @@ def test_k_equals_L_and_k_equals_1():
     S = dsv.lowrank_scores_rows(p, Qlr, Klr, 0, 1, torch.arange(200, dtype=torch.int32).cuda())
     torch.cuda.synchronize()
     assert np.array_equal(case.idx_rows(idx, 1)[:, 0], S.cpu().numpy().argmax(axis=1))
+
+
+# ------------------------------------------------------------------------------ transposed index
+def _check_transpose(idx_rows, idx_t_head, col, L, sorted_lists):
+    """idx_rows [L, k]; idx_t_head: the head's block of the key-major index; col [L+1]."""
+    k = idx_rows.shape[1]
+    counts = np.bincount(idx_rows.reshape(-1), minlength=L)
+    assert col[0] == 0 and col[-1] == L * k and np.array_equal(np.diff(col), counts)
+    # reference transpose: stable sort of the (query, key) pairs by key keeps queries ascending
+    q_of_pair = np.repeat(np.arange(L, dtype=np.int32), k)
+    order = np.argsort(idx_rows.reshape(-1), kind="stable")
+    ref = q_of_pair[order]
+    if sorted_lists:
+        assert np.array_equal(idx_t_head, ref)
+    else:
+        got = idx_t_head.copy()
+        for j in range(L):
+            got[col[j]:col[j + 1]].sort()
+        assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("kind,dtype,L,d,r,ks", [("ternary", "bf16", 777, 128, 16, [100, 33]),
+                                                 ("gauss", "bf16", 3000, 128, 16, [187, 1500, 40]),
+                                                 ("gauss", "f32", 1024, 64, 16, [128, 1024]),
+                                                 ("ternary", "bf16", 95, 64, 32, [95, 1, 17])])
+def test_lowrank_topk_t_emits_the_exact_transpose(kind, dtype, L, d, r, ks):
+    H = len(ks)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    if kind == "ternary":
+        Qs, Ks, Wqs, Wks = zip(*(wl.ternary_head_tensors(L, d, r, seed=2, head=h) for h in range(H)))
+        dev = lambda a: torch.from_numpy(np.stack(a)).cuda().to(td).contiguous()
+        Q, K, Wq, Wk = dev(Qs)[None], dev(Ks)[None], dev(Wqs), dev(Wks)
+        p = dsv.Problem(1, H, L, d, r, dtype, ks, 1.0)
+    else:
+        case = Case(make_cfg(L, d, r, H, dtype, basis_rank=32), ks, names=("Q", "K"))
+        Q, K, Wq, Wk = case.dev["Q"], case.dev["K"], case.dWq, case.dWk
+        p = case.problem(dsv)
+    idx_plain = _run_topk(p, Q, K, Wq, Wk)
+    idx, idx_t, col = dsv.lowrank_topk_t(p, Q, K, Wq, Wk)
+    idx_t2, col2 = dsv.idx_transpose(p, idx)
+    torch.cuda.synchronize()
+    idx, idx_t, col, idx_t2, col2 = (x.cpu().numpy() for x in (idx, idx_t, col, idx_t2, col2))
+    assert np.array_equal(idx, idx_plain)                          # same selection with or without the transpose
+    off = wl.idx_offsets(1, H, L, ks)
+    for h in range(H):
+        rows = idx[off[h]:off[h + 1]].reshape(L, ks[h])
+        _check_transpose(rows, idx_t[off[h]:off[h + 1]], col[h], L, sorted_lists=True)
+        _check_transpose(rows, idx_t2[off[h]:off[h + 1]], col2[h], L, sorted_lists=False)
