@@ -34,6 +34,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark config list (headline: 2)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--unsorted", action="store_true", help="do not set DSV_FLAG_SORTED_INDEX (plain gather kernels)")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention comparator")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-rows", type=int, default=0, help="query rows of the oracle sample (0 = auto)")
@@ -107,7 +108,8 @@ def main():
     dev = torch.device("cuda:0")
     cfg = wl.get_config(args.config)
     ks = wl.k_per_head(cfg, seed=args.seed)
-    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, ks.tolist(), cfg.scale)
+    # stage 1 writes ascending rows and lists, so stage 2 may be told so (DSV_FLAG_SORTED_INDEX)
+    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, ks.tolist(), cfg.scale, sorted_index=not args.unsorted)
     esize = 2 if cfg.dtype == "bf16" else 4
     nnz = int(cfg.L * ks.astype(np.int64).sum())
     n_scores = cfg.H * cfg.L * cfg.L
@@ -124,13 +126,14 @@ def main():
     lse = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
     delta = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
     ws1 = torch.empty(dsv.lowrank_topk_t_workspace(p), dtype=torch.uint8, device=dev)
+    wsf = torch.empty(max(dsv.sparse_attn_fwd_workspace(p), 256), dtype=torch.uint8, device=dev)
 
     names = ("lowrank_topk_t", "sparse_attn_fwd", "sparse_attn_bwd_dq", "sparse_attn_bwd_dkdv")
 
     def step(events=None):
         calls = (
             lambda: dsv.lowrank_topk_t(p, g["Q"], g["K"], Wq, Wk, idx=idx, idx_t=idx_t, col_ptr=col_ptr, workspace=ws1),
-            lambda: dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx, O=O, lse=lse),
+            lambda: dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx, O=O, lse=lse, workspace=wsf),
             lambda: dsv.sparse_attn_bwd_dq(p, g["Q"], g["K"], g["V"], idx, lse, g["dO"], dQ=dQ, delta=delta),
             lambda: dsv.sparse_attn_bwd_dkdv(p, g["Q"], g["K"], g["V"], idx_t, col_ptr, lse, delta, g["dO"], dK=dK, dV=dV),
         )

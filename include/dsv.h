@@ -67,7 +67,15 @@ typedef struct dsv_problem {
     const int32_t *k_per_head;  /* HOST array [H]: KV kept per query in head h, 1 <= k_h <= L
                                    (one sparsity level per head: Sec. "Limitations and Future Work") */
     float scale;                /* softmax scale applied to q.k; the paper uses 1/sqrt(d_k) */
+    uint32_t flags;             /* DSV_FLAG_* bits, 0 for none */
 } dsv_problem;
+
+/* The caller promises that every idx row, and every idx_t list, is in ascending order -- which is
+ * how dsv_lowrank_topk / dsv_lowrank_topk_t write them.  Stage 2 then runs its L2-blocked kernels
+ * (the key axis cut into cache-sized ranges, one contiguous segment of each row per range), which
+ * need more workspace and are several times faster on long sequences.  Without the flag stage 2
+ * makes no assumption on the order.  Setting it for unsorted indices gives wrong results. */
+#define DSV_FLAG_SORTED_INDEX 1u
 
 DSV_API const char *dsv_version(void);
 DSV_API const char *dsv_status_string(dsv_status s);
@@ -108,8 +116,9 @@ DSV_API dsv_status dsv_lowrank_topk_t(const dsv_problem *p, const void *Q, const
  * attention of Sec. "Various Self-Attention Paradigms":
  *     s_j = scale * q_i . k_j  for j in idx row (b, h, i);   p = softmax over those j only;
  *     O_i = sum_j p_j v_j;     lse_i = log sum_j exp(s_j).
- * O is written in `dtype`, lse in float.  Needs no workspace today (the query returns 0, and a
- * null workspace is accepted when it does). */
+ * O is written in `dtype`, lse in float.  Workspace: none without DSV_FLAG_SORTED_INDEX (the query
+ * returns 0 and a null workspace is accepted); with it, the segment pointers and the per-range
+ * partial results. */
 DSV_API size_t dsv_sparse_attn_fwd_workspace(const dsv_problem *p);
 DSV_API dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, const void *K, const void *V,
                                const int32_t *idx, void *O, float *lse,

@@ -14,6 +14,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libdsv.so")
 
 DSV_F32, DSV_BF16 = 0, 1
+DSV_FLAG_SORTED_INDEX = 1
 _DTYPE_CODE = {torch.float32: DSV_F32, torch.bfloat16: DSV_BF16}
 _DTYPE_NAME = {"f32": torch.float32, "bf16": torch.bfloat16}
 
@@ -34,7 +35,8 @@ class DsvError(RuntimeError):
 class _CProblem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("r", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("k_per_head", ctypes.POINTER(ctypes.c_int32)), ("scale", ctypes.c_float)]
+                ("k_per_head", ctypes.POINTER(ctypes.c_int32)), ("scale", ctypes.c_float),
+                ("flags", ctypes.c_uint32)]
 
 
 _lib = None
@@ -99,7 +101,8 @@ def _check(status: int, what: str):
 class Problem:
     """Host-side problem descriptor (mirrors struct dsv_problem)."""
 
-    def __init__(self, B: int, H: int, L: int, d: int, r: int, dtype, k_per_head: Sequence[int], scale: float):
+    def __init__(self, B: int, H: int, L: int, d: int, r: int, dtype, k_per_head: Sequence[int], scale: float,
+                 sorted_index: bool = False):
         if isinstance(dtype, str):
             dtype = _DTYPE_NAME[dtype]
         self.B, self.H, self.L, self.d, self.r = int(B), int(H), int(L), int(d), int(r)
@@ -108,7 +111,9 @@ class Problem:
         self.scale = float(scale)
         self._k_arr = (ctypes.c_int32 * len(self.k_per_head))(*self.k_per_head)
         self._c = _CProblem(self.B, self.H, self.L, self.d, self.r, _DTYPE_CODE.get(dtype, -1),
-                            ctypes.cast(self._k_arr, ctypes.POINTER(ctypes.c_int32)), self.scale)
+                            ctypes.cast(self._k_arr, ctypes.POINTER(ctypes.c_int32)), self.scale,
+                            DSV_FLAG_SORTED_INDEX if sorted_index else 0)
+        self.sorted_index = bool(sorted_index)
 
     @property
     def c(self):
@@ -141,7 +146,7 @@ def _stream(stream):
 
 
 def _workspace(nbytes: int, device, workspace):
-    if nbytes == 0:
+    if nbytes == 0 and workspace is None:
         return None, 0
     if workspace is None:
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)

@@ -68,6 +68,31 @@ Stage1Workspace stage1_layout(const dsv_problem &p, bool transposed)
     return w;
 }
 
+// Whether stage 2 runs its L2-blocked kernels: sorted indices promised and more than one range.
+bool use_split(const dsv_problem &p, const SplitPlan &pl) { return (p.flags & DSV_FLAG_SORTED_INDEX) && pl.S > 1; }
+
+struct FwdLayout {
+    bool split;
+    SplitPlan plan;
+    size_t seg, pm, pl, pacc, total;
+};
+
+FwdLayout fwd_layout(const dsv_problem &p)
+{
+    FwdLayout w{};
+    w.plan = make_split_plan(p);
+    w.split = use_split(p, w.plan);
+    if (!w.split) return w;
+    const size_t rows = (size_t)p.B * p.H * p.L;
+    size_t o = 0;
+    w.seg = o; o = align_up(o + rows * (w.plan.S + 1) * 4, 256);
+    w.pm = o; o = align_up(o + rows * w.plan.S * 4, 256);
+    w.pl = o; o = align_up(o + rows * w.plan.S * 4, 256);
+    w.pacc = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
+    w.total = o;
+    return w;
+}
+
 struct BwdLayout {
     size_t delta, cnt, cnt_bytes256, col, idxT, total;
 };
@@ -181,23 +206,31 @@ dsv_status dsv_lowrank_topk_t(const dsv_problem *p, const void *Q, const void *K
 
 size_t dsv_sparse_attn_fwd_workspace(const dsv_problem *p)
 {
-    (void)p;
-    return 0;
+    if (check_problem(p, false) != DSV_OK) return 0;
+    return fwd_layout(*p).total;
 }
 
 dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, const void *K, const void *V, const int32_t *idx,
                                void *O, float *lse, void *workspace, size_t ws_bytes, void *hip_stream)
 {
-    (void)workspace;
-    (void)ws_bytes;
     dsv_status st = check_problem(p, false);
     if (st != DSV_OK) return st;
     if (!Q || !K || !V || !idx || !O || !lse) return DSV_EINVAL;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(O) || !aligned16(lse))
         return DSV_EINVAL;
+    const FwdLayout w = fwd_layout(*p);
+    st = check_workspace(workspace, ws_bytes, w.total);
+    if (st != DSV_OK) return st;
     const std::vector<HeadTable> tabs = make_tables(*p);
-    return launch_sparse_fwd(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse,
-                             static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!w.split) return launch_sparse_fwd(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse, stream);
+    char *ws = static_cast<char *>(workspace);
+    FwdSplitWorkspace b;
+    b.seg = reinterpret_cast<int32_t *>(ws + w.seg);
+    b.pm = reinterpret_cast<float *>(ws + w.pm);
+    b.pl = reinterpret_cast<float *>(ws + w.pl);
+    b.pacc = reinterpret_cast<float *>(ws + w.pacc);
+    return launch_sparse_fwd_split(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse, w.plan, b, stream);
 }
 
 size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p)

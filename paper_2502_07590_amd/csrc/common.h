@@ -163,6 +163,29 @@ dsv_status launch_project(const dsv_problem &p, const void *Q, const void *K, co
                           void *Qlr, void *Klr, hipStream_t st);
 dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void *Klr, int bh,
                               const int32_t *rows, int n_rows, float *scores, hipStream_t st);
+// ---- L2-blocked (split-K) form of stage 2 -----------------------------------------------------
+// Bytes of K+V (or Q+dO) rows one key (query) range may hold: sized to sit in one XCD's 4 MB L2
+// next to the streamed indices and partial results.
+constexpr size_t kSplitRangeBytes = 2u << 20;
+
+struct SplitPlan {
+    int range_len;  // keys (queries) per range
+    int S;          // ranges
+    int S_pad;      // S rounded up to a multiple of 8 (one XCD per residue class)
+    int nqb;        // blocks of 16 rows per range
+};
+SplitPlan make_split_plan(const dsv_problem &p);
+
+struct FwdSplitWorkspace {
+    int32_t *seg;  // [B*H, L, S+1] segment pointers into every idx row
+    float *pm;     // [B*H, L, S]    partial running max (log2 domain)
+    float *pl;     // [B*H, L, S]    partial normaliser
+    float *pacc;   // [B*H, L, S, d] partial unnormalised output
+};
+dsv_status launch_sparse_fwd_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
+                                   const void *K, const void *V, const int32_t *idx, void *O, float *lse,
+                                   const SplitPlan &pl, const FwdSplitWorkspace &w, hipStream_t st);
+
 // Device buffers of the selection.  idx_t == nullptr skips the key-major emission (then jcut, cnt,
 // col may be null as well).
 struct SelectBuffers {

@@ -37,9 +37,9 @@ class Case:
         self.dWk = torch.from_numpy(np.stack(self.Wk)).to(device).to(td).contiguous()
         self.off = wl.idx_offsets(1, cfg.H, cfg.L, self.ks)
 
-    def problem(self, dsv):
+    def problem(self, dsv, sorted_index=False):
         c = self.cfg
-        return dsv.Problem(1, c.H, c.L, c.d, c.r, c.dtype, self.ks, c.scale)
+        return dsv.Problem(1, c.H, c.L, c.d, c.r, c.dtype, self.ks, c.scale, sorted_index=sorted_index)
 
     def idx_rows(self, idx_flat: np.ndarray, h: int) -> np.ndarray:
         return idx_flat[self.off[h]:self.off[h + 1]].reshape(self.cfg.L, self.ks[h])

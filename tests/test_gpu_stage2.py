@@ -23,8 +23,8 @@ def _oracle_idx(case):
     return out
 
 
-def _run_stage2(case, idx_rows):
-    p = case.problem(dsv)
+def _run_stage2(case, idx_rows, sorted_index=False):
+    p = case.problem(dsv, sorted_index=sorted_index)
     flat = torch.from_numpy(np.concatenate([r.reshape(-1) for r in idx_rows])).cuda()
     d = case.dev
     O, lse = dsv.sparse_attn_fwd(p, d["Q"], d["K"], d["V"], flat)
@@ -62,6 +62,16 @@ def test_ragged_sizes_and_mixed_k(dtype, L, d, ks):
     case = Case(cfg, ks)
     idx_rows = _oracle_idx(case)
     print(_check_all(case, idx_rows, _run_stage2(case, idx_rows)))
+
+
+@pytest.mark.parametrize("dtype,L,d,ks", [("bf16", 9000, 128, [300, 64]), ("f32", 5000, 128, [40, 700]),
+                                          ("bf16", 8200, 64, [1, 8200])])
+def test_l2_blocked_kernels_on_sorted_indices(dtype, L, d, ks):
+    """Several key ranges with a ragged last one; DSV_FLAG_SORTED_INDEX set."""
+    cfg = make_cfg(L, d, 16, len(ks), dtype, basis_rank=64 if d == 128 else 32, scale_num=2.0)
+    case = Case(cfg, ks)
+    idx_rows = _oracle_idx(case)
+    print(_check_all(case, idx_rows, _run_stage2(case, idx_rows, sorted_index=True)))
 
 
 def test_row_order_does_not_matter_and_unselected_keys_get_zero():
