@@ -126,7 +126,8 @@ def main():
     lse = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
     delta = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
     ws1 = torch.empty(dsv.lowrank_topk_t_workspace(p), dtype=torch.uint8, device=dev)
-    wsf = torch.empty(max(dsv.sparse_attn_fwd_workspace(p), 256), dtype=torch.uint8, device=dev)
+    wsf = torch.empty(max(dsv.sparse_attn_fwd_workspace(p), dsv.sparse_attn_bwd_dq_workspace(p),
+                          dsv.sparse_attn_bwd_dkdv_workspace(p), 256), dtype=torch.uint8, device=dev)
 
     names = ("lowrank_topk_t", "sparse_attn_fwd", "sparse_attn_bwd_dq", "sparse_attn_bwd_dkdv")
 
@@ -134,8 +135,9 @@ def main():
         calls = (
             lambda: dsv.lowrank_topk_t(p, g["Q"], g["K"], Wq, Wk, idx=idx, idx_t=idx_t, col_ptr=col_ptr, workspace=ws1),
             lambda: dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx, O=O, lse=lse, workspace=wsf),
-            lambda: dsv.sparse_attn_bwd_dq(p, g["Q"], g["K"], g["V"], idx, lse, g["dO"], dQ=dQ, delta=delta),
-            lambda: dsv.sparse_attn_bwd_dkdv(p, g["Q"], g["K"], g["V"], idx_t, col_ptr, lse, delta, g["dO"], dK=dK, dV=dV),
+            lambda: dsv.sparse_attn_bwd_dq(p, g["Q"], g["K"], g["V"], idx, lse, g["dO"], dQ=dQ, delta=delta, workspace=wsf),
+            lambda: dsv.sparse_attn_bwd_dkdv(p, g["Q"], g["K"], g["V"], idx_t, col_ptr, lse, delta, g["dO"], dK=dK, dV=dV,
+                                             workspace=wsf),
         )
         if events is None:
             for c in calls:

@@ -141,32 +141,49 @@ DSV_API dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, cons
                                void *dQ, void *dK, void *dV,
                                void *workspace, size_t ws_bytes, void *hip_stream);
 
-/* ---- The three steps of the backward, callable one by one -------------------------------------
- * dsv_sparse_attn_bwd runs exactly these, in this order, with delta / idx_t / col_ptr placed in
- * its workspace.  They are exported so that a caller can keep the transposed index across
- * calls that share idx, and so that each step can be timed on its own.
+/* Whole backward with the transposed index supplied by the caller (from dsv_lowrank_topk_t, or
+ * from an earlier dsv_idx_transpose): dq step then dkdv step; nothing is built here, so with
+ * DSV_FLAG_SORTED_INDEX both steps run L2-blocked.  Same outputs as dsv_sparse_attn_bwd. */
+DSV_API size_t dsv_sparse_attn_bwd_t_workspace(const dsv_problem *p);
+DSV_API dsv_status dsv_sparse_attn_bwd_t(const dsv_problem *p, const void *Q, const void *K, const void *V,
+                                         const int32_t *idx, const int32_t *idx_t, const int64_t *col_ptr,
+                                         const void *O, const float *lse, const void *dO,
+                                         void *dQ, void *dK, void *dV,
+                                         void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* ---- The steps of the backward, callable one by one ----------------------------------------------
+ * dsv_sparse_attn_bwd runs dq, transpose, dkdv in this order (dsv_sparse_attn_bwd_t: dq, dkdv).
+ * They are exported so that a caller can keep the transposed index across calls that share idx,
+ * and so that each step can be timed on its own.
  *
  * dsv_sparse_attn_bwd_dq: query-major sweep.  Writes dQ [B, H, L, d] (`dtype`) and
- *   delta [B, H, L] (float) = Delta_i = sum_j p_ij (dO_i . v_j), which equals dO_i . O_i.  No workspace.
+ *   delta [B, H, L] (float) = Delta_i = sum_j p_ij (dO_i . v_j), which equals dO_i . O_i.
  *
  * dsv_idx_transpose: for every (b, h) and key j, the list of queries i whose idx row holds j.
  *   idx_t: int32, same ragged layout and size as idx (per head, the lists of key 0, 1, ... back to
  *   back); col_ptr: int64 [B*H, L+1], list of key j of head bh = idx_t[off[bh] + col_ptr[bh][j] ..
- *   off[bh] + col_ptr[bh][j+1]).  The order of the queries inside a list is unspecified.
- *   Workspace: one int32 counter per (b, h, key).
+ *   off[bh] + col_ptr[bh][j+1]).  The order of the queries inside a list is unspecified (it comes
+ *   from atomic cursors), so its output must not be combined with DSV_FLAG_SORTED_INDEX in the
+ *   dkdv step.  Workspace: one int32 counter per (b, h, key).
  *
  * dsv_sparse_attn_bwd_dkdv: key-major sweep over idx_t.  Writes dK, dV [B, H, L, d] (`dtype`);
- *   keys with an empty list get zeros.  No workspace. */
+ *   keys with an empty list get zeros.
+ *
+ * Workspace of dq and dkdv: none without DSV_FLAG_SORTED_INDEX (query returns 0, null accepted);
+ * with it, segment pointers and per-range partial sums. */
+DSV_API size_t dsv_sparse_attn_bwd_dq_workspace(const dsv_problem *p);
 DSV_API dsv_status dsv_sparse_attn_bwd_dq(const dsv_problem *p, const void *Q, const void *K, const void *V,
                                           const int32_t *idx, const float *lse, const void *dO,
-                                          void *dQ, float *delta, void *hip_stream);
+                                          void *dQ, float *delta,
+                                          void *workspace, size_t ws_bytes, void *hip_stream);
 DSV_API size_t dsv_idx_transpose_workspace(const dsv_problem *p);
 DSV_API dsv_status dsv_idx_transpose(const dsv_problem *p, const int32_t *idx, int32_t *idx_t, int64_t *col_ptr,
                                      void *workspace, size_t ws_bytes, void *hip_stream);
+DSV_API size_t dsv_sparse_attn_bwd_dkdv_workspace(const dsv_problem *p);
 DSV_API dsv_status dsv_sparse_attn_bwd_dkdv(const dsv_problem *p, const void *Q, const void *K, const void *V,
                                             const int32_t *idx_t, const int64_t *col_ptr, const float *lse,
                                             const float *delta, const void *dO, void *dK, void *dV,
-                                            void *hip_stream);
+                                            void *workspace, size_t ws_bytes, void *hip_stream);
 
 /* ---- Stage-1 internals exported for parity checks ---------------------------------------------
  * dsv_lowrank_project: only the projection step of stage 1 (Sec. "Low-Rank based Sparsity

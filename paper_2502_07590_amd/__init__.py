@@ -19,6 +19,10 @@ from .binding import (  # noqa: F401
     sparse_attn_bwd,
     sparse_attn_bwd_workspace,
     sparse_attn_bwd_dq,
+    sparse_attn_bwd_dq_workspace,
+    sparse_attn_bwd_dkdv_workspace,
+    sparse_attn_bwd_t,
+    sparse_attn_bwd_t_workspace,
     idx_transpose,
     idx_transpose_workspace,
     sparse_attn_bwd_dkdv,

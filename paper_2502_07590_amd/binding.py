@@ -23,7 +23,9 @@ EXPORTED_SYMBOLS = (
     "dsv_lowrank_topk_workspace", "dsv_lowrank_topk", "dsv_lowrank_topk_t_workspace", "dsv_lowrank_topk_t",
     "dsv_sparse_attn_fwd_workspace", "dsv_sparse_attn_fwd",
     "dsv_sparse_attn_bwd_workspace", "dsv_sparse_attn_bwd",
-    "dsv_sparse_attn_bwd_dq", "dsv_idx_transpose_workspace", "dsv_idx_transpose", "dsv_sparse_attn_bwd_dkdv",
+    "dsv_sparse_attn_bwd_t_workspace", "dsv_sparse_attn_bwd_t",
+    "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dq", "dsv_idx_transpose_workspace", "dsv_idx_transpose",
+    "dsv_sparse_attn_bwd_dkdv_workspace", "dsv_sparse_attn_bwd_dkdv",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
 )
 
@@ -63,7 +65,8 @@ def load_library():
     lib.dsv_idx_offsets.restype = ctypes.c_int
     lib.dsv_idx_offsets.argtypes = [P, ctypes.POINTER(ctypes.c_int64)]
     for name in ("dsv_lowrank_topk_workspace", "dsv_sparse_attn_fwd_workspace", "dsv_sparse_attn_bwd_workspace",
-                 "dsv_idx_transpose_workspace", "dsv_lowrank_topk_t_workspace"):
+                 "dsv_idx_transpose_workspace", "dsv_lowrank_topk_t_workspace", "dsv_sparse_attn_bwd_t_workspace",
+                 "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dkdv_workspace"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [P]
     lib.dsv_lowrank_topk.restype = ctypes.c_int
@@ -75,11 +78,13 @@ def load_library():
     lib.dsv_sparse_attn_bwd.restype = ctypes.c_int
     lib.dsv_sparse_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_bwd_dq.restype = ctypes.c_int
-    lib.dsv_sparse_attn_bwd_dq.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.dsv_sparse_attn_bwd_dq.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dsv_sparse_attn_bwd_t.restype = ctypes.c_int
+    lib.dsv_sparse_attn_bwd_t.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_idx_transpose.restype = ctypes.c_int
     lib.dsv_idx_transpose.argtypes = [P, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_bwd_dkdv.restype = ctypes.c_int
-    lib.dsv_sparse_attn_bwd_dkdv.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.dsv_sparse_attn_bwd_dkdv.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_lowrank_project.restype = ctypes.c_int
     lib.dsv_lowrank_project.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
     lib.dsv_lowrank_scores_rows.restype = ctypes.c_int
@@ -216,13 +221,35 @@ def sparse_attn_bwd(p: Problem, Q, K, V, idx, O, lse, dO, dQ=None, dK=None, dV=N
     return dQ, dK, dV
 
 
-def sparse_attn_bwd_dq(p: Problem, Q, K, V, idx, lse, dO, dQ=None, delta=None, stream=None):
+def sparse_attn_bwd_dq_workspace(p: Problem) -> int:
+    return int(load_library().dsv_sparse_attn_bwd_dq_workspace(p.c))
+
+
+def sparse_attn_bwd_dq(p: Problem, Q, K, V, idx, lse, dO, dQ=None, delta=None, workspace=None, stream=None):
     lib = load_library()
     dQ = torch.empty_like(Q) if dQ is None else dQ
     delta = torch.empty((p.B, p.H, p.L), dtype=torch.float32, device=Q.device) if delta is None else delta
+    ws, nbytes = _workspace(sparse_attn_bwd_dq_workspace(p), Q.device, workspace)
     _check(lib.dsv_sparse_attn_bwd_dq(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(lse), _ptr(dO), _ptr(dQ),
-                                      _ptr(delta), _stream(stream)), "dsv_sparse_attn_bwd_dq")
+                                      _ptr(delta), _ptr(ws), nbytes, _stream(stream)), "dsv_sparse_attn_bwd_dq")
     return dQ, delta
+
+
+def sparse_attn_bwd_t_workspace(p: Problem) -> int:
+    return int(load_library().dsv_sparse_attn_bwd_t_workspace(p.c))
+
+
+def sparse_attn_bwd_t(p: Problem, Q, K, V, idx, idx_t, col_ptr, O, lse, dO, dQ=None, dK=None, dV=None,
+                      workspace=None, stream=None):
+    lib = load_library()
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    ws, nbytes = _workspace(sparse_attn_bwd_t_workspace(p), Q.device, workspace)
+    _check(lib.dsv_sparse_attn_bwd_t(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(idx_t), _ptr(col_ptr), _ptr(O),
+                                     _ptr(lse), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws), nbytes,
+                                     _stream(stream)), "dsv_sparse_attn_bwd_t")
+    return dQ, dK, dV
 
 
 def idx_transpose_workspace(p: Problem) -> int:
@@ -239,12 +266,18 @@ def idx_transpose(p: Problem, idx, idx_t=None, col_ptr=None, workspace=None, str
     return idx_t, col_ptr
 
 
-def sparse_attn_bwd_dkdv(p: Problem, Q, K, V, idx_t, col_ptr, lse, delta, dO, dK=None, dV=None, stream=None):
+def sparse_attn_bwd_dkdv_workspace(p: Problem) -> int:
+    return int(load_library().dsv_sparse_attn_bwd_dkdv_workspace(p.c))
+
+
+def sparse_attn_bwd_dkdv(p: Problem, Q, K, V, idx_t, col_ptr, lse, delta, dO, dK=None, dV=None, workspace=None,
+                         stream=None):
     lib = load_library()
     dK = torch.empty_like(K) if dK is None else dK
     dV = torch.empty_like(V) if dV is None else dV
+    ws, nbytes = _workspace(sparse_attn_bwd_dkdv_workspace(p), Q.device, workspace)
     _check(lib.dsv_sparse_attn_bwd_dkdv(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx_t), _ptr(col_ptr), _ptr(lse),
-                                        _ptr(delta), _ptr(dO), _ptr(dK), _ptr(dV), _stream(stream)),
+                                        _ptr(delta), _ptr(dO), _ptr(dK), _ptr(dV), _ptr(ws), nbytes, _stream(stream)),
            "dsv_sparse_attn_bwd_dkdv")
     return dK, dV
 

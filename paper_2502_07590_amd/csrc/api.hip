@@ -1,6 +1,7 @@
 // C ABI of libdsv: argument checks, workspace layout, launch order.  All checks run on the host
 // before anything is enqueued; the library never allocates device memory.
 #include <algorithm>
+#include <initializer_list>
 #include <vector>
 
 #include "common.h"
@@ -14,11 +15,20 @@ bool supported_dtype(int t) { return t == DSV_F32 || t == DSV_BF16; }
 size_t esize(int dtype) { return dtype == DSV_BF16 ? 2 : 4; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// true when every pointer is non-null and 16-byte aligned
+bool ok_ptrs(std::initializer_list<const void *> ps)
+{
+    for (const void *p : ps)
+        if (!p || !aligned16(p)) return false;
+    return true;
+}
+
 dsv_status check_problem(const dsv_problem *p, bool need_r)
 {
     if (!p || !p->k_per_head) return DSV_EINVAL;
     if (p->B < 1 || p->H < 1 || p->L < 1) return DSV_EINVAL;
     if ((int64_t)p->B * p->H > (1 << 20)) return DSV_EINVAL;
+    if (p->flags & ~DSV_FLAG_SORTED_INDEX) return DSV_EINVAL;
     if (!supported_dtype(p->dtype) || !supported_d(p->d)) return DSV_EUNSUPPORTED;
     if (need_r && !supported_r(p->r)) return DSV_EUNSUPPORTED;
     for (int h = 0; h < p->H; ++h)
@@ -48,15 +58,30 @@ std::vector<HeadTable> make_tables(const dsv_problem &p)
     return tabs;
 }
 
-struct Stage1Workspace {
+size_t total_pairs(const dsv_problem &p)
+{
+    size_t nnz = 0;
+    for (int bh = 0; bh < p.B * p.H; ++bh) nnz += (size_t)p.L * p.k_per_head[bh % p.H];
+    return nnz;
+}
+
+dsv_status check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return DSV_OK;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || have < need) return DSV_EWORKSPACE;
+    return DSV_OK;
+}
+
+// ---- workspace layouts (byte offsets, every block aligned to 256) ------------------------------
+struct Stage1Layout {
     size_t qlr, klr, prefix, krem, jcut, cnt, total;
 };
 
 // transposed: also room for jcut and the per-key list lengths of the key-major emission
-Stage1Workspace stage1_layout(const dsv_problem &p, bool transposed)
+Stage1Layout stage1_layout(const dsv_problem &p, bool transposed)
 {
     const size_t tok = (size_t)p.B * p.H * p.L;
-    Stage1Workspace w;
+    Stage1Layout w{};
     size_t o = 0;
     w.qlr = o; o = align_up(o + tok * p.r * esize(p.dtype), 256);
     w.klr = o; o = align_up(o + tok * p.r * esize(p.dtype), 256);
@@ -93,31 +118,61 @@ FwdLayout fwd_layout(const dsv_problem &p)
     return w;
 }
 
-struct BwdLayout {
-    size_t delta, cnt, cnt_bytes256, col, idxT, total;
+// One split backward step (dq or dkdv): segment pointers and two [rows, S, d] partial arrays
+// (+ [rows, S] for the dq step's Delta partials; laid out for both so that the steps can share it).
+struct StepLayout {
+    bool split;
+    SplitPlan plan;
+    size_t seg, pa, pb, pdelta, total;
 };
 
-BwdLayout bwd_layout(const dsv_problem &p)
+StepLayout step_layout(const dsv_problem &p)
 {
-    const size_t nbh = (size_t)p.B * p.H;
-    const size_t tok = nbh * p.L;
-    size_t nnz = 0;
-    for (size_t bh = 0; bh < nbh; ++bh) nnz += (size_t)p.L * p.k_per_head[bh % p.H];
-    BwdLayout w;
+    StepLayout w{};
+    w.plan = make_split_plan(p);
+    w.split = use_split(p, w.plan);
+    if (!w.split) return w;
+    const size_t rows = (size_t)p.B * p.H * p.L;
     size_t o = 0;
-    w.delta = o; o = align_up(o + tok * 4, 256);
-    w.cnt = o; w.cnt_bytes256 = align_up(tok * 4, 256); o += w.cnt_bytes256;
-    w.col = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
-    w.idxT = o; o = align_up(o + nnz * 4, 256);
+    w.seg = o; o = align_up(o + rows * (w.plan.S + 1) * 4, 256);
+    w.pa = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
+    w.pb = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
+    w.pdelta = o; o = align_up(o + rows * w.plan.S * 4, 256);
     w.total = o;
     return w;
 }
 
-dsv_status check_workspace(const void *ws, size_t have, size_t need)
+BwdSplitWorkspace step_buffers(char *ws, const StepLayout &w)
 {
-    if (need == 0) return DSV_OK;
-    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || have < need) return DSV_EWORKSPACE;
-    return DSV_OK;
+    BwdSplitWorkspace b;
+    b.seg = reinterpret_cast<int32_t *>(ws + w.seg);
+    b.pa = reinterpret_cast<float *>(ws + w.pa);
+    b.pb = reinterpret_cast<float *>(ws + w.pb);
+    b.pdelta = reinterpret_cast<float *>(ws + w.pdelta);
+    return b;
+}
+
+// Whole backward.  own_transpose: the call builds the key-major index itself (dsv_sparse_attn_bwd);
+// otherwise the caller brings it (dsv_sparse_attn_bwd_t).
+struct BwdLayout {
+    size_t delta, cnt, cnt_bytes, col, idxT, step, step_bytes, total;
+};
+
+BwdLayout bwd_layout(const dsv_problem &p, bool own_transpose)
+{
+    const size_t nbh = (size_t)p.B * p.H;
+    const size_t tok = nbh * p.L;
+    BwdLayout w{};
+    size_t o = 0;
+    w.delta = o; o = align_up(o + tok * 4, 256);
+    if (own_transpose) {
+        w.cnt = o; w.cnt_bytes = align_up(tok * 4, 256); o += w.cnt_bytes;
+        w.col = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
+        w.idxT = o; o = align_up(o + total_pairs(p) * 4, 256);
+    }
+    w.step = o; w.step_bytes = step_layout(p).total; o += w.step_bytes;
+    w.total = o;
+    return w;
 }
 
 }  // namespace
@@ -127,7 +182,7 @@ using namespace dsv;
 
 extern "C" {
 
-const char *dsv_version(void) { return "dsv 0.1 (gfx950)"; }
+const char *dsv_version(void) { return "dsv 0.2 (gfx950)"; }
 
 const char *dsv_status_string(dsv_status s)
 {
@@ -151,16 +206,16 @@ dsv_status dsv_idx_offsets(const dsv_problem *p, int64_t *off)
     return DSV_OK;
 }
 
+// ------------------------------------------------------------------------------------ stage 1
 static dsv_status lowrank_topk_impl(const dsv_problem *p, const void *Q, const void *K, const void *Wq,
                                     const void *Wk, int32_t *idx, int32_t *idx_t, int64_t *col_ptr, bool transposed,
                                     void *workspace, size_t ws_bytes, void *hip_stream)
 {
     dsv_status st = check_problem(p, true);
     if (st != DSV_OK) return st;
-    if (!Q || !K || !Wq || !Wk || !idx) return DSV_EINVAL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(Wq) || !aligned16(Wk) || !aligned16(idx)) return DSV_EINVAL;
-    if (transposed && (!idx_t || !col_ptr || !aligned16(idx_t) || !aligned16(col_ptr))) return DSV_EINVAL;
-    const Stage1Workspace w = stage1_layout(*p, transposed);
+    if (!ok_ptrs({Q, K, Wq, Wk, idx})) return DSV_EINVAL;
+    if (transposed && !ok_ptrs({idx_t, col_ptr})) return DSV_EINVAL;
+    const Stage1Layout w = stage1_layout(*p, transposed);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
     char *ws = static_cast<char *>(workspace);
@@ -204,6 +259,7 @@ dsv_status dsv_lowrank_topk_t(const dsv_problem *p, const void *Q, const void *K
     return lowrank_topk_impl(p, Q, K, Wq, Wk, idx, idx_t, col_ptr, true, workspace, ws_bytes, hip_stream);
 }
 
+// ------------------------------------------------------------------------------------ stage 2 forward
 size_t dsv_sparse_attn_fwd_workspace(const dsv_problem *p)
 {
     if (check_problem(p, false) != DSV_OK) return 0;
@@ -215,9 +271,7 @@ dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, const void *
 {
     dsv_status st = check_problem(p, false);
     if (st != DSV_OK) return st;
-    if (!Q || !K || !V || !idx || !O || !lse) return DSV_EINVAL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(O) || !aligned16(lse))
-        return DSV_EINVAL;
+    if (!ok_ptrs({Q, K, V, idx, O, lse})) return DSV_EINVAL;
     const FwdLayout w = fwd_layout(*p);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
@@ -233,25 +287,28 @@ dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, const void *
     return launch_sparse_fwd_split(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse, w.plan, b, stream);
 }
 
-size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p)
+// ------------------------------------------------------------------------------------ stage 2 backward
+size_t dsv_sparse_attn_bwd_dq_workspace(const dsv_problem *p)
 {
     if (check_problem(p, false) != DSV_OK) return 0;
-    return bwd_layout(*p).total;
+    return step_layout(*p).total;
 }
 
 dsv_status dsv_sparse_attn_bwd_dq(const dsv_problem *p, const void *Q, const void *K, const void *V,
                                   const int32_t *idx, const float *lse, const void *dO, void *dQ, float *delta,
-                                  void *hip_stream)
+                                  void *workspace, size_t ws_bytes, void *hip_stream)
 {
     dsv_status st = check_problem(p, false);
     if (st != DSV_OK) return st;
-    if (!Q || !K || !V || !idx || !lse || !dO || !dQ || !delta) return DSV_EINVAL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx) || !aligned16(lse) || !aligned16(dO) ||
-        !aligned16(dQ) || !aligned16(delta))
-        return DSV_EINVAL;
+    if (!ok_ptrs({Q, K, V, idx, lse, dO, dQ, delta})) return DSV_EINVAL;
+    const StepLayout w = step_layout(*p);
+    st = check_workspace(workspace, ws_bytes, w.total);
+    if (st != DSV_OK) return st;
     const std::vector<HeadTable> tabs = make_tables(*p);
-    return launch_bwd_dq(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, lse, dO, dQ, delta,
-                         static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!w.split) return launch_bwd_dq(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, lse, dO, dQ, delta, stream);
+    return launch_bwd_dq_split(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, lse, dO, dQ, delta, w.plan,
+                               step_buffers(static_cast<char *>(workspace), w), stream);
 }
 
 size_t dsv_idx_transpose_workspace(const dsv_problem *p)
@@ -265,30 +322,45 @@ dsv_status dsv_idx_transpose(const dsv_problem *p, const int32_t *idx, int32_t *
 {
     dsv_status st = check_problem(p, false);
     if (st != DSV_OK) return st;
-    if (!idx || !idx_t || !col_ptr) return DSV_EINVAL;
-    if (!aligned16(idx) || !aligned16(idx_t) || !aligned16(col_ptr)) return DSV_EINVAL;
+    if (!ok_ptrs({idx, idx_t, col_ptr})) return DSV_EINVAL;
     const size_t need = dsv_idx_transpose_workspace(p);
     st = check_workspace(workspace, ws_bytes, need);
     if (st != DSV_OK) return st;
     const std::vector<HeadTable> tabs = make_tables(*p);
     return launch_idx_transpose(*p, tabs.data(), (int)tabs.size(), idx, idx_t, col_ptr,
-                                static_cast<int32_t *>(workspace), align_up((size_t)p->B * p->H * p->L * 4, 16),
-                                static_cast<hipStream_t>(hip_stream));
+                                static_cast<int32_t *>(workspace), need, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t dsv_sparse_attn_bwd_dkdv_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, false) != DSV_OK) return 0;
+    return step_layout(*p).total;
 }
 
 dsv_status dsv_sparse_attn_bwd_dkdv(const dsv_problem *p, const void *Q, const void *K, const void *V,
                                     const int32_t *idx_t, const int64_t *col_ptr, const float *lse, const float *delta,
-                                    const void *dO, void *dK, void *dV, void *hip_stream)
+                                    const void *dO, void *dK, void *dV, void *workspace, size_t ws_bytes,
+                                    void *hip_stream)
 {
     dsv_status st = check_problem(p, false);
     if (st != DSV_OK) return st;
-    if (!Q || !K || !V || !idx_t || !col_ptr || !lse || !delta || !dO || !dK || !dV) return DSV_EINVAL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(idx_t) || !aligned16(col_ptr) ||
-        !aligned16(lse) || !aligned16(delta) || !aligned16(dO) || !aligned16(dK) || !aligned16(dV))
-        return DSV_EINVAL;
+    if (!ok_ptrs({Q, K, V, idx_t, col_ptr, lse, delta, dO, dK, dV})) return DSV_EINVAL;
+    const StepLayout w = step_layout(*p);
+    st = check_workspace(workspace, ws_bytes, w.total);
+    if (st != DSV_OK) return st;
     const std::vector<HeadTable> tabs = make_tables(*p);
-    return launch_bwd_dkdv(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx_t, col_ptr, lse, delta, dO, dK, dV,
-                           static_cast<hipStream_t>(hip_stream));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!w.split)
+        return launch_bwd_dkdv(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx_t, col_ptr, lse, delta, dO, dK, dV,
+                               stream);
+    return launch_bwd_dkdv_split(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx_t, col_ptr, lse, delta, dO, dK, dV,
+                                 w.plan, step_buffers(static_cast<char *>(workspace), w), stream);
+}
+
+size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, false) != DSV_OK) return 0;
+    return bwd_layout(*p, true).total;
 }
 
 dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *K, const void *V, const int32_t *idx,
@@ -297,30 +369,56 @@ dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *
 {
     dsv_status st = check_problem(p, false);
     if (st != DSV_OK) return st;
-    if (!O || !dQ || !dK || !dV) return DSV_EINVAL;
-    if (!aligned16(O)) return DSV_EINVAL;
-    const BwdLayout w = bwd_layout(*p);
+    if (!ok_ptrs({O, dQ, dK, dV})) return DSV_EINVAL;
+    const BwdLayout w = bwd_layout(*p, true);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
     char *ws = static_cast<char *>(workspace);
     float *delta = reinterpret_cast<float *>(ws + w.delta);
     int64_t *col = reinterpret_cast<int64_t *>(ws + w.col);
     int32_t *idx_t = reinterpret_cast<int32_t *>(ws + w.idxT);
-    st = dsv_sparse_attn_bwd_dq(p, Q, K, V, idx, lse, dO, dQ, delta, hip_stream);
+    st = dsv_sparse_attn_bwd_dq(p, Q, K, V, idx, lse, dO, dQ, delta, ws + w.step, w.step_bytes, hip_stream);
     if (st != DSV_OK) return st;
-    st = dsv_idx_transpose(p, idx, idx_t, col, ws + w.cnt, w.cnt_bytes256, hip_stream);
+    st = dsv_idx_transpose(p, idx, idx_t, col, ws + w.cnt, w.cnt_bytes, hip_stream);
     if (st != DSV_OK) return st;
-    return dsv_sparse_attn_bwd_dkdv(p, Q, K, V, idx_t, col, lse, delta, dO, dK, dV, hip_stream);
+    // the lists built here are in no particular order: the dkdv step must not assume sorted lists
+    dsv_problem unsorted = *p;
+    unsorted.flags &= ~DSV_FLAG_SORTED_INDEX;
+    return dsv_sparse_attn_bwd_dkdv(&unsorted, Q, K, V, idx_t, col, lse, delta, dO, dK, dV, nullptr, 0, hip_stream);
 }
 
+size_t dsv_sparse_attn_bwd_t_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, false) != DSV_OK) return 0;
+    return bwd_layout(*p, false).total;
+}
+
+dsv_status dsv_sparse_attn_bwd_t(const dsv_problem *p, const void *Q, const void *K, const void *V,
+                                 const int32_t *idx, const int32_t *idx_t, const int64_t *col_ptr, const void *O,
+                                 const float *lse, const void *dO, void *dQ, void *dK, void *dV, void *workspace,
+                                 size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if (!ok_ptrs({O, dQ, dK, dV, idx_t, col_ptr})) return DSV_EINVAL;
+    const BwdLayout w = bwd_layout(*p, false);
+    st = check_workspace(workspace, ws_bytes, w.total);
+    if (st != DSV_OK) return st;
+    char *ws = static_cast<char *>(workspace);
+    float *delta = reinterpret_cast<float *>(ws + w.delta);
+    st = dsv_sparse_attn_bwd_dq(p, Q, K, V, idx, lse, dO, dQ, delta, ws + w.step, w.step_bytes, hip_stream);
+    if (st != DSV_OK) return st;
+    return dsv_sparse_attn_bwd_dkdv(p, Q, K, V, idx_t, col_ptr, lse, delta, dO, dK, dV, ws + w.step, w.step_bytes,
+                                    hip_stream);
+}
+
+// ------------------------------------------------------------------------------------ parity exports
 dsv_status dsv_lowrank_project(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,
                                void *Qlr, void *Klr, void *hip_stream)
 {
     dsv_status st = check_problem(p, true);
     if (st != DSV_OK) return st;
-    if (!Q || !K || !Wq || !Wk || !Qlr || !Klr) return DSV_EINVAL;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(Wq) || !aligned16(Wk) || !aligned16(Qlr) || !aligned16(Klr))
-        return DSV_EINVAL;
+    if (!ok_ptrs({Q, K, Wq, Wk, Qlr, Klr})) return DSV_EINVAL;
     return launch_project(*p, Q, K, Wq, Wk, Qlr, Klr, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -329,9 +427,9 @@ dsv_status dsv_lowrank_scores_rows(const dsv_problem *p, const void *Qlr, const 
 {
     dsv_status st = check_problem(p, true);
     if (st != DSV_OK) return st;
-    if (!Qlr || !Klr || !rows || !scores || n_rows < 1) return DSV_EINVAL;
+    if (!rows || !scores || n_rows < 1) return DSV_EINVAL;
     if (b < 0 || b >= p->B || h < 0 || h >= p->H) return DSV_EINVAL;
-    if (!aligned16(Qlr) || !aligned16(Klr)) return DSV_EINVAL;
+    if (!ok_ptrs({Qlr, Klr})) return DSV_EINVAL;
     return launch_scores_rows(*p, Qlr, Klr, b * p->H + h, rows, n_rows, scores, static_cast<hipStream_t>(hip_stream));
 }
 

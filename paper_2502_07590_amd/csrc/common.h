@@ -186,6 +186,21 @@ dsv_status launch_sparse_fwd_split(const dsv_problem &p, const HeadTable *tabs, 
                                    const void *K, const void *V, const int32_t *idx, void *O, float *lse,
                                    const SplitPlan &pl, const FwdSplitWorkspace &w, hipStream_t st);
 
+// Scratch of one split backward step (dq: A, B, Delta partials; dkdv: dK, dV partials).
+struct BwdSplitWorkspace {
+    int32_t *seg;   // [B*H, L, S+1]
+    float *pa;      // [B*H, L, S, d]
+    float *pb;      // [B*H, L, S, d]
+    float *pdelta;  // [B*H, L, S]   (dq step only)
+};
+dsv_status launch_bwd_dq_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                               const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ,
+                               float *delta, const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st);
+dsv_status launch_bwd_dkdv_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
+                                 const void *K, const void *V, const int32_t *idxT, const int64_t *col,
+                                 const float *lse, const float *delta, const void *dO, void *dK, void *dV,
+                                 const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st);
+
 // Device buffers of the selection.  idx_t == nullptr skips the key-major emission (then jcut, cnt,
 // col may be null as well).
 struct SelectBuffers {

@@ -183,6 +183,217 @@ __global__ __launch_bounds__(256) void sparse_fwd_merge_kernel(const float *__re
     if (s == 0) lse[row] = (M + log2f(lsum)) * kLn2;
 }
 
+// ---- backward, dq step ---------------------------------------------------------------------------
+// Per (query, key range): A = sum p dP k, B = sum p k, Delta = sum p dP over the segment (all three
+// are plain sums over the selected keys, so partials simply add).
+template <typename T, int D>
+__global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                                  const T *__restrict__ V,
+                                                                  const int32_t *__restrict__ idx,
+                                                                  const int32_t *__restrict__ seg,
+                                                                  const float *__restrict__ lse,
+                                                                  const T *__restrict__ dO, float *__restrict__ pa,
+                                                                  float *__restrict__ pb, float *__restrict__ pdelta,
+                                                                  int L, float scale, HeadTable tab, SplitPlan pl)
+{
+    constexpr int CH = D / 16;
+    constexpr int U = 2;
+    typedef RowChunk<T, CH> Chunk;
+    int slot, range, qb;
+    if (!decode_item(pl, blockIdx.x, slot, range, qb)) return;
+    const int bh = tab.bh[slot];
+    const int k = tab.k[slot];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = lane >> 4, s = lane & 15;
+    const int64_t iq = (int64_t)qb * 16 + wave * 4 + grp;
+    const bool live = iq < L;
+    const int64_t i = live ? iq : L - 1;
+    const int64_t head_base = (int64_t)bh * L * D;
+    const T *Kb = K + head_base + s * CH;
+    const T *Vb = V + head_base + s * CH;
+    const int32_t *row = idx + tab.off[slot] + i * k;
+    const int32_t *sp = seg + ((int64_t)bh * L + i) * (pl.S + 1) + range;
+    const int tb = sp[0], te = sp[1];
+
+    const Chunk q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
+    const Chunk go = load_chunk<T, CH>(dO + head_base + i * D + s * CH);
+    const float c2 = scale * kLog2e;
+    const float lse2 = lse[(int64_t)bh * L + i] * kLog2e;
+
+    float a[CH], bsum[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) { a[c] = 0.f; bsum[c] = 0.f; }
+    float delta = 0.f;
+
+    for (int t0 = tb; t0 < te; t0 += U) {
+        int j[U];
+        Chunk kc[U], vc[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) j[u] = row[min(t0 + u, te - 1)];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            kc[u] = load_chunk<T, CH>(Kb + (int64_t)j[u] * D);
+            vc[u] = load_chunk<T, CH>(Vb + (int64_t)j[u] * D);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float sc = row16_sum(dot_chunk<T, CH>(q, kc[u]));
+            const float dp = row16_sum(dot_chunk<T, CH>(go, vc[u]));
+            const float p = (t0 + u < te) ? exp2f(sc * c2 - lse2) : 0.f;
+            const float pdp = p * dp;
+            delta += pdp;
+            float kf[CH];
+            unpack_chunk<T, CH>(kc[u], kf);
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                a[c] = fmaf(pdp, kf[c], a[c]);
+                bsum[c] = fmaf(p, kf[c], bsum[c]);
+            }
+        }
+    }
+    if (live) {
+        const int64_t slot_id = ((int64_t)bh * L + i) * pl.S + range;
+        store_chunk<float, CH>(pa + slot_id * D + s * CH, a);
+        store_chunk<float, CH>(pb + slot_id * D + s * CH, bsum);
+        if (s == 0) pdelta[slot_id] = delta;
+    }
+}
+
+// dQ_i = scale * (sum_s A_s - Delta_i * sum_s B_s), Delta_i = sum_s Delta_s.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void sparse_bwd_dq_merge_kernel(const float *__restrict__ pa,
+                                                                  const float *__restrict__ pb,
+                                                                  const float *__restrict__ pdelta,
+                                                                  T *__restrict__ dQ, float *__restrict__ delta_out,
+                                                                  int64_t n_rows, int S, float scale)
+{
+    constexpr int CH = D / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = lane >> 4, s = lane & 15;
+    const int64_t row = (int64_t)blockIdx.x * 16 + wave * 4 + grp;
+    if (row >= n_rows) return;
+    float a[CH], b[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) { a[c] = 0.f; b[c] = 0.f; }
+    float delta = 0.f;
+    for (int t = 0; t < S; ++t) {
+        const RowChunk<float, CH> ca = load_chunk<float, CH>(pa + (row * S + t) * D + s * CH);
+        const RowChunk<float, CH> cb = load_chunk<float, CH>(pb + (row * S + t) * D + s * CH);
+        delta += pdelta[row * S + t];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) { a[c] += __uint_as_float(ca.w[c]); b[c] += __uint_as_float(cb.w[c]); }
+    }
+    float dq[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) dq[c] = scale * (a[c] - delta * b[c]);
+    store_chunk<T, CH>(dQ + row * D + s * CH, dq);
+    if (s == 0) delta_out[row] = delta;
+}
+
+// ---- backward, dkdv step -------------------------------------------------------------------------
+// Key-major: work item = (head, QUERY range, block of 16 keys); a key's ascending query list has one
+// contiguous segment per query range, whose Q / dO rows (and lse, Delta entries) stay in L2.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                                    const T *__restrict__ V,
+                                                                    const int32_t *__restrict__ idxT,
+                                                                    const int64_t *__restrict__ col,
+                                                                    const int32_t *__restrict__ seg,
+                                                                    const float *__restrict__ lse,
+                                                                    const float *__restrict__ delta,
+                                                                    const T *__restrict__ dO, float *__restrict__ pdk,
+                                                                    float *__restrict__ pdv, int L, float scale,
+                                                                    HeadTable tab, SplitPlan pl)
+{
+    constexpr int CH = D / 16;
+    constexpr int U = 2;
+    typedef RowChunk<T, CH> Chunk;
+    int slot, range, kb;
+    if (!decode_item(pl, blockIdx.x, slot, range, kb)) return;
+    const int bh = tab.bh[slot];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = lane >> 4, s = lane & 15;
+    const int64_t jq = (int64_t)kb * 16 + wave * 4 + grp;
+    const bool live = jq < L;
+    const int64_t j = live ? jq : L - 1;
+    const int64_t head_base = (int64_t)bh * L * D;
+    const T *Qb = Q + head_base + s * CH;
+    const T *Gb = dO + head_base + s * CH;
+    const float *lse_b = lse + (int64_t)bh * L;
+    const float *delta_b = delta + (int64_t)bh * L;
+    const int32_t *list = idxT + tab.off[slot] + col[(int64_t)bh * (L + 1) + j];
+    const int32_t *sp = seg + ((int64_t)bh * L + j) * (pl.S + 1) + range;
+    const int tb = sp[0], te = live ? sp[1] : sp[0];
+
+    const Chunk kc = load_chunk<T, CH>(K + head_base + j * D + s * CH);
+    const Chunk vc = load_chunk<T, CH>(V + head_base + j * D + s * CH);
+    const float c2 = scale * kLog2e;
+    float dk[CH], dv[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) { dk[c] = 0.f; dv[c] = 0.f; }
+
+    for (int t0 = tb; t0 < te; t0 += U) {
+        int iq[U];
+        Chunk qc[U], gc[U];
+        float l2[U], dl[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) iq[u] = list[min(t0 + u, te - 1)];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            qc[u] = load_chunk<T, CH>(Qb + (int64_t)iq[u] * D);
+            gc[u] = load_chunk<T, CH>(Gb + (int64_t)iq[u] * D);
+            l2[u] = lse_b[iq[u]] * kLog2e;
+            dl[u] = delta_b[iq[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float sc = row16_sum(dot_chunk<T, CH>(qc[u], kc));
+            const float dp = row16_sum(dot_chunk<T, CH>(gc[u], vc));
+            const float p = (t0 + u < te) ? exp2f(sc * c2 - l2[u]) : 0.f;
+            const float ds = p * (dp - dl[u]);
+            float qf[CH], gf[CH];
+            unpack_chunk<T, CH>(qc[u], qf);
+            unpack_chunk<T, CH>(gc[u], gf);
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                dk[c] = fmaf(ds, qf[c], dk[c]);
+                dv[c] = fmaf(p, gf[c], dv[c]);
+            }
+        }
+    }
+    if (live) {
+        const int64_t slot_id = ((int64_t)bh * L + j) * pl.S + range;
+        store_chunk<float, CH>(pdk + slot_id * D + s * CH, dk);
+        store_chunk<float, CH>(pdv + slot_id * D + s * CH, dv);
+    }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void sparse_bwd_dkdv_merge_kernel(const float *__restrict__ pdk,
+                                                                    const float *__restrict__ pdv,
+                                                                    T *__restrict__ dK, T *__restrict__ dV,
+                                                                    int64_t n_rows, int S, float scale)
+{
+    constexpr int CH = D / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = lane >> 4, s = lane & 15;
+    const int64_t row = (int64_t)blockIdx.x * 16 + wave * 4 + grp;
+    if (row >= n_rows) return;
+    float a[CH], b[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) { a[c] = 0.f; b[c] = 0.f; }
+    for (int t = 0; t < S; ++t) {
+        const RowChunk<float, CH> ca = load_chunk<float, CH>(pdk + (row * S + t) * D + s * CH);
+        const RowChunk<float, CH> cb = load_chunk<float, CH>(pdv + (row * S + t) * D + s * CH);
+#pragma unroll
+        for (int c = 0; c < CH; ++c) { a[c] += __uint_as_float(ca.w[c]); b[c] += __uint_as_float(cb.w[c]); }
+    }
+#pragma unroll
+    for (int c = 0; c < CH; ++c) a[c] *= scale;
+    store_chunk<T, CH>(dK + row * D + s * CH, a);
+    store_chunk<T, CH>(dV + row * D + s * CH, b);
+}
+
 // ------------------------------------------------------------------------------------ host
 SplitPlan make_split_plan(const dsv_problem &p)
 {
@@ -241,6 +452,79 @@ dsv_status launch_sparse_fwd_split(const dsv_problem &p, const HeadTable *tabs, 
         if (p.d == 128) return fwd_split_t<float, 128>(p, tabs, n_tabs, Q, K, V, idx, O, lse, pl, w, st);
     }
     return DSV_EUNSUPPORTED;
+}
+
+template <typename T, int D>
+static dsv_status bwd_dq_split_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
+                                 const void *K, const void *V, const int32_t *idx, const float *lse, const void *dO,
+                                 void *dQ, float *delta, const SplitPlan &pl, const BwdSplitWorkspace &w,
+                                 hipStream_t st)
+{
+    dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idx, nullptr, w.seg, st);
+    if (rc != DSV_OK) return rc;
+    for (int t = 0; t < n_tabs; ++t) {
+        const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
+        if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
+        hipLaunchKernelGGL((sparse_bwd_dq_split_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
+                           (const T *)K, (const T *)V, idx, w.seg, lse, (const T *)dO, w.pa, w.pb, w.pdelta, p.L,
+                           p.scale, tabs[t], pl);
+        DSV_LAUNCH_CHECK();
+    }
+    const int64_t n_rows = (int64_t)p.B * p.H * p.L;
+    hipLaunchKernelGGL((sparse_bwd_dq_merge_kernel<T, D>), dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st, w.pa,
+                       w.pb, w.pdelta, (T *)dQ, delta, n_rows, pl.S, p.scale);
+    DSV_LAUNCH_CHECK();
+    return DSV_OK;
+}
+
+template <typename T, int D>
+static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
+                                   const void *K, const void *V, const int32_t *idxT, const int64_t *col,
+                                   const float *lse, const float *delta, const void *dO, void *dK, void *dV,
+                                   const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st)
+{
+    dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idxT, col, w.seg, st);
+    if (rc != DSV_OK) return rc;
+    for (int t = 0; t < n_tabs; ++t) {
+        const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
+        if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
+        hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, st,
+                           (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, lse, delta, (const T *)dO, w.pa,
+                           w.pb, p.L, p.scale, tabs[t], pl);
+        DSV_LAUNCH_CHECK();
+    }
+    const int64_t n_rows = (int64_t)p.B * p.H * p.L;
+    hipLaunchKernelGGL((sparse_bwd_dkdv_merge_kernel<T, D>), dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st,
+                       w.pa, w.pb, (T *)dK, (T *)dV, n_rows, pl.S, p.scale);
+    DSV_LAUNCH_CHECK();
+    return DSV_OK;
+}
+
+#define DSV_DISPATCH_TD(FN, ...)                                        \
+    do {                                                                \
+        if (p.dtype == DSV_BF16) {                                      \
+            if (p.d == 64) return FN<bf16_t, 64>(__VA_ARGS__);          \
+            if (p.d == 128) return FN<bf16_t, 128>(__VA_ARGS__);        \
+        } else if (p.dtype == DSV_F32) {                                \
+            if (p.d == 64) return FN<float, 64>(__VA_ARGS__);           \
+            if (p.d == 128) return FN<float, 128>(__VA_ARGS__);         \
+        }                                                               \
+        return DSV_EUNSUPPORTED;                                        \
+    } while (0)
+
+dsv_status launch_bwd_dq_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                               const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ,
+                               float *delta, const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st)
+{
+    DSV_DISPATCH_TD(bwd_dq_split_t, p, tabs, n_tabs, Q, K, V, idx, lse, dO, dQ, delta, pl, w, st);
+}
+
+dsv_status launch_bwd_dkdv_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
+                                 const void *K, const void *V, const int32_t *idxT, const int64_t *col,
+                                 const float *lse, const float *delta, const void *dO, void *dK, void *dV,
+                                 const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st)
+{
+    DSV_DISPATCH_TD(bwd_dkdv_split_t, p, tabs, n_tabs, Q, K, V, idxT, col, lse, delta, dO, dK, dV, pl, w, st);
 }
 
 }  // namespace dsv

@@ -30,6 +30,21 @@ def _run_stage2(case, idx_rows, sorted_index=False):
     O, lse = dsv.sparse_attn_fwd(p, d["Q"], d["K"], d["V"], flat)
     dQ, dK, dV = dsv.sparse_attn_bwd(p, d["Q"], d["K"], d["V"], flat, O, lse, d["dO"])
     torch.cuda.synchronize()
+    if sorted_index:
+        # the same backward with an ascending transposed index supplied: both steps L2-blocked.
+        # The reference transpose is a stable sort of the pairs by key (plain numpy, no library code).
+        idx_t, col = [], []
+        for h, rows in enumerate(idx_rows):
+            L, k = rows.shape
+            order = np.argsort(rows.reshape(-1), kind="stable")
+            idx_t.append((order // k).astype(np.int32))
+            col.append(np.concatenate([[0], np.cumsum(np.bincount(rows.reshape(-1), minlength=L))]).astype(np.int64))
+        idx_t = torch.from_numpy(np.concatenate(idx_t)).cuda()
+        col = torch.from_numpy(np.stack(col)).cuda()
+        dQ2, dK2, dV2 = dsv.sparse_attn_bwd_t(p, d["Q"], d["K"], d["V"], flat, idx_t, col, O, lse, d["dO"])
+        torch.cuda.synchronize()
+        assert torch.equal(dQ2, dQ)
+        return O, lse, dQ2, dK2, dV2
     return O, lse, dQ, dK, dV
 
 
