@@ -135,7 +135,7 @@ def main():
         calls = (
             lambda: dsv.lowrank_topk_t(p, g["Q"], g["K"], Wq, Wk, idx=idx, idx_t=idx_t, col_ptr=col_ptr, workspace=ws1),
             lambda: dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx, O=O, lse=lse, workspace=wsf),
-            lambda: dsv.sparse_attn_bwd_dq(p, g["Q"], g["K"], g["V"], idx, lse, g["dO"], dQ=dQ, delta=delta, workspace=wsf),
+            lambda: dsv.sparse_attn_bwd_dq(p, g["Q"], g["K"], g["V"], idx, O, lse, g["dO"], dQ=dQ, delta=delta, workspace=wsf),
             lambda: dsv.sparse_attn_bwd_dkdv(p, g["Q"], g["K"], g["V"], idx_t, col_ptr, lse, delta, g["dO"], dK=dK, dV=dV,
                                              workspace=wsf),
         )

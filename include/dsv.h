@@ -132,8 +132,9 @@ DSV_API dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, cons
  *     dQ_i = scale sum_j dS_ij k_j;
  *     dK_j = scale sum_{i: j in row i} dS_ij q_i;   dV_j = sum_{i: j in row i} p_ij dO_i.
  * Keys no query selected get zeros.  dQ, dK, dV are written in `dtype` (accumulated in fp32).
- * O is accepted for interface symmetry and not read: Delta is formed from the per-pair terms in
- * fp32 rather than from the storage-rounded O.  The workspace holds Delta, the transposed index
+ * Delta is formed from the per-pair terms in fp32 rather than from the storage-rounded O, whose
+ * rounding alone would cost more than the output tolerance; O only serves as a centring value
+ * (dO . O is within rounding of Delta) that keeps the accumulated weights small.  The workspace holds Delta, the transposed index
  * (as large as idx) and its column pointers. */
 DSV_API size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p);
 DSV_API dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *K, const void *V,
@@ -173,7 +174,7 @@ DSV_API dsv_status dsv_sparse_attn_bwd_t(const dsv_problem *p, const void *Q, co
  * with it, segment pointers and per-range partial sums. */
 DSV_API size_t dsv_sparse_attn_bwd_dq_workspace(const dsv_problem *p);
 DSV_API dsv_status dsv_sparse_attn_bwd_dq(const dsv_problem *p, const void *Q, const void *K, const void *V,
-                                          const int32_t *idx, const float *lse, const void *dO,
+                                          const int32_t *idx, const void *O, const float *lse, const void *dO,
                                           void *dQ, float *delta,
                                           void *workspace, size_t ws_bytes, void *hip_stream);
 DSV_API size_t dsv_idx_transpose_workspace(const dsv_problem *p);

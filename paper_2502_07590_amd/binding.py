@@ -78,7 +78,7 @@ def load_library():
     lib.dsv_sparse_attn_bwd.restype = ctypes.c_int
     lib.dsv_sparse_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_bwd_dq.restype = ctypes.c_int
-    lib.dsv_sparse_attn_bwd_dq.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dsv_sparse_attn_bwd_dq.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_bwd_t.restype = ctypes.c_int
     lib.dsv_sparse_attn_bwd_t.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_idx_transpose.restype = ctypes.c_int
@@ -225,13 +225,14 @@ def sparse_attn_bwd_dq_workspace(p: Problem) -> int:
     return int(load_library().dsv_sparse_attn_bwd_dq_workspace(p.c))
 
 
-def sparse_attn_bwd_dq(p: Problem, Q, K, V, idx, lse, dO, dQ=None, delta=None, workspace=None, stream=None):
+def sparse_attn_bwd_dq(p: Problem, Q, K, V, idx, O, lse, dO, dQ=None, delta=None, workspace=None, stream=None):
     lib = load_library()
     dQ = torch.empty_like(Q) if dQ is None else dQ
     delta = torch.empty((p.B, p.H, p.L), dtype=torch.float32, device=Q.device) if delta is None else delta
     ws, nbytes = _workspace(sparse_attn_bwd_dq_workspace(p), Q.device, workspace)
-    _check(lib.dsv_sparse_attn_bwd_dq(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(lse), _ptr(dO), _ptr(dQ),
-                                      _ptr(delta), _ptr(ws), nbytes, _stream(stream)), "dsv_sparse_attn_bwd_dq")
+    _check(lib.dsv_sparse_attn_bwd_dq(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(lse), _ptr(dO),
+                                      _ptr(dQ), _ptr(delta), _ptr(ws), nbytes, _stream(stream)),
+           "dsv_sparse_attn_bwd_dq")
     return dQ, delta
 
 

@@ -123,7 +123,7 @@ FwdLayout fwd_layout(const dsv_problem &p)
 struct StepLayout {
     bool split;
     SplitPlan plan;
-    size_t seg, pa, pb, pdelta, total;
+    size_t seg, pa, pb, pdelta, hist, order, total;
 };
 
 StepLayout step_layout(const dsv_problem &p)
@@ -132,12 +132,15 @@ StepLayout step_layout(const dsv_problem &p)
     w.plan = make_split_plan(p);
     w.split = use_split(p, w.plan);
     if (!w.split) return w;
-    const size_t rows = (size_t)p.B * p.H * p.L;
+    const size_t nbh = (size_t)p.B * p.H;
+    const size_t rows = nbh * p.L;
     size_t o = 0;
     w.seg = o; o = align_up(o + rows * (w.plan.S + 1) * 4, 256);
     w.pa = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
     w.pb = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
     w.pdelta = o; o = align_up(o + rows * w.plan.S * 4, 256);
+    w.hist = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 4, 256);
+    w.order = o; o = align_up(o + rows * 4, 256);
     w.total = o;
     return w;
 }
@@ -149,6 +152,8 @@ BwdSplitWorkspace step_buffers(char *ws, const StepLayout &w)
     b.pa = reinterpret_cast<float *>(ws + w.pa);
     b.pb = reinterpret_cast<float *>(ws + w.pb);
     b.pdelta = reinterpret_cast<float *>(ws + w.pdelta);
+    b.hist = reinterpret_cast<int32_t *>(ws + w.hist);
+    b.order = reinterpret_cast<int32_t *>(ws + w.order);
     return b;
 }
 
@@ -295,19 +300,19 @@ size_t dsv_sparse_attn_bwd_dq_workspace(const dsv_problem *p)
 }
 
 dsv_status dsv_sparse_attn_bwd_dq(const dsv_problem *p, const void *Q, const void *K, const void *V,
-                                  const int32_t *idx, const float *lse, const void *dO, void *dQ, float *delta,
-                                  void *workspace, size_t ws_bytes, void *hip_stream)
+                                  const int32_t *idx, const void *O, const float *lse, const void *dO, void *dQ,
+                                  float *delta, void *workspace, size_t ws_bytes, void *hip_stream)
 {
     dsv_status st = check_problem(p, false);
     if (st != DSV_OK) return st;
-    if (!ok_ptrs({Q, K, V, idx, lse, dO, dQ, delta})) return DSV_EINVAL;
+    if (!ok_ptrs({Q, K, V, idx, O, lse, dO, dQ, delta})) return DSV_EINVAL;
     const StepLayout w = step_layout(*p);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
     const std::vector<HeadTable> tabs = make_tables(*p);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (!w.split) return launch_bwd_dq(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, lse, dO, dQ, delta, stream);
-    return launch_bwd_dq_split(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, lse, dO, dQ, delta, w.plan,
+    if (!w.split) return launch_bwd_dq(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse, dO, dQ, delta, stream);
+    return launch_bwd_dq_split(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse, dO, dQ, delta, w.plan,
                                step_buffers(static_cast<char *>(workspace), w), stream);
 }
 
@@ -377,7 +382,7 @@ dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *
     float *delta = reinterpret_cast<float *>(ws + w.delta);
     int64_t *col = reinterpret_cast<int64_t *>(ws + w.col);
     int32_t *idx_t = reinterpret_cast<int32_t *>(ws + w.idxT);
-    st = dsv_sparse_attn_bwd_dq(p, Q, K, V, idx, lse, dO, dQ, delta, ws + w.step, w.step_bytes, hip_stream);
+    st = dsv_sparse_attn_bwd_dq(p, Q, K, V, idx, O, lse, dO, dQ, delta, ws + w.step, w.step_bytes, hip_stream);
     if (st != DSV_OK) return st;
     st = dsv_idx_transpose(p, idx, idx_t, col, ws + w.cnt, w.cnt_bytes, hip_stream);
     if (st != DSV_OK) return st;
@@ -406,7 +411,7 @@ dsv_status dsv_sparse_attn_bwd_t(const dsv_problem *p, const void *Q, const void
     if (st != DSV_OK) return st;
     char *ws = static_cast<char *>(workspace);
     float *delta = reinterpret_cast<float *>(ws + w.delta);
-    st = dsv_sparse_attn_bwd_dq(p, Q, K, V, idx, lse, dO, dQ, delta, ws + w.step, w.step_bytes, hip_stream);
+    st = dsv_sparse_attn_bwd_dq(p, Q, K, V, idx, O, lse, dO, dQ, delta, ws + w.step, w.step_bytes, hip_stream);
     if (st != DSV_OK) return st;
     return dsv_sparse_attn_bwd_dkdv(p, Q, K, V, idx_t, col_ptr, lse, delta, dO, dK, dV, ws + w.step, w.step_bytes,
                                     hip_stream);

@@ -192,10 +192,12 @@ struct BwdSplitWorkspace {
     float *pa;      // [B*H, L, S, d]
     float *pb;      // [B*H, L, S, d]
     float *pdelta;  // [B*H, L, S]   (dq step only)
+    int32_t *hist;  // [B*H, L+1]    keys per list length (dkdv step only)
+    int32_t *order; // [B*H, L]      keys by descending list length (dkdv step only)
 };
 dsv_status launch_bwd_dq_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
-                               const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ,
-                               float *delta, const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st);
+                               const void *V, const int32_t *idx, const void *O, const float *lse, const void *dO,
+                               void *dQ, float *delta, const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st);
 dsv_status launch_bwd_dkdv_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
                                  const void *K, const void *V, const int32_t *idxT, const int64_t *col,
                                  const float *lse, const float *delta, const void *dO, void *dK, void *dV,
@@ -217,8 +219,8 @@ dsv_status launch_select(const dsv_problem &p, const HeadTable *tabs, int n_tabs
 dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                              const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st);
 dsv_status launch_bwd_dq(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
-                         const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ, float *delta,
-                         hipStream_t st);
+                         const void *V, const int32_t *idx, const void *O, const float *lse, const void *dO, void *dQ,
+                         float *delta, hipStream_t st);
 dsv_status launch_bwd_dkdv(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                            const void *V, const int32_t *idxT, const int64_t *col, const float *lse, const float *delta,
                            const void *dO, void *dK, void *dV, hipStream_t st);

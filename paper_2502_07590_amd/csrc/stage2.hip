@@ -1,20 +1,14 @@
-// Stage 2: exact softmax attention over the selected KV only, forward and backward
-// (paper Sec. "Sparse Attention with Query Grouping", per-query form; attention formula of
-// Sec. "Various Self-Attention Paradigms").
+// Stage 2, order-agnostic form: exact softmax attention over the selected KV only, forward and
+// backward (paper Sec. "Sparse Attention with Query Grouping", per-query form; attention formula
+// of Sec. "Various Self-Attention Paradigms"), for index rows in ANY order; also the generic
+// index transposition.  The inner loops live in stage2_core.h.
 //
-// Work layout shared by the kernels here: a group of 16 lanes (one DPP row) owns one query row;
-// lane s of the group holds channels [s*CH, (s+1)*CH) of every [d]-vector, CH = d/16, so one
-// wave-wide load instruction fetches four whole K (or V) rows as four contiguous segments.
-// Dot products are reduced inside the row with DPP rotations.  A wave handles 4 queries, a block
-// 16 consecutive queries of one head.
+// A wave handles 4 rows (one per 16-lane group), a block 16 consecutive rows of one head.
 #include <algorithm>
 
-#include "common.h"
+#include "stage2_core.h"
 
 namespace dsv {
-
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 
 // ------------------------------------------------------------------------------------ forward
 template <typename T, int D>
@@ -24,8 +18,6 @@ __global__ __launch_bounds__(256) void sparse_fwd_kernel(const T *__restrict__ Q
                                                          float scale, HeadTable tab)
 {
     constexpr int CH = D / 16;
-    constexpr int U = 4;  // keys in flight per group
-    typedef RowChunk<T, CH> Chunk;
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
@@ -35,83 +27,45 @@ __global__ __launch_bounds__(256) void sparse_fwd_kernel(const T *__restrict__ Q
     const bool live = iq < L;
     const int64_t i = live ? iq : L - 1;
     const int64_t head_base = (int64_t)bh * L * D;
-    const T *Kb = K + head_base + s * CH;
-    const T *Vb = V + head_base + s * CH;
     const int32_t *row = idx + tab.off[slot] + i * k;
 
-    const Chunk q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
-    const float c2 = scale * kLog2e;  // logits are kept in the log2 domain
+    const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
+    FwdState<CH> st;
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) st.acc[c] = 0.f;
+    fwd_sweep<T, D>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e);
 
-    float m = -INFINITY, l = 0.f;
-    float acc[CH];
+    const float inv = 1.f / st.l;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) acc[c] = 0.f;
-
-    for (int t0 = 0; t0 < k; t0 += U) {
-        int j[U];
-        Chunk kc[U], vc[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) j[u] = row[min(t0 + u, k - 1)];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            kc[u] = load_chunk<T, CH>(Kb + (int64_t)j[u] * D);
-            vc[u] = load_chunk<T, CH>(Vb + (int64_t)j[u] * D);
-        }
-        float sc[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) sc[u] = dot_chunk<T, CH>(q, kc[u]);
-#pragma unroll
-        for (int u = 0; u < U; ++u) sc[u] = row16_sum(sc[u]) * c2;
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (t0 + u >= k) sc[u] = -INFINITY;
-        float mnew = m;
-#pragma unroll
-        for (int u = 0; u < U; ++u) mnew = fmaxf(mnew, sc[u]);
-        const float corr = exp2f(m - mnew);  // first block: exp2(-inf) = 0
-        m = mnew;
-        l *= corr;
-#pragma unroll
-        for (int c = 0; c < CH; ++c) acc[c] *= corr;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float pu = exp2f(sc[u] - mnew);
-            l += pu;
-            float vf[CH];
-            unpack_chunk<T, CH>(vc[u], vf);
-#pragma unroll
-            for (int c = 0; c < CH; ++c) acc[c] = fmaf(pu, vf[c], acc[c]);
-        }
-    }
-    const float inv = 1.f / l;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) acc[c] *= inv;
+    for (int c = 0; c < CH; ++c) st.acc[c] *= inv;
     if (live) {
-        store_chunk<T, CH>(O + head_base + i * D + s * CH, acc);
-        if (s == 0) lse[(int64_t)bh * L + i] = (m + log2f(l)) * kLn2;
+        store_chunk<T, CH>(O + head_base + i * D + s * CH, st.acc);
+        if (s == 0) lse[(int64_t)bh * L + i] = (st.m + log2f(st.l)) * kLn2;
     }
 }
 
 // ------------------------------------------------------------------------------------ backward
-// The backward runs as two gather passes with no floating-point atomics:
+// Two gather passes with no floating-point atomics:
 //   dq pass    query-major over idx: dQ and the row term Delta_i;
 //   dkdv pass  key-major over the transposed index (for each key, the queries that selected it):
 //              dK and dV, each output row owned by one lane group.
-// Delta_i = dO_i . O_i equals sum_j p_ij (dO_i . v_j) over the selected keys; the dq pass forms it
-// from that sum in fp32 instead of from the stored (storage-type rounded) O, and expands
-//   dQ_i = scale * ( sum_j p_ij dP_ij k_j  -  Delta_i * sum_j p_ij k_j ),   dP_ij = dO_i . v_j,
-// so one sweep over the row yields both.  Delta is kept for the dkdv pass.
+// Delta_i = dO_i . O_i equals sum_j p_ij dP_ij over the selected keys (dP_ij = dO_i . v_j); the dq
+// pass forms it from that sum in fp32, because the stored O is rounded to the storage type and the
+// error of dO . O_stored alone would exceed the output tolerance.  One sweep yields both Delta and dQ:
+// with D0 = dO_i . O_stored as a centring value,
+//   dQ_i = scale * ( sum_j p_ij (dP_ij - D0) k_j  -  (Delta_i - D0) * sum_j p_ij k_j ).
+// Delta is kept for the dkdv pass.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                             const T *__restrict__ V,
-                                                            const int32_t *__restrict__ idx,
+                                                            const int32_t *__restrict__ idx, const T *__restrict__ O,
                                                             const float *__restrict__ lse, const T *__restrict__ dO,
                                                             T *__restrict__ dQ, float *__restrict__ delta_out, int L,
                                                             float scale, HeadTable tab)
 {
     constexpr int CH = D / 16;
-    constexpr int U = 2;
-    typedef RowChunk<T, CH> Chunk;
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
@@ -121,52 +75,66 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict_
     const bool live = iq < L;
     const int64_t i = live ? iq : L - 1;
     const int64_t head_base = (int64_t)bh * L * D;
-    const T *Kb = K + head_base + s * CH;
-    const T *Vb = V + head_base + s * CH;
     const int32_t *row = idx + tab.off[slot] + i * k;
 
-    const Chunk q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
-    const Chunk go = load_chunk<T, CH>(dO + head_base + i * D + s * CH);
-    const float c2 = scale * kLog2e;
-    const float lse2 = lse[(int64_t)bh * L + i] * kLog2e;
-
-    float a[CH], bsum[CH];
+    const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
+    const RowChunk<T, CH> go = load_chunk<T, CH>(dO + head_base + i * D + s * CH);
+    const RowChunk<T, CH> o = load_chunk<T, CH>(O + head_base + i * D + s * CH);
+    const float delta0 = row16_sum(dot_chunk<T, CH>(go, o));
+    DqState<CH> st;
+    st.delta = 0.f;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) { a[c] = 0.f; bsum[c] = 0.f; }
-    float delta = 0.f;
-
-    for (int t0 = 0; t0 < k; t0 += U) {
-        int j[U];
-        Chunk kc[U], vc[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) j[u] = row[min(t0 + u, k - 1)];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            kc[u] = load_chunk<T, CH>(Kb + (int64_t)j[u] * D);
-            vc[u] = load_chunk<T, CH>(Vb + (int64_t)j[u] * D);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float sc = row16_sum(dot_chunk<T, CH>(q, kc[u]));
-            const float dp = row16_sum(dot_chunk<T, CH>(go, vc[u]));
-            const float p = (t0 + u < k) ? exp2f(sc * c2 - lse2) : 0.f;
-            const float pdp = p * dp;
-            delta += pdp;
-            float kf[CH];
-            unpack_chunk<T, CH>(kc[u], kf);
-#pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                a[c] = fmaf(pdp, kf[c], a[c]);
-                bsum[c] = fmaf(p, kf[c], bsum[c]);
-            }
-        }
-    }
+    for (int c = 0; c < CH; ++c) { st.a[c] = 0.f; st.b[c] = 0.f; }
+    dq_sweep<T, D>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e,
+                   lse[(int64_t)bh * L + i] * kLog2e, delta0);
     if (live) {
         float dq[CH];
 #pragma unroll
-        for (int c = 0; c < CH; ++c) dq[c] = scale * (a[c] - delta * bsum[c]);
+        for (int c = 0; c < CH; ++c) dq[c] = scale * (st.a[c] - (st.delta - delta0) * st.b[c]);
         store_chunk<T, CH>(dQ + head_base + i * D + s * CH, dq);
-        if (s == 0) delta_out[(int64_t)bh * L + i] = delta;
+        if (s == 0) delta_out[(int64_t)bh * L + i] = st.delta;
+    }
+}
+
+// dkdv pass: a group of 16 lanes owns key j and walks the queries that selected it.
+//   dK_j = scale * sum_i dS_ij q_i,  dV_j = sum_i p_ij dO_i,  dS_ij = p_ij (dO_i . v_j - Delta_i).
+// Keys with an empty list get zeros; every output row is written exactly once.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void sparse_bwd_dkdv_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                              const T *__restrict__ V,
+                                                              const int32_t *__restrict__ idxT,
+                                                              const int64_t *__restrict__ col,
+                                                              const float *__restrict__ lse,
+                                                              const float *__restrict__ delta,
+                                                              const T *__restrict__ dO, T *__restrict__ dK,
+                                                              T *__restrict__ dV, int L, float scale, HeadTable tab)
+{
+    constexpr int CH = D / 16;
+    const int slot = blockIdx.y;
+    const int bh = tab.bh[slot];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = lane >> 4, s = lane & 15;
+    const int64_t jq = (int64_t)blockIdx.x * 16 + wave * 4 + grp;
+    const bool live = jq < L;
+    const int64_t j = live ? jq : L - 1;
+    const int64_t head_base = (int64_t)bh * L * D;
+    const int64_t *cp = col + (int64_t)bh * (L + 1);
+    const int64_t beg = cp[j];
+    const int n = live ? (int)(cp[j + 1] - beg) : 0;
+    const int32_t *list = idxT + tab.off[slot] + beg;
+
+    const RowChunk<T, CH> kc = load_chunk<T, CH>(K + head_base + j * D + s * CH);
+    const RowChunk<T, CH> vc = load_chunk<T, CH>(V + head_base + j * D + s * CH);
+    DkdvState<CH> st;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) { st.dk[c] = 0.f; st.dv[c] = 0.f; }
+    dkdv_sweep<T, D>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L, delta + (int64_t)bh * L,
+                     (uint32_t)(s * CH), list, 0, n, scale * kLog2e);
+    if (live) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) st.dk[c] *= scale;
+        store_chunk<T, CH>(dK + head_base + j * D + s * CH, st.dk);
+        store_chunk<T, CH>(dV + head_base + j * D + s * CH, st.dv);
     }
 }
 
@@ -239,88 +207,6 @@ __global__ __launch_bounds__(256) void tindex_fill_kernel(const int32_t *__restr
     }
 }
 
-// dkdv pass: a group of 16 lanes owns key j and walks the queries that selected it.
-//   dK_j = scale * sum_i dS_ij q_i,  dV_j = sum_i p_ij dO_i,  dS_ij = p_ij (dO_i . v_j - Delta_i).
-// Keys with an empty list get zeros; every output row is written exactly once.
-template <typename T, int D>
-__global__ __launch_bounds__(256) void sparse_bwd_dkdv_kernel(const T *__restrict__ Q, const T *__restrict__ K,
-                                                              const T *__restrict__ V,
-                                                              const int32_t *__restrict__ idxT,
-                                                              const int64_t *__restrict__ col,
-                                                              const float *__restrict__ lse,
-                                                              const float *__restrict__ delta,
-                                                              const T *__restrict__ dO, T *__restrict__ dK,
-                                                              T *__restrict__ dV, int L, float scale, HeadTable tab)
-{
-    constexpr int CH = D / 16;
-    constexpr int U = 2;
-    typedef RowChunk<T, CH> Chunk;
-    const int slot = blockIdx.y;
-    const int bh = tab.bh[slot];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane >> 4, s = lane & 15;
-    const int64_t jq = (int64_t)blockIdx.x * 16 + wave * 4 + grp;
-    const bool live = jq < L;
-    const int64_t j = live ? jq : L - 1;
-    const int64_t head_base = (int64_t)bh * L * D;
-    const T *Qb = Q + head_base + s * CH;
-    const T *Gb = dO + head_base + s * CH;
-    const float *lse_b = lse + (int64_t)bh * L;
-    const float *delta_b = delta + (int64_t)bh * L;
-    const int64_t *cp = col + (int64_t)bh * (L + 1);
-    const int64_t beg = cp[j];
-    const int n = live ? (int)(cp[j + 1] - beg) : 0;
-    const int32_t *list = idxT + tab.off[slot] + beg;
-
-    const Chunk kc = load_chunk<T, CH>(K + head_base + j * D + s * CH);
-    const Chunk vc = load_chunk<T, CH>(V + head_base + j * D + s * CH);
-    const float c2 = scale * kLog2e;
-
-    float dk[CH], dv[CH];
-#pragma unroll
-    for (int c = 0; c < CH; ++c) { dk[c] = 0.f; dv[c] = 0.f; }
-
-    // every group of the wave runs the longest list's trip count; shorter lists idle with p = 0
-    int nmax = n;
-    nmax = max(nmax, __shfl_xor(nmax, 16));
-    nmax = max(nmax, __shfl_xor(nmax, 32));
-    for (int t0 = 0; t0 < nmax; t0 += U) {
-        int iq[U];
-        Chunk qc[U], gc[U];
-        float l2[U], dl[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) iq[u] = (t0 + u < n) ? list[t0 + u] : (int)j;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            qc[u] = load_chunk<T, CH>(Qb + (int64_t)iq[u] * D);
-            gc[u] = load_chunk<T, CH>(Gb + (int64_t)iq[u] * D);
-            l2[u] = lse_b[iq[u]] * kLog2e;
-            dl[u] = delta_b[iq[u]];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float sc = row16_sum(dot_chunk<T, CH>(qc[u], kc));
-            const float dp = row16_sum(dot_chunk<T, CH>(gc[u], vc));
-            const float p = (t0 + u < n) ? exp2f(sc * c2 - l2[u]) : 0.f;
-            const float ds = p * (dp - dl[u]);
-            float qf[CH], gf[CH];
-            unpack_chunk<T, CH>(qc[u], qf);
-            unpack_chunk<T, CH>(gc[u], gf);
-#pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                dk[c] = fmaf(ds, qf[c], dk[c]);
-                dv[c] = fmaf(p, gf[c], dv[c]);
-            }
-        }
-    }
-    if (live) {
-#pragma unroll
-        for (int c = 0; c < CH; ++c) dk[c] *= scale;
-        store_chunk<T, CH>(dK + head_base + j * D + s * CH, dk);
-        store_chunk<T, CH>(dV + head_base + j * D + s * CH, dv);
-    }
-}
-
 __global__ __launch_bounds__(256) void fill_zero_i32_kernel(int4 *__restrict__ p, int64_t n4)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -341,28 +227,15 @@ static dsv_status fwd_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs,
     return DSV_OK;
 }
 
-dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
-                             const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st)
-{
-    if (p.dtype == DSV_BF16) {
-        if (p.d == 64) return fwd_t<bf16_t, 64>(p, tabs, n_tabs, Q, K, V, idx, O, lse, st);
-        if (p.d == 128) return fwd_t<bf16_t, 128>(p, tabs, n_tabs, Q, K, V, idx, O, lse, st);
-    } else if (p.dtype == DSV_F32) {
-        if (p.d == 64) return fwd_t<float, 64>(p, tabs, n_tabs, Q, K, V, idx, O, lse, st);
-        if (p.d == 128) return fwd_t<float, 128>(p, tabs, n_tabs, Q, K, V, idx, O, lse, st);
-    }
-    return DSV_EUNSUPPORTED;
-}
-
 template <typename T, int D>
 static dsv_status bwd_dq_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
-                           const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ,
-                           float *delta, hipStream_t st)
+                           const void *V, const int32_t *idx, const void *O, const float *lse, const void *dO,
+                           void *dQ, float *delta, hipStream_t st)
 {
     for (int t = 0; t < n_tabs; ++t) {
         dim3 qgrid((p.L + 15) / 16, tabs[t].n);
         hipLaunchKernelGGL((sparse_bwd_dq_kernel<T, D>), qgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
-                           (const T *)V, idx, lse, (const T *)dO, (T *)dQ, delta, p.L, p.scale, tabs[t]);
+                           (const T *)V, idx, (const T *)O, lse, (const T *)dO, (T *)dQ, delta, p.L, p.scale, tabs[t]);
         DSV_LAUNCH_CHECK();
     }
     return DSV_OK;
@@ -394,11 +267,17 @@ static dsv_status bwd_dkdv_t(const dsv_problem &p, const HeadTable *tabs, int n_
         return DSV_EUNSUPPORTED;                                        \
     } while (0)
 
-dsv_status launch_bwd_dq(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
-                         const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ, float *delta,
-                         hipStream_t st)
+dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                             const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st)
 {
-    DSV_DISPATCH_TD(bwd_dq_t, p, tabs, n_tabs, Q, K, V, idx, lse, dO, dQ, delta, st);
+    DSV_DISPATCH_TD(fwd_t, p, tabs, n_tabs, Q, K, V, idx, O, lse, st);
+}
+
+dsv_status launch_bwd_dq(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                         const void *V, const int32_t *idx, const void *O, const float *lse, const void *dO, void *dQ,
+                         float *delta, hipStream_t st)
+{
+    DSV_DISPATCH_TD(bwd_dq_t, p, tabs, n_tabs, Q, K, V, idx, O, lse, dO, dQ, delta, st);
 }
 
 dsv_status launch_bwd_dkdv(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,

@@ -1,0 +1,310 @@
+// Inner loops of stage 2, shared by the plain gather kernels (stage2.hip) and the L2-blocked
+// kernels (stage2_split.hip).
+//
+// Lane layout: a group of 16 lanes (one DPP row) owns one output row; lane s of the group holds
+// channels [s*CH, (s+1)*CH) of every [d]-vector, CH = d/16.  One wave-wide 16-byte load per lane
+// fetches four whole gathered rows (one per group) as four contiguous 256-byte segments.
+//
+// Each sweep walks positions [tb, te) of one index row (or key-major list):
+//   fwd_sweep   online softmax over the segment: running max m (log2 domain), l, acc = sum p v
+//   dq_sweep    C = sum p (dP - D0) k,  B = sum p k,  Delta = sum p dP   (dP = dO . v; D0 = dO . O from
+//               the stored O: a centring value within rounding of Delta, so that the weights of C are
+//               the small, centred dS and survive bf16 rounding; dQ = scale (C - (Delta - D0) B))
+//   dkdv_sweep  dK = sum dS q,   dV = sum p dO                            (dS = p (dP - Delta_i))
+//
+// bf16 rows: dots use v_dot2_f32_bf16 on the packed words; the accumulations "acc += w * row"
+// take two gathered rows at a time, interleave their words with v_perm so that one packed word
+// holds the same channel of both rows, and issue one v_dot2_f32_bf16 per channel with the two
+// weights packed as bf16 -- half the VALU work of unpack + FMA.  The probabilities p are thereby
+// rounded to bf16 (relative 2^-9, as any bf16 flash-attention kernel rounds P before its second
+// GEMM); the signed, possibly large dS weights go in as two bf16 words (head + tail, 16
+// significant bits, two dot2 per channel).  Accumulators stay fp32.  fp32 rows use plain FMAs.
+#pragma once
+
+#include "common.h"
+
+namespace dsv {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2_t;
+
+// 2^x by the bare hardware instruction (denormal results flush to zero; arguments here are <= 0
+// up to rounding, results are weights in [0, 1]).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    floatx2_t f = {lo, hi};
+    bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// acc[c] += w_a * a[c] + w_b * b[c] for this lane's CH channels; wab = (bf16 w_a, bf16 w_b) packed
+// (bf16 rows), or fa / fb the fp32 weights (fp32 rows).
+template <typename T, int CH>
+__device__ __forceinline__ void axpy_pair(float (&acc)[CH], const RowChunk<T, CH> &a, const RowChunk<T, CH> &b,
+                                          float fa, float fb, uint32_t wab)
+{
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            acc[c] = fmaf(fa, __uint_as_float(a.w[c]), acc[c]);
+            acc[c] = fmaf(fb, __uint_as_float(b.w[c]), acc[c]);
+        }
+    } else {
+        const bf16x2_t w = __builtin_bit_cast(bf16x2_t, wab);
+#pragma unroll
+        for (int i = 0; i < CH / 2; ++i) {
+            const uint32_t lo = __builtin_amdgcn_perm(b.w[i], a.w[i], 0x05040100u);  // (a.ch[2i],   b.ch[2i])
+            const uint32_t hi = __builtin_amdgcn_perm(b.w[i], a.w[i], 0x07060302u);  // (a.ch[2i+1], b.ch[2i+1])
+            acc[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, lo), w, acc[2 * i], false);
+            acc[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, hi), w, acc[2 * i + 1], false);
+        }
+    }
+}
+
+// A weight pair as two packed bf16 words whose sum carries 16 significant bits: w = head + tail.
+// Used where the weights are signed and large (the centred dS terms): a single bf16 rounding of a
+// weight of magnitude ~10 is an absolute error of ~0.02 in the accumulated gradient.
+struct SplitWeights {
+    uint32_t head, tail;
+};
+__device__ __forceinline__ SplitWeights split_weights(float wa, float wb)
+{
+    SplitWeights s;
+    s.head = pack_bf16x2(wa, wb);
+    s.tail = pack_bf16x2(wa - __uint_as_float(s.head << 16), wb - __uint_as_float(s.head & 0xFFFF0000u));
+    return s;
+}
+
+// acc[c] += w_a * a[c] + w_b * b[c] with 16-bit weights (bf16 rows) or fp32 weights (fp32 rows).
+template <typename T, int CH>
+__device__ __forceinline__ void axpy_pair_precise(float (&acc)[CH], const RowChunk<T, CH> &a,
+                                                  const RowChunk<T, CH> &b, float fa, float fb)
+{
+    if constexpr (sizeof(T) == 4) {
+        axpy_pair<T, CH>(acc, a, b, fa, fb, 0u);
+    } else {
+        const SplitWeights w = split_weights(fa, fb);
+        const bf16x2_t wh = __builtin_bit_cast(bf16x2_t, w.head), wt = __builtin_bit_cast(bf16x2_t, w.tail);
+#pragma unroll
+        for (int i = 0; i < CH / 2; ++i) {
+            const bf16x2_t lo = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(b.w[i], a.w[i], 0x05040100u));
+            const bf16x2_t hi = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(b.w[i], a.w[i], 0x07060302u));
+            acc[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(lo, wt, acc[2 * i], false);
+            acc[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(lo, wh, acc[2 * i], false);
+            acc[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(hi, wt, acc[2 * i + 1], false);
+            acc[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(hi, wh, acc[2 * i + 1], false);
+        }
+    }
+}
+
+// Two accumulators fed by the same pair of rows with different weights (dq sweep: C and B); the
+// first weight pair (signed, centred dS terms) is applied with 16-bit weights, the second (the
+// probabilities) with bf16 weights.
+template <typename T, int CH>
+__device__ __forceinline__ void axpy_pair2(float (&acc1)[CH], float (&acc2)[CH], const RowChunk<T, CH> &a,
+                                           const RowChunk<T, CH> &b, float f1a, float f1b, float f2a, float f2b)
+{
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const float av = __uint_as_float(a.w[c]), bv = __uint_as_float(b.w[c]);
+            acc1[c] = fmaf(f1a, av, acc1[c]);
+            acc1[c] = fmaf(f1b, bv, acc1[c]);
+            acc2[c] = fmaf(f2a, av, acc2[c]);
+            acc2[c] = fmaf(f2b, bv, acc2[c]);
+        }
+    } else {
+        const SplitWeights w1s = split_weights(f1a, f1b);
+        const bf16x2_t w1 = __builtin_bit_cast(bf16x2_t, w1s.head), w1t = __builtin_bit_cast(bf16x2_t, w1s.tail);
+        const bf16x2_t w2 = __builtin_bit_cast(bf16x2_t, pack_bf16x2(f2a, f2b));
+#pragma unroll
+        for (int i = 0; i < CH / 2; ++i) {
+            const bf16x2_t lo = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(b.w[i], a.w[i], 0x05040100u));
+            const bf16x2_t hi = __builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(b.w[i], a.w[i], 0x07060302u));
+            acc1[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(lo, w1t, acc1[2 * i], false);
+            acc1[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(lo, w1, acc1[2 * i], false);
+            acc1[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(hi, w1t, acc1[2 * i + 1], false);
+            acc1[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(hi, w1, acc1[2 * i + 1], false);
+            acc2[2 * i] = __builtin_amdgcn_fdot2_f32_bf16(lo, w2, acc2[2 * i], false);
+            acc2[2 * i + 1] = __builtin_amdgcn_fdot2_f32_bf16(hi, w2, acc2[2 * i + 1], false);
+        }
+    }
+}
+
+// Row chunk of a gathered row: base is the head's [L, d] matrix (uniform across the wave), the
+// per-lane part is a 32-bit element offset (row * D + lane channel offset), so the load can use a
+// scalar base with a 32-bit vector offset.
+template <typename T, int CH>
+__device__ __forceinline__ RowChunk<T, CH> gather_chunk(const T *__restrict__ head, uint32_t row, uint32_t D,
+                                                        uint32_t lane_off)
+{
+    const uint32_t byte_off = (row * D + lane_off) * (uint32_t)sizeof(T);  // < 2^32: a head's matrix is < 4 GB
+    return load_chunk<T, CH>(reinterpret_cast<const T *>(reinterpret_cast<const char *>(head) + byte_off));
+}
+
+// ------------------------------------------------------------------------------------ forward sweep
+template <int CH> struct FwdState {
+    float m, l;
+    float acc[CH];
+};
+
+template <typename T, int D, bool TAIL>
+__device__ __forceinline__ void fwd_step(FwdState<D / 16> &st, const RowChunk<T, D / 16> &q, const T *__restrict__ Kh,
+                                         const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
+                                         int t0, int te, float c2)
+{
+    constexpr int CH = D / 16;
+    constexpr int U = 4;
+    typedef RowChunk<T, CH> Chunk;
+    int j[U];
+    Chunk kc[U], vc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) j[u] = row[TAIL ? min(t0 + u, te - 1) : t0 + u];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        kc[u] = gather_chunk<T, CH>(Kh, (uint32_t)j[u], D, lane_off);
+        vc[u] = gather_chunk<T, CH>(Vh, (uint32_t)j[u], D, lane_off);
+    }
+    float sc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) sc[u] = dot_chunk<T, CH>(q, kc[u]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) sc[u] = row16_sum(sc[u]) * c2;
+    if (TAIL) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (t0 + u >= te) sc[u] = -INFINITY;
+    }
+    const float mblk = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+    if (mblk > st.m) {  // rescale only when the running max moves (rare after the first blocks)
+        const float corr = fast_exp2(st.m - mblk);
+        st.m = mblk;
+        st.l *= corr;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) st.acc[c] *= corr;
+    }
+    float p[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) p[u] = fast_exp2(sc[u] - st.m);
+    st.l += (p[0] + p[1]) + (p[2] + p[3]);
+    axpy_pair<T, CH>(st.acc, vc[0], vc[1], p[0], p[1], sizeof(T) == 2 ? pack_bf16x2(p[0], p[1]) : 0u);
+    axpy_pair<T, CH>(st.acc, vc[2], vc[3], p[2], p[3], sizeof(T) == 2 ? pack_bf16x2(p[2], p[3]) : 0u);
+}
+
+// positions [tb, te) of `row`; all 16 lanes of the group call with the same arguments.
+template <typename T, int D>
+__device__ __forceinline__ void fwd_sweep(FwdState<D / 16> &st, const RowChunk<T, D / 16> &q, const T *__restrict__ Kh,
+                                          const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
+                                          int tb, int te, float c2)
+{
+    int t0 = tb;
+    for (; t0 + 4 <= te; t0 += 4) fwd_step<T, D, false>(st, q, Kh, Vh, lane_off, row, t0, te, c2);
+    if (t0 < te) fwd_step<T, D, true>(st, q, Kh, Vh, lane_off, row, t0, te, c2);
+}
+
+// ------------------------------------------------------------------------------------ dq sweep
+template <int CH> struct DqState {
+    float delta;
+    float a[CH], b[CH];  // a: the centred sum C
+};
+
+template <typename T, int D, bool TAIL>
+__device__ __forceinline__ void dq_step(DqState<D / 16> &st, const RowChunk<T, D / 16> &q,
+                                        const RowChunk<T, D / 16> &go, const T *__restrict__ Kh,
+                                        const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
+                                        int t0, int te, float c2, float lse2, float delta0)
+{
+    constexpr int CH = D / 16;
+    constexpr int U = 2;
+    typedef RowChunk<T, CH> Chunk;
+    int j[U];
+    Chunk kc[U], vc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) j[u] = row[TAIL ? min(t0 + u, te - 1) : t0 + u];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        kc[u] = gather_chunk<T, CH>(Kh, (uint32_t)j[u], D, lane_off);
+        vc[u] = gather_chunk<T, CH>(Vh, (uint32_t)j[u], D, lane_off);
+    }
+    float p[U], wc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float sc = row16_sum(dot_chunk<T, CH>(q, kc[u]));
+        const float dp = row16_sum(dot_chunk<T, CH>(go, vc[u]));
+        p[u] = fast_exp2(sc * c2 - lse2);
+        if (TAIL && t0 + u >= te) p[u] = 0.f;
+        st.delta = fmaf(p[u], dp, st.delta);
+        wc[u] = p[u] * (dp - delta0);
+    }
+    axpy_pair2<T, CH>(st.a, st.b, kc[0], kc[1], wc[0], wc[1], p[0], p[1]);
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void dq_sweep(DqState<D / 16> &st, const RowChunk<T, D / 16> &q,
+                                         const RowChunk<T, D / 16> &go, const T *__restrict__ Kh,
+                                         const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
+                                         int tb, int te, float c2, float lse2, float delta0)
+{
+    int t0 = tb;
+    for (; t0 + 2 <= te; t0 += 2) dq_step<T, D, false>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
+    if (t0 < te) dq_step<T, D, true>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
+}
+
+// ------------------------------------------------------------------------------------ dkdv sweep
+template <int CH> struct DkdvState {
+    float dk[CH], dv[CH];
+};
+
+template <typename T, int D, bool TAIL>
+__device__ __forceinline__ void dkdv_step(DkdvState<D / 16> &st, const RowChunk<T, D / 16> &kc,
+                                          const RowChunk<T, D / 16> &vc, const T *__restrict__ Qh,
+                                          const T *__restrict__ Gh, const float *__restrict__ lse_h,
+                                          const float *__restrict__ delta_h, uint32_t lane_off,
+                                          const int32_t *__restrict__ list, int t0, int te, float c2)
+{
+    constexpr int CH = D / 16;
+    constexpr int U = 2;
+    typedef RowChunk<T, CH> Chunk;
+    int iq[U];
+    Chunk qc[U], gc[U];
+    float l2[U], dl[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) iq[u] = list[TAIL ? min(t0 + u, te - 1) : t0 + u];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        qc[u] = gather_chunk<T, CH>(Qh, (uint32_t)iq[u], D, lane_off);
+        gc[u] = gather_chunk<T, CH>(Gh, (uint32_t)iq[u], D, lane_off);
+        l2[u] = lse_h[iq[u]] * kLog2e;
+        dl[u] = delta_h[iq[u]];
+    }
+    float p[U], ds[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float sc = row16_sum(dot_chunk<T, CH>(qc[u], kc));
+        const float dp = row16_sum(dot_chunk<T, CH>(gc[u], vc));
+        p[u] = fast_exp2(sc * c2 - l2[u]);
+        if (TAIL && t0 + u >= te) p[u] = 0.f;
+        ds[u] = p[u] * (dp - dl[u]);
+    }
+    axpy_pair_precise<T, CH>(st.dk, qc[0], qc[1], ds[0], ds[1]);
+    // dV of a popular key sums thousands of terms: bf16 weights alone would leave ~1e-2 of noise
+    axpy_pair_precise<T, CH>(st.dv, gc[0], gc[1], p[0], p[1]);
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void dkdv_sweep(DkdvState<D / 16> &st, const RowChunk<T, D / 16> &kc,
+                                           const RowChunk<T, D / 16> &vc, const T *__restrict__ Qh,
+                                           const T *__restrict__ Gh, const float *__restrict__ lse_h,
+                                           const float *__restrict__ delta_h, uint32_t lane_off,
+                                           const int32_t *__restrict__ list, int tb, int te, float c2)
+{
+    int t0 = tb;
+    for (; t0 + 2 <= te; t0 += 2) dkdv_step<T, D, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
+    if (t0 < te) dkdv_step<T, D, true>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
+}
+
+}  // namespace dsv

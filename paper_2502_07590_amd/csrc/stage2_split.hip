@@ -7,23 +7,21 @@
 // selected inside one range are one contiguous segment of its row.  Work item = (head, range,
 // block of 16 queries); the 1-D grid is laid out so that workgroup b runs on XCD b % 8 and every
 // XCD walks "its" ranges one after the other with all of its CUs inside the same range, which
-// keeps that range's rows resident in that XCD's L2.  Each item leaves a partial result per query
-// (split-K); a small second kernel merges the partials.
+// keeps that range's rows resident in that XCD's L2.  Each item leaves a partial result per row
+// (split-K); a small second kernel merges the partials.  The backward's dkdv step does the same
+// key-major: lists of queries cut by QUERY ranges, Q / dO rows resident.
 //
-// Same lane layout as stage2.hip: 16 lanes per query, lane s holds channels [s*CH, (s+1)*CH).
+// Inner loops and lane layout: stage2_core.h.
 #include <algorithm>
 
-#include "common.h"
+#include "stage2_core.h"
 
 namespace dsv {
 
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-
-// Decode a linear block id into (head slot, range, query block).  Consecutive ids go to
-// consecutive XCDs; ids b, b+8, b+16, ... (one XCD) walk the query blocks of one range, then the
+// Decode a linear block id into (head slot, range, row block).  Consecutive ids go to
+// consecutive XCDs; ids b, b+8, b+16, ... (one XCD) walk the row blocks of one range, then the
 // next range of that XCD.  Ranges are padded to a multiple of 8; padded ranges return false.
-__device__ __forceinline__ bool decode_item(const SplitPlan &pl, int64_t b, int &slot, int &range, int &qb)
+__device__ __forceinline__ bool decode_item(const SplitPlan &pl, int64_t b, int &slot, int &range, int &rb)
 {
     const int64_t per_head = (int64_t)pl.S_pad * pl.nqb;
     slot = (int)(b / per_head);
@@ -31,7 +29,7 @@ __device__ __forceinline__ bool decode_item(const SplitPlan &pl, int64_t b, int 
     const int xcd = (int)(rem & 7);
     const int64_t local = rem >> 3;
     const int t = (int)(local / pl.nqb);
-    qb = (int)(local - (int64_t)t * pl.nqb);
+    rb = (int)(local - (int64_t)t * pl.nqb);
     range = t * 8 + xcd;
     return range < pl.S;
 }
@@ -40,9 +38,9 @@ __device__ __forceinline__ bool decode_item(const SplitPlan &pl, int64_t b, int 
 // seg[bh, row, s] = first position in the (ascending) row whose value is >= s * range_len, for
 // s = 0 .. S.  Query-major: rows of idx (length k).  Key-major: lists of idx_t (start and length
 // from col_ptr), cut by QUERY ranges.
-__global__ __launch_bounds__(256) void segment_ptr_kernel(const int32_t *__restrict__ index, const int64_t *__restrict__ col,
-                                                          int L, HeadTable tab, SplitPlan pl,
-                                                          int32_t *__restrict__ seg)
+__global__ __launch_bounds__(256) void segment_ptr_kernel(const int32_t *__restrict__ index,
+                                                          const int64_t *__restrict__ col, int L, HeadTable tab,
+                                                          SplitPlan pl, int32_t *__restrict__ seg)
 {
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
@@ -82,8 +80,6 @@ __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restri
                                                                float scale, HeadTable tab, SplitPlan pl)
 {
     constexpr int CH = D / 16;
-    constexpr int U = 4;
-    typedef RowChunk<T, CH> Chunk;
     int slot, range, qb;
     if (!decode_item(pl, blockIdx.x, slot, range, qb)) return;
     const int bh = tab.bh[slot];
@@ -94,59 +90,21 @@ __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restri
     const bool live = iq < L;
     const int64_t i = live ? iq : L - 1;
     const int64_t head_base = (int64_t)bh * L * D;
-    const T *Kb = K + head_base + s * CH;
-    const T *Vb = V + head_base + s * CH;
     const int32_t *row = idx + tab.off[slot] + i * k;
     const int32_t *sp = seg + ((int64_t)bh * L + i) * (pl.S + 1) + range;
     const int tb = sp[0], te = sp[1];
 
-    const Chunk q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
-    const float c2 = scale * kLog2e;
-    float m = -INFINITY, l = 0.f;
-    float acc[CH];
+    const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
+    FwdState<CH> st;
+    st.m = -INFINITY;
+    st.l = 0.f;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) acc[c] = 0.f;
-
-    for (int t0 = tb; t0 < te; t0 += U) {
-        int j[U];
-        Chunk kc[U], vc[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) j[u] = row[min(t0 + u, te - 1)];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            kc[u] = load_chunk<T, CH>(Kb + (int64_t)j[u] * D);
-            vc[u] = load_chunk<T, CH>(Vb + (int64_t)j[u] * D);
-        }
-        float sc[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) sc[u] = dot_chunk<T, CH>(q, kc[u]);
-#pragma unroll
-        for (int u = 0; u < U; ++u) sc[u] = row16_sum(sc[u]) * c2;
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (t0 + u >= te) sc[u] = -INFINITY;
-        float mnew = m;
-#pragma unroll
-        for (int u = 0; u < U; ++u) mnew = fmaxf(mnew, sc[u]);
-        const float corr = exp2f(m - mnew);
-        m = mnew;
-        l *= corr;
-#pragma unroll
-        for (int c = 0; c < CH; ++c) acc[c] *= corr;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float pu = exp2f(sc[u] - mnew);
-            l += pu;
-            float vf[CH];
-            unpack_chunk<T, CH>(vc[u], vf);
-#pragma unroll
-            for (int c = 0; c < CH; ++c) acc[c] = fmaf(pu, vf[c], acc[c]);
-        }
-    }
+    for (int c = 0; c < CH; ++c) st.acc[c] = 0.f;
+    fwd_sweep<T, D>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + i) * pl.S + range;
-        store_chunk<float, CH>(pacc + slot_id * D + s * CH, acc);
-        if (s == 0) { pm[slot_id] = m; pl_[slot_id] = l; }
+        store_chunk<float, CH>(pacc + slot_id * D + s * CH, st.acc);
+        if (s == 0) { pm[slot_id] = st.m; pl_[slot_id] = st.l; }
     }
 }
 
@@ -184,21 +142,20 @@ __global__ __launch_bounds__(256) void sparse_fwd_merge_kernel(const float *__re
 }
 
 // ---- backward, dq step ---------------------------------------------------------------------------
-// Per (query, key range): A = sum p dP k, B = sum p k, Delta = sum p dP over the segment (all three
-// are plain sums over the selected keys, so partials simply add).
+// Per (query, key range): C = sum p (dP - D0) k, B = sum p k, Delta = sum p dP over the segment, with
+// D0 = dO . O_stored (all three are plain sums over the selected keys, so partials simply add).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                   const T *__restrict__ V,
                                                                   const int32_t *__restrict__ idx,
                                                                   const int32_t *__restrict__ seg,
+                                                                  const T *__restrict__ O,
                                                                   const float *__restrict__ lse,
                                                                   const T *__restrict__ dO, float *__restrict__ pa,
                                                                   float *__restrict__ pb, float *__restrict__ pdelta,
                                                                   int L, float scale, HeadTable tab, SplitPlan pl)
 {
     constexpr int CH = D / 16;
-    constexpr int U = 2;
-    typedef RowChunk<T, CH> Chunk;
     int slot, range, qb;
     if (!decode_item(pl, blockIdx.x, slot, range, qb)) return;
     const int bh = tab.bh[slot];
@@ -209,61 +166,34 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__res
     const bool live = iq < L;
     const int64_t i = live ? iq : L - 1;
     const int64_t head_base = (int64_t)bh * L * D;
-    const T *Kb = K + head_base + s * CH;
-    const T *Vb = V + head_base + s * CH;
     const int32_t *row = idx + tab.off[slot] + i * k;
     const int32_t *sp = seg + ((int64_t)bh * L + i) * (pl.S + 1) + range;
     const int tb = sp[0], te = sp[1];
 
-    const Chunk q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
-    const Chunk go = load_chunk<T, CH>(dO + head_base + i * D + s * CH);
-    const float c2 = scale * kLog2e;
-    const float lse2 = lse[(int64_t)bh * L + i] * kLog2e;
-
-    float a[CH], bsum[CH];
+    const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
+    const RowChunk<T, CH> go = load_chunk<T, CH>(dO + head_base + i * D + s * CH);
+    const RowChunk<T, CH> o = load_chunk<T, CH>(O + head_base + i * D + s * CH);
+    const float delta0 = row16_sum(dot_chunk<T, CH>(go, o));
+    DqState<CH> st;
+    st.delta = 0.f;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) { a[c] = 0.f; bsum[c] = 0.f; }
-    float delta = 0.f;
-
-    for (int t0 = tb; t0 < te; t0 += U) {
-        int j[U];
-        Chunk kc[U], vc[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) j[u] = row[min(t0 + u, te - 1)];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            kc[u] = load_chunk<T, CH>(Kb + (int64_t)j[u] * D);
-            vc[u] = load_chunk<T, CH>(Vb + (int64_t)j[u] * D);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float sc = row16_sum(dot_chunk<T, CH>(q, kc[u]));
-            const float dp = row16_sum(dot_chunk<T, CH>(go, vc[u]));
-            const float p = (t0 + u < te) ? exp2f(sc * c2 - lse2) : 0.f;
-            const float pdp = p * dp;
-            delta += pdp;
-            float kf[CH];
-            unpack_chunk<T, CH>(kc[u], kf);
-#pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                a[c] = fmaf(pdp, kf[c], a[c]);
-                bsum[c] = fmaf(p, kf[c], bsum[c]);
-            }
-        }
-    }
+    for (int c = 0; c < CH; ++c) { st.a[c] = 0.f; st.b[c] = 0.f; }
+    dq_sweep<T, D>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e,
+                   lse[(int64_t)bh * L + i] * kLog2e, delta0);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + i) * pl.S + range;
-        store_chunk<float, CH>(pa + slot_id * D + s * CH, a);
-        store_chunk<float, CH>(pb + slot_id * D + s * CH, bsum);
-        if (s == 0) pdelta[slot_id] = delta;
+        store_chunk<float, CH>(pa + slot_id * D + s * CH, st.a);
+        store_chunk<float, CH>(pb + slot_id * D + s * CH, st.b);
+        if (s == 0) pdelta[slot_id] = st.delta;
     }
 }
 
-// dQ_i = scale * (sum_s A_s - Delta_i * sum_s B_s), Delta_i = sum_s Delta_s.
+// dQ_i = scale * (sum_s C_s - (Delta_i - D0) * sum_s B_s), Delta_i = sum_s Delta_s, D0 = dO_i . O_i(stored).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void sparse_bwd_dq_merge_kernel(const float *__restrict__ pa,
                                                                   const float *__restrict__ pb,
                                                                   const float *__restrict__ pdelta,
+                                                                  const T *__restrict__ O, const T *__restrict__ dO,
                                                                   T *__restrict__ dQ, float *__restrict__ delta_out,
                                                                   int64_t n_rows, int S, float scale)
 {
@@ -283,9 +213,12 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_merge_kernel(const float *_
 #pragma unroll
         for (int c = 0; c < CH; ++c) { a[c] += __uint_as_float(ca.w[c]); b[c] += __uint_as_float(cb.w[c]); }
     }
+    const RowChunk<T, CH> go = load_chunk<T, CH>(dO + row * D + s * CH);
+    const RowChunk<T, CH> o = load_chunk<T, CH>(O + row * D + s * CH);
+    const float delta0 = row16_sum(dot_chunk<T, CH>(go, o));  // same instruction sequence as in the sweep
     float dq[CH];
 #pragma unroll
-    for (int c = 0; c < CH; ++c) dq[c] = scale * (a[c] - delta * b[c]);
+    for (int c = 0; c < CH; ++c) dq[c] = scale * (a[c] - (delta - delta0) * b[c]);
     store_chunk<T, CH>(dQ + row * D + s * CH, dq);
     if (s == 0) delta_out[row] = delta;
 }
@@ -293,12 +226,15 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_merge_kernel(const float *_
 // ---- backward, dkdv step -------------------------------------------------------------------------
 // Key-major: work item = (head, QUERY range, block of 16 keys); a key's ascending query list has one
 // contiguous segment per query range, whose Q / dO rows (and lse, Delta entries) stay in L2.
+// `order` (optional): keys sorted by descending list length, so that the four keys of a wave (and
+// the sixteen of a block) have segments of similar length; without it key = block position.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                     const T *__restrict__ V,
                                                                     const int32_t *__restrict__ idxT,
                                                                     const int64_t *__restrict__ col,
                                                                     const int32_t *__restrict__ seg,
+                                                                    const int32_t *__restrict__ order,
                                                                     const float *__restrict__ lse,
                                                                     const float *__restrict__ delta,
                                                                     const T *__restrict__ dO, float *__restrict__ pdk,
@@ -306,65 +242,31 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
                                                                     HeadTable tab, SplitPlan pl)
 {
     constexpr int CH = D / 16;
-    constexpr int U = 2;
-    typedef RowChunk<T, CH> Chunk;
     int slot, range, kb;
     if (!decode_item(pl, blockIdx.x, slot, range, kb)) return;
     const int bh = tab.bh[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane >> 4, s = lane & 15;
-    const int64_t jq = (int64_t)kb * 16 + wave * 4 + grp;
-    const bool live = jq < L;
-    const int64_t j = live ? jq : L - 1;
+    const int64_t jpos = (int64_t)kb * 16 + wave * 4 + grp;
+    const bool live = jpos < L;
+    const int64_t jp = live ? jpos : L - 1;
+    const int64_t j = order ? order[(int64_t)bh * L + jp] : jp;
     const int64_t head_base = (int64_t)bh * L * D;
-    const T *Qb = Q + head_base + s * CH;
-    const T *Gb = dO + head_base + s * CH;
-    const float *lse_b = lse + (int64_t)bh * L;
-    const float *delta_b = delta + (int64_t)bh * L;
     const int32_t *list = idxT + tab.off[slot] + col[(int64_t)bh * (L + 1) + j];
     const int32_t *sp = seg + ((int64_t)bh * L + j) * (pl.S + 1) + range;
     const int tb = sp[0], te = live ? sp[1] : sp[0];
 
-    const Chunk kc = load_chunk<T, CH>(K + head_base + j * D + s * CH);
-    const Chunk vc = load_chunk<T, CH>(V + head_base + j * D + s * CH);
-    const float c2 = scale * kLog2e;
-    float dk[CH], dv[CH];
+    const RowChunk<T, CH> kc = load_chunk<T, CH>(K + head_base + j * D + s * CH);
+    const RowChunk<T, CH> vc = load_chunk<T, CH>(V + head_base + j * D + s * CH);
+    DkdvState<CH> st;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) { dk[c] = 0.f; dv[c] = 0.f; }
-
-    for (int t0 = tb; t0 < te; t0 += U) {
-        int iq[U];
-        Chunk qc[U], gc[U];
-        float l2[U], dl[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) iq[u] = list[min(t0 + u, te - 1)];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            qc[u] = load_chunk<T, CH>(Qb + (int64_t)iq[u] * D);
-            gc[u] = load_chunk<T, CH>(Gb + (int64_t)iq[u] * D);
-            l2[u] = lse_b[iq[u]] * kLog2e;
-            dl[u] = delta_b[iq[u]];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float sc = row16_sum(dot_chunk<T, CH>(qc[u], kc));
-            const float dp = row16_sum(dot_chunk<T, CH>(gc[u], vc));
-            const float p = (t0 + u < te) ? exp2f(sc * c2 - l2[u]) : 0.f;
-            const float ds = p * (dp - dl[u]);
-            float qf[CH], gf[CH];
-            unpack_chunk<T, CH>(qc[u], qf);
-            unpack_chunk<T, CH>(gc[u], gf);
-#pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                dk[c] = fmaf(ds, qf[c], dk[c]);
-                dv[c] = fmaf(p, gf[c], dv[c]);
-            }
-        }
-    }
+    for (int c = 0; c < CH; ++c) { st.dk[c] = 0.f; st.dv[c] = 0.f; }
+    dkdv_sweep<T, D>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L, delta + (int64_t)bh * L,
+                     (uint32_t)(s * CH), list, tb, te, scale * kLog2e);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + j) * pl.S + range;
-        store_chunk<float, CH>(pdk + slot_id * D + s * CH, dk);
-        store_chunk<float, CH>(pdv + slot_id * D + s * CH, dv);
+        store_chunk<float, CH>(pdk + slot_id * D + s * CH, st.dk);
+        store_chunk<float, CH>(pdv + slot_id * D + s * CH, st.dv);
     }
 }
 
@@ -392,6 +294,62 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_merge_kernel(const float 
     for (int c = 0; c < CH; ++c) a[c] *= scale;
     store_chunk<T, CH>(dK + row * D + s * CH, a);
     store_chunk<T, CH>(dV + row * D + s * CH, b);
+}
+
+// ---- keys in order of descending list length (counting sort on the length) ---------------------
+// hist[bh, L - len] counts keys per length; after an exclusive scan it holds, for every length,
+// the first rank of the keys that long; the scatter hands out ranks through atomic cursors (the
+// order among keys of equal length is arbitrary and does not affect any result).
+__global__ __launch_bounds__(256) void keylen_hist_kernel(const int64_t *__restrict__ col, int L, int32_t *__restrict__ hist)
+{
+    const int bh = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= L) return;
+    const int64_t *cp = col + (int64_t)bh * (L + 1);
+    const int len = (int)(cp[j + 1] - cp[j]);
+    atomicAdd(&hist[(int64_t)bh * (L + 1) + (L - len)], 1);
+}
+
+__global__ __launch_bounds__(1024) void keylen_scan_kernel(int32_t *__restrict__ hist, int n)
+{
+    __shared__ int32_t part[1024];
+    int32_t *h = hist + (int64_t)blockIdx.x * n;
+    const int per = (n + 1023) / 1024;
+    const int lo = min((int)threadIdx.x * per, n), hi = min(lo + per, n);
+    int32_t sum = 0;
+    for (int e = lo; e < hi; ++e) sum += h[e];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int step = 1; step < 1024; step <<= 1) {
+        const int32_t add = threadIdx.x >= (unsigned)step ? part[threadIdx.x - step] : 0;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    int32_t run = part[threadIdx.x] - sum;
+    for (int e = lo; e < hi; ++e) {
+        const int32_t v = h[e];
+        h[e] = run;
+        run += v;
+    }
+}
+
+__global__ __launch_bounds__(256) void keylen_scatter_kernel(const int64_t *__restrict__ col, int L,
+                                                             int32_t *__restrict__ hist, int32_t *__restrict__ order)
+{
+    const int bh = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= L) return;
+    const int64_t *cp = col + (int64_t)bh * (L + 1);
+    const int len = (int)(cp[j + 1] - cp[j]);
+    const int rank = atomicAdd(&hist[(int64_t)bh * (L + 1) + (L - len)], 1);
+    order[(int64_t)bh * L + rank] = j;
+}
+
+__global__ __launch_bounds__(256) void zero_i32_kernel(int32_t *__restrict__ p, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) p[e] = 0;
 }
 
 // ------------------------------------------------------------------------------------ host
@@ -440,25 +398,11 @@ static dsv_status fwd_split_t(const dsv_problem &p, const HeadTable *tabs, int n
     return DSV_OK;
 }
 
-dsv_status launch_sparse_fwd_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
-                                   const void *K, const void *V, const int32_t *idx, void *O, float *lse,
-                                   const SplitPlan &pl, const FwdSplitWorkspace &w, hipStream_t st)
-{
-    if (p.dtype == DSV_BF16) {
-        if (p.d == 64) return fwd_split_t<bf16_t, 64>(p, tabs, n_tabs, Q, K, V, idx, O, lse, pl, w, st);
-        if (p.d == 128) return fwd_split_t<bf16_t, 128>(p, tabs, n_tabs, Q, K, V, idx, O, lse, pl, w, st);
-    } else if (p.dtype == DSV_F32) {
-        if (p.d == 64) return fwd_split_t<float, 64>(p, tabs, n_tabs, Q, K, V, idx, O, lse, pl, w, st);
-        if (p.d == 128) return fwd_split_t<float, 128>(p, tabs, n_tabs, Q, K, V, idx, O, lse, pl, w, st);
-    }
-    return DSV_EUNSUPPORTED;
-}
-
 template <typename T, int D>
 static dsv_status bwd_dq_split_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
-                                 const void *K, const void *V, const int32_t *idx, const float *lse, const void *dO,
-                                 void *dQ, float *delta, const SplitPlan &pl, const BwdSplitWorkspace &w,
-                                 hipStream_t st)
+                                 const void *K, const void *V, const int32_t *idx, const void *O, const float *lse,
+                                 const void *dO, void *dQ, float *delta, const SplitPlan &pl,
+                                 const BwdSplitWorkspace &w, hipStream_t st)
 {
     dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idx, nullptr, w.seg, st);
     if (rc != DSV_OK) return rc;
@@ -466,13 +410,13 @@ static dsv_status bwd_dq_split_t(const dsv_problem &p, const HeadTable *tabs, in
         const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
         if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
         hipLaunchKernelGGL((sparse_bwd_dq_split_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
-                           (const T *)K, (const T *)V, idx, w.seg, lse, (const T *)dO, w.pa, w.pb, w.pdelta, p.L,
-                           p.scale, tabs[t], pl);
+                           (const T *)K, (const T *)V, idx, w.seg, (const T *)O, lse, (const T *)dO, w.pa, w.pb,
+                           w.pdelta, p.L, p.scale, tabs[t], pl);
         DSV_LAUNCH_CHECK();
     }
     const int64_t n_rows = (int64_t)p.B * p.H * p.L;
     hipLaunchKernelGGL((sparse_bwd_dq_merge_kernel<T, D>), dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st, w.pa,
-                       w.pb, w.pdelta, (T *)dQ, delta, n_rows, pl.S, p.scale);
+                       w.pb, w.pdelta, (const T *)O, (const T *)dO, (T *)dQ, delta, n_rows, pl.S, p.scale);
     DSV_LAUNCH_CHECK();
     return DSV_OK;
 }
@@ -483,14 +427,24 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
                                    const float *lse, const float *delta, const void *dO, void *dK, void *dV,
                                    const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st)
 {
+    const int nbh = p.B * p.H;
     dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idxT, col, w.seg, st);
     if (rc != DSV_OK) return rc;
+    // keys by descending list length (w.hist: [B*H, L+1] counters, w.order: [B*H, L])
+    const int64_t nh = (int64_t)nbh * (p.L + 1);
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nh + 255) / 256, 4096)), dim3(256), 0, st,
+                       w.hist, nh);
+    dim3 kgrid((p.L + 255) / 256, nbh);
+    hipLaunchKernelGGL(keylen_hist_kernel, kgrid, dim3(256), 0, st, col, p.L, w.hist);
+    hipLaunchKernelGGL(keylen_scan_kernel, dim3(nbh), dim3(1024), 0, st, w.hist, p.L + 1);
+    hipLaunchKernelGGL(keylen_scatter_kernel, kgrid, dim3(256), 0, st, col, p.L, w.hist, w.order);
+    DSV_LAUNCH_CHECK();
     for (int t = 0; t < n_tabs; ++t) {
         const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
         if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
         hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, st,
-                           (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, lse, delta, (const T *)dO, w.pa,
-                           w.pb, p.L, p.scale, tabs[t], pl);
+                           (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, w.order, lse, delta,
+                           (const T *)dO, w.pa, w.pb, p.L, p.scale, tabs[t], pl);
         DSV_LAUNCH_CHECK();
     }
     const int64_t n_rows = (int64_t)p.B * p.H * p.L;
@@ -512,11 +466,18 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
         return DSV_EUNSUPPORTED;                                        \
     } while (0)
 
-dsv_status launch_bwd_dq_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
-                               const void *V, const int32_t *idx, const float *lse, const void *dO, void *dQ,
-                               float *delta, const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st)
+dsv_status launch_sparse_fwd_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
+                                   const void *K, const void *V, const int32_t *idx, void *O, float *lse,
+                                   const SplitPlan &pl, const FwdSplitWorkspace &w, hipStream_t st)
 {
-    DSV_DISPATCH_TD(bwd_dq_split_t, p, tabs, n_tabs, Q, K, V, idx, lse, dO, dQ, delta, pl, w, st);
+    DSV_DISPATCH_TD(fwd_split_t, p, tabs, n_tabs, Q, K, V, idx, O, lse, pl, w, st);
+}
+
+dsv_status launch_bwd_dq_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
+                               const void *V, const int32_t *idx, const void *O, const float *lse, const void *dO,
+                               void *dQ, float *delta, const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st)
+{
+    DSV_DISPATCH_TD(bwd_dq_split_t, p, tabs, n_tabs, Q, K, V, idx, O, lse, dO, dQ, delta, pl, w, st);
 }
 
 dsv_status launch_bwd_dkdv_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
