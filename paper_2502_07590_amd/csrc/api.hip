@@ -74,21 +74,23 @@ dsv_status check_workspace(const void *ws, size_t have, size_t need)
 
 // ---- workspace layouts (byte offsets, every block aligned to 256) ------------------------------
 struct Stage1Layout {
-    size_t qlr, klr, prefix, krem, jcut, cnt, total;
+    size_t qlr, klr, prefix, krem, jcut, cnt, tflag, total;
 };
 
 // transposed: also room for jcut and the per-key list lengths of the key-major emission
 Stage1Layout stage1_layout(const dsv_problem &p, bool transposed)
 {
     const size_t tok = (size_t)p.B * p.H * p.L;
+    const size_t tokp = (size_t)p.B * p.H * ((p.L + 31) / 32 * 32);  // per-query state rows are padded to tiles
     Stage1Layout w{};
     size_t o = 0;
     w.qlr = o; o = align_up(o + tok * p.r * esize(p.dtype), 256);
     w.klr = o; o = align_up(o + tok * p.r * esize(p.dtype), 256);
-    w.prefix = o; o = align_up(o + tok * 4, 256);
-    w.krem = o; o = align_up(o + tok * 4, 256);
-    w.jcut = o; if (transposed) o = align_up(o + tok * 4, 256);
+    w.prefix = o; o = align_up(o + tokp * 4, 256);
+    w.krem = o; o = align_up(o + tokp * 4, 256);
+    w.jcut = o; if (transposed) o = align_up(o + tokp * 4, 256);
     w.cnt = o; if (transposed) o = align_up(o + tok * 4, 256);
+    w.tflag = o; if (transposed) o = align_up(o + (size_t)p.B * p.H * ((p.L + 31) / 32) * 4, 256);
     w.total = o;
     return w;
 }
@@ -233,6 +235,7 @@ static dsv_status lowrank_topk_impl(const dsv_problem *p, const void *Q, const v
     b.idx = idx;
     b.jcut = transposed ? reinterpret_cast<int32_t *>(ws + w.jcut) : nullptr;
     b.cnt = transposed ? reinterpret_cast<int32_t *>(ws + w.cnt) : nullptr;
+    b.tile_flag = transposed ? reinterpret_cast<int32_t *>(ws + w.tflag) : nullptr;
     b.col = transposed ? col_ptr : nullptr;
     b.idx_t = transposed ? idx_t : nullptr;
     const std::vector<HeadTable> tabs = make_tables(*p);

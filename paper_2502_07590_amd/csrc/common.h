@@ -210,12 +210,15 @@ struct SelectBuffers {
     int32_t *krem;     // [B*H, L]   number of keys equal to the threshold that belong to the top-k
     int32_t *idx;      // out: ragged query-major index
     int32_t *jcut;     // [B*H, L]   index of the last tie taken
+    int32_t *tile_flag;  // [B*H, ceil(L/32)]  1: every query of the tile takes all its threshold ties
     int32_t *cnt;      // [B*H, L]   list length of every key
     int64_t *col;      // out: [B*H, L+1]
     int32_t *idx_t;    // out: ragged key-major index
 };
 dsv_status launch_select(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                          const SelectBuffers &b, hipStream_t st);
+dsv_status launch_emit(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
+                       const SelectBuffers &b, hipStream_t st);
 dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                              const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st);
 dsv_status launch_bwd_dq(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,

@@ -6,12 +6,12 @@
 //   select       per (head, query): exact value of the k-th largest score by a radix search on the
 //                order-preserving bit pattern of the fp32 score (four 8-bit digits, one pass over
 //                all keys per digit, histograms in LDS), then
-//   emit         one more pass that writes every key above the threshold plus the lowest-index
-//                ties, in ascending key order.
+//   emit         (stage1_emit.hip) one more pass that writes every key above the threshold plus the
+//                lowest-index ties, in ascending key order; optionally the same key-major.
 // Scores are recomputed in every pass on the matrix cores (one 32x32 MFMA tile = 32 keys x 32
 // queries); the L x L matrix never exists in memory.  Every pass uses the same instruction
 // sequence for a score, so a score has the same bits in every pass.
-#include "common.h"
+#include "stage1_core.h"
 
 namespace dsv {
 
@@ -59,69 +59,6 @@ __global__ __launch_bounds__(256) void project_kernel(const T *__restrict__ Q, c
     }
 }
 
-// ------------------------------------------------------------------------------------ score tiles
-// MFMA operand fragment of 32 rows of a [*, R] low-rank matrix.  Lane l holds row (l % 32) and the
-// K-slice selected by (l / 32); keys go in as the A operand, queries as the B operand, so that
-// acc[v] of lane l is the score of query (l % 32) against key 8*(v/4) + 4*(l/32) + (v%4) of the tile.
-template <typename T, int R> struct Frag;
-template <int R> struct Frag<bf16_t, R> { bf16x8_t v[R / 16]; };
-template <int R> struct Frag<float, R> { float v[R / 2]; };
-
-template <typename T, int R>
-__device__ __forceinline__ Frag<T, R> load_frag_row(const T *__restrict__ base, int64_t row, int lane)
-{
-    Frag<T, R> f;
-    const int half = lane >> 5;
-    const T *p = base + row * R;
-    if constexpr (sizeof(T) == 2) {
-#pragma unroll
-        for (int m = 0; m < R / 16; ++m) f.v[m] = *reinterpret_cast<const bf16x8_t *>(p + m * 16 + half * 8);
-    } else {
-#pragma unroll
-        for (int m = 0; m < R / 2; ++m) f.v[m] = p[2 * m + half];
-    }
-    return f;
-}
-
-// Rows row0 .. row0+31 of the matrix; rows past the end are clamped (callers mask their results).
-template <typename T, int R>
-__device__ __forceinline__ Frag<T, R> load_frag(const T *__restrict__ base, int row0, int L, int lane)
-{
-    return load_frag_row<T, R>(base, min(row0 + (lane & 31), L - 1), lane);
-}
-
-template <typename T, int R>
-__device__ __forceinline__ floatx16_t score_tile(const Frag<T, R> &keys, const Frag<T, R> &queries)
-{
-    floatx16_t acc;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-    if constexpr (sizeof(T) == 2) {
-#pragma unroll
-        for (int m = 0; m < R / 16; ++m)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(keys.v[m], queries.v[m], acc, 0, 0, 0);
-    } else {
-#pragma unroll
-        for (int m = 0; m < R / 2; ++m)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(keys.v[m], queries.v[m], acc, 0, 0, 0);
-    }
-    return acc;
-}
-
-// Position inside a 32-key tile of accumulator v for a lane in half 0 (half 1 adds 4).
-__device__ __forceinline__ constexpr int tile_pos(int v) { return 8 * (v / 4) + (v % 4); }
-
-// Order-preserving map fp32 -> uint32 (larger float <=> larger key), and its inverse.
-__device__ __forceinline__ uint32_t score_key(float s)
-{
-    uint32_t u = __float_as_uint(s);
-    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
-}
-__device__ __forceinline__ float key_score(uint32_t key)
-{
-    return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
-}
-
 // ------------------------------------------------------------------------------------ radix pass
 // One digit of the search for the k-th largest score of each query.  Block = 32 queries of one
 // head, 4 waves striding over the key tiles, one shared [32][256] histogram in LDS (row stride 257
@@ -129,8 +66,8 @@ __device__ __forceinline__ float key_score(uint32_t key)
 //   PASS 0 counts every key by the top digit; PASS p counts only keys whose higher digits equal
 //   the prefix found so far.  Afterwards: the digit whose bucket holds the k_rem-th largest
 //   remaining key is appended to the prefix and k_rem is reduced by the keys in higher buckets.
-// After pass 3 the prefix is the full key of the k-th largest score and k_rem is the number of
-// keys equal to it that belong to the top-k (at least 1).
+// After pass 3 the prefix is the full key of the k-th largest score and |k_rem| is the number of
+// keys equal to it that belong to the top-k (at least 1); k_rem < 0 marks "all of them".
 template <typename T, int R, int PASS>
 __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
                                                          HeadTable tab, uint32_t *__restrict__ prefix,
@@ -152,26 +89,58 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
 
     const int qi = min(q0 + n, L - 1);
     uint32_t pre = 0;
-    if constexpr (PASS > 0) pre = prefix[(int64_t)bh * L + qi];
+    if constexpr (PASS > 0) pre = prefix[(int64_t)bh * padded_len(L) + qi];
     const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
     const int ntiles = (L + 31) >> 5;
-    for (int tile = wave; tile < ntiles; tile += 4) {
-        const int j0 = tile * 32;
+    const int nfull = L >> 5;  // tiles with all 32 keys in range
+    uint32_t *hrow_mine = hist + n * STRIDE;
+    // When every query of the tile has a threshold prefix in the positive floats (the usual case:
+    // k < L/2), a score matches the prefix iff its RAW bits do: negative scores have the sign bit
+    // set and can never match, and for positive floats the raw pattern is already monotone.  That
+    // drops the key transform from the hot loop: one xor + one compare per score, digits are only
+    // extracted for the few matches.
+    bool fast = false;
+    if constexpr (PASS > 0) fast = __all((pre & 0x80000000u) != 0u);
+    if (fast) {
+        const uint32_t raw_pre = pre ^ 0x80000000u;
+        for (int tile = wave; tile < nfull; tile += 4) {
+            const Frag<T, R> kf = load_frag<T, R>(Kb, tile * 32, L, lane);
+            const floatx16_t acc = score_tile<T, R>(kf, qf);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t bits = __float_as_uint(acc[v]);
+                if ((bits ^ raw_pre) < (1u << ((SHIFT + 8) & 31))) atomicAdd(&hrow_mine[(bits >> SHIFT) & 255u], 1u);
+            }
+        }
+    } else {
+        for (int tile = wave; tile < nfull; tile += 4) {
+            const Frag<T, R> kf = load_frag<T, R>(Kb, tile * 32, L, lane);
+            const floatx16_t acc = score_tile<T, R>(kf, qf);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t key = score_key(acc[v]);
+                bool ok = true;
+                if constexpr (PASS > 0) ok = (key >> (SHIFT + 8)) == (pre >> (SHIFT + 8));
+                if (ok) atomicAdd(&hrow_mine[(key >> SHIFT) & 255u], 1u);
+            }
+        }
+    }
+    if (nfull < ntiles && wave == (nfull & 3)) {  // the ragged last tile
+        const int j0 = nfull * 32;
         const Frag<T, R> kf = load_frag<T, R>(Kb, j0, L, lane);
         const floatx16_t acc = score_tile<T, R>(kf, qf);
-        const bool full = j0 + 32 <= L;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const uint32_t key = score_key(acc[v]);
-            bool ok = full || (j0 + tile_pos(v) + 4 * half < L);
+            bool ok = j0 + tile_pos(v) + 4 * half < L;
             if constexpr (PASS > 0) ok = ok && ((key >> (SHIFT + 8)) == (pre >> (SHIFT + 8)));
-            if (ok) atomicAdd(&hist[n * STRIDE + ((key >> SHIFT) & 255u)], 1u);
+            if (ok) atomicAdd(&hrow_mine[(key >> SHIFT) & 255u], 1u);
         }
     }
     __syncthreads();
 
     if (threadIdx.x < 32 && q0 + (int)threadIdx.x < L) {
-        const int64_t g = (int64_t)bh * L + q0 + threadIdx.x;
+        const int64_t g = (int64_t)bh * padded_len(L) + q0 + threadIdx.x;
         const int kr = PASS == 0 ? tab.k[slot] : krem[g];
         const uint32_t *hrow = hist + threadIdx.x * STRIDE;
         int above = 0, digit = 0;
@@ -182,169 +151,11 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
         }
         const uint32_t mypre = PASS == 0 ? 0u : prefix[g];
         prefix[g] = mypre | ((uint32_t)digit << SHIFT);
-        krem[g] = kr - above;
+        // after the last digit the bucket holds exactly the keys equal to the threshold: a negative
+        // k_rem tells the emission that all of them are taken (then "score >= threshold" decides)
+        const int want = kr - above;
+        krem[g] = (PASS == 3 && want == (int)hrow[digit]) ? -want : want;
     }
-}
-
-// ------------------------------------------------------------------------------------ emit
-// One wave owns 32 queries of one head and walks the key tiles in ascending order.  A key is
-// selected when its score is above the query's threshold, or equal to it while fewer than k_rem
-// equal keys have been taken (lowest index first).  Lanes l and l+32 (same query) merge their 16
-// predicate bits into one 32-bit mask in key order; each lane then writes its own selected keys at
-// cursor + rank, so every row comes out in ascending key index.  jcut[query] receives the index of
-// the last tie taken (the k-th key itself is one, so there always is one), so that
-//   selected(i, j)  <=>  s_ij > tau_i  or  (s_ij == tau_i and j <= jcut_i)
-// is a pure function of the pair, which the key-major emission below re-evaluates.
-template <typename T, int R>
-__global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
-                                                  HeadTable tab, const uint32_t *__restrict__ prefix,
-                                                  const int32_t *__restrict__ krem, int32_t *__restrict__ idx,
-                                                  int32_t *__restrict__ jcut)
-{
-    const int slot = blockIdx.y;
-    const int bh = tab.bh[slot];
-    const int k = tab.k[slot];
-    const int q0 = blockIdx.x * 32;
-    const T *Qb = Qlr + (int64_t)bh * L * R;
-    const T *Kb = Klr + (int64_t)bh * L * R;
-    const int lane = threadIdx.x;
-    const int n = lane & 31, half = lane >> 5;
-    const bool live = q0 + n < L;
-    const int qi = min(q0 + n, L - 1);
-    const float tau = key_score(prefix[(int64_t)bh * L + qi]);
-    const int ties_wanted = krem[(int64_t)bh * L + qi];
-    int32_t *row = idx + tab.off[slot] + (int64_t)qi * k;
-
-    const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
-    const uint32_t mine_pos = 0x0F0F0F0Fu << (4 * half);
-    int cursor = 0, ties_taken = 0, last_tie = -1;
-    const int ntiles = (L + 31) >> 5;
-    for (int tile = 0; tile < ntiles; ++tile) {
-        const int j0 = tile * 32;
-        const Frag<T, R> kf = load_frag<T, R>(Kb, j0, L, lane);
-        const floatx16_t acc = score_tile<T, R>(kf, qf);
-        uint32_t mgt = 0, meq = 0;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            mgt |= (uint32_t)(acc[v] > tau) << tile_pos(v);
-            meq |= (uint32_t)(acc[v] == tau) << tile_pos(v);
-        }
-        mgt <<= 4 * half;
-        meq <<= 4 * half;
-        mgt |= (uint32_t)__shfl_xor((int)mgt, 32);
-        meq |= (uint32_t)__shfl_xor((int)meq, 32);
-        const uint32_t valid = (j0 + 32 <= L) ? 0xFFFFFFFFu : ((1u << (L - j0)) - 1u);
-        mgt &= valid;
-        meq &= valid;
-        if (meq) {
-            const int room = ties_wanted - ties_taken;
-            while (__popc(meq) > room) meq &= ~(0x80000000u >> __clz(meq));  // drop the highest index
-            ties_taken += __popc(meq);
-            if (meq) last_tie = j0 + 31 - __clz(meq);
-        }
-        const uint32_t sel = mgt | meq;
-        uint32_t mine = sel & mine_pos;
-        while (mine) {
-            const int pos = __ffs(mine) - 1;
-            const int w = cursor + __popc(sel & ((1u << pos) - 1u));
-            if (live && w < k) row[w] = j0 + pos;
-            mine &= mine - 1;
-        }
-        cursor += __popc(sel);
-    }
-    if (jcut && live && half == 0) jcut[(int64_t)bh * L + qi] = last_tie;
-}
-
-// ------------------------------------------------------------------------------------ key-major emit
-// The transposed index: for every key j, the ascending list of queries that selected it.  One wave
-// owns 32 keys of one head and walks the QUERY tiles in ascending order, recomputing each 32x32
-// tile with the same operand roles as every other pass (identical score bits) and re-evaluating
-// selected(i, j) from tau_i and jcut_i.  For accumulator v the wave-wide ballot is, in its low half,
-// the query mask of key tile_pos(v) and, in its high half, that of key tile_pos(v)+4.
-//   WRITE = false: count list lengths  -> cnt[bh, j]
-//   WRITE = true : lists start at col[bh, j] (exclusive scan of the counts); lanes with a set bit
-//                  write their query index at position + rank.
-template <typename T, int R, bool WRITE>
-__global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
-                                                    HeadTable tab, const uint32_t *__restrict__ prefix,
-                                                    const int32_t *__restrict__ jcut, int32_t *__restrict__ cnt,
-                                                    const int64_t *__restrict__ col, int32_t *__restrict__ idxT)
-{
-    const int slot = blockIdx.y;
-    const int bh = tab.bh[slot];
-    const int j0 = blockIdx.x * 32;
-    const T *Qb = Qlr + (int64_t)bh * L * R;
-    const T *Kb = Klr + (int64_t)bh * L * R;
-    const uint32_t *pre_b = prefix + (int64_t)bh * L;
-    const int32_t *jcut_b = jcut + (int64_t)bh * L;
-    const int lane = threadIdx.x;
-    const int n = lane & 31, half = lane >> 5;
-    const uint32_t below = (1u << n) - 1u;  // lanes of my half with a lower query index
-
-    const Frag<T, R> kf = load_frag<T, R>(Kb, j0, L, lane);
-    int32_t *out = WRITE ? idxT + tab.off[slot] : nullptr;
-    int64_t pos[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int j = j0 + tile_pos(v) + 4 * half;
-        pos[v] = (WRITE && j < L) ? col[(int64_t)bh * (L + 1) + j] : 0;
-    }
-    const int ntiles = (L + 31) >> 5;
-    for (int qt = 0; qt < ntiles; ++qt) {
-        const int q0 = qt * 32;
-        const bool live = q0 + n < L;
-        const int qi = min(q0 + n, L - 1);
-        const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
-        const float tau = key_score(pre_b[qi]);
-        const int jc = jcut_b[qi];
-        const floatx16_t acc = score_tile<T, R>(kf, qf);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int j = j0 + tile_pos(v) + 4 * half;
-            const bool pred = live && j < L && (acc[v] > tau || (acc[v] == tau && j <= jc));
-            const uint64_t m = __ballot(pred);
-            const uint32_t mh = half ? (uint32_t)(m >> 32) : (uint32_t)m;
-            if (WRITE) {
-                if (pred) out[pos[v] + __popc(mh & below)] = q0 + n;
-            }
-            pos[v] += __popc(mh);
-        }
-    }
-    if (!WRITE && n == 0) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int j = j0 + tile_pos(v) + 4 * half;
-            if (j < L) cnt[(int64_t)bh * L + j] = (int32_t)pos[v];
-        }
-    }
-}
-
-// One block per (b, h): exclusive scan of cnt [L] into col [L+1] (int64).
-__global__ __launch_bounds__(1024) void list_scan_kernel(const int32_t *__restrict__ cnt, int64_t *__restrict__ col,
-                                                         int L)
-{
-    __shared__ int64_t part[1024];
-    const int bh = blockIdx.x;
-    const int32_t *c = cnt + (int64_t)bh * L;
-    int64_t *o = col + (int64_t)bh * (L + 1);
-    const int per = (L + 1023) / 1024;
-    const int lo = min((int)threadIdx.x * per, L), hi = min(lo + per, L);
-    int64_t sum = 0;
-    for (int j = lo; j < hi; ++j) sum += c[j];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    for (int step = 1; step < 1024; step <<= 1) {
-        const int64_t add = threadIdx.x >= (unsigned)step ? part[threadIdx.x - step] : 0;
-        __syncthreads();
-        part[threadIdx.x] += add;
-        __syncthreads();
-    }
-    int64_t run = part[threadIdx.x] - sum;
-    for (int j = lo; j < hi; ++j) {
-        o[j] = run;
-        run += c[j];
-    }
-    if (threadIdx.x == 1023) o[L] = part[1023];
 }
 
 // ------------------------------------------------------------------------------------ debug scores
@@ -451,26 +262,9 @@ static dsv_status select_t(const dsv_problem &p, const HeadTable *tabs, int n_ta
         hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
         hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
         hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-        hipLaunchKernelGGL((emit_kernel<T, R>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem, b.idx,
-                           b.jcut);
         DSV_LAUNCH_CHECK();
-        if (b.idx_t) {
-            hipLaunchKernelGGL((emit_t_kernel<T, R, false>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], b.prefix,
-                               b.jcut, b.cnt, (const int64_t *)nullptr, (int32_t *)nullptr);
-            DSV_LAUNCH_CHECK();
-        }
     }
-    if (b.idx_t) {
-        hipLaunchKernelGGL(list_scan_kernel, dim3(p.B * p.H), dim3(1024), 0, st, b.cnt, b.col, p.L);
-        DSV_LAUNCH_CHECK();
-        for (int t = 0; t < n_tabs; ++t) {
-            dim3 grid(qtiles, tabs[t].n);
-            hipLaunchKernelGGL((emit_t_kernel<T, R, true>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], b.prefix,
-                               b.jcut, (int32_t *)nullptr, b.col, b.idx_t);
-            DSV_LAUNCH_CHECK();
-        }
-    }
-    return DSV_OK;
+    return launch_emit(p, tabs, n_tabs, Qlr, Klr, b, st);
 }
 
 dsv_status launch_select(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
