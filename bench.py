@@ -38,6 +38,9 @@ def parse_args():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention comparator")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-rows", type=int, default=0, help="query rows of the oracle sample (0 = auto)")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before the steps, run one plain elementwise copy kernel (x + 0 over this many MiB of int32) "
+                         "so that a rocprofv3 --pmc run holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
 
 
@@ -149,6 +152,12 @@ def main():
             c()
             ev[i + 1].record()
         events.append(ev)
+
+    if args.calibration_copy_mib:
+        src = torch.zeros(args.calibration_copy_mib * (1 << 18), dtype=torch.int32, device=dev)
+        dst = torch.add(src, 0)          # one elementwise kernel: reads and writes calibration_copy_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -9,8 +9,9 @@
 // Layout of both kernels: one wave owns 32 "owners" (queries for idx, keys for idx_t) as the MFMA
 // column operand and walks the other axis in tiles of 32, ascending.  Lanes l and l+32 hold the same
 // owner; each has 16 predicate bits, which are merged into one 32-bit mask in ascending order of the
-// other axis.  Each lane then writes its own half of the selected entries at cursor + rank, so every
-// row / list comes out ascending without any sorting.
+// other axis.  The two lanes split the selected entries by rank and append them to the owner's ring in
+// LDS, from where they leave in order as 128-byte stores, so every row / list comes out ascending
+// without any sorting.
 #include "stage1_core.h"
 
 namespace dsv {
@@ -42,17 +43,68 @@ __device__ __forceinline__ uint32_t merge_halves(uint32_t m, int half)
     return m | (uint32_t)__shfl_xor((int)m, 32);
 }
 
-// Append the set bits of `sel` that belong to this lane (mine_pos) to out[cursor + rank], value
-// base + bit position.  Both lanes of an owner see the same sel and cursor.
-__device__ __forceinline__ void append_selected(int32_t *__restrict__ out, int cursor, int limit, uint32_t sel,
-                                                uint32_t mine_pos, int base, bool live)
+// ---- output staging -------------------------------------------------------------------------------
+// A selected entry is 4 bytes and consecutive entries of one owner are produced ~16 tiles apart, so
+// writing them straight to memory makes every store a partial cache line (measured: 5x write
+// amplification plus read-for-ownership traffic).  Instead each owner has a ring of kRing entries in
+// LDS; entries are appended there, and whenever an owner holds 32 or more, 32 of them leave as one
+// contiguous 128-byte store issued by 32 lanes (two owners per step, one per half-wave).
+constexpr int kRing = 64;  // a tile adds at most 32 entries to an owner that holds fewer than 32
+
+// Append the set bits of `sel` (ascending = ranks 0..c-1) to the owner's ring at wpos + rank, value
+// base + bit position.  The two lanes of an owner split the work by rank: half 0 takes the lower
+// ceil(c/2) entries scanning upwards, half 1 the upper floor(c/2) scanning downwards.
+// Entries of rank >= c_ok are dropped (c_ok < c only if the row would overflow, which a correct
+// threshold rules out; the clamp keeps a wrong one from writing out of bounds).
+__device__ __forceinline__ void ring_append(int32_t *__restrict__ ring, int wpos, uint32_t sel, int c, int c_ok,
+                                            int half, int base)
 {
-    uint32_t mine = sel & mine_pos;
-    while (mine) {
-        const int pos = __ffs(mine) - 1;
-        const int w = cursor + __popc(sel & ((1u << pos) - 1u));
-        if (live && w < limit) out[w] = base + pos;
-        mine &= mine - 1;
+    uint32_t work = half ? __builtin_bitreverse32(sel) : sel;
+    const int mine = half ? (c >> 1) : ((c + 1) >> 1);
+    for (int i = 0; i < mine; ++i) {
+        const int p = __ffs(work) - 1;
+        work &= work - 1;
+        const int pos = half ? 31 - p : p;
+        const int rank = half ? c - 1 - i : i;
+        if (rank < c_ok) ring[(wpos + rank) & (kRing - 1)] = base + pos;
+    }
+}
+
+// Flush 32 entries of every owner that holds at least 32.  wpos / done: entries appended / already
+// written for this lane's owner (identical in both lanes of the owner); out_base: where the owner's
+// row starts in memory (element pointer, identical in both lanes).  Returns the new `done`.
+__device__ __forceinline__ int ring_flush_full(const int32_t *__restrict__ rings, int wpos, int done,
+                                               int32_t *__restrict__ out_base, int lane)
+{
+    const int n = lane & 31, half = lane >> 5;
+    uint32_t pending = (uint32_t)__ballot(wpos - done >= 32);  // low half: one bit per owner
+    while (pending) {
+        const int o1 = __ffs(pending) - 1;
+        pending &= pending - 1;
+        const int o2 = pending ? __ffs(pending) - 1 : -1;
+        if (o2 >= 0) pending &= pending - 1;
+        const int o = half ? o2 : o1;  // lanes 0..31 move owner o1, lanes 32..63 owner o2
+        if (o >= 0) {
+            const int d = __shfl(done, o);
+            int32_t *dst = reinterpret_cast<int32_t *>(__shfl((long long)out_base, o));
+            dst[d + n] = rings[o * kRing + ((d + n) & (kRing - 1))];
+        }
+        if (n == o1 || n == o2) done += 32;
+    }
+    return done;
+}
+
+// Write out whatever is left (fewer than 32 entries per owner after the last ring_flush_full).
+__device__ __forceinline__ void ring_flush_rest(const int32_t *__restrict__ rings, int wpos, int done,
+                                                int32_t *__restrict__ out_base, int lane)
+{
+    const int n = lane & 31, half = lane >> 5;
+    for (int o0 = 0; o0 < 32; o0 += 2) {
+        const int o = o0 + half;
+        const int d = __shfl(done, o);
+        const int left = __shfl(wpos, o) - d;
+        int32_t *dst = reinterpret_cast<int32_t *>(__shfl((long long)out_base, o));
+        if (n < left) dst[d + n] = rings[o * kRing + ((d + n) & (kRing - 1))];
     }
 }
 
@@ -85,8 +137,8 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
     int32_t *row = idx + tab.off[slot] + (int64_t)qi * k;
 
     const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
-    const uint32_t mine_pos = 0x0F0F0F0Fu << (4 * half);
-    int cursor = 0, ties_taken = 0, last_tie = -1;
+    __shared__ int32_t rings[32 * kRing];
+    int wpos = 0, done = 0, ties_taken = 0, last_tie = -1;
     const int ntiles = (L + 31) >> 5;
     for (int tile = 0; tile < ntiles; ++tile) {
         const int j0 = tile * 32;
@@ -112,9 +164,14 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
             }
             sel = mgt | meq;
         }
-        append_selected(row, cursor, k, sel, mine_pos, j0, live);
-        cursor += __popc(sel);
+        if (!live) sel = 0u;
+        const int c = __popc(sel);
+        const int c_ok = min(c, k - wpos);
+        ring_append(rings + n * kRing, wpos, sel, c, c_ok, half, j0);
+        wpos += c_ok;
+        done = ring_flush_full(rings, wpos, done, row, lane);
     }
+    ring_flush_rest(rings, wpos, done, row, lane);
     if (live && half == 0) {
         prefix[g] = __float_as_uint(tau);
         if (jcut) jcut[g] = kr < 0 ? kAllTies : last_tie;
@@ -150,9 +207,15 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
     const int j = min(j0 + n, L - 1);
 
     const Frag<T, R> kf = load_frag<T, R>(Kb, j0, L, lane);
-    const uint32_t mine_pos = 0x0F0F0F0Fu << (4 * half);
-    int32_t *list = WRITE ? idxT + tab.off[slot] + col[(int64_t)bh * (L + 1) + j] : nullptr;
-    int cursor = 0;
+    __shared__ int32_t rings[WRITE ? 32 * kRing : 1];
+    int32_t *list = nullptr;
+    int limit = 0x7FFFFFFF;
+    if (WRITE) {
+        const int64_t *cp = col + (int64_t)bh * (L + 1) + j;
+        list = idxT + tab.off[slot] + cp[0];
+        limit = (int)(cp[1] - cp[0]);
+    }
+    int wpos = 0, done = 0;
     for (int qt = 0; qt < ntiles; ++qt) {
         const int q0 = qt * 32;
         const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
@@ -180,10 +243,18 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
         }
         uint32_t sel = merge_halves(m, half) & valid;
         if (!live) sel = 0u;
-        if (WRITE) append_selected(list, cursor, 0x7FFFFFFF, sel, mine_pos, q0, live);
-        cursor += __popc(sel);
+        const int c = __popc(sel);
+        if (WRITE) {
+            const int c_ok = min(c, limit - wpos);
+            ring_append(rings + n * kRing, wpos, sel, c, c_ok, half, q0);
+            wpos += c_ok;
+            done = ring_flush_full(rings, wpos, done, list, lane);
+        } else {
+            wpos += c;
+        }
     }
-    if (!WRITE && live && half == 0) cnt[(int64_t)bh * L + j] = cursor;
+    if (WRITE) ring_flush_rest(rings, wpos, done, list, lane);
+    if (!WRITE && live && half == 0) cnt[(int64_t)bh * L + j] = wpos;
 }
 
 // One block per (b, h): exclusive scan of cnt [L] into col [L+1] (int64).
