@@ -11,7 +11,8 @@ from typing import Optional, Sequence
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libdsv.so")
+# DSV_LIBRARY: load another build of the same library (tuning builds); default: the in-tree build
+_LIB_PATH = os.environ.get("DSV_LIBRARY") or os.path.join(_PKG, "libdsv.so")
 
 DSV_F32, DSV_BF16 = 0, 1
 DSV_FLAG_SORTED_INDEX = 1

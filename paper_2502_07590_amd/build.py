@@ -27,14 +27,18 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every source for gfx950 and link libdsv.so.  Always recompiles."""
+def build_library(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    """Compile every source for gfx950 and link libdsv.so.  Always recompiles.
+
+    extra_flags / out: for tuning builds (e.g. ("-DDSV_LPR_DQ=8",) into another file name); the
+    environment variable DSV_HIPCC_FLAGS adds flags as well."""
     os.makedirs(OBJ, exist_ok=True)
     hipcc = _hipcc()
+    extra = list(extra_flags) + os.environ.get("DSV_HIPCC_FLAGS", "").split()
 
     def compile_one(src: str) -> str:
         obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-        cmd = [hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         res = subprocess.run(cmd, capture_output=True, text=True)
         noise = "is not a recognized feature for this target"
         err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
@@ -46,11 +50,11 @@ def build_library(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stderr}")
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

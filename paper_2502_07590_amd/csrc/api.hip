@@ -125,7 +125,7 @@ FwdLayout fwd_layout(const dsv_problem &p)
 struct StepLayout {
     bool split;
     SplitPlan plan;
-    size_t seg, pa, pb, pdelta, hist, order, total;
+    size_t seg, pa, pb, pdelta, hist, order, rowstat, total;
 };
 
 StepLayout step_layout(const dsv_problem &p)
@@ -143,6 +143,7 @@ StepLayout step_layout(const dsv_problem &p)
     w.pdelta = o; o = align_up(o + rows * w.plan.S * 4, 256);
     w.hist = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 4, 256);
     w.order = o; o = align_up(o + rows * 4, 256);
+    w.rowstat = o; o = align_up(o + rows * 8, 256);
     w.total = o;
     return w;
 }
@@ -156,6 +157,7 @@ BwdSplitWorkspace step_buffers(char *ws, const StepLayout &w)
     b.pdelta = reinterpret_cast<float *>(ws + w.pdelta);
     b.hist = reinterpret_cast<int32_t *>(ws + w.hist);
     b.order = reinterpret_cast<int32_t *>(ws + w.order);
+    b.rowstat = reinterpret_cast<float2 *>(ws + w.rowstat);
     return b;
 }
 

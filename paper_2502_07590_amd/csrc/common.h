@@ -56,6 +56,21 @@ __device__ __forceinline__ float row16_sum(float x)
     return x;
 }
 
+// Sum over the LPR (4, 8 or 16) consecutive lanes that share one row; every lane ends with the total.
+template <int LPR> __device__ __forceinline__ float row_sum(float x)
+{
+    static_assert(LPR == 4 || LPR == 8 || LPR == 16, "lanes per row");
+    if constexpr (LPR == 16) {
+        return row16_sum(x);
+    } else {
+        if constexpr (LPR == 8)  // row_half_mirror: lane i <-> 7 - i inside each group of 8
+            x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, false));
+        x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+        x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+        return x;
+    }
+}
+
 __device__ __forceinline__ float row16_max(float x)
 {
     x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x128, 0xF, 0xF, false)));
@@ -173,7 +188,7 @@ struct SplitPlan {
     int range_len;  // keys (queries) per range
     int S;          // ranges
     int S_pad;      // S rounded up to a multiple of 8 (one XCD per residue class)
-    int nqb;        // blocks of 16 rows per range
+    int nqb;        // row blocks per range (each kernel sets it from its own rows per block)
 };
 SplitPlan make_split_plan(const dsv_problem &p);
 
@@ -195,6 +210,7 @@ struct BwdSplitWorkspace {
     float *pdelta;  // [B*H, L, S]   (dq step only)
     int32_t *hist;  // [B*H, L+1]    keys per list length (dkdv step only)
     int32_t *order; // [B*H, L]      keys by descending list length (dkdv step only)
+    float2 *rowstat;  // [B*H, L]    {lse * log2(e), Delta} per query (dkdv step only)
 };
 dsv_status launch_bwd_dq_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                                const void *V, const int32_t *idx, const void *O, const float *lse, const void *dO,

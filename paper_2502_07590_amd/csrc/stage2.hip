@@ -11,19 +11,20 @@
 namespace dsv {
 
 // ------------------------------------------------------------------------------------ forward
-template <typename T, int D>
+template <typename T, int D, int LPR>
 __global__ __launch_bounds__(256) void sparse_fwd_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                          const T *__restrict__ V, const int32_t *__restrict__ idx,
                                                          T *__restrict__ O, float *__restrict__ lse, int L,
                                                          float scale, HeadTable tab)
 {
-    constexpr int CH = D / 16;
+    constexpr int CH = D / LPR;
+    constexpr int RPW = 64 / LPR;  // rows per wave
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane >> 4, s = lane & 15;
-    const int64_t iq = (int64_t)blockIdx.x * 16 + wave * 4 + grp;
+    const int grp = lane / LPR, s = lane % LPR;
+    const int64_t iq = (int64_t)blockIdx.x * (4 * RPW) + wave * RPW + grp;
     const bool live = iq < L;
     const int64_t i = live ? iq : L - 1;
     const int64_t head_base = (int64_t)bh * L * D;
@@ -35,7 +36,7 @@ __global__ __launch_bounds__(256) void sparse_fwd_kernel(const T *__restrict__ Q
     st.l = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) st.acc[c] = 0.f;
-    fwd_sweep<T, D>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e);
+    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e);
 
     const float inv = 1.f / st.l;
 #pragma unroll
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(256) void sparse_fwd_kernel(const T *__restrict__ Q
 // with D0 = dO_i . O_stored as a centring value,
 //   dQ_i = scale * ( sum_j p_ij (dP_ij - D0) k_j  -  (Delta_i - D0) * sum_j p_ij k_j ).
 // Delta is kept for the dkdv pass.
-template <typename T, int D>
+template <typename T, int D, int LPR>
 __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                             const T *__restrict__ V,
                                                             const int32_t *__restrict__ idx, const T *__restrict__ O,
@@ -65,13 +66,14 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict_
                                                             T *__restrict__ dQ, float *__restrict__ delta_out, int L,
                                                             float scale, HeadTable tab)
 {
-    constexpr int CH = D / 16;
+    constexpr int CH = D / LPR;
+    constexpr int RPW = 64 / LPR;  // rows per wave
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane >> 4, s = lane & 15;
-    const int64_t iq = (int64_t)blockIdx.x * 16 + wave * 4 + grp;
+    const int grp = lane / LPR, s = lane % LPR;
+    const int64_t iq = (int64_t)blockIdx.x * (4 * RPW) + wave * RPW + grp;
     const bool live = iq < L;
     const int64_t i = live ? iq : L - 1;
     const int64_t head_base = (int64_t)bh * L * D;
@@ -80,12 +82,12 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict_
     const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
     const RowChunk<T, CH> go = load_chunk<T, CH>(dO + head_base + i * D + s * CH);
     const RowChunk<T, CH> o = load_chunk<T, CH>(O + head_base + i * D + s * CH);
-    const float delta0 = row16_sum(dot_chunk<T, CH>(go, o));
+    const float delta0 = row_sum<LPR>(dot_chunk<T, CH>(go, o));
     DqState<CH> st;
     st.delta = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.a[c] = 0.f; st.b[c] = 0.f; }
-    dq_sweep<T, D>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e,
+    dq_sweep<T, D, LPR>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e,
                    lse[(int64_t)bh * L + i] * kLog2e, delta0);
     if (live) {
         float dq[CH];
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict_
 // dkdv pass: a group of 16 lanes owns key j and walks the queries that selected it.
 //   dK_j = scale * sum_i dS_ij q_i,  dV_j = sum_i p_ij dO_i,  dS_ij = p_ij (dO_i . v_j - Delta_i).
 // Keys with an empty list get zeros; every output row is written exactly once.
-template <typename T, int D>
+template <typename T, int D, int LPR>
 __global__ __launch_bounds__(256) void sparse_bwd_dkdv_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                               const T *__restrict__ V,
                                                               const int32_t *__restrict__ idxT,
@@ -109,12 +111,13 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_kernel(const T *__restric
                                                               const T *__restrict__ dO, T *__restrict__ dK,
                                                               T *__restrict__ dV, int L, float scale, HeadTable tab)
 {
-    constexpr int CH = D / 16;
+    constexpr int CH = D / LPR;
+    constexpr int RPW = 64 / LPR;  // rows per wave
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane >> 4, s = lane & 15;
-    const int64_t jq = (int64_t)blockIdx.x * 16 + wave * 4 + grp;
+    const int grp = lane / LPR, s = lane % LPR;
+    const int64_t jq = (int64_t)blockIdx.x * (4 * RPW) + wave * RPW + grp;
     const bool live = jq < L;
     const int64_t j = live ? jq : L - 1;
     const int64_t head_base = (int64_t)bh * L * D;
@@ -128,7 +131,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_kernel(const T *__restric
     DkdvState<CH> st;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.dk[c] = 0.f; st.dv[c] = 0.f; }
-    dkdv_sweep<T, D>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L, delta + (int64_t)bh * L,
+    dkdv_sweep<T, D, LPR>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L, delta + (int64_t)bh * L,
                      (uint32_t)(s * CH), list, 0, n, scale * kLog2e);
     if (live) {
 #pragma unroll
@@ -219,8 +222,8 @@ static dsv_status fwd_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs,
                         const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st)
 {
     for (int t = 0; t < n_tabs; ++t) {
-        dim3 grid((p.L + 15) / 16, tabs[t].n);
-        hipLaunchKernelGGL((sparse_fwd_kernel<T, D>), grid, dim3(256), 0, st, (const T *)Q, (const T *)K, (const T *)V,
+        dim3 grid((p.L + 256 / kLprFwd - 1) / (256 / kLprFwd), tabs[t].n);
+        hipLaunchKernelGGL((sparse_fwd_kernel<T, D, kLprFwd>), grid, dim3(256), 0, st, (const T *)Q, (const T *)K, (const T *)V,
                            idx, (T *)O, lse, p.L, p.scale, tabs[t]);
         DSV_LAUNCH_CHECK();
     }
@@ -233,8 +236,8 @@ static dsv_status bwd_dq_t(const dsv_problem &p, const HeadTable *tabs, int n_ta
                            void *dQ, float *delta, hipStream_t st)
 {
     for (int t = 0; t < n_tabs; ++t) {
-        dim3 qgrid((p.L + 15) / 16, tabs[t].n);
-        hipLaunchKernelGGL((sparse_bwd_dq_kernel<T, D>), qgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
+        dim3 qgrid((p.L + 256 / kLprDq - 1) / (256 / kLprDq), tabs[t].n);
+        hipLaunchKernelGGL((sparse_bwd_dq_kernel<T, D, kLprDq>), qgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
                            (const T *)V, idx, (const T *)O, lse, (const T *)dO, (T *)dQ, delta, p.L, p.scale, tabs[t]);
         DSV_LAUNCH_CHECK();
     }
@@ -247,8 +250,8 @@ static dsv_status bwd_dkdv_t(const dsv_problem &p, const HeadTable *tabs, int n_
                              const float *delta, const void *dO, void *dK, void *dV, hipStream_t st)
 {
     for (int t = 0; t < n_tabs; ++t) {
-        dim3 kgrid((p.L + 15) / 16, tabs[t].n);
-        hipLaunchKernelGGL((sparse_bwd_dkdv_kernel<T, D>), kgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
+        dim3 kgrid((p.L + 256 / kLprDkdv - 1) / (256 / kLprDkdv), tabs[t].n);
+        hipLaunchKernelGGL((sparse_bwd_dkdv_kernel<T, D, kLprDkdv>), kgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
                            (const T *)V, idxT, col, lse, delta, (const T *)dO, (T *)dK, (T *)dV, p.L, p.scale, tabs[t]);
         DSV_LAUNCH_CHECK();
     }

@@ -1,9 +1,11 @@
 // Inner loops of stage 2, shared by the plain gather kernels (stage2.hip) and the L2-blocked
 // kernels (stage2_split.hip).
 //
-// Lane layout: a group of 16 lanes (one DPP row) owns one output row; lane s of the group holds
-// channels [s*CH, (s+1)*CH) of every [d]-vector, CH = d/16.  One wave-wide 16-byte load per lane
-// fetches four whole gathered rows (one per group) as four contiguous 256-byte segments.
+// Lane layout: a group of LPR consecutive lanes (4, 8 or 16) owns one output row; lane s of the group
+// holds channels [s*CH, (s+1)*CH) of every [d]-vector, CH = d/LPR, so a gathered row is fetched by its
+// group as contiguous 16-byte pieces (every quad of lanes covers 64 contiguous bytes).  Fewer lanes per
+// row mean more channels per lane: the per-pair bookkeeping (reductions, exponentials, weights,
+// addresses) is shared by more arithmetic, at the price of more registers.
 //
 // Each sweep walks positions [tb, te) of one index row (or key-major list):
 //   fwd_sweep   online softmax over the segment: running max m (log2 domain), l, acc = sum p v
@@ -24,6 +26,19 @@
 #include "common.h"
 
 namespace dsv {
+
+// Lanes per row of each sweep (rows per 256-thread block = 256 / lanes).  Tuned on MI355X at
+// L = 128k, bf16, d = 128; see the stage-2 notes of the design document.
+#ifndef DSV_LPR_FWD
+#define DSV_LPR_FWD 16
+#endif
+#ifndef DSV_LPR_DQ
+#define DSV_LPR_DQ 16
+#endif
+#ifndef DSV_LPR_DKDV
+#define DSV_LPR_DKDV 16
+#endif
+constexpr int kLprFwd = DSV_LPR_FWD, kLprDq = DSV_LPR_DQ, kLprDkdv = DSV_LPR_DKDV;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -152,12 +167,12 @@ template <int CH> struct FwdState {
     float acc[CH];
 };
 
-template <typename T, int D, bool TAIL>
-__device__ __forceinline__ void fwd_step(FwdState<D / 16> &st, const RowChunk<T, D / 16> &q, const T *__restrict__ Kh,
+template <typename T, int D, int LPR, bool TAIL>
+__device__ __forceinline__ void fwd_step(FwdState<D / LPR> &st, const RowChunk<T, D / LPR> &q, const T *__restrict__ Kh,
                                          const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
                                          int t0, int te, float c2)
 {
-    constexpr int CH = D / 16;
+    constexpr int CH = D / LPR;
     constexpr int U = 4;
     typedef RowChunk<T, CH> Chunk;
     int j[U];
@@ -173,7 +188,7 @@ __device__ __forceinline__ void fwd_step(FwdState<D / 16> &st, const RowChunk<T,
 #pragma unroll
     for (int u = 0; u < U; ++u) sc[u] = dot_chunk<T, CH>(q, kc[u]);
 #pragma unroll
-    for (int u = 0; u < U; ++u) sc[u] = row16_sum(sc[u]) * c2;
+    for (int u = 0; u < U; ++u) sc[u] = row_sum<LPR>(sc[u]) * c2;
     if (TAIL) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -196,14 +211,14 @@ __device__ __forceinline__ void fwd_step(FwdState<D / 16> &st, const RowChunk<T,
 }
 
 // positions [tb, te) of `row`; all 16 lanes of the group call with the same arguments.
-template <typename T, int D>
-__device__ __forceinline__ void fwd_sweep(FwdState<D / 16> &st, const RowChunk<T, D / 16> &q, const T *__restrict__ Kh,
+template <typename T, int D, int LPR>
+__device__ __forceinline__ void fwd_sweep(FwdState<D / LPR> &st, const RowChunk<T, D / LPR> &q, const T *__restrict__ Kh,
                                           const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
                                           int tb, int te, float c2)
 {
     int t0 = tb;
-    for (; t0 + 4 <= te; t0 += 4) fwd_step<T, D, false>(st, q, Kh, Vh, lane_off, row, t0, te, c2);
-    if (t0 < te) fwd_step<T, D, true>(st, q, Kh, Vh, lane_off, row, t0, te, c2);
+    for (; t0 + 4 <= te; t0 += 4) fwd_step<T, D, LPR, false>(st, q, Kh, Vh, lane_off, row, t0, te, c2);
+    if (t0 < te) fwd_step<T, D, LPR, true>(st, q, Kh, Vh, lane_off, row, t0, te, c2);
 }
 
 // ------------------------------------------------------------------------------------ dq sweep
@@ -212,13 +227,13 @@ template <int CH> struct DqState {
     float a[CH], b[CH];  // a: the centred sum C
 };
 
-template <typename T, int D, bool TAIL>
-__device__ __forceinline__ void dq_step(DqState<D / 16> &st, const RowChunk<T, D / 16> &q,
-                                        const RowChunk<T, D / 16> &go, const T *__restrict__ Kh,
+template <typename T, int D, int LPR, bool TAIL>
+__device__ __forceinline__ void dq_step(DqState<D / LPR> &st, const RowChunk<T, D / LPR> &q,
+                                        const RowChunk<T, D / LPR> &go, const T *__restrict__ Kh,
                                         const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
                                         int t0, int te, float c2, float lse2, float delta0)
 {
-    constexpr int CH = D / 16;
+    constexpr int CH = D / LPR;
     constexpr int U = 2;
     typedef RowChunk<T, CH> Chunk;
     int j[U];
@@ -233,8 +248,8 @@ __device__ __forceinline__ void dq_step(DqState<D / 16> &st, const RowChunk<T, D
     float p[U], wc[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const float sc = row16_sum(dot_chunk<T, CH>(q, kc[u]));
-        const float dp = row16_sum(dot_chunk<T, CH>(go, vc[u]));
+        const float sc = row_sum<LPR>(dot_chunk<T, CH>(q, kc[u]));
+        const float dp = row_sum<LPR>(dot_chunk<T, CH>(go, vc[u]));
         p[u] = fast_exp2(sc * c2 - lse2);
         if (TAIL && t0 + u >= te) p[u] = 0.f;
         st.delta = fmaf(p[u], dp, st.delta);
@@ -243,15 +258,15 @@ __device__ __forceinline__ void dq_step(DqState<D / 16> &st, const RowChunk<T, D
     axpy_pair2<T, CH>(st.a, st.b, kc[0], kc[1], wc[0], wc[1], p[0], p[1]);
 }
 
-template <typename T, int D>
-__device__ __forceinline__ void dq_sweep(DqState<D / 16> &st, const RowChunk<T, D / 16> &q,
-                                         const RowChunk<T, D / 16> &go, const T *__restrict__ Kh,
+template <typename T, int D, int LPR>
+__device__ __forceinline__ void dq_sweep(DqState<D / LPR> &st, const RowChunk<T, D / LPR> &q,
+                                         const RowChunk<T, D / LPR> &go, const T *__restrict__ Kh,
                                          const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
                                          int tb, int te, float c2, float lse2, float delta0)
 {
     int t0 = tb;
-    for (; t0 + 2 <= te; t0 += 2) dq_step<T, D, false>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
-    if (t0 < te) dq_step<T, D, true>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
+    for (; t0 + 2 <= te; t0 += 2) dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
+    if (t0 < te) dq_step<T, D, LPR, true>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
 }
 
 // ------------------------------------------------------------------------------------ dkdv sweep
@@ -259,14 +274,14 @@ template <int CH> struct DkdvState {
     float dk[CH], dv[CH];
 };
 
-template <typename T, int D, bool TAIL>
-__device__ __forceinline__ void dkdv_step(DkdvState<D / 16> &st, const RowChunk<T, D / 16> &kc,
-                                          const RowChunk<T, D / 16> &vc, const T *__restrict__ Qh,
+template <typename T, int D, int LPR, bool TAIL>
+__device__ __forceinline__ void dkdv_step(DkdvState<D / LPR> &st, const RowChunk<T, D / LPR> &kc,
+                                          const RowChunk<T, D / LPR> &vc, const T *__restrict__ Qh,
                                           const T *__restrict__ Gh, const float *__restrict__ lse_h,
                                           const float *__restrict__ delta_h, uint32_t lane_off,
                                           const int32_t *__restrict__ list, int t0, int te, float c2)
 {
-    constexpr int CH = D / 16;
+    constexpr int CH = D / LPR;
     constexpr int U = 2;
     typedef RowChunk<T, CH> Chunk;
     int iq[U];
@@ -278,14 +293,20 @@ __device__ __forceinline__ void dkdv_step(DkdvState<D / 16> &st, const RowChunk<
     for (int u = 0; u < U; ++u) {
         qc[u] = gather_chunk<T, CH>(Qh, (uint32_t)iq[u], D, lane_off);
         gc[u] = gather_chunk<T, CH>(Gh, (uint32_t)iq[u], D, lane_off);
-        l2[u] = lse_h[iq[u]] * kLog2e;
-        dl[u] = delta_h[iq[u]];
+        if (delta_h) {
+            l2[u] = lse_h[iq[u]] * kLog2e;
+            dl[u] = delta_h[iq[u]];
+        } else {  // lse_h is a packed array {lse * log2(e), Delta} per query: one 8-byte load
+            const float2 rs = reinterpret_cast<const float2 *>(lse_h)[iq[u]];
+            l2[u] = rs.x;
+            dl[u] = rs.y;
+        }
     }
     float p[U], ds[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const float sc = row16_sum(dot_chunk<T, CH>(qc[u], kc));
-        const float dp = row16_sum(dot_chunk<T, CH>(gc[u], vc));
+        const float sc = row_sum<LPR>(dot_chunk<T, CH>(qc[u], kc));
+        const float dp = row_sum<LPR>(dot_chunk<T, CH>(gc[u], vc));
         p[u] = fast_exp2(sc * c2 - l2[u]);
         if (TAIL && t0 + u >= te) p[u] = 0.f;
         ds[u] = p[u] * (dp - dl[u]);
@@ -295,16 +316,16 @@ __device__ __forceinline__ void dkdv_step(DkdvState<D / 16> &st, const RowChunk<
     axpy_pair_precise<T, CH>(st.dv, gc[0], gc[1], p[0], p[1]);
 }
 
-template <typename T, int D>
-__device__ __forceinline__ void dkdv_sweep(DkdvState<D / 16> &st, const RowChunk<T, D / 16> &kc,
-                                           const RowChunk<T, D / 16> &vc, const T *__restrict__ Qh,
+template <typename T, int D, int LPR>
+__device__ __forceinline__ void dkdv_sweep(DkdvState<D / LPR> &st, const RowChunk<T, D / LPR> &kc,
+                                           const RowChunk<T, D / LPR> &vc, const T *__restrict__ Qh,
                                            const T *__restrict__ Gh, const float *__restrict__ lse_h,
                                            const float *__restrict__ delta_h, uint32_t lane_off,
                                            const int32_t *__restrict__ list, int tb, int te, float c2)
 {
     int t0 = tb;
-    for (; t0 + 2 <= te; t0 += 2) dkdv_step<T, D, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
-    if (t0 < te) dkdv_step<T, D, true>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
+    for (; t0 + 2 <= te; t0 += 2) dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
+    if (t0 < te) dkdv_step<T, D, LPR, true>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
 }
 
 }  // namespace dsv

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void segment_ptr_kernel(const int32_t *__restr
 // ---- forward ----------------------------------------------------------------------------------
 // Partial softmax state of one (query, range): running max m (log2 domain), l = sum 2^(s-m),
 // acc = sum 2^(s-m) v.  Empty segments leave (m = -inf, l = 0, acc = 0).
-template <typename T, int D>
+template <typename T, int D, int LPR>
 __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                const T *__restrict__ V,
                                                                const int32_t *__restrict__ idx,
@@ -79,14 +79,15 @@ __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restri
                                                                float *__restrict__ pl_, float *__restrict__ pacc, int L,
                                                                float scale, HeadTable tab, SplitPlan pl)
 {
-    constexpr int CH = D / 16;
+    constexpr int CH = D / LPR;
+    constexpr int RPW = 64 / LPR;  // rows per wave
     int slot, range, qb;
     if (!decode_item(pl, blockIdx.x, slot, range, qb)) return;
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane >> 4, s = lane & 15;
-    const int64_t iq = (int64_t)qb * 16 + wave * 4 + grp;
+    const int grp = lane / LPR, s = lane % LPR;
+    const int64_t iq = (int64_t)qb * (4 * RPW) + wave * RPW + grp;
     const bool live = iq < L;
     const int64_t i = live ? iq : L - 1;
     const int64_t head_base = (int64_t)bh * L * D;
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restri
     st.l = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) st.acc[c] = 0.f;
-    fwd_sweep<T, D>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e);
+    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + i) * pl.S + range;
         store_chunk<float, CH>(pacc + slot_id * D + s * CH, st.acc);
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(256) void sparse_fwd_merge_kernel(const float *__re
 // ---- backward, dq step ---------------------------------------------------------------------------
 // Per (query, key range): C = sum p (dP - D0) k, B = sum p k, Delta = sum p dP over the segment, with
 // D0 = dO . O_stored (all three are plain sums over the selected keys, so partials simply add).
-template <typename T, int D>
+template <typename T, int D, int LPR>
 __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                   const T *__restrict__ V,
                                                                   const int32_t *__restrict__ idx,
@@ -155,14 +156,15 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__res
                                                                   float *__restrict__ pb, float *__restrict__ pdelta,
                                                                   int L, float scale, HeadTable tab, SplitPlan pl)
 {
-    constexpr int CH = D / 16;
+    constexpr int CH = D / LPR;
+    constexpr int RPW = 64 / LPR;  // rows per wave
     int slot, range, qb;
     if (!decode_item(pl, blockIdx.x, slot, range, qb)) return;
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane >> 4, s = lane & 15;
-    const int64_t iq = (int64_t)qb * 16 + wave * 4 + grp;
+    const int grp = lane / LPR, s = lane % LPR;
+    const int64_t iq = (int64_t)qb * (4 * RPW) + wave * RPW + grp;
     const bool live = iq < L;
     const int64_t i = live ? iq : L - 1;
     const int64_t head_base = (int64_t)bh * L * D;
@@ -173,12 +175,12 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__res
     const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
     const RowChunk<T, CH> go = load_chunk<T, CH>(dO + head_base + i * D + s * CH);
     const RowChunk<T, CH> o = load_chunk<T, CH>(O + head_base + i * D + s * CH);
-    const float delta0 = row16_sum(dot_chunk<T, CH>(go, o));
+    const float delta0 = row_sum<LPR>(dot_chunk<T, CH>(go, o));
     DqState<CH> st;
     st.delta = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.a[c] = 0.f; st.b[c] = 0.f; }
-    dq_sweep<T, D>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e,
+    dq_sweep<T, D, LPR>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e,
                    lse[(int64_t)bh * L + i] * kLog2e, delta0);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + i) * pl.S + range;
@@ -228,7 +230,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_merge_kernel(const float *_
 // contiguous segment per query range, whose Q / dO rows (and lse, Delta entries) stay in L2.
 // `order` (optional): keys sorted by descending list length, so that the four keys of a wave (and
 // the sixteen of a block) have segments of similar length; without it key = block position.
-template <typename T, int D>
+template <typename T, int D, int LPR>
 __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                     const T *__restrict__ V,
                                                                     const int32_t *__restrict__ idxT,
@@ -241,13 +243,14 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
                                                                     float *__restrict__ pdv, int L, float scale,
                                                                     HeadTable tab, SplitPlan pl)
 {
-    constexpr int CH = D / 16;
+    constexpr int CH = D / LPR;
+    constexpr int RPW = 64 / LPR;  // rows per wave
     int slot, range, kb;
     if (!decode_item(pl, blockIdx.x, slot, range, kb)) return;
     const int bh = tab.bh[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane >> 4, s = lane & 15;
-    const int64_t jpos = (int64_t)kb * 16 + wave * 4 + grp;
+    const int grp = lane / LPR, s = lane % LPR;
+    const int64_t jpos = (int64_t)kb * (4 * RPW) + wave * RPW + grp;
     const bool live = jpos < L;
     const int64_t jp = live ? jpos : L - 1;
     const int64_t j = order ? order[(int64_t)bh * L + jp] : jp;
@@ -261,8 +264,9 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
     DkdvState<CH> st;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.dk[c] = 0.f; st.dv[c] = 0.f; }
-    dkdv_sweep<T, D>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L, delta + (int64_t)bh * L,
-                     (uint32_t)(s * CH), list, tb, te, scale * kLog2e);
+    // delta == nullptr: lse is the packed {lse * log2(e), Delta} array (two floats per query)
+    dkdv_sweep<T, D, LPR>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L * (delta ? 1 : 2),
+                          delta ? delta + (int64_t)bh * L : nullptr, (uint32_t)(s * CH), list, tb, te, scale * kLog2e);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + j) * pl.S + range;
         store_chunk<float, CH>(pdk + slot_id * D + s * CH, st.dk);
@@ -294,6 +298,14 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_merge_kernel(const float 
     for (int c = 0; c < CH; ++c) a[c] *= scale;
     store_chunk<T, CH>(dK + row * D + s * CH, a);
     store_chunk<T, CH>(dV + row * D + s * CH, b);
+}
+
+// {lse * log2(e), Delta} of every query side by side, so that the dkdv sweep fetches both with one load.
+__global__ __launch_bounds__(256) void pack_rowstat_kernel(const float *__restrict__ lse, const float *__restrict__ delta,
+                                                           float2 *__restrict__ out, int64_t n)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e < n) out[e] = make_float2(lse[e] * kLog2e, delta[e]);
 }
 
 // ---- keys in order of descending list length (counting sort on the length) ---------------------
@@ -389,10 +401,12 @@ static dsv_status fwd_split_t(const dsv_problem &p, const HeadTable *tabs, int n
     dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idx, nullptr, w.seg, st);
     if (rc != DSV_OK) return rc;
     for (int t = 0; t < n_tabs; ++t) {
-        const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
+        SplitPlan lp = pl;
+        lp.nqb = (p.L + 256 / kLprFwd - 1) / (256 / kLprFwd);  // row blocks of this kernel's layout
+        const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
         if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-        hipLaunchKernelGGL((sparse_fwd_split_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
-                           (const T *)K, (const T *)V, idx, w.seg, w.pm, w.pl, w.pacc, p.L, p.scale, tabs[t], pl);
+        hipLaunchKernelGGL((sparse_fwd_split_kernel<T, D, kLprFwd>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
+                           (const T *)K, (const T *)V, idx, w.seg, w.pm, w.pl, w.pacc, p.L, p.scale, tabs[t], lp);
         DSV_LAUNCH_CHECK();
     }
     const int64_t n_rows = (int64_t)p.B * p.H * p.L;
@@ -411,11 +425,13 @@ static dsv_status bwd_dq_split_t(const dsv_problem &p, const HeadTable *tabs, in
     dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idx, nullptr, w.seg, st);
     if (rc != DSV_OK) return rc;
     for (int t = 0; t < n_tabs; ++t) {
-        const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
+        SplitPlan lp = pl;
+        lp.nqb = (p.L + 256 / kLprDq - 1) / (256 / kLprDq);  // row blocks of this kernel's layout
+        const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
         if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-        hipLaunchKernelGGL((sparse_bwd_dq_split_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
+        hipLaunchKernelGGL((sparse_bwd_dq_split_kernel<T, D, kLprDq>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
                            (const T *)K, (const T *)V, idx, w.seg, (const T *)O, lse, (const T *)dO, w.pa, w.pb,
-                           w.pdelta, p.L, p.scale, tabs[t], pl);
+                           w.pdelta, p.L, p.scale, tabs[t], lp);
         DSV_LAUNCH_CHECK();
     }
     const int64_t n_rows = (int64_t)p.B * p.H * p.L;
@@ -434,6 +450,9 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
     const int nbh = p.B * p.H;
     dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idxT, col, w.seg, st);
     if (rc != DSV_OK) return rc;
+    const int64_t nrows = (int64_t)nbh * p.L;
+    hipLaunchKernelGGL(pack_rowstat_kernel, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, st, lse, delta,
+                       w.rowstat, nrows);
     // keys by descending list length (w.hist: [B*H, L+1] counters, w.order: [B*H, L])
     const int64_t nh = (int64_t)nbh * (p.L + 1);
     hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nh + 255) / 256, 4096)), dim3(256), 0, st,
@@ -444,11 +463,14 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
     hipLaunchKernelGGL(keylen_scatter_kernel, kgrid, dim3(256), 0, st, col, p.L, w.hist, w.order);
     DSV_LAUNCH_CHECK();
     for (int t = 0; t < n_tabs; ++t) {
-        const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
+        SplitPlan lp = pl;
+        lp.nqb = (p.L + 256 / kLprDkdv - 1) / (256 / kLprDkdv);  // row blocks of this kernel's layout
+        const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
         if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-        hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, st,
-                           (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, w.order, lse, delta,
-                           (const T *)dO, w.pa, w.pb, p.L, p.scale, tabs[t], pl);
+        hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D, kLprDkdv>), dim3((unsigned)blocks), dim3(256), 0, st,
+                           (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, w.order,
+                           reinterpret_cast<const float *>(w.rowstat), (const float *)nullptr, (const T *)dO, w.pa,
+                           w.pb, p.L, p.scale, tabs[t], lp);
         DSV_LAUNCH_CHECK();
     }
     const int64_t n_rows = (int64_t)p.B * p.H * p.L;
