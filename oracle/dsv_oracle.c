@@ -274,28 +274,40 @@ void dsv_oracle_sparse_bwd_dq_rows(const float *Q, const float *K, const float *
 
 /* dK_j and dV_j for ONE key j, given the n queries that selected it.  For each such query the
  * caller passes its row data: Qs, dOs, Os [n, d], lses [n], and its index row idxs [n, k]
- * (every row contains j).  K, V [L, d].  Outputs dKj, dVj [d]. */
+ * (every row contains j).  K, V [L, d].  Outputs dKj, dVj [d].
+ * Each query's term (scale dS_aj q_a and p_aj dO_a) is formed independently (OpenMP across the
+ * queries), then the terms are summed in query order. */
 void dsv_oracle_sparse_bwd_dkdv_key(int32_t j, const float *Qs, const float *dOs, const double *Os,
                                     const double *lses, const int32_t *idxs, int64_t n,
                                     const float *K, const float *V, int d, int64_t k, double scale,
                                     double *dKj, double *dVj)
 {
-    double *p = (double *)malloc((size_t)k * sizeof(double));
-    double *dS = (double *)malloc((size_t)k * sizeof(double));
-    for (int c = 0; c < d; ++c) { dKj[c] = 0.0; dVj[c] = 0.0; }
-    for (int64_t a = 0; a < n; ++a) {
-        const int32_t *row = idxs + a * k;
-        row_p_and_ds(Qs + a * d, dOs + a * d, Os + a * d, lses[a], K, V, row, d, k, scale, p, dS);
-        for (int64_t t = 0; t < k; ++t) {
-            if (row[t] != j) continue;
-            for (int c = 0; c < d; ++c) {
-                dKj[c] += scale * dS[t] * (double)Qs[a * d + c];
-                dVj[c] += p[t] * (double)dOs[a * d + c];
+    double *termK = (double *)calloc((size_t)n * d, sizeof(double));
+    double *termV = (double *)calloc((size_t)n * d, sizeof(double));
+#pragma omp parallel
+    {
+        double *p = (double *)malloc((size_t)k * sizeof(double));
+        double *dS = (double *)malloc((size_t)k * sizeof(double));
+#pragma omp for schedule(static)
+        for (int64_t a = 0; a < n; ++a) {
+            const int32_t *row = idxs + a * k;
+            row_p_and_ds(Qs + a * d, dOs + a * d, Os + a * d, lses[a], K, V, row, d, k, scale, p, dS);
+            for (int64_t t = 0; t < k; ++t) {
+                if (row[t] != j) continue;
+                for (int c = 0; c < d; ++c) {
+                    termK[a * d + c] += scale * dS[t] * (double)Qs[a * d + c];
+                    termV[a * d + c] += p[t] * (double)dOs[a * d + c];
+                }
             }
         }
+        free(p);
+        free(dS);
     }
-    free(p);
-    free(dS);
+    for (int c = 0; c < d; ++c) { dKj[c] = 0.0; dVj[c] = 0.0; }
+    for (int64_t a = 0; a < n; ++a)
+        for (int c = 0; c < d; ++c) { dKj[c] += termK[a * d + c]; dVj[c] += termV[a * d + c]; }
+    free(termK);
+    free(termV);
 }
 
 /* Dense (full, non-causal) attention of one head, brute force: the L x L probability matrix
