@@ -5,12 +5,12 @@ One step = one pass of the whole path over one synthetic batch that is already r
     stage 1  dsv_lowrank_topk_t        (project, threshold search, emit idx and its transpose)
     stage 2  dsv_sparse_attn_fwd
              dsv_sparse_attn_bwd_dq, dsv_sparse_attn_bwd_dkdv
-             (the steps dsv_sparse_attn_bwd runs, called one by one so that each can be timed; the
-             transposed index comes from stage 1 instead of dsv_idx_transpose)
+             (the two steps dsv_sparse_attn_bwd_t runs, called one by one so that each can be timed)
 Workload: the L = 128k configuration of the benchmark list (6 heads = one GPU's head-parallel share
 of 24, d = 128, r = 16, k = 8192 per query, bf16).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-dense] [--no-cpu-baseline]
+                    [--density-sweep] [--unsorted] [--calibration-copy-mib N]
 """
 from __future__ import annotations
 
@@ -24,7 +24,18 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9   # 256 CUs x 64 fp32 lanes x 2.4 GHz, one (unpacked) VALU op per lane per clock
+
+# L2 -> fabric traffic of the stage-2 kernels at config 2, bytes per launch, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE, in KiB), each scaled by what the same counter reads for a plain 1 GiB
+# elementwise copy in the same run (FETCH_SIZE reads 0.5 GiB for it: factor 2.0; WRITE_SIZE reads
+# 1 GiB: factor 1.0).  See profiles/stage2_config2_pmc_traffic.md.
+PMC_TRAFFIC_CONFIG2 = {
+    "sparse_attn_fwd": int((83645683 * 2.0 + 7077955 * 1.0) * 1024),
+    "sparse_attn_bwd_dq": int((112355175 * 2.0 + 12976235 * 1.0) * 1024),
+    "sparse_attn_bwd_dkdv": int((209275407 * 2.0 + 12582978 * 1.0) * 1024),
+}
 
 
 def parse_args():
@@ -38,13 +49,15 @@ def parse_args():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-attention comparator")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-rows", type=int, default=0, help="query rows of the oracle sample (0 = auto)")
+    ap.add_argument("--density-sweep", action="store_true",
+                    help="also time the whole path at k/L = 0.5 .. 12.5 %% (same shape) and report the crossover with dense")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the steps, run one plain elementwise copy kernel (x + 0 over this many MiB of int32) "
                          "so that a rocprofv3 --pmc run holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
 
 
-def upload_inputs(cfg, seed, dev, torch, wl, np):
+def upload_inputs(cfg, seed, dev, torch, wl):
     td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     shape = (1, cfg.H, cfg.L, cfg.d)
     g = {n: torch.empty(shape, dtype=td, device=dev) for n in ("Q", "K", "V", "dO")}
@@ -58,6 +71,62 @@ def upload_inputs(cfg, seed, dev, torch, wl, np):
         Wq[h].copy_(torch.from_numpy(wq).to(td))
         Wk[h].copy_(torch.from_numpy(wk).to(td))
     return g, Wq, Wk
+
+
+class Path:
+    """Device buffers of one problem, allocated once, and the step that runs the whole path."""
+    NAMES = ("lowrank_topk_t", "sparse_attn_fwd", "sparse_attn_bwd_dq", "sparse_attn_bwd_dkdv")
+
+    def __init__(self, dsv, torch, cfg, ks, g, Wq, Wk, sorted_index):
+        self.dsv, self.torch, self.g, self.Wq, self.Wk = dsv, torch, g, Wq, Wk
+        dev = g["Q"].device
+        # stage 1 writes ascending rows and lists, so stage 2 may be told so (DSV_FLAG_SORTED_INDEX)
+        self.p = p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, [int(k) for k in ks], cfg.scale,
+                                 sorted_index=sorted_index)
+        self.nnz = p.nnz
+        self.idx = torch.empty(p.nnz, dtype=torch.int32, device=dev)
+        self.idx_t = torch.empty(p.nnz, dtype=torch.int32, device=dev)
+        self.col_ptr = torch.empty((cfg.H, cfg.L + 1), dtype=torch.int64, device=dev)
+        self.O, self.dQ, self.dK, self.dV = (torch.empty_like(g["Q"]) for _ in range(4))
+        self.lse = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
+        self.delta = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
+        self.ws1 = torch.empty(dsv.lowrank_topk_t_workspace(p), dtype=torch.uint8, device=dev)
+        self.ws2 = torch.empty(max(dsv.sparse_attn_fwd_workspace(p), dsv.sparse_attn_bwd_dq_workspace(p),
+                                   dsv.sparse_attn_bwd_dkdv_workspace(p), 256), dtype=torch.uint8, device=dev)
+
+    def calls(self):
+        d, p, g = self.dsv, self.p, self.g
+        return (
+            lambda: d.lowrank_topk_t(p, g["Q"], g["K"], self.Wq, self.Wk, idx=self.idx, idx_t=self.idx_t,
+                                     col_ptr=self.col_ptr, workspace=self.ws1),
+            lambda: d.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], self.idx, O=self.O, lse=self.lse, workspace=self.ws2),
+            lambda: d.sparse_attn_bwd_dq(p, g["Q"], g["K"], g["V"], self.idx, self.O, self.lse, g["dO"], dQ=self.dQ,
+                                         delta=self.delta, workspace=self.ws2),
+            lambda: d.sparse_attn_bwd_dkdv(p, g["Q"], g["K"], g["V"], self.idx_t, self.col_ptr, self.lse, self.delta,
+                                           g["dO"], dK=self.dK, dV=self.dV, workspace=self.ws2),
+        )
+
+    def time(self, steps, warmup):
+        """(ms_per_step by the host clock around `steps` steps, per-call ms from events on the launch stream)."""
+        torch = self.torch
+        calls = self.calls()
+        for _ in range(warmup):
+            for c in calls:
+                c()
+        torch.cuda.synchronize()
+        events = []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
+            ev[0].record()
+            for i, c in enumerate(calls):
+                c()
+                ev[i + 1].record()
+            events.append(ev)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        call_ms = {n: sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / steps for i, n in enumerate(self.NAMES)}
+        return wall_ms, call_ms
 
 
 def cpu_baseline(cfg, ks, seed, n_rows, wl, np):
@@ -83,10 +152,9 @@ def cpu_baseline(cfg, ks, seed, n_rows, wl, np):
     t0 = time.perf_counter()
     oracle.sparse_bwd_rows(t["Q"][rows], t["K"], t["V"], idx, t["dO"][rows], cfg.scale)
     t_bwd = time.perf_counter() - t0           # includes the forward it needs for O and lse
-    per_head = t_keys + (cfg.L / n_rows) * (t_s1 + t_fwd + t_bwd)
     mean_k_scale = float(np.mean(ks)) / k      # other heads scale with their own k in stage 2 only
     total = cfg.H * (t_keys + (cfg.L / n_rows) * (t_s1 + (t_fwd + t_bwd) * mean_k_scale))
-    return {"seconds_full_problem_extrapolated": total, "per_head_s": per_head, "sample_s": t_keys + t_s1 + t_fwd + t_bwd,
+    return {"seconds_full_problem_extrapolated": total, "sample_s": t_keys + t_s1 + t_fwd + t_bwd,
             "threads": oracle.max_threads(),
             "parts_s": {"project_keys": t_keys, "stage1_rows": t_s1, "fwd_rows": t_fwd, "bwd_rows": t_bwd}}
 
@@ -111,47 +179,12 @@ def main():
     dev = torch.device("cuda:0")
     cfg = wl.get_config(args.config)
     ks = wl.k_per_head(cfg, seed=args.seed)
-    # stage 1 writes ascending rows and lists, so stage 2 may be told so (DSV_FLAG_SORTED_INDEX)
-    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, ks.tolist(), cfg.scale, sorted_index=not args.unsorted)
     esize = 2 if cfg.dtype == "bf16" else 4
-    nnz = int(cfg.L * ks.astype(np.int64).sum())
     n_scores = cfg.H * cfg.L * cfg.L
 
     t_gen = time.perf_counter()
-    g, Wq, Wk = upload_inputs(cfg, args.seed, dev, torch, wl, np)
+    g, Wq, Wk = upload_inputs(cfg, args.seed, dev, torch, wl)
     t_gen = time.perf_counter() - t_gen
-
-    # device buffers, allocated once
-    idx = torch.empty(nnz, dtype=torch.int32, device=dev)
-    idx_t = torch.empty(nnz, dtype=torch.int32, device=dev)
-    col_ptr = torch.empty((cfg.H, cfg.L + 1), dtype=torch.int64, device=dev)
-    O = torch.empty_like(g["Q"]); dQ = torch.empty_like(g["Q"]); dK = torch.empty_like(g["Q"]); dV = torch.empty_like(g["Q"])
-    lse = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
-    delta = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
-    ws1 = torch.empty(dsv.lowrank_topk_t_workspace(p), dtype=torch.uint8, device=dev)
-    wsf = torch.empty(max(dsv.sparse_attn_fwd_workspace(p), dsv.sparse_attn_bwd_dq_workspace(p),
-                          dsv.sparse_attn_bwd_dkdv_workspace(p), 256), dtype=torch.uint8, device=dev)
-
-    names = ("lowrank_topk_t", "sparse_attn_fwd", "sparse_attn_bwd_dq", "sparse_attn_bwd_dkdv")
-
-    def step(events=None):
-        calls = (
-            lambda: dsv.lowrank_topk_t(p, g["Q"], g["K"], Wq, Wk, idx=idx, idx_t=idx_t, col_ptr=col_ptr, workspace=ws1),
-            lambda: dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx, O=O, lse=lse, workspace=wsf),
-            lambda: dsv.sparse_attn_bwd_dq(p, g["Q"], g["K"], g["V"], idx, O, lse, g["dO"], dQ=dQ, delta=delta, workspace=wsf),
-            lambda: dsv.sparse_attn_bwd_dkdv(p, g["Q"], g["K"], g["V"], idx_t, col_ptr, lse, delta, g["dO"], dK=dK, dV=dV,
-                                             workspace=wsf),
-        )
-        if events is None:
-            for c in calls:
-                c()
-            return
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
-        ev[0].record()
-        for i, c in enumerate(calls):
-            c()
-            ev[i + 1].record()
-        events.append(ev)
 
     if args.calibration_copy_mib:
         src = torch.zeros(args.calibration_copy_mib * (1 << 18), dtype=torch.int32, device=dev)
@@ -159,20 +192,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    events = []
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(events)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    call_ms = {n: 0.0 for n in names}
-    for ev in events:
-        for i, n in enumerate(names):
-            call_ms[n] += ev[i].elapsed_time(ev[i + 1]) / args.steps
+    path = Path(dsv, torch, cfg, ks, g, Wq, Wk, sorted_index=not args.unsorted)
+    nnz = path.nnz
+    ms_per_step, call_ms = path.time(args.steps, args.warmup)
 
     # ---- derived figures ------------------------------------------------------------------------
     flops_alg = 4.0 * cfg.H * cfg.L * cfg.d * cfg.r + 2.0 * cfg.r * n_scores + 14.0 * cfg.d * nnz
@@ -182,11 +204,23 @@ def main():
     # (forward, dq); one Q row + one dO row + the index + lse_i + Delta_i (dkdv)
     pair_bytes = {"sparse_attn_fwd": 2 * cfg.d * esize + 4, "sparse_attn_bwd_dq": 2 * cfg.d * esize + 4,
                   "sparse_attn_bwd_dkdv": 2 * cfg.d * esize + 12}
+    stage2 = {}
+    for n, pb in pair_bytes.items():
+        gbs = pb * nnz / (call_ms[n] * 1e-3) / 1e9
+        stage2[n] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4),
+                     "traffic": PMC_TRAFFIC_CONFIG2.get(n) if (args.config == 2 and not args.unsorted) else None,
+                     "algorithmic_bytes_per_launch": pb * nnz, "launch_ms": round(call_ms[n], 3)}
     dominant = max(pair_bytes, key=lambda n: call_ms[n])
-    achieved = pair_bytes[dominant] * nnz / (call_ms[dominant] * 1e-3) / 1e9
-    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "algorithmic_bytes_per_launch": pair_bytes[dominant] * nnz, "launch_ms": round(call_ms[dominant], 3)}
+    roofline = dict(stage2[dominant], kernel=dominant)
+    # stage 1 is selection work on plain VALU lanes: per score at least one subtract/compare and one
+    # mask update in each of its passes (4 threshold passes + emit + 2 key-major passes = 7)
+    s1_lane_ops = 2.0 * 7 * n_scores
+    s1 = {"bound": "alu", "achieved": round(s1_lane_ops / (call_ms["lowrank_topk_t"] * 1e-3) / 1e12, 3),
+          "peak": round(VALU_LANE_OPS_PER_S / 1e12, 2), "unit": "T lane-ops/s",
+          "frac": round(s1_lane_ops / (call_ms["lowrank_topk_t"] * 1e-3) / VALU_LANE_OPS_PER_S, 4),
+          "algorithmic_lane_ops_per_launch": s1_lane_ops, "launch_ms": round(call_ms["lowrank_topk_t"], 3),
+          "mfma_tflops": round(2.0 * cfg.r * n_scores * 7 / (call_ms["lowrank_topk_t"] * 1e-3) / 1e12, 2)}
 
     out = {
         "metric": "sparse attention fwd+bwd (stage 1 + stage 2) effective TFLOP/s at L=128k" if args.config == 2
@@ -195,14 +229,17 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "B": 1, "H": cfg.H, "L": cfg.L, "d": cfg.d, "r": cfg.r,
-                   "k_per_head": sorted(set(ks.tolist())), "nnz_pairs": nnz, "scale": cfg.scale, "seed": args.seed},
+                   "k_per_head": sorted(set(ks.tolist())), "nnz_pairs": nnz, "scale": cfg.scale, "seed": args.seed,
+                   "sorted_index_flag": not args.unsorted},
         "stage_ms": {n: round(v, 3) for n, v in call_ms.items()},
         "algorithmic_tflops": round(flops_alg / (ms_per_step * 1e-3) / 1e12, 2),
         "input_generation_s": round(t_gen, 1),
         "roofline": roofline,
+        "stage_rooflines": dict(stage2, lowrank_topk_t=s1),
     }
 
     # ---- dense comparator: library flash attention fwd+bwd at the same shape ----------------------
+    dense_ms = None
     if not args.no_dense:
         try:
             import torch.nn.functional as F
@@ -211,6 +248,7 @@ def main():
                 o = F.scaled_dot_product_attention(q, k_, v, scale=cfg.scale)
                 o.backward(g["dO"])
                 q.grad = k_.grad = v.grad = None
+            dense()
             dense()
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -227,6 +265,25 @@ def main():
             del q, k_, v
         except Exception as e:  # the comparator is optional context; the sparse path above is the product
             out["dense"] = {"error": repr(e)[:200]}
+
+    # ---- whole path at other densities, same shape (the table a dispatcher would consume) -----------
+    if args.density_sweep:
+        del path
+        torch.cuda.empty_cache()
+        sweep = []
+        for frac in (0.005, 0.01, 0.02, 0.03125, 0.0625, 0.10, 0.125):
+            kk = max(1, int(round(cfg.L * frac)))
+            pth = Path(dsv, torch, cfg, [kk] * cfg.H, g, Wq, Wk, sorted_index=not args.unsorted)
+            ms, cms = pth.time(2, 1)
+            sweep.append({"density": frac, "k": kk, "ms_per_step": round(ms, 2), "stage1_ms": round(cms["lowrank_topk_t"], 2),
+                          "stage2_ms": round(ms - cms["lowrank_topk_t"], 2),
+                          "speedup_over_dense": round(dense_ms / ms, 3) if dense_ms else None})
+            del pth
+            torch.cuda.empty_cache()
+        out["density_sweep"] = sweep
+        if dense_ms:
+            below = [s for s in sweep if s["ms_per_step"] <= dense_ms]
+            out["crossover_density"] = max(s["density"] for s in below) if below else None
 
     # ---- CPU oracle timed on a bounded sample ------------------------------------------------------
     if not args.no_cpu_baseline:

@@ -27,8 +27,14 @@
 
 namespace dsv {
 
-// Lanes per row of each sweep (rows per 256-thread block = 256 / lanes).  Tuned on MI355X at
-// L = 128k, bf16, d = 128; see the stage-2 notes of the design document.
+// Lanes per row of each sweep (rows per 256-thread block = 256 / lanes).  Measured on MI355X at
+// L = 128k, bf16, d = 128, k = 8192 (ms per launch): forward 16: 153, 8: 161, 4: 239; dq 16: 162, 8: 180+,
+// 4: 309; dkdv 16: 210, 8: 200, 4: 286 -- the dkdv sweep carries the most per-pair arithmetic and is the
+// one that gains from sharing it over 16 channels per lane; 4 lanes per row cost too many registers.
+// Backward sweeps issue two independent two-row steps per loop trip (more gathers in flight).
+#ifndef DSV_BWD_REP
+#define DSV_BWD_REP 2
+#endif
 #ifndef DSV_LPR_FWD
 #define DSV_LPR_FWD 16
 #endif
@@ -36,7 +42,7 @@ namespace dsv {
 #define DSV_LPR_DQ 16
 #endif
 #ifndef DSV_LPR_DKDV
-#define DSV_LPR_DKDV 16
+#define DSV_LPR_DKDV 8
 #endif
 constexpr int kLprFwd = DSV_LPR_FWD, kLprDq = DSV_LPR_DQ, kLprDkdv = DSV_LPR_DKDV;
 
@@ -265,6 +271,12 @@ __device__ __forceinline__ void dq_sweep(DqState<D / LPR> &st, const RowChunk<T,
                                          int tb, int te, float c2, float lse2, float delta0)
 {
     int t0 = tb;
+#if DSV_BWD_REP == 2
+    for (; t0 + 4 <= te; t0 += 4) {
+        dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
+        dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, row, t0 + 2, te, c2, lse2, delta0);
+    }
+#endif
     for (; t0 + 2 <= te; t0 += 2) dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
     if (t0 < te) dq_step<T, D, LPR, true>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
 }
@@ -324,6 +336,12 @@ __device__ __forceinline__ void dkdv_sweep(DkdvState<D / LPR> &st, const RowChun
                                            const int32_t *__restrict__ list, int tb, int te, float c2)
 {
     int t0 = tb;
+#if DSV_BWD_REP == 2
+    for (; t0 + 4 <= te; t0 += 4) {
+        dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
+        dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0 + 2, te, c2);
+    }
+#endif
     for (; t0 + 2 <= te; t0 += 2) dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
     if (t0 < te) dkdv_step<T, D, LPR, true>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
 }
