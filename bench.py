@@ -32,10 +32,13 @@ VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9   # 256 CUs x 64 fp32 lanes x 2.4 GHz, on
 # elementwise copy in the same run (FETCH_SIZE reads 0.5 GiB for it: factor 2.0; WRITE_SIZE reads
 # 1 GiB: factor 1.0).  See profiles/stage2_config2_pmc_traffic.md.
 PMC_TRAFFIC_CONFIG2 = {
-    "sparse_attn_fwd": int((83645683 * 2.0 + 7077955 * 1.0) * 1024),
-    "sparse_attn_bwd_dq": int((112355175 * 2.0 + 12976235 * 1.0) * 1024),
-    "sparse_attn_bwd_dkdv": int((209275407 * 2.0 + 12582978 * 1.0) * 1024),
+    "sparse_attn_fwd": int((83260913 * 2.0 + 7077939 * 1.0) * 1024),
+    "sparse_attn_bwd_dq": int((113600933 * 2.0 + 12976236 * 1.0) * 1024),
+    "sparse_attn_bwd_dkdv": int((82538253 * 2.0 + 12583079 * 1.0) * 1024),
 }
+# the gather sweep inside each stage-2 call (the kernel the roofline object is about)
+SWEEP_OF_CALL = {"sparse_attn_fwd": "fwd_sweep", "sparse_attn_bwd_dq": "dq_sweep", "sparse_attn_bwd_dkdv": "dkdv_sweep"}
+L1_PEAK_GBS = 256 * 64 * 2.4          # 256 CUs x 64 B per clock (vector L1 -> registers) x 2.4 GHz
 
 
 def parse_args():
@@ -107,26 +110,35 @@ class Path:
         )
 
     def time(self, steps, warmup):
-        """(ms_per_step by the host clock around `steps` steps, per-call ms from events on the launch stream)."""
+        """(ms_per_step by the host clock around `steps` steps, per-call ms from events on the launch stream,
+        per-kernel ms from the library's own events around single kernels, same stream, averaged over the steps)."""
         torch = self.torch
+        spans = self.dsv.KERNEL_SPANS
+        kern_ms = {s: 0.0 for s in spans}
         calls = self.calls()
         for _ in range(warmup):
             for c in calls:
                 c()
         torch.cuda.synchronize()
         events = []
+        self.dsv.kernel_timing(True)
         t0 = time.perf_counter()
-        for _ in range(steps):
+        for step in range(steps):
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
             ev[0].record()
             for i, c in enumerate(calls):
                 c()
                 ev[i + 1].record()
             events.append(ev)
+            # the library keeps one event pair per kernel, so they are read once per step; the read waits for
+            # this step's kernels (the wait is inside the timed region: ms_per_step includes it)
+            for s in spans:
+                kern_ms[s] += self.dsv.kernel_ms(s) / steps
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        self.dsv.kernel_timing(False)
         call_ms = {n: sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / steps for i, n in enumerate(self.NAMES)}
-        return wall_ms, call_ms
+        return wall_ms, call_ms, kern_ms
 
 
 def cpu_baseline(cfg, ks, seed, n_rows, wl, np):
@@ -194,7 +206,7 @@ def main():
 
     path = Path(dsv, torch, cfg, ks, g, Wq, Wk, sorted_index=not args.unsorted)
     nnz = path.nnz
-    ms_per_step, call_ms = path.time(args.steps, args.warmup)
+    ms_per_step, call_ms, kern_ms = path.time(args.steps, args.warmup)
 
     # ---- derived figures ------------------------------------------------------------------------
     flops_alg = 4.0 * cfg.H * cfg.L * cfg.d * cfg.r + 2.0 * cfg.r * n_scores + 14.0 * cfg.d * nnz
@@ -206,13 +218,18 @@ def main():
                   "sparse_attn_bwd_dkdv": 2 * cfg.d * esize + 12}
     stage2 = {}
     for n, pb in pair_bytes.items():
-        gbs = pb * nnz / (call_ms[n] * 1e-3) / 1e9
+        k_ms = kern_ms[SWEEP_OF_CALL[n]]          # the sweep kernel alone, by HIP events on its own stream
+        gbs = pb * nnz / (k_ms * 1e-3) / 1e9
         stage2[n] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4),
                      "traffic": PMC_TRAFFIC_CONFIG2.get(n) if (args.config == 2 and not args.unsorted) else None,
-                     "algorithmic_bytes_per_launch": pb * nnz, "launch_ms": round(call_ms[n], 3)}
-    dominant = max(pair_bytes, key=lambda n: call_ms[n])
-    roofline = dict(stage2[dominant], kernel=dominant)
+                     "algorithmic_bytes_per_launch": pb * nnz, "kernel": SWEEP_OF_CALL[n] + " kernel of " + n,
+                     "kernel_ms": round(k_ms, 3), "call_ms": round(call_ms[n], 3),
+                     # the requested bytes are served by L2 and the vector L1, not by HBM (see traffic): the
+                     # path that bounds the kernel is L1 -> registers, 64 B per clock per CU
+                     "l1_path": {"peak": round(L1_PEAK_GBS, 1), "unit": "GB/s", "frac": round(gbs / L1_PEAK_GBS, 4)}}
+    dominant = max(pair_bytes, key=lambda n: kern_ms[SWEEP_OF_CALL[n]])
+    roofline = dict(stage2[dominant])
     # stage 1 is selection work on plain VALU lanes: per score at least one subtract/compare and one
     # mask update in each of its passes (4 threshold passes + emit + 2 key-major passes = 7)
     s1_lane_ops = 2.0 * 7 * n_scores
@@ -232,6 +249,7 @@ def main():
                    "k_per_head": sorted(set(ks.tolist())), "nnz_pairs": nnz, "scale": cfg.scale, "seed": args.seed,
                    "sorted_index_flag": not args.unsorted},
         "stage_ms": {n: round(v, 3) for n, v in call_ms.items()},
+        "kernel_ms": {n: round(v, 3) for n, v in kern_ms.items()},
         "algorithmic_tflops": round(flops_alg / (ms_per_step * 1e-3) / 1e12, 2),
         "input_generation_s": round(t_gen, 1),
         "roofline": roofline,
@@ -274,7 +292,7 @@ def main():
         for frac in (0.005, 0.01, 0.02, 0.03125, 0.0625, 0.10, 0.125):
             kk = max(1, int(round(cfg.L * frac)))
             pth = Path(dsv, torch, cfg, [kk] * cfg.H, g, Wq, Wk, sorted_index=not args.unsorted)
-            ms, cms = pth.time(2, 1)
+            ms, cms, _ = pth.time(2, 1)
             sweep.append({"density": frac, "k": kk, "ms_per_step": round(ms, 2), "stage1_ms": round(cms["lowrank_topk_t"], 2),
                           "stage2_ms": round(ms - cms["lowrank_topk_t"], 2),
                           "speedup_over_dense": round(dense_ms / ms, 3) if dense_ms else None})

@@ -201,6 +201,30 @@ DSV_API dsv_status dsv_lowrank_scores_rows(const dsv_problem *p, const void *Qlr
                                    int32_t b, int32_t h, const int32_t *rows, int32_t n_rows,
                                    float *scores, void *hip_stream);
 
+/* ---- measurement aid -------------------------------------------------------------------------
+ * Not an operation of the method: lets a benchmark time single kernels inside the calls above with
+ * HIP events on the stream they are launched on.
+ * dsv_kernel_timing(1): from now on every call records a pair of events around each kernel span
+ * listed below (created on the current device at the first enable); (0) switches that off.
+ * Process-wide and not thread-safe; off by default; with it on, calls must not be captured into a
+ * HIP graph.
+ * dsv_kernel_ms: waits for the span's stop event of the most recent call that ran it and writes the
+ * elapsed milliseconds to *ms (HOST).  DSV_EINVAL if the span has not run since timing was enabled.
+ * When a call launches a span's kernel once per group of up to 64 heads, the span covers all of
+ * those launches. */
+typedef enum {
+  DSV_KERNEL_FWD_SWEEP = 0,   /* sparse forward gather sweep */
+  DSV_KERNEL_DQ_SWEEP = 1,    /* backward, query-major sweep */
+  DSV_KERNEL_DKDV_SWEEP = 2,  /* backward, key-major sweep */
+  DSV_KERNEL_THRESHOLD = 3,   /* stage 1: the four threshold-search passes together */
+  DSV_KERNEL_EMIT = 4,        /* stage 1: query-major emission */
+  DSV_KERNEL_EMIT_T_COUNT = 5,/* stage 1: key-major counting pass */
+  DSV_KERNEL_EMIT_T_WRITE = 6,/* stage 1: key-major emission */
+  DSV_KERNEL_COUNT = 7
+} dsv_kernel_span;
+DSV_API dsv_status dsv_kernel_timing(int32_t enable);
+DSV_API dsv_status dsv_kernel_ms(int32_t span, float *ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,5 +28,8 @@ from .binding import (  # noqa: F401
     sparse_attn_bwd_dkdv,
     lowrank_project,
     lowrank_scores_rows,
+    kernel_timing,
+    kernel_ms,
+    KERNEL_SPANS,
     EXPORTED_SYMBOLS,
 )

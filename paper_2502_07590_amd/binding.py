@@ -28,6 +28,7 @@ EXPORTED_SYMBOLS = (
     "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dq", "dsv_idx_transpose_workspace", "dsv_idx_transpose",
     "dsv_sparse_attn_bwd_dkdv_workspace", "dsv_sparse_attn_bwd_dkdv",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
+    "dsv_kernel_timing", "dsv_kernel_ms",
 )
 
 
@@ -90,6 +91,10 @@ def load_library():
     lib.dsv_lowrank_project.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
     lib.dsv_lowrank_scores_rows.restype = ctypes.c_int
     lib.dsv_lowrank_scores_rows.argtypes = [P, vp, vp, i32, i32, vp, i32, vp, vp]
+    lib.dsv_kernel_timing.restype = ctypes.c_int
+    lib.dsv_kernel_timing.argtypes = [i32]
+    lib.dsv_kernel_ms.restype = ctypes.c_int
+    lib.dsv_kernel_ms.argtypes = [i32, ctypes.POINTER(ctypes.c_float)]
     _lib = lib
     return lib
 
@@ -301,3 +306,16 @@ def lowrank_scores_rows(p: Problem, Qlr, Klr, b: int, h: int, rows, scores=None,
     _check(lib.dsv_lowrank_scores_rows(p.c, _ptr(Qlr), _ptr(Klr), int(b), int(h), _ptr(rows), n, _ptr(scores),
                                        _stream(stream)), "dsv_lowrank_scores_rows")
     return scores
+
+
+KERNEL_SPANS = ("fwd_sweep", "dq_sweep", "dkdv_sweep", "threshold", "emit", "emit_t_count", "emit_t_write")
+
+
+def kernel_timing(enable: bool):
+    _check(load_library().dsv_kernel_timing(1 if enable else 0), "dsv_kernel_timing")
+
+
+def kernel_ms(span: str) -> float:
+    ms = ctypes.c_float(0.0)
+    _check(load_library().dsv_kernel_ms(KERNEL_SPANS.index(span), ctypes.byref(ms)), "dsv_kernel_ms")
+    return float(ms.value)

@@ -7,6 +7,7 @@
 #include "common.h"
 
 namespace dsv {
+KernelTimer g_kernel_timer;
 namespace {
 
 bool supported_d(int d) { return d == 64 || d == 128; }
@@ -441,6 +442,29 @@ dsv_status dsv_lowrank_scores_rows(const dsv_problem *p, const void *Qlr, const 
     if (b < 0 || b >= p->B || h < 0 || h >= p->H) return DSV_EINVAL;
     if (!ok_ptrs({Qlr, Klr})) return DSV_EINVAL;
     return launch_scores_rows(*p, Qlr, Klr, b * p->H + h, rows, n_rows, scores, static_cast<hipStream_t>(hip_stream));
+}
+
+// ------------------------------------------------------------------------------------ measurement aid
+dsv_status dsv_kernel_timing(int32_t enable)
+{
+    dsv::KernelTimer &t = dsv::g_kernel_timer;
+    if (enable && !t.ev[0][0]) {
+        for (int i = 0; i < DSV_KERNEL_COUNT; ++i)
+            for (int e = 0; e < 2; ++e)
+                if (hipEventCreate(&t.ev[i][e]) != hipSuccess) return DSV_EHIP;
+    }
+    for (int i = 0; i < DSV_KERNEL_COUNT; ++i) t.recorded[i] = false;
+    t.on = enable != 0;
+    return DSV_OK;
+}
+
+dsv_status dsv_kernel_ms(int32_t span, float *ms)
+{
+    dsv::KernelTimer &t = dsv::g_kernel_timer;
+    if (!ms || span < 0 || span >= DSV_KERNEL_COUNT || !t.recorded[span]) return DSV_EINVAL;
+    if (hipEventSynchronize(t.ev[span][1]) != hipSuccess) return DSV_EHIP;
+    if (hipEventElapsedTime(ms, t.ev[span][0], t.ev[span][1]) != hipSuccess) return DSV_EHIP;
+    return DSV_OK;
 }
 
 }  // extern "C"

@@ -173,6 +173,27 @@ __device__ __forceinline__ float dot_chunk(const RowChunk<T, CH> &a, const RowCh
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Measurement aid behind dsv_kernel_timing / dsv_kernel_ms: when switched on, a KernelSpan records one
+// HIP event on the launch stream before and one after the kernel launches it encloses.
+struct KernelTimer {
+    bool on = false;
+    hipEvent_t ev[DSV_KERNEL_COUNT][2] = {};
+    bool recorded[DSV_KERNEL_COUNT] = {};
+};
+extern KernelTimer g_kernel_timer;
+struct KernelSpan {
+    int id;
+    hipStream_t st;
+    KernelSpan(int id_, hipStream_t st_) : id(id_), st(st_)
+    {
+        if (g_kernel_timer.on) (void)hipEventRecord(g_kernel_timer.ev[id][0], st);
+    }
+    ~KernelSpan()
+    {
+        if (g_kernel_timer.on) g_kernel_timer.recorded[id] = hipEventRecord(g_kernel_timer.ev[id][1], st) == hipSuccess;
+    }
+};
+
 // Host: entry points of the per-stage translation units (called from api.hip).
 dsv_status launch_project(const dsv_problem &p, const void *Q, const void *K, const void *Wq, const void *Wk,
                           void *Qlr, void *Klr, hipStream_t st);

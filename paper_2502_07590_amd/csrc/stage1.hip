@@ -256,13 +256,16 @@ static dsv_status select_t(const dsv_problem &p, const HeadTable *tabs, int n_ta
     const T *Ql = (const T *)Qlr;
     const T *Kl = (const T *)Klr;
     const int qtiles = (p.L + 31) / 32;
-    for (int t = 0; t < n_tabs; ++t) {
-        dim3 grid(qtiles, tabs[t].n);
-        hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-        hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-        hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-        hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-        DSV_LAUNCH_CHECK();
+    {
+        KernelSpan span(DSV_KERNEL_THRESHOLD, st);
+        for (int t = 0; t < n_tabs; ++t) {
+            dim3 grid(qtiles, tabs[t].n);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+            DSV_LAUNCH_CHECK();
+        }
     }
     return launch_emit(p, tabs, n_tabs, Qlr, Klr, b, st);
 }

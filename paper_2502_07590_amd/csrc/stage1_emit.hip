@@ -294,20 +294,28 @@ static dsv_status emit_all_t(const dsv_problem &p, const HeadTable *tabs, int n_
     const T *Kl = (const T *)Klr;
     const int tiles = (p.L + 31) / 32;
     const float *tau_f = reinterpret_cast<const float *>(b.prefix);
-    for (int t = 0; t < n_tabs; ++t) {
-        dim3 grid(tiles, tabs[t].n);
-        hipLaunchKernelGGL((emit_kernel<T, R>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem, b.idx,
-                           b.jcut, b.tile_flag);
-        DSV_LAUNCH_CHECK();
-        if (b.idx_t) {
-            hipLaunchKernelGGL((emit_t_kernel<T, R, false>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], tau_f, b.jcut,
-                               b.tile_flag, b.cnt, (const int64_t *)nullptr, (int32_t *)nullptr);
+    {
+        KernelSpan span(DSV_KERNEL_EMIT, st);
+        for (int t = 0; t < n_tabs; ++t) {
+            dim3 grid(tiles, tabs[t].n);
+            hipLaunchKernelGGL((emit_kernel<T, R>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem, b.idx,
+                               b.jcut, b.tile_flag);
             DSV_LAUNCH_CHECK();
         }
     }
     if (b.idx_t) {
+        {
+            KernelSpan span(DSV_KERNEL_EMIT_T_COUNT, st);
+            for (int t = 0; t < n_tabs; ++t) {
+                dim3 grid(tiles, tabs[t].n);
+                hipLaunchKernelGGL((emit_t_kernel<T, R, false>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], tau_f,
+                                   b.jcut, b.tile_flag, b.cnt, (const int64_t *)nullptr, (int32_t *)nullptr);
+                DSV_LAUNCH_CHECK();
+            }
+        }
         hipLaunchKernelGGL(list_scan_kernel, dim3(p.B * p.H), dim3(1024), 0, st, b.cnt, b.col, p.L);
         DSV_LAUNCH_CHECK();
+        KernelSpan span(DSV_KERNEL_EMIT_T_WRITE, st);
         for (int t = 0; t < n_tabs; ++t) {
             dim3 grid(tiles, tabs[t].n);
             hipLaunchKernelGGL((emit_t_kernel<T, R, true>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], tau_f, b.jcut,

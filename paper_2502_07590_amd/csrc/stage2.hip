@@ -221,6 +221,7 @@ template <typename T, int D>
 static dsv_status fwd_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                         const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st)
 {
+    KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
     for (int t = 0; t < n_tabs; ++t) {
         dim3 grid((p.L + 256 / kLprFwd - 1) / (256 / kLprFwd), tabs[t].n);
         hipLaunchKernelGGL((sparse_fwd_kernel<T, D, kLprFwd>), grid, dim3(256), 0, st, (const T *)Q, (const T *)K, (const T *)V,
@@ -235,6 +236,7 @@ static dsv_status bwd_dq_t(const dsv_problem &p, const HeadTable *tabs, int n_ta
                            const void *V, const int32_t *idx, const void *O, const float *lse, const void *dO,
                            void *dQ, float *delta, hipStream_t st)
 {
+    KernelSpan span(DSV_KERNEL_DQ_SWEEP, st);
     for (int t = 0; t < n_tabs; ++t) {
         dim3 qgrid((p.L + 256 / kLprDq - 1) / (256 / kLprDq), tabs[t].n);
         hipLaunchKernelGGL((sparse_bwd_dq_kernel<T, D, kLprDq>), qgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
@@ -249,6 +251,7 @@ static dsv_status bwd_dkdv_t(const dsv_problem &p, const HeadTable *tabs, int n_
                              const void *V, const int32_t *idxT, const int64_t *col, const float *lse,
                              const float *delta, const void *dO, void *dK, void *dV, hipStream_t st)
 {
+    KernelSpan span(DSV_KERNEL_DKDV_SWEEP, st);
     for (int t = 0; t < n_tabs; ++t) {
         dim3 kgrid((p.L + 256 / kLprDkdv - 1) / (256 / kLprDkdv), tabs[t].n);
         hipLaunchKernelGGL((sparse_bwd_dkdv_kernel<T, D, kLprDkdv>), kgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,

@@ -400,14 +400,17 @@ static dsv_status fwd_split_t(const dsv_problem &p, const HeadTable *tabs, int n
 {
     dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idx, nullptr, w.seg, st);
     if (rc != DSV_OK) return rc;
-    for (int t = 0; t < n_tabs; ++t) {
-        SplitPlan lp = pl;
-        lp.nqb = (p.L + 256 / kLprFwd - 1) / (256 / kLprFwd);  // row blocks of this kernel's layout
-        const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
-        if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-        hipLaunchKernelGGL((sparse_fwd_split_kernel<T, D, kLprFwd>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
-                           (const T *)K, (const T *)V, idx, w.seg, w.pm, w.pl, w.pacc, p.L, p.scale, tabs[t], lp);
-        DSV_LAUNCH_CHECK();
+    {
+        KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
+        for (int t = 0; t < n_tabs; ++t) {
+            SplitPlan lp = pl;
+            lp.nqb = (p.L + 256 / kLprFwd - 1) / (256 / kLprFwd);  // row blocks of this kernel's layout
+            const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
+            if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
+            hipLaunchKernelGGL((sparse_fwd_split_kernel<T, D, kLprFwd>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
+                               (const T *)K, (const T *)V, idx, w.seg, w.pm, w.pl, w.pacc, p.L, p.scale, tabs[t], lp);
+            DSV_LAUNCH_CHECK();
+        }
     }
     const int64_t n_rows = (int64_t)p.B * p.H * p.L;
     hipLaunchKernelGGL((sparse_fwd_merge_kernel<T, D>), dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st, w.pm,
@@ -424,15 +427,18 @@ static dsv_status bwd_dq_split_t(const dsv_problem &p, const HeadTable *tabs, in
 {
     dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idx, nullptr, w.seg, st);
     if (rc != DSV_OK) return rc;
-    for (int t = 0; t < n_tabs; ++t) {
-        SplitPlan lp = pl;
-        lp.nqb = (p.L + 256 / kLprDq - 1) / (256 / kLprDq);  // row blocks of this kernel's layout
-        const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
-        if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-        hipLaunchKernelGGL((sparse_bwd_dq_split_kernel<T, D, kLprDq>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
-                           (const T *)K, (const T *)V, idx, w.seg, (const T *)O, lse, (const T *)dO, w.pa, w.pb,
-                           w.pdelta, p.L, p.scale, tabs[t], lp);
-        DSV_LAUNCH_CHECK();
+    {
+        KernelSpan span(DSV_KERNEL_DQ_SWEEP, st);
+        for (int t = 0; t < n_tabs; ++t) {
+            SplitPlan lp = pl;
+            lp.nqb = (p.L + 256 / kLprDq - 1) / (256 / kLprDq);  // row blocks of this kernel's layout
+            const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
+            if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
+            hipLaunchKernelGGL((sparse_bwd_dq_split_kernel<T, D, kLprDq>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
+                               (const T *)K, (const T *)V, idx, w.seg, (const T *)O, lse, (const T *)dO, w.pa, w.pb,
+                               w.pdelta, p.L, p.scale, tabs[t], lp);
+            DSV_LAUNCH_CHECK();
+        }
     }
     const int64_t n_rows = (int64_t)p.B * p.H * p.L;
     hipLaunchKernelGGL((sparse_bwd_dq_merge_kernel<T, D>), dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st, w.pa,
@@ -462,16 +468,19 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
     hipLaunchKernelGGL(keylen_scan_kernel, dim3(nbh), dim3(1024), 0, st, w.hist, p.L + 1);
     hipLaunchKernelGGL(keylen_scatter_kernel, kgrid, dim3(256), 0, st, col, p.L, w.hist, w.order);
     DSV_LAUNCH_CHECK();
-    for (int t = 0; t < n_tabs; ++t) {
-        SplitPlan lp = pl;
-        lp.nqb = (p.L + 256 / kLprDkdv - 1) / (256 / kLprDkdv);  // row blocks of this kernel's layout
-        const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
-        if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-        hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D, kLprDkdv>), dim3((unsigned)blocks), dim3(256), 0, st,
-                           (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, w.order,
-                           reinterpret_cast<const float *>(w.rowstat), (const float *)nullptr, (const T *)dO, w.pa,
-                           w.pb, p.L, p.scale, tabs[t], lp);
-        DSV_LAUNCH_CHECK();
+    {
+        KernelSpan span(DSV_KERNEL_DKDV_SWEEP, st);
+        for (int t = 0; t < n_tabs; ++t) {
+            SplitPlan lp = pl;
+            lp.nqb = (p.L + 256 / kLprDkdv - 1) / (256 / kLprDkdv);  // row blocks of this kernel's layout
+            const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
+            if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
+            hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D, kLprDkdv>), dim3((unsigned)blocks), dim3(256), 0, st,
+                               (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, w.order,
+                               reinterpret_cast<const float *>(w.rowstat), (const float *)nullptr, (const T *)dO, w.pa,
+                               w.pb, p.L, p.scale, tabs[t], lp);
+            DSV_LAUNCH_CHECK();
+        }
     }
     const int64_t n_rows = (int64_t)p.B * p.H * p.L;
     hipLaunchKernelGGL((sparse_bwd_dkdv_merge_kernel<T, D>), dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st,

@@ -110,3 +110,27 @@ def test_k_equals_L_is_dense_attention():
     dQ_ref, dK_ref, dV_ref = oracle.dense_bwd(Q, K, V, dO, cfg.scale)
     for name, got, ref in (("O", O, O_ref), ("lse", lse, lse_ref), ("dQ", dQ, dQ_ref), ("dK", dK, dK_ref), ("dV", dV, dV_ref)):
         assert_close(name, got[0, 0], ref, "f32")
+
+
+def test_kernel_timing_spans():
+    """The measurement aid: spans report a positive time after a call, results are unchanged, and a
+    span that has not run since timing was switched on is an error."""
+    L, d, k = 640, 128, 48
+    cfg = make_cfg(L, d, 16, 1, "bf16", basis_rank=64, scale_num=2.0)
+    case = Case(cfg, [k])
+    idx = wl.random_subset_idx(L, k, L, seed=6, ascending=True)
+    plain = _run_stage2(case, [idx], sorted_index=True)
+    dsv.kernel_timing(True)
+    try:
+        with pytest.raises(dsv.DsvError):
+            dsv.kernel_ms("fwd_sweep")
+        timed = _run_stage2(case, [idx], sorted_index=True)
+        for span in ("fwd_sweep", "dq_sweep", "dkdv_sweep"):
+            ms = dsv.kernel_ms(span)
+            assert 0.0 < ms < 1000.0, (span, ms)
+        with pytest.raises(dsv.DsvError):
+            dsv.kernel_ms("emit")
+    finally:
+        dsv.kernel_timing(False)
+    for a, b in zip(plain, timed):
+        assert torch.equal(a, b)
