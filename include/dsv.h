@@ -14,7 +14,8 @@
  *                                    off[b*H+h] = sum over earlier (b', h') of L * k_per_head[h'],
  *                                    and holds [L, k_h] row-major (dsv_idx_offsets computes off).
  *     dsv_problem and the arrays it points to (k_per_head) are HOST memory, read during the call.
- *   - The library allocates and frees no device memory and keeps no state between calls.  Scratch
+ *   - The library allocates and frees no device memory and keeps no state between calls (the
+ *     optional measurement aid at the end of this header aside).  Scratch
  *     comes from the caller: ask dsv_*_workspace() for the size, pass a device buffer of at least
  *     that many bytes, aligned to 256 bytes.  Its contents are undefined afterwards.
  *   - Work is enqueued on the caller's HIP stream (hip_stream is a hipStream_t; NULL = the default
