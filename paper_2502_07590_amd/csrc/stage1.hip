@@ -61,8 +61,9 @@ __global__ __launch_bounds__(256) void project_kernel(const T *__restrict__ Q, c
 
 // ------------------------------------------------------------------------------------ radix pass
 // One digit of the search for the k-th largest score of each query.  Block = 32 queries of one
-// head, 4 waves striding over the key tiles, one shared [32][256] histogram in LDS (row stride 257
-// words so that equal digits of different queries fall in different banks).
+// head, 4 waves striding over the key tiles, one shared histogram in LDS laid out [256 digits][32
+// queries]: the bank of a counter depends on the query alone, so the 32 lanes of a half-wave (32
+// different queries) never collide, whatever their digits are.
 //   PASS 0 counts every key by the top digit; PASS p counts only keys whose higher digits equal
 //   the prefix found so far.  Afterwards: the digit whose bucket holds the k_rem-th largest
 //   remaining key is appended to the prefix and k_rem is reduced by the keys in higher buckets.
@@ -73,9 +74,8 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
                                                          HeadTable tab, uint32_t *__restrict__ prefix,
                                                          int32_t *__restrict__ krem)
 {
-    constexpr int STRIDE = 257;
     constexpr int SHIFT = 24 - 8 * PASS;
-    __shared__ uint32_t hist[32 * STRIDE];
+    __shared__ uint32_t hist[256 * 32];
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int q0 = blockIdx.x * 32;
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, half = lane >> 5;
 
-    for (int e = threadIdx.x; e < 32 * STRIDE; e += 256) hist[e] = 0;
+    for (int e = threadIdx.x; e < 256 * 32; e += 256) hist[e] = 0;
     __syncthreads();
 
     const int qi = min(q0 + n, L - 1);
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
     const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
     const int ntiles = (L + 31) >> 5;
     const int nfull = L >> 5;  // tiles with all 32 keys in range
-    uint32_t *hrow_mine = hist + n * STRIDE;
+    uint32_t *hcol_mine = hist + n;  // counter of digit b: hcol_mine[32 * b]
     // When every query of the tile has a threshold prefix in the positive floats (the usual case:
     // k < L/2), a score matches the prefix iff its RAW bits do: negative scores have the sign bit
     // set and can never match, and for positive floats the raw pattern is already monotone.  That
@@ -106,10 +106,29 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
         for (int tile = wave; tile < nfull; tile += 4) {
             const Frag<T, R> kf = load_frag<T, R>(Kb, tile * 32, L, lane);
             const floatx16_t acc = score_tile<T, R>(kf, qf);
+            constexpr uint32_t kLimit = 1u << ((SHIFT + 8) & 31);
+            if constexpr (PASS >= 2) {
+                // Matches are rare from the third digit on (a 16-bit prefix leaves about one score in a
+                // thousand): look at four scores at a time with plain xor / min, and only enter the
+                // masked histogram update for a group in which some lane has a match.
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const uint32_t bits = __float_as_uint(acc[v]);
-                if ((bits ^ raw_pre) < (1u << ((SHIFT + 8) & 31))) atomicAdd(&hrow_mine[(bits >> SHIFT) & 255u], 1u);
+                for (int v0 = 0; v0 < 16; v0 += 4) {
+                    uint32_t x[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) x[u] = __float_as_uint(acc[v0 + u]) ^ raw_pre;
+                    const uint32_t lo = min(min(x[0], x[1]), min(x[2], x[3]));
+                    if (__any(lo < kLimit)) {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            if (x[u] < kLimit) atomicAdd(&hcol_mine[((x[u] >> SHIFT) & 255u) * 32], 1u);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t bits = __float_as_uint(acc[v]);
+                    if ((bits ^ raw_pre) < kLimit) atomicAdd(&hcol_mine[((bits >> SHIFT) & 255u) * 32], 1u);
+                }
             }
         }
     } else {
@@ -121,7 +140,7 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
                 const uint32_t key = score_key(acc[v]);
                 bool ok = true;
                 if constexpr (PASS > 0) ok = (key >> (SHIFT + 8)) == (pre >> (SHIFT + 8));
-                if (ok) atomicAdd(&hrow_mine[(key >> SHIFT) & 255u], 1u);
+                if (ok) atomicAdd(&hcol_mine[((key >> SHIFT) & 255u) * 32], 1u);
             }
         }
     }
@@ -134,7 +153,7 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
             const uint32_t key = score_key(acc[v]);
             bool ok = j0 + tile_pos(v) + 4 * half < L;
             if constexpr (PASS > 0) ok = ok && ((key >> (SHIFT + 8)) == (pre >> (SHIFT + 8)));
-            if (ok) atomicAdd(&hrow_mine[(key >> SHIFT) & 255u], 1u);
+            if (ok) atomicAdd(&hcol_mine[((key >> SHIFT) & 255u) * 32], 1u);
         }
     }
     __syncthreads();
@@ -142,10 +161,10 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
     if (threadIdx.x < 32 && q0 + (int)threadIdx.x < L) {
         const int64_t g = (int64_t)bh * padded_len(L) + q0 + threadIdx.x;
         const int kr = PASS == 0 ? tab.k[slot] : krem[g];
-        const uint32_t *hrow = hist + threadIdx.x * STRIDE;
+        const uint32_t *hcol = hist + threadIdx.x;
         int above = 0, digit = 0;
         for (int b = 255; b >= 0; --b) {
-            const int c = (int)hrow[b];
+            const int c = (int)hcol[32 * b];
             if (above + c >= kr) { digit = b; break; }
             above += c;
         }
@@ -154,7 +173,7 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
         // after the last digit the bucket holds exactly the keys equal to the threshold: a negative
         // k_rem tells the emission that all of them are taken (then "score >= threshold" decides)
         const int want = kr - above;
-        krem[g] = (PASS == 3 && want == (int)hrow[digit]) ? -want : want;
+        krem[g] = (PASS == 3 && want == (int)hcol[32 * digit]) ? -want : want;
     }
 }
 
