@@ -36,7 +36,9 @@ __global__ __launch_bounds__(256) void sparse_fwd_kernel(const T *__restrict__ Q
     st.l = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) st.acc[c] = 0.f;
-    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e);
+    __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
+    int32_t *stage = stage_all[threadIdx.x / LPR];
+    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e, stage, s);
 
     const float inv = 1.f / st.l;
 #pragma unroll
@@ -87,8 +89,10 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict_
     st.delta = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.a[c] = 0.f; st.b[c] = 0.f; }
+    __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
+    int32_t *stage = stage_all[threadIdx.x / LPR];
     dq_sweep<T, D, LPR>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e,
-                   lse[(int64_t)bh * L + i] * kLog2e, delta0);
+                   lse[(int64_t)bh * L + i] * kLog2e, delta0, stage, s);
     if (live) {
         float dq[CH];
 #pragma unroll
@@ -131,8 +135,10 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_kernel(const T *__restric
     DkdvState<CH> st;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.dk[c] = 0.f; st.dv[c] = 0.f; }
+    __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
+    int32_t *stage = stage_all[threadIdx.x / LPR];
     dkdv_sweep<T, D, LPR>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L, delta + (int64_t)bh * L,
-                     (uint32_t)(s * CH), list, 0, n, scale * kLog2e);
+                     (uint32_t)(s * CH), list, 0, n, scale * kLog2e, stage, s);
     if (live) {
 #pragma unroll
         for (int c = 0; c < CH; ++c) st.dk[c] *= scale;

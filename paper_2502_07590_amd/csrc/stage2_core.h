@@ -173,10 +173,12 @@ template <int CH> struct FwdState {
     float acc[CH];
 };
 
+// jsrc: U staged index entries (LDS); TAIL: only the first nvalid of them count (the rest are valid
+// row numbers too -- duplicates of the segment's last entry -- and get weight zero).
 template <typename T, int D, int LPR, bool TAIL>
 __device__ __forceinline__ void fwd_step(FwdState<D / LPR> &st, const RowChunk<T, D / LPR> &q, const T *__restrict__ Kh,
-                                         const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
-                                         int t0, int te, float c2)
+                                         const T *__restrict__ Vh, uint32_t lane_off, const int32_t *jsrc, int nvalid,
+                                         float c2)
 {
     constexpr int CH = D / LPR;
     constexpr int U = 4;
@@ -184,7 +186,7 @@ __device__ __forceinline__ void fwd_step(FwdState<D / LPR> &st, const RowChunk<T
     int j[U];
     Chunk kc[U], vc[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) j[u] = row[TAIL ? min(t0 + u, te - 1) : t0 + u];
+    for (int u = 0; u < U; ++u) j[u] = jsrc[u];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         kc[u] = gather_chunk<T, CH>(Kh, (uint32_t)j[u], D, lane_off);
@@ -198,7 +200,7 @@ __device__ __forceinline__ void fwd_step(FwdState<D / LPR> &st, const RowChunk<T
     if (TAIL) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (t0 + u >= te) sc[u] = -INFINITY;
+            if (u >= nvalid) sc[u] = -INFINITY;
     }
     const float mblk = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
     if (mblk > st.m) {  // rescale only when the running max moves (rare after the first blocks)
@@ -216,15 +218,49 @@ __device__ __forceinline__ void fwd_step(FwdState<D / LPR> &st, const RowChunk<T
     axpy_pair<T, CH>(st.acc, vc[2], vc[3], p[2], p[3], sizeof(T) == 2 ? pack_bf16x2(p[2], p[3]) : 0u);
 }
 
-// positions [tb, te) of `row`; all 16 lanes of the group call with the same arguments.
+// ---- index staging ------------------------------------------------------------------------------
+// The lanes of a group all need the same index entries.  Reading them straight from memory costs one
+// full-width vector-memory instruction per step (as much address-path time as a whole gathered row)
+// and re-fetches each 128-byte line of the row eight times through a cache that the gathers keep
+// flushing.  Instead the group reads kStage entries at a time, each lane a different one (one
+// coalesced request), parks them in its own slot of LDS, and the steps fetch them from there with
+// 16-byte broadcast reads.  The next chunk is requested before the current one is consumed.
+constexpr int kStage = 32;
+
+template <int LPR> struct StagedIndex {
+    static constexpr int EPL = kStage / LPR;  // entries each lane fetches per chunk
+    int a[EPL];
+    // request entries [c0, c0 + kStage) of `row`, clamped to the segment's last entry te - 1
+    __device__ __forceinline__ void request(const int32_t *__restrict__ row, int c0, int te, int s)
+    {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) a[e] = row[min(c0 + e * LPR + s, te - 1)];
+    }
+    __device__ __forceinline__ void park(int32_t *stage, int s) const
+    {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) stage[e * LPR + s] = a[e];
+    }
+};
+
+// positions [tb, te) of `row`; all lanes of the group call with the same arguments.  stage: the
+// group's kStage-entry LDS slot (16-byte aligned); s: this lane's number inside the group.
 template <typename T, int D, int LPR>
 __device__ __forceinline__ void fwd_sweep(FwdState<D / LPR> &st, const RowChunk<T, D / LPR> &q, const T *__restrict__ Kh,
                                           const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
-                                          int tb, int te, float c2)
+                                          int tb, int te, float c2, int32_t *stage, int s)
 {
-    int t0 = tb;
-    for (; t0 + 4 <= te; t0 += 4) fwd_step<T, D, LPR, false>(st, q, Kh, Vh, lane_off, row, t0, te, c2);
-    if (t0 < te) fwd_step<T, D, LPR, true>(st, q, Kh, Vh, lane_off, row, t0, te, c2);
+    if (tb >= te) return;
+    StagedIndex<LPR> si;
+    si.request(row, tb, te, s);
+    for (int c0 = tb; c0 < te; c0 += kStage) {
+        si.park(stage, s);
+        if (c0 + kStage < te) si.request(row, c0 + kStage, te, s);
+        const int n = min(kStage, te - c0);
+        int it = 0;
+        for (; it + 4 <= n; it += 4) fwd_step<T, D, LPR, false>(st, q, Kh, Vh, lane_off, stage + it, 4, c2);
+        if (it < n) fwd_step<T, D, LPR, true>(st, q, Kh, Vh, lane_off, stage + it, n - it, c2);
+    }
 }
 
 // ------------------------------------------------------------------------------------ dq sweep
@@ -236,8 +272,8 @@ template <int CH> struct DqState {
 template <typename T, int D, int LPR, bool TAIL>
 __device__ __forceinline__ void dq_step(DqState<D / LPR> &st, const RowChunk<T, D / LPR> &q,
                                         const RowChunk<T, D / LPR> &go, const T *__restrict__ Kh,
-                                        const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
-                                        int t0, int te, float c2, float lse2, float delta0)
+                                        const T *__restrict__ Vh, uint32_t lane_off, const int32_t *jsrc, int nvalid,
+                                        float c2, float lse2, float delta0)
 {
     constexpr int CH = D / LPR;
     constexpr int U = 2;
@@ -245,7 +281,7 @@ __device__ __forceinline__ void dq_step(DqState<D / LPR> &st, const RowChunk<T, 
     int j[U];
     Chunk kc[U], vc[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) j[u] = row[TAIL ? min(t0 + u, te - 1) : t0 + u];
+    for (int u = 0; u < U; ++u) j[u] = jsrc[u];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         kc[u] = gather_chunk<T, CH>(Kh, (uint32_t)j[u], D, lane_off);
@@ -257,7 +293,7 @@ __device__ __forceinline__ void dq_step(DqState<D / LPR> &st, const RowChunk<T, 
         const float sc = row_sum<LPR>(dot_chunk<T, CH>(q, kc[u]));
         const float dp = row_sum<LPR>(dot_chunk<T, CH>(go, vc[u]));
         p[u] = fast_exp2(sc * c2 - lse2);
-        if (TAIL && t0 + u >= te) p[u] = 0.f;
+        if (TAIL && u >= nvalid) p[u] = 0.f;
         st.delta = fmaf(p[u], dp, st.delta);
         wc[u] = p[u] * (dp - delta0);
     }
@@ -268,17 +304,25 @@ template <typename T, int D, int LPR>
 __device__ __forceinline__ void dq_sweep(DqState<D / LPR> &st, const RowChunk<T, D / LPR> &q,
                                          const RowChunk<T, D / LPR> &go, const T *__restrict__ Kh,
                                          const T *__restrict__ Vh, uint32_t lane_off, const int32_t *__restrict__ row,
-                                         int tb, int te, float c2, float lse2, float delta0)
+                                         int tb, int te, float c2, float lse2, float delta0, int32_t *stage, int s)
 {
-    int t0 = tb;
+    if (tb >= te) return;
+    StagedIndex<LPR> si;
+    si.request(row, tb, te, s);
+    for (int c0 = tb; c0 < te; c0 += kStage) {
+        si.park(stage, s);
+        if (c0 + kStage < te) si.request(row, c0 + kStage, te, s);
+        const int n = min(kStage, te - c0);
+        int it = 0;
 #if DSV_BWD_REP == 2
-    for (; t0 + 4 <= te; t0 += 4) {
-        dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
-        dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, row, t0 + 2, te, c2, lse2, delta0);
-    }
+        for (; it + 4 <= n; it += 4) {
+            dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, stage + it, 2, c2, lse2, delta0);
+            dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, stage + it + 2, 2, c2, lse2, delta0);
+        }
 #endif
-    for (; t0 + 2 <= te; t0 += 2) dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
-    if (t0 < te) dq_step<T, D, LPR, true>(st, q, go, Kh, Vh, lane_off, row, t0, te, c2, lse2, delta0);
+        for (; it + 2 <= n; it += 2) dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, stage + it, 2, c2, lse2, delta0);
+        if (it < n) dq_step<T, D, LPR, true>(st, q, go, Kh, Vh, lane_off, stage + it, n - it, c2, lse2, delta0);
+    }
 }
 
 // ------------------------------------------------------------------------------------ dkdv sweep
@@ -291,7 +335,7 @@ __device__ __forceinline__ void dkdv_step(DkdvState<D / LPR> &st, const RowChunk
                                           const RowChunk<T, D / LPR> &vc, const T *__restrict__ Qh,
                                           const T *__restrict__ Gh, const float *__restrict__ lse_h,
                                           const float *__restrict__ delta_h, uint32_t lane_off,
-                                          const int32_t *__restrict__ list, int t0, int te, float c2)
+                                          const int32_t *jsrc, int nvalid, float c2)
 {
     constexpr int CH = D / LPR;
     constexpr int U = 2;
@@ -300,7 +344,7 @@ __device__ __forceinline__ void dkdv_step(DkdvState<D / LPR> &st, const RowChunk
     Chunk qc[U], gc[U];
     float l2[U], dl[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) iq[u] = list[TAIL ? min(t0 + u, te - 1) : t0 + u];
+    for (int u = 0; u < U; ++u) iq[u] = jsrc[u];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         qc[u] = gather_chunk<T, CH>(Qh, (uint32_t)iq[u], D, lane_off);
@@ -320,7 +364,7 @@ __device__ __forceinline__ void dkdv_step(DkdvState<D / LPR> &st, const RowChunk
         const float sc = row_sum<LPR>(dot_chunk<T, CH>(qc[u], kc));
         const float dp = row_sum<LPR>(dot_chunk<T, CH>(gc[u], vc));
         p[u] = fast_exp2(sc * c2 - l2[u]);
-        if (TAIL && t0 + u >= te) p[u] = 0.f;
+        if (TAIL && u >= nvalid) p[u] = 0.f;
         ds[u] = p[u] * (dp - dl[u]);
     }
     axpy_pair_precise<T, CH>(st.dk, qc[0], qc[1], ds[0], ds[1]);
@@ -333,17 +377,26 @@ __device__ __forceinline__ void dkdv_sweep(DkdvState<D / LPR> &st, const RowChun
                                            const RowChunk<T, D / LPR> &vc, const T *__restrict__ Qh,
                                            const T *__restrict__ Gh, const float *__restrict__ lse_h,
                                            const float *__restrict__ delta_h, uint32_t lane_off,
-                                           const int32_t *__restrict__ list, int tb, int te, float c2)
+                                           const int32_t *__restrict__ list, int tb, int te, float c2, int32_t *stage,
+                                           int s)
 {
-    int t0 = tb;
+    if (tb >= te) return;
+    StagedIndex<LPR> si;
+    si.request(list, tb, te, s);
+    for (int c0 = tb; c0 < te; c0 += kStage) {
+        si.park(stage, s);
+        if (c0 + kStage < te) si.request(list, c0 + kStage, te, s);
+        const int n = min(kStage, te - c0);
+        int it = 0;
 #if DSV_BWD_REP == 2
-    for (; t0 + 4 <= te; t0 += 4) {
-        dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
-        dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0 + 2, te, c2);
-    }
+        for (; it + 4 <= n; it += 4) {
+            dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it, 2, c2);
+            dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it + 2, 2, c2);
+        }
 #endif
-    for (; t0 + 2 <= te; t0 += 2) dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
-    if (t0 < te) dkdv_step<T, D, LPR, true>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, list, t0, te, c2);
+        for (; it + 2 <= n; it += 2) dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it, 2, c2);
+        if (it < n) dkdv_step<T, D, LPR, true>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it, n - it, c2);
+    }
 }
 
 }  // namespace dsv

@@ -101,7 +101,9 @@ __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restri
     st.l = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) st.acc[c] = 0.f;
-    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e);
+    __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
+    int32_t *stage = stage_all[threadIdx.x / LPR];
+    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e, stage, s);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + i) * pl.S + range;
         store_chunk<float, CH>(pacc + slot_id * D + s * CH, st.acc);
@@ -180,8 +182,10 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__res
     st.delta = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.a[c] = 0.f; st.b[c] = 0.f; }
+    __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
+    int32_t *stage = stage_all[threadIdx.x / LPR];
     dq_sweep<T, D, LPR>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e,
-                   lse[(int64_t)bh * L + i] * kLog2e, delta0);
+                   lse[(int64_t)bh * L + i] * kLog2e, delta0, stage, s);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + i) * pl.S + range;
         store_chunk<float, CH>(pa + slot_id * D + s * CH, st.a);
@@ -265,8 +269,10 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.dk[c] = 0.f; st.dv[c] = 0.f; }
     // delta == nullptr: lse is the packed {lse * log2(e), Delta} array (two floats per query)
+    __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
+    int32_t *stage = stage_all[threadIdx.x / LPR];
     dkdv_sweep<T, D, LPR>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L * (delta ? 1 : 2),
-                          delta ? delta + (int64_t)bh * L : nullptr, (uint32_t)(s * CH), list, tb, te, scale * kLog2e);
+                          delta ? delta + (int64_t)bh * L : nullptr, (uint32_t)(s * CH), list, tb, te, scale * kLog2e, stage, s);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + j) * pl.S + range;
         store_chunk<float, CH>(pdk + slot_id * D + s * CH, st.dk);
