@@ -80,13 +80,31 @@ __device__ __forceinline__ float row16_max(float x)
     return x;
 }
 
-// ---- a lane's share of one [d]-row: CH consecutive channels, kept as raw 32-bit words -------
+// ---- a lane's share of one [d]-row: CH channels, kept as raw 32-bit words --------------------
 template <typename T, int CH> struct RowChunk {
     static constexpr int NW = CH * (int)sizeof(T) / 4;
     uint32_t w[NW];
 };
 
-template <typename T, int CH>
+// How the LPR lanes of a group share a row of D elements.  A lane's chunk is made of 16-byte pieces;
+// its i-th piece is the lane's slot in the row's i-th strip of LPR * 16 bytes, so that one load
+// instruction of the whole group covers whole strips -- whole cache lines -- instead of every other
+// 16 bytes of twice as many lines (the vector memory path charges by the lines an instruction touches).
+// Chunks shorter than 16 bytes are a single piece and lie side by side.
+template <typename T, int D, int LPR> struct LaneLayout {
+    static constexpr int CH = D / LPR;
+    static constexpr int BYTES = CH * (int)sizeof(T);
+    static constexpr int PE = BYTES >= 16 ? 16 / (int)sizeof(T) : CH;  // elements per piece
+    static constexpr int PIECES = CH / PE;
+    static constexpr int PSB = BYTES >= 16 ? LPR * 16 : 16;            // bytes from one piece to the next
+    // element offset of lane s's first piece inside the row
+    __device__ __forceinline__ static constexpr int off(int s) { return s * PE; }
+    // true channel of the lane's c-th chunk element
+    __device__ __forceinline__ static constexpr int channel(int s, int c) { return (c / PE) * (LPR * PE) + s * PE + c % PE; }
+};
+
+// PSB: bytes between the chunk's consecutive 16-byte pieces (16 = contiguous).
+template <typename T, int CH, int PSB = 16>
 __device__ __forceinline__ RowChunk<T, CH> load_chunk(const T *p)
 {
     RowChunk<T, CH> c;
@@ -98,7 +116,7 @@ __device__ __forceinline__ RowChunk<T, CH> load_chunk(const T *p)
         static_assert(NW % 4 == 0, "row chunk must be 8 bytes or a multiple of 16 bytes");
 #pragma unroll
         for (int i = 0; i < NW / 4; ++i) {
-            uint4 v = reinterpret_cast<const uint4 *>(p)[i];
+            uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(p) + i * PSB);
             c.w[4 * i + 0] = v.x; c.w[4 * i + 1] = v.y; c.w[4 * i + 2] = v.z; c.w[4 * i + 3] = v.w;
         }
     }
@@ -120,7 +138,7 @@ __device__ __forceinline__ void unpack_chunk(const RowChunk<T, CH> &c, float (&f
     }
 }
 
-template <typename T, int CH>
+template <typename T, int CH, int PSB = 16>
 __device__ __forceinline__ void store_chunk(T *p, const float (&f)[CH])
 {
     constexpr int NW = RowChunk<T, CH>::NW;
@@ -138,7 +156,23 @@ __device__ __forceinline__ void store_chunk(T *p, const float (&f)[CH])
     } else {
 #pragma unroll
         for (int i = 0; i < NW / 4; ++i)
-            reinterpret_cast<uint4 *>(p)[i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
+            *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(p) + i * PSB) =
+                make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
+    }
+}
+
+// fp32 accumulators of a lane whose chunk follows LaneLayout<T, D, LPR>, written to a plain [D] float
+// row in true channel order (the partial results of the split kernels).
+template <typename T, int D, int LPR>
+__device__ __forceinline__ void store_acc(float *row, int s, const float (&f)[D / LPR])
+{
+    typedef LaneLayout<T, D, LPR> LL;
+#pragma unroll
+    for (int i = 0; i < LL::PIECES; ++i) {
+        float *dst = row + LL::channel(s, i * LL::PE);
+#pragma unroll
+        for (int e = 0; e < LL::PE; e += 4)
+            *reinterpret_cast<float4 *>(dst + e) = make_float4(f[i * LL::PE + e], f[i * LL::PE + e + 1], f[i * LL::PE + e + 2], f[i * LL::PE + e + 3]);
     }
 }
 

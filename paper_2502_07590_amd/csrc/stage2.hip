@@ -17,6 +17,7 @@ __global__ __launch_bounds__(256) void sparse_fwd_kernel(const T *__restrict__ Q
                                                          T *__restrict__ O, float *__restrict__ lse, int L,
                                                          float scale, HeadTable tab)
 {
+    typedef LaneLayout<T, D, LPR> LL;
     constexpr int CH = D / LPR;
     constexpr int RPW = 64 / LPR;  // rows per wave
     const int slot = blockIdx.y;
@@ -30,7 +31,7 @@ __global__ __launch_bounds__(256) void sparse_fwd_kernel(const T *__restrict__ Q
     const int64_t head_base = (int64_t)bh * L * D;
     const int32_t *row = idx + tab.off[slot] + i * k;
 
-    const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
+    const RowChunk<T, CH> q = load_chunk<T, CH, LL::PSB>(Q + head_base + i * D + LL::off(s));
     FwdState<CH> st;
     st.m = -INFINITY;
     st.l = 0.f;
@@ -38,13 +39,13 @@ __global__ __launch_bounds__(256) void sparse_fwd_kernel(const T *__restrict__ Q
     for (int c = 0; c < CH; ++c) st.acc[c] = 0.f;
     __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
     int32_t *stage = stage_all[threadIdx.x / LPR];
-    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e, stage, s);
+    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)LL::off(s), row, 0, k, scale * kLog2e, stage, s);
 
     const float inv = 1.f / st.l;
 #pragma unroll
     for (int c = 0; c < CH; ++c) st.acc[c] *= inv;
     if (live) {
-        store_chunk<T, CH>(O + head_base + i * D + s * CH, st.acc);
+        store_chunk<T, CH, LL::PSB>(O + head_base + i * D + LL::off(s), st.acc);
         if (s == 0) lse[(int64_t)bh * L + i] = (st.m + log2f(st.l)) * kLn2;
     }
 }
@@ -68,6 +69,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict_
                                                             T *__restrict__ dQ, float *__restrict__ delta_out, int L,
                                                             float scale, HeadTable tab)
 {
+    typedef LaneLayout<T, D, LPR> LL;
     constexpr int CH = D / LPR;
     constexpr int RPW = 64 / LPR;  // rows per wave
     const int slot = blockIdx.y;
@@ -81,9 +83,9 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict_
     const int64_t head_base = (int64_t)bh * L * D;
     const int32_t *row = idx + tab.off[slot] + i * k;
 
-    const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
-    const RowChunk<T, CH> go = load_chunk<T, CH>(dO + head_base + i * D + s * CH);
-    const RowChunk<T, CH> o = load_chunk<T, CH>(O + head_base + i * D + s * CH);
+    const RowChunk<T, CH> q = load_chunk<T, CH, LL::PSB>(Q + head_base + i * D + LL::off(s));
+    const RowChunk<T, CH> go = load_chunk<T, CH, LL::PSB>(dO + head_base + i * D + LL::off(s));
+    const RowChunk<T, CH> o = load_chunk<T, CH, LL::PSB>(O + head_base + i * D + LL::off(s));
     const float delta0 = row_sum<LPR>(dot_chunk<T, CH>(go, o));
     DqState<CH> st;
     st.delta = 0.f;
@@ -91,13 +93,13 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_kernel(const T *__restrict_
     for (int c = 0; c < CH; ++c) { st.a[c] = 0.f; st.b[c] = 0.f; }
     __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
     int32_t *stage = stage_all[threadIdx.x / LPR];
-    dq_sweep<T, D, LPR>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, 0, k, scale * kLog2e,
+    dq_sweep<T, D, LPR>(st, q, go, K + head_base, V + head_base, (uint32_t)LL::off(s), row, 0, k, scale * kLog2e,
                    lse[(int64_t)bh * L + i] * kLog2e, delta0, stage, s);
     if (live) {
         float dq[CH];
 #pragma unroll
         for (int c = 0; c < CH; ++c) dq[c] = scale * (st.a[c] - (st.delta - delta0) * st.b[c]);
-        store_chunk<T, CH>(dQ + head_base + i * D + s * CH, dq);
+        store_chunk<T, CH, LL::PSB>(dQ + head_base + i * D + LL::off(s), dq);
         if (s == 0) delta_out[(int64_t)bh * L + i] = st.delta;
     }
 }
@@ -115,6 +117,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_kernel(const T *__restric
                                                               const T *__restrict__ dO, T *__restrict__ dK,
                                                               T *__restrict__ dV, int L, float scale, HeadTable tab)
 {
+    typedef LaneLayout<T, D, LPR> LL;
     constexpr int CH = D / LPR;
     constexpr int RPW = 64 / LPR;  // rows per wave
     const int slot = blockIdx.y;
@@ -130,20 +133,20 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_kernel(const T *__restric
     const int n = live ? (int)(cp[j + 1] - beg) : 0;
     const int32_t *list = idxT + tab.off[slot] + beg;
 
-    const RowChunk<T, CH> kc = load_chunk<T, CH>(K + head_base + j * D + s * CH);
-    const RowChunk<T, CH> vc = load_chunk<T, CH>(V + head_base + j * D + s * CH);
+    const RowChunk<T, CH> kc = load_chunk<T, CH, LL::PSB>(K + head_base + j * D + LL::off(s));
+    const RowChunk<T, CH> vc = load_chunk<T, CH, LL::PSB>(V + head_base + j * D + LL::off(s));
     DkdvState<CH> st;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.dk[c] = 0.f; st.dv[c] = 0.f; }
     __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
     int32_t *stage = stage_all[threadIdx.x / LPR];
     dkdv_sweep<T, D, LPR>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L, delta + (int64_t)bh * L,
-                     (uint32_t)(s * CH), list, 0, n, scale * kLog2e, stage, s);
+                     (uint32_t)LL::off(s), list, 0, n, scale * kLog2e, stage, s);
     if (live) {
 #pragma unroll
         for (int c = 0; c < CH; ++c) st.dk[c] *= scale;
-        store_chunk<T, CH>(dK + head_base + j * D + s * CH, st.dk);
-        store_chunk<T, CH>(dV + head_base + j * D + s * CH, st.dv);
+        store_chunk<T, CH, LL::PSB>(dK + head_base + j * D + LL::off(s), st.dk);
+        store_chunk<T, CH, LL::PSB>(dV + head_base + j * D + LL::off(s), st.dv);
     }
 }
 

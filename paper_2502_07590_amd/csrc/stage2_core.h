@@ -157,14 +157,14 @@ __device__ __forceinline__ void axpy_pair2(float (&acc1)[CH], float (&acc2)[CH],
 }
 
 // Row chunk of a gathered row: base is the head's [L, d] matrix (uniform across the wave), the
-// per-lane part is a 32-bit element offset (row * D + lane channel offset), so the load can use a
+// per-lane part is a 32-bit element offset (row * D + the lane's LaneLayout offset), so the load can use a
 // scalar base with a 32-bit vector offset.
-template <typename T, int CH>
-__device__ __forceinline__ RowChunk<T, CH> gather_chunk(const T *__restrict__ head, uint32_t row, uint32_t D,
-                                                        uint32_t lane_off)
+template <typename T, int D, int LPR>
+__device__ __forceinline__ RowChunk<T, D / LPR> gather_chunk(const T *__restrict__ head, uint32_t row, uint32_t lane_off)
 {
-    const uint32_t byte_off = (row * D + lane_off) * (uint32_t)sizeof(T);  // < 2^32: a head's matrix is < 4 GB
-    return load_chunk<T, CH>(reinterpret_cast<const T *>(reinterpret_cast<const char *>(head) + byte_off));
+    typedef LaneLayout<T, D, LPR> LL;
+    const uint32_t byte_off = (row * (uint32_t)D + lane_off) * (uint32_t)sizeof(T);  // < 2^32: a head's matrix is < 4 GB
+    return load_chunk<T, LL::CH, LL::PSB>(reinterpret_cast<const T *>(reinterpret_cast<const char *>(head) + byte_off));
 }
 
 // ------------------------------------------------------------------------------------ forward sweep
@@ -189,8 +189,8 @@ __device__ __forceinline__ void fwd_step(FwdState<D / LPR> &st, const RowChunk<T
     for (int u = 0; u < U; ++u) j[u] = jsrc[u];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        kc[u] = gather_chunk<T, CH>(Kh, (uint32_t)j[u], D, lane_off);
-        vc[u] = gather_chunk<T, CH>(Vh, (uint32_t)j[u], D, lane_off);
+        kc[u] = gather_chunk<T, D, LPR>(Kh, (uint32_t)j[u], lane_off);
+        vc[u] = gather_chunk<T, D, LPR>(Vh, (uint32_t)j[u], lane_off);
     }
     float sc[U];
 #pragma unroll
@@ -284,8 +284,8 @@ __device__ __forceinline__ void dq_step(DqState<D / LPR> &st, const RowChunk<T, 
     for (int u = 0; u < U; ++u) j[u] = jsrc[u];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        kc[u] = gather_chunk<T, CH>(Kh, (uint32_t)j[u], D, lane_off);
-        vc[u] = gather_chunk<T, CH>(Vh, (uint32_t)j[u], D, lane_off);
+        kc[u] = gather_chunk<T, D, LPR>(Kh, (uint32_t)j[u], lane_off);
+        vc[u] = gather_chunk<T, D, LPR>(Vh, (uint32_t)j[u], lane_off);
     }
     float p[U], wc[U];
 #pragma unroll
@@ -347,8 +347,8 @@ __device__ __forceinline__ void dkdv_step(DkdvState<D / LPR> &st, const RowChunk
     for (int u = 0; u < U; ++u) iq[u] = jsrc[u];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        qc[u] = gather_chunk<T, CH>(Qh, (uint32_t)iq[u], D, lane_off);
-        gc[u] = gather_chunk<T, CH>(Gh, (uint32_t)iq[u], D, lane_off);
+        qc[u] = gather_chunk<T, D, LPR>(Qh, (uint32_t)iq[u], lane_off);
+        gc[u] = gather_chunk<T, D, LPR>(Gh, (uint32_t)iq[u], lane_off);
         if (delta_h) {
             l2[u] = lse_h[iq[u]] * kLog2e;
             dl[u] = delta_h[iq[u]];

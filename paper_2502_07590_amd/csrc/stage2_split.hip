@@ -79,6 +79,7 @@ __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restri
                                                                float *__restrict__ pl_, float *__restrict__ pacc, int L,
                                                                float scale, HeadTable tab, SplitPlan pl)
 {
+    typedef LaneLayout<T, D, LPR> LL;
     constexpr int CH = D / LPR;
     constexpr int RPW = 64 / LPR;  // rows per wave
     int slot, range, qb;
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restri
     const int32_t *sp = seg + ((int64_t)bh * L + i) * (pl.S + 1) + range;
     const int tb = sp[0], te = sp[1];
 
-    const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
+    const RowChunk<T, CH> q = load_chunk<T, CH, LL::PSB>(Q + head_base + i * D + LL::off(s));
     FwdState<CH> st;
     st.m = -INFINITY;
     st.l = 0.f;
@@ -103,10 +104,10 @@ __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restri
     for (int c = 0; c < CH; ++c) st.acc[c] = 0.f;
     __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
     int32_t *stage = stage_all[threadIdx.x / LPR];
-    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e, stage, s);
+    fwd_sweep<T, D, LPR>(st, q, K + head_base, V + head_base, (uint32_t)LL::off(s), row, tb, te, scale * kLog2e, stage, s);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + i) * pl.S + range;
-        store_chunk<float, CH>(pacc + slot_id * D + s * CH, st.acc);
+        store_acc<T, D, LPR>(pacc + slot_id * D, s, st.acc);
         if (s == 0) { pm[slot_id] = st.m; pl_[slot_id] = st.l; }
     }
 }
@@ -158,6 +159,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__res
                                                                   float *__restrict__ pb, float *__restrict__ pdelta,
                                                                   int L, float scale, HeadTable tab, SplitPlan pl)
 {
+    typedef LaneLayout<T, D, LPR> LL;
     constexpr int CH = D / LPR;
     constexpr int RPW = 64 / LPR;  // rows per wave
     int slot, range, qb;
@@ -174,9 +176,9 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__res
     const int32_t *sp = seg + ((int64_t)bh * L + i) * (pl.S + 1) + range;
     const int tb = sp[0], te = sp[1];
 
-    const RowChunk<T, CH> q = load_chunk<T, CH>(Q + head_base + i * D + s * CH);
-    const RowChunk<T, CH> go = load_chunk<T, CH>(dO + head_base + i * D + s * CH);
-    const RowChunk<T, CH> o = load_chunk<T, CH>(O + head_base + i * D + s * CH);
+    const RowChunk<T, CH> q = load_chunk<T, CH, LL::PSB>(Q + head_base + i * D + LL::off(s));
+    const RowChunk<T, CH> go = load_chunk<T, CH, LL::PSB>(dO + head_base + i * D + LL::off(s));
+    const RowChunk<T, CH> o = load_chunk<T, CH, LL::PSB>(O + head_base + i * D + LL::off(s));
     const float delta0 = row_sum<LPR>(dot_chunk<T, CH>(go, o));
     DqState<CH> st;
     st.delta = 0.f;
@@ -184,12 +186,12 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__res
     for (int c = 0; c < CH; ++c) { st.a[c] = 0.f; st.b[c] = 0.f; }
     __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
     int32_t *stage = stage_all[threadIdx.x / LPR];
-    dq_sweep<T, D, LPR>(st, q, go, K + head_base, V + head_base, (uint32_t)(s * CH), row, tb, te, scale * kLog2e,
+    dq_sweep<T, D, LPR>(st, q, go, K + head_base, V + head_base, (uint32_t)LL::off(s), row, tb, te, scale * kLog2e,
                    lse[(int64_t)bh * L + i] * kLog2e, delta0, stage, s);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + i) * pl.S + range;
-        store_chunk<float, CH>(pa + slot_id * D + s * CH, st.a);
-        store_chunk<float, CH>(pb + slot_id * D + s * CH, st.b);
+        store_acc<T, D, LPR>(pa + slot_id * D, s, st.a);
+        store_acc<T, D, LPR>(pb + slot_id * D, s, st.b);
         if (s == 0) pdelta[slot_id] = st.delta;
     }
 }
@@ -247,6 +249,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
                                                                     float *__restrict__ pdv, int L, float scale,
                                                                     HeadTable tab, SplitPlan pl)
 {
+    typedef LaneLayout<T, D, LPR> LL;
     constexpr int CH = D / LPR;
     constexpr int RPW = 64 / LPR;  // rows per wave
     int slot, range, kb;
@@ -263,8 +266,8 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
     const int32_t *sp = seg + ((int64_t)bh * L + j) * (pl.S + 1) + range;
     const int tb = sp[0], te = live ? sp[1] : sp[0];
 
-    const RowChunk<T, CH> kc = load_chunk<T, CH>(K + head_base + j * D + s * CH);
-    const RowChunk<T, CH> vc = load_chunk<T, CH>(V + head_base + j * D + s * CH);
+    const RowChunk<T, CH> kc = load_chunk<T, CH, LL::PSB>(K + head_base + j * D + LL::off(s));
+    const RowChunk<T, CH> vc = load_chunk<T, CH, LL::PSB>(V + head_base + j * D + LL::off(s));
     DkdvState<CH> st;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.dk[c] = 0.f; st.dv[c] = 0.f; }
@@ -272,11 +275,11 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
     __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
     int32_t *stage = stage_all[threadIdx.x / LPR];
     dkdv_sweep<T, D, LPR>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L * (delta ? 1 : 2),
-                          delta ? delta + (int64_t)bh * L : nullptr, (uint32_t)(s * CH), list, tb, te, scale * kLog2e, stage, s);
+                          delta ? delta + (int64_t)bh * L : nullptr, (uint32_t)LL::off(s), list, tb, te, scale * kLog2e, stage, s);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + j) * pl.S + range;
-        store_chunk<float, CH>(pdk + slot_id * D + s * CH, st.dk);
-        store_chunk<float, CH>(pdv + slot_id * D + s * CH, st.dv);
+        store_acc<T, D, LPR>(pdk + slot_id * D, s, st.dk);
+        store_acc<T, D, LPR>(pdv + slot_id * D, s, st.dv);
     }
 }
 
