@@ -27,19 +27,25 @@
 
 namespace dsv {
 
-// Lanes per row of each sweep (rows per 256-thread block = 256 / lanes).  Measured on MI355X at
-// L = 128k, bf16, d = 128, k = 8192 (ms per launch): forward 16: 153, 8: 161, 4: 239; dq 16: 162, 8: 180+,
-// 4: 309; dkdv 16: 210, 8: 200, 4: 286 -- the dkdv sweep carries the most per-pair arithmetic and is the
-// one that gains from sharing it over 16 channels per lane; 4 lanes per row cost too many registers.
-// Backward sweeps issue two independent two-row steps per loop trip (more gathers in flight).
-#ifndef DSV_BWD_REP
-#define DSV_BWD_REP 2
+// Lanes per row of each sweep (rows per 256-thread block = 256 / lanes), steps per loop trip of the
+// backward sweeps and keys per forward step.  Measured on MI355X at L = 128k, bf16, d = 128, k = 8192
+// (ms per launch) with the strip-interleaved lane layout and the staged index: forward 16 lanes: 131,
+// 8: 124, 4: 123; dq 16: 145, 8: 132, 4: 202 (registers); dkdv 16: 190, 8: 158, 4: 153.  Two steps per
+// trip or 8 keys per forward step change nothing measurable (the gathers already fill the memory path).
+#ifndef DSV_DQ_REP
+#define DSV_DQ_REP 1
+#endif
+#ifndef DSV_DKDV_REP
+#define DSV_DKDV_REP 1
+#endif
+#ifndef DSV_FWD_U
+#define DSV_FWD_U 4   // keys per forward step (4 or 8)
 #endif
 #ifndef DSV_LPR_FWD
-#define DSV_LPR_FWD 16
+#define DSV_LPR_FWD 8
 #endif
 #ifndef DSV_LPR_DQ
-#define DSV_LPR_DQ 16
+#define DSV_LPR_DQ 8
 #endif
 #ifndef DSV_LPR_DKDV
 #define DSV_LPR_DKDV 8
@@ -181,7 +187,7 @@ __device__ __forceinline__ void fwd_step(FwdState<D / LPR> &st, const RowChunk<T
                                          float c2)
 {
     constexpr int CH = D / LPR;
-    constexpr int U = 4;
+    constexpr int U = DSV_FWD_U;
     typedef RowChunk<T, CH> Chunk;
     int j[U];
     Chunk kc[U], vc[U];
@@ -202,7 +208,8 @@ __device__ __forceinline__ void fwd_step(FwdState<D / LPR> &st, const RowChunk<T
         for (int u = 0; u < U; ++u)
             if (u >= nvalid) sc[u] = -INFINITY;
     }
-    const float mblk = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+    float mblk = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+    if constexpr (U == 8) mblk = fmaxf(mblk, fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
     if (mblk > st.m) {  // rescale only when the running max moves (rare after the first blocks)
         const float corr = fast_exp2(st.m - mblk);
         st.m = mblk;
@@ -213,9 +220,11 @@ __device__ __forceinline__ void fwd_step(FwdState<D / LPR> &st, const RowChunk<T
     float p[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) p[u] = fast_exp2(sc[u] - st.m);
-    st.l += (p[0] + p[1]) + (p[2] + p[3]);
-    axpy_pair<T, CH>(st.acc, vc[0], vc[1], p[0], p[1], sizeof(T) == 2 ? pack_bf16x2(p[0], p[1]) : 0u);
-    axpy_pair<T, CH>(st.acc, vc[2], vc[3], p[2], p[3], sizeof(T) == 2 ? pack_bf16x2(p[2], p[3]) : 0u);
+#pragma unroll
+    for (int u = 0; u < U; u += 4) st.l += (p[u] + p[u + 1]) + (p[u + 2] + p[u + 3]);
+#pragma unroll
+    for (int u = 0; u < U; u += 2)
+        axpy_pair<T, CH>(st.acc, vc[u], vc[u + 1], p[u], p[u + 1], sizeof(T) == 2 ? pack_bf16x2(p[u], p[u + 1]) : 0u);
 }
 
 // ---- index staging ------------------------------------------------------------------------------
@@ -258,7 +267,7 @@ __device__ __forceinline__ void fwd_sweep(FwdState<D / LPR> &st, const RowChunk<
         if (c0 + kStage < te) si.request(row, c0 + kStage, te, s);
         const int n = min(kStage, te - c0);
         int it = 0;
-        for (; it + 4 <= n; it += 4) fwd_step<T, D, LPR, false>(st, q, Kh, Vh, lane_off, stage + it, 4, c2);
+        for (; it + DSV_FWD_U <= n; it += DSV_FWD_U) fwd_step<T, D, LPR, false>(st, q, Kh, Vh, lane_off, stage + it, DSV_FWD_U, c2);
         if (it < n) fwd_step<T, D, LPR, true>(st, q, Kh, Vh, lane_off, stage + it, n - it, c2);
     }
 }
@@ -314,7 +323,7 @@ __device__ __forceinline__ void dq_sweep(DqState<D / LPR> &st, const RowChunk<T,
         if (c0 + kStage < te) si.request(row, c0 + kStage, te, s);
         const int n = min(kStage, te - c0);
         int it = 0;
-#if DSV_BWD_REP == 2
+#if DSV_DQ_REP == 2
         for (; it + 4 <= n; it += 4) {
             dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, stage + it, 2, c2, lse2, delta0);
             dq_step<T, D, LPR, false>(st, q, go, Kh, Vh, lane_off, stage + it + 2, 2, c2, lse2, delta0);
@@ -388,7 +397,7 @@ __device__ __forceinline__ void dkdv_sweep(DkdvState<D / LPR> &st, const RowChun
         if (c0 + kStage < te) si.request(list, c0 + kStage, te, s);
         const int n = min(kStage, te - c0);
         int it = 0;
-#if DSV_BWD_REP == 2
+#if DSV_DKDV_REP == 2
         for (; it + 4 <= n; it += 4) {
             dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it, 2, c2);
             dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it + 2, 2, c2);
