@@ -103,8 +103,11 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
     if constexpr (PASS > 0) fast = __all((pre & 0x80000000u) != 0u);
     if (fast) {
         const uint32_t raw_pre = pre ^ 0x80000000u;
+        Frag<T, R> kf_next = load_frag<T, R>(Kb, wave * 32, L, lane);
         for (int tile = wave; tile < nfull; tile += 4) {
-            const Frag<T, R> kf = load_frag<T, R>(Kb, tile * 32, L, lane);
+            // the next tile's fragment is requested before this tile is scored (rows past the end clamp)
+            const Frag<T, R> kf = kf_next;
+            kf_next = load_frag<T, R>(Kb, (tile + 4) * 32, L, lane);
             const floatx16_t acc = score_tile<T, R>(kf, qf);
             constexpr uint32_t kLimit = 1u << ((SHIFT + 8) & 31);
             if constexpr (PASS >= 2) {
@@ -132,8 +135,10 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
             }
         }
     } else {
+        Frag<T, R> kf_next = load_frag<T, R>(Kb, wave * 32, L, lane);
         for (int tile = wave; tile < nfull; tile += 4) {
-            const Frag<T, R> kf = load_frag<T, R>(Kb, tile * 32, L, lane);
+            const Frag<T, R> kf = kf_next;
+            kf_next = load_frag<T, R>(Kb, (tile + 4) * 32, L, lane);
             const floatx16_t acc = score_tile<T, R>(kf, qf);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {

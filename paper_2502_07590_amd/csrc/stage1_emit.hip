@@ -140,9 +140,12 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
     __shared__ int32_t rings[32 * kRing];
     int wpos = 0, done = 0, ties_taken = 0, last_tie = -1;
     const int ntiles = (L + 31) >> 5;
+    Frag<T, R> kf_next = load_frag<T, R>(Kb, 0, L, lane);
     for (int tile = 0; tile < ntiles; ++tile) {
         const int j0 = tile * 32;
-        const Frag<T, R> kf = load_frag<T, R>(Kb, j0, L, lane);
+        // the next tile's fragment is requested before this tile is scored (rows past the end clamp)
+        const Frag<T, R> kf = kf_next;
+        kf_next = load_frag<T, R>(Kb, j0 + 32, L, lane);
         const floatx16_t acc = score_tile<T, R>(kf, qf);
         const uint32_t valid = (j0 + 32 <= L) ? 0xFFFFFFFFu : ((1u << (L - j0)) - 1u);
         uint32_t sel;
@@ -182,8 +185,8 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
 // ------------------------------------------------------------------------------------ key-major
 // tau_f: the fp32 thresholds left in `prefix` by emit_kernel.  The tile is computed with the query
 // fragment as the row operand and the key fragment as the column operand, so lane l owns key
-// (l % 32) and accumulator v is query tile_pos(v) + 4*(l/32) of the tile; a lane fetches the
-// thresholds of its 16 queries with four aligned 16-byte loads per tile (state rows are padded).
+// (l % 32) and accumulator v is query tile_pos(v) + 4*(l/32) of the tile; the thresholds of a lane's 16
+// queries come from a chunk staged in LDS (state rows are padded to whole tiles).
 //   WRITE = false: list lengths -> cnt[bh, j];   WRITE = true: lists, starting at col[bh, j].
 template <typename T, int R, bool WRITE>
 __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
@@ -216,41 +219,57 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
         limit = (int)(cp[1] - cp[0]);
     }
     int wpos = 0, done = 0;
-    for (int qt = 0; qt < ntiles; ++qt) {
-        const int q0 = qt * 32;
-        const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
-        const floatx16_t acc = score_tile<T, R>(qf, kf);
-        const uint32_t valid = (q0 + 32 <= L) ? 0xFFFFFFFFu : ((1u << (L - q0)) - 1u);
-        // thresholds of this lane's 16 queries (tile rows 8g + 4*half + 0..3): four aligned 16-byte loads
-        float tq[16];
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const float4 t4 = *reinterpret_cast<const float4 *>(tau_b + q0 + 8 * gq + 4 * half);
-            tq[4 * gq + 0] = t4.x; tq[4 * gq + 1] = t4.y; tq[4 * gq + 2] = t4.z; tq[4 * gq + 3] = t4.w;
-        }
-        uint32_t m;
-        if (flag_b[qt]) {
-            DSV_SIGNMASK16(m, acc[v] - tq[v]);  // score < tau as the sign of (score - tau)
-            m = ~m & 0x0F0F0F0Fu;
-        } else {
-            int jq[16];
+    // Thresholds of the queries, kTauTiles tiles at a time: one coalesced 16-byte load per lane, parked in
+    // LDS, from where each lane picks the 16 values of its accumulators with broadcast reads.  (Fetching
+    // them per tile straight from memory took four full-width load instructions per tile -- four times
+    // the address-path time of the tile's own fragment.)
+    constexpr int kTauTiles = 8;
+    __shared__ __align__(16) float tau_s[kTauTiles * 32];
+    const int npad = padded_len(L);
+    float4 tau_next = *reinterpret_cast<const float4 *>(tau_b + min(lane * 4, npad - 4));
+    Frag<T, R> qf_next = load_frag<T, R>(Qb, 0, L, lane);
+    for (int qc = 0; qc < ntiles; qc += kTauTiles) {
+        *reinterpret_cast<float4 *>(tau_s + lane * 4) = tau_next;
+        tau_next = *reinterpret_cast<const float4 *>(tau_b + min((qc + kTauTiles) * 32 + lane * 4, npad - 4));
+        const int tn = min(kTauTiles, ntiles - qc);
+        for (int t = 0; t < tn; ++t) {
+            const int qt = qc + t;
+            const int q0 = qt * 32;
+            const Frag<T, R> qf = qf_next;
+            qf_next = load_frag<T, R>(Qb, q0 + 32, L, lane);
+            const floatx16_t acc = score_tile<T, R>(qf, kf);
+            const uint32_t valid = (q0 + 32 <= L) ? 0xFFFFFFFFu : ((1u << (L - q0)) - 1u);
+            // thresholds of this lane's 16 queries (tile rows 8g + 4*half + 0..3)
+            float tq[16];
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
-                const int4 c4 = *reinterpret_cast<const int4 *>(jcut_b + q0 + 8 * gq + 4 * half);
-                jq[4 * gq + 0] = c4.x; jq[4 * gq + 1] = c4.y; jq[4 * gq + 2] = c4.z; jq[4 * gq + 3] = c4.w;
+                const float4 t4 = *reinterpret_cast<const float4 *>(tau_s + t * 32 + 8 * gq + 4 * half);
+                tq[4 * gq + 0] = t4.x; tq[4 * gq + 1] = t4.y; tq[4 * gq + 2] = t4.z; tq[4 * gq + 3] = t4.w;
             }
-            DSV_MASK16(m, acc[v] > tq[v] || (acc[v] == tq[v] && j <= jq[v]));
-        }
-        uint32_t sel = merge_halves(m, half) & valid;
-        if (!live) sel = 0u;
-        const int c = __popc(sel);
-        if (WRITE) {
-            const int c_ok = min(c, limit - wpos);
-            ring_append(rings + n * kRing, wpos, sel, c, c_ok, half, q0);
-            wpos += c_ok;
-            done = ring_flush_full(rings, wpos, done, list, lane);
-        } else {
-            wpos += c;
+            uint32_t m;
+            if (flag_b[qt]) {
+                DSV_SIGNMASK16(m, acc[v] - tq[v]);  // score < tau as the sign of (score - tau)
+                m = ~m & 0x0F0F0F0Fu;
+            } else {
+                int jq[16];
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int4 c4 = *reinterpret_cast<const int4 *>(jcut_b + q0 + 8 * gq + 4 * half);
+                    jq[4 * gq + 0] = c4.x; jq[4 * gq + 1] = c4.y; jq[4 * gq + 2] = c4.z; jq[4 * gq + 3] = c4.w;
+                }
+                DSV_MASK16(m, acc[v] > tq[v] || (acc[v] == tq[v] && j <= jq[v]));
+            }
+            uint32_t sel = merge_halves(m, half) & valid;
+            if (!live) sel = 0u;
+            const int c = __popc(sel);
+            if (WRITE) {
+                const int c_ok = min(c, limit - wpos);
+                ring_append(rings + n * kRing, wpos, sel, c, c_ok, half, q0);
+                wpos += c_ok;
+                done = ring_flush_full(rings, wpos, done, list, lane);
+            } else {
+                wpos += c;
+            }
         }
     }
     if (WRITE) ring_flush_rest(rings, wpos, done, list, lane);
