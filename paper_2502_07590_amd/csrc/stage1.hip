@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void project_kernel(const T *__restrict__ Q, c
 
 // ------------------------------------------------------------------------------------ radix pass
 // One digit of the search for the k-th largest score of each query.  Block = 32 queries of one
-// head, 4 waves striding over the key tiles, one shared histogram in LDS laid out [256 digits][32
+// head, kRadixWaves waves striding over the key tiles, one shared histogram in LDS laid out [256 digits][32
 // queries]: the bank of a counter depends on the query alone, so the 32 lanes of a half-wave (32
 // different queries) never collide, whatever their digits are.
 //   PASS 0 counts every key by the top digit; PASS p counts only keys whose higher digits equal
@@ -69,8 +69,13 @@ __global__ __launch_bounds__(256) void project_kernel(const T *__restrict__ Q, c
 //   remaining key is appended to the prefix and k_rem is reduced by the keys in higher buckets.
 // After pass 3 the prefix is the full key of the k-th largest score and |k_rem| is the number of
 // keys equal to it that belong to the top-k (at least 1); k_rem < 0 marks "all of them".
+#ifndef DSV_RADIX_WAVES
+#define DSV_RADIX_WAVES 8
+#endif
+constexpr int kRadixWaves = DSV_RADIX_WAVES;  // waves per block; the 32 KB histogram allows 4 blocks per CU
+
 template <typename T, int R, int PASS>
-__global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
+__global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
                                                          HeadTable tab, uint32_t *__restrict__ prefix,
                                                          int32_t *__restrict__ krem)
 {
@@ -84,7 +89,7 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, half = lane >> 5;
 
-    for (int e = threadIdx.x; e < 256 * 32; e += 256) hist[e] = 0;
+    for (int e = threadIdx.x; e < 256 * 32; e += 64 * kRadixWaves) hist[e] = 0;
     __syncthreads();
 
     const int qi = min(q0 + n, L - 1);
@@ -104,10 +109,10 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
     if (fast) {
         const uint32_t raw_pre = pre ^ 0x80000000u;
         Frag<T, R> kf_next = load_frag<T, R>(Kb, wave * 32, L, lane);
-        for (int tile = wave; tile < nfull; tile += 4) {
+        for (int tile = wave; tile < nfull; tile += kRadixWaves) {
             // the next tile's fragment is requested before this tile is scored (rows past the end clamp)
             const Frag<T, R> kf = kf_next;
-            kf_next = load_frag<T, R>(Kb, (tile + 4) * 32, L, lane);
+            kf_next = load_frag<T, R>(Kb, (tile + kRadixWaves) * 32, L, lane);
             const floatx16_t acc = score_tile<T, R>(kf, qf);
             constexpr uint32_t kLimit = 1u << ((SHIFT + 8) & 31);
             if constexpr (PASS >= 2) {
@@ -136,20 +141,24 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
         }
     } else {
         Frag<T, R> kf_next = load_frag<T, R>(Kb, wave * 32, L, lane);
-        for (int tile = wave; tile < nfull; tile += 4) {
+        for (int tile = wave; tile < nfull; tile += kRadixWaves) {
             const Frag<T, R> kf = kf_next;
-            kf_next = load_frag<T, R>(Kb, (tile + 4) * 32, L, lane);
+            kf_next = load_frag<T, R>(Kb, (tile + kRadixWaves) * 32, L, lane);
             const floatx16_t acc = score_tile<T, R>(kf, qf);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const uint32_t key = score_key(acc[v]);
-                bool ok = true;
-                if constexpr (PASS > 0) ok = (key >> (SHIFT + 8)) == (pre >> (SHIFT + 8));
-                if (ok) atomicAdd(&hcol_mine[((key >> SHIFT) & 255u) * 32], 1u);
+                if constexpr (PASS == 0) {
+                    // first digit: counted by the RAW top byte (no key transform in the loop); the scan
+                    // below visits the raw buckets in key order
+                    atomicAdd(&hcol_mine[(__float_as_uint(acc[v]) >> 24) * 32], 1u);
+                } else {
+                    const uint32_t key = score_key(acc[v]);
+                    if ((key >> (SHIFT + 8)) == (pre >> (SHIFT + 8))) atomicAdd(&hcol_mine[((key >> SHIFT) & 255u) * 32], 1u);
+                }
             }
         }
     }
-    if (nfull < ntiles && wave == (nfull & 3)) {  // the ragged last tile
+    if (nfull < ntiles && wave == nfull % kRadixWaves) {  // the ragged last tile
         const int j0 = nfull * 32;
         const Frag<T, R> kf = load_frag<T, R>(Kb, j0, L, lane);
         const floatx16_t acc = score_tile<T, R>(kf, qf);
@@ -158,7 +167,8 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
             const uint32_t key = score_key(acc[v]);
             bool ok = j0 + tile_pos(v) + 4 * half < L;
             if constexpr (PASS > 0) ok = ok && ((key >> (SHIFT + 8)) == (pre >> (SHIFT + 8)));
-            if (ok) atomicAdd(&hcol_mine[((key >> SHIFT) & 255u) * 32], 1u);
+            const uint32_t bucket = PASS == 0 ? __float_as_uint(acc[v]) >> 24 : (key >> SHIFT) & 255u;
+            if (ok) atomicAdd(&hcol_mine[bucket * 32], 1u);
         }
     }
     __syncthreads();
@@ -168,8 +178,11 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
         const int kr = PASS == 0 ? tab.k[slot] : krem[g];
         const uint32_t *hcol = hist + threadIdx.x;
         int above = 0, digit = 0;
+        // bucket of key digit b: the digit itself, except in pass 0, whose buckets are raw top bytes
+        // (positive floats: key digit = raw ^ 0x80; negative floats: key digit = ~raw)
+        auto bucket_of = [](int b) { return PASS == 0 ? (b >= 128 ? b ^ 0x80 : b ^ 0xFF) : b; };
         for (int b = 255; b >= 0; --b) {
-            const int c = (int)hcol[32 * b];
+            const int c = (int)hcol[32 * bucket_of(b)];
             if (above + c >= kr) { digit = b; break; }
             above += c;
         }
@@ -178,7 +191,7 @@ __global__ __launch_bounds__(256) void radix_pass_kernel(const T *__restrict__ Q
         // after the last digit the bucket holds exactly the keys equal to the threshold: a negative
         // k_rem tells the emission that all of them are taken (then "score >= threshold" decides)
         const int want = kr - above;
-        krem[g] = (PASS == 3 && want == (int)hcol[32 * digit]) ? -want : want;
+        krem[g] = (PASS == 3 && want == (int)hcol[32 * bucket_of(digit)]) ? -want : want;
     }
 }
 
@@ -284,10 +297,10 @@ static dsv_status select_t(const dsv_problem &p, const HeadTable *tabs, int n_ta
         KernelSpan span(DSV_KERNEL_THRESHOLD, st);
         for (int t = 0; t < n_tabs; ++t) {
             dim3 grid(qtiles, tabs[t].n);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(256), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
             DSV_LAUNCH_CHECK();
         }
     }
