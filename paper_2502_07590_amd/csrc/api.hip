@@ -108,7 +108,7 @@ struct FwdLayout {
 FwdLayout fwd_layout(const dsv_problem &p)
 {
     FwdLayout w{};
-    w.plan = make_split_plan(p);
+    w.plan = make_split_plan(p, kFwdRangeBytes);
     w.split = use_split(p, w.plan);
     if (!w.split) return w;
     const size_t rows = (size_t)p.B * p.H * p.L;
@@ -132,7 +132,7 @@ struct StepLayout {
 StepLayout step_layout(const dsv_problem &p)
 {
     StepLayout w{};
-    w.plan = make_split_plan(p);
+    w.plan = make_split_plan(p, kBwdRangeBytes);
     w.split = use_split(p, w.plan);
     if (!w.split) return w;
     const size_t nbh = (size_t)p.B * p.H;

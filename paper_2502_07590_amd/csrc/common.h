@@ -234,10 +234,12 @@ dsv_status launch_project(const dsv_problem &p, const void *Q, const void *K, co
 dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void *Klr, int bh,
                               const int32_t *rows, int n_rows, float *scores, hipStream_t st);
 // ---- L2-blocked (split-K) form of stage 2 -----------------------------------------------------
-// Target bytes of K+V (or Q+dO) rows per key (query) range.  Measured at L = 128k (bf16, d = 128):
-// 16 to 32 ranges per head (4 MB to 2 MB each, against a 4 MB L2 per XCD) run within 1 % of each other,
-// 8 ranges are 20 % slower, 64 ranges 3 % slower; the larger size halves the partial-result workspace.
-constexpr size_t kSplitRangeBytes = 4u << 20;
+// Target bytes of K+V (or Q+dO) rows per key (query) range, against a 4 MB L2 per XCD.  Measured at
+// L = 128k (bf16, d = 128): the forward runs best with 2 MB ranges (32 per head: 121 ms, 3 MB: 123,
+// 4 MB: 124), the backward steps -- whose partial results are twice as large per range -- with 4 MB
+// (dq 132 / 131 / 135 ms and dkdv 158 / 162 / 164 ms at 4 / 3 / 2 MB); 8 ranges per head are 20 % slower.
+constexpr size_t kFwdRangeBytes = 2u << 20;
+constexpr size_t kBwdRangeBytes = 4u << 20;
 
 struct SplitPlan {
     int range_len;  // keys (queries) per range
@@ -245,7 +247,7 @@ struct SplitPlan {
     int S_pad;      // S rounded up to a multiple of 8 (one XCD per residue class)
     int nqb;        // row blocks per range (each kernel sets it from its own rows per block)
 };
-SplitPlan make_split_plan(const dsv_problem &p);
+SplitPlan make_split_plan(const dsv_problem &p, size_t range_bytes);
 
 struct FwdSplitWorkspace {
     int32_t *seg;  // [B*H, L, S+1] segment pointers into every idx row

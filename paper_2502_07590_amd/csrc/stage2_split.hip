@@ -374,14 +374,14 @@ __global__ __launch_bounds__(256) void zero_i32_kernel(int32_t *__restrict__ p, 
 }
 
 // ------------------------------------------------------------------------------------ host
-SplitPlan make_split_plan(const dsv_problem &p)
+SplitPlan make_split_plan(const dsv_problem &p, size_t range_bytes)
 {
     const size_t esz = p.dtype == DSV_BF16 ? 2 : 4;
     const size_t row_pair_bytes = 2 * (size_t)p.d * esz;  // one K row + one V row (or Q + dO)
     SplitPlan pl;
-    // ranges of about kSplitRangeBytes, their number a multiple of 8 so that every XCD gets the same
+    // ranges of about range_bytes, their number a multiple of 8 so that every XCD gets the same
     // number of ranges (a 6-5 split of ranges over XCDs costs ~10 %)
-    const size_t target = std::max<size_t>(256, kSplitRangeBytes / row_pair_bytes);
+    const size_t target = std::max<size_t>(256, range_bytes / row_pair_bytes);
     int S = (int)((p.L + 8 * target - 1) / (8 * target)) * 8;
     pl.range_len = (p.L + S - 1) / S;
     pl.S = (p.L + pl.range_len - 1) / pl.range_len;
