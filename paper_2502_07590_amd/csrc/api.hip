@@ -102,7 +102,7 @@ bool use_split(const dsv_problem &p, const SplitPlan &pl) { return (p.flags & DS
 struct FwdLayout {
     bool split;
     SplitPlan plan;
-    size_t seg, pm, pl, pacc, total;
+    size_t seg, pm, pl, pacc, hist, order, total;
 };
 
 FwdLayout fwd_layout(const dsv_problem &p)
@@ -117,6 +117,8 @@ FwdLayout fwd_layout(const dsv_problem &p)
     w.pm = o; o = align_up(o + rows * w.plan.S * 4, 256);
     w.pl = o; o = align_up(o + rows * w.plan.S * 4, 256);
     w.pacc = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
+    w.hist = o; o = align_up(o + (size_t)p.B * p.H * w.plan.S * ((size_t)w.plan.range_len + 1) * 4, 256);
+    w.order = o; o = align_up(o + rows * w.plan.S * 4, 256);
     w.total = o;
     return w;
 }
@@ -142,8 +144,8 @@ StepLayout step_layout(const dsv_problem &p)
     w.pa = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
     w.pb = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
     w.pdelta = o; o = align_up(o + rows * w.plan.S * 4, 256);
-    w.hist = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 4, 256);
-    w.order = o; o = align_up(o + rows * 4, 256);
+    w.hist = o; o = align_up(o + nbh * w.plan.S * ((size_t)w.plan.range_len + 1) * 4, 256);
+    w.order = o; o = align_up(o + rows * w.plan.S * 4, 256);
     w.rowstat = o; o = align_up(o + rows * 8, 256);
     w.total = o;
     return w;
@@ -295,6 +297,8 @@ dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, const void *
     b.pm = reinterpret_cast<float *>(ws + w.pm);
     b.pl = reinterpret_cast<float *>(ws + w.pl);
     b.pacc = reinterpret_cast<float *>(ws + w.pacc);
+    b.hist = reinterpret_cast<int32_t *>(ws + w.hist);
+    b.order = reinterpret_cast<int32_t *>(ws + w.order);
     return launch_sparse_fwd_split(*p, tabs.data(), (int)tabs.size(), Q, K, V, idx, O, lse, w.plan, b, stream);
 }
 

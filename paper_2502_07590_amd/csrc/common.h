@@ -254,6 +254,8 @@ struct FwdSplitWorkspace {
     float *pm;     // [B*H, L, S]    partial running max (log2 domain)
     float *pl;     // [B*H, L, S]    partial normaliser
     float *pacc;   // [B*H, L, S, d] partial unnormalised output
+    int32_t *hist;   // [B*H, S, range_len + 1]  rows per segment length (then their start offsets)
+    int32_t *order;  // [B*H, S, L]  rows of every (head, range) by descending segment length
 };
 dsv_status launch_sparse_fwd_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
                                    const void *K, const void *V, const int32_t *idx, void *O, float *lse,
@@ -265,8 +267,8 @@ struct BwdSplitWorkspace {
     float *pa;      // [B*H, L, S, d]
     float *pb;      // [B*H, L, S, d]
     float *pdelta;  // [B*H, L, S]   (dq step only)
-    int32_t *hist;  // [B*H, L+1]    keys per list length (dkdv step only)
-    int32_t *order; // [B*H, L]      keys by descending list length (dkdv step only)
+    int32_t *hist;  // [B*H, S, range_len + 1]  rows per segment length (then their start offsets)
+    int32_t *order; // [B*H, S, L]   rows of every (head, range) by descending segment length
     float2 *rowstat;  // [B*H, L]    {lse * log2(e), Delta} per query (dkdv step only)
 };
 dsv_status launch_bwd_dq_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,

@@ -75,7 +75,8 @@ template <typename T, int D, int LPR>
 __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                const T *__restrict__ V,
                                                                const int32_t *__restrict__ idx,
-                                                               const int32_t *__restrict__ seg, float *__restrict__ pm,
+                                                               const int32_t *__restrict__ seg,
+                                                               const int32_t *__restrict__ order, float *__restrict__ pm,
                                                                float *__restrict__ pl_, float *__restrict__ pacc, int L,
                                                                float scale, HeadTable tab, SplitPlan pl)
 {
@@ -88,13 +89,13 @@ __global__ __launch_bounds__(256) void sparse_fwd_split_kernel(const T *__restri
     const int k = tab.k[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPR, s = lane % LPR;
-    const int64_t iq = (int64_t)qb * (4 * RPW) + wave * RPW + grp;
-    const bool live = iq < L;
-    const int64_t i = live ? iq : L - 1;
+    const int64_t ipos = (int64_t)qb * (4 * RPW) + wave * RPW + grp;  // position in this range's row order
+    const bool live = ipos < L;
+    const int64_t i = order[((int64_t)bh * pl.S + range) * L + (live ? ipos : L - 1)];
     const int64_t head_base = (int64_t)bh * L * D;
     const int32_t *row = idx + tab.off[slot] + i * k;
     const int32_t *sp = seg + ((int64_t)bh * L + i) * (pl.S + 1) + range;
-    const int tb = sp[0], te = sp[1];
+    const int tb = sp[0], te = live ? sp[1] : sp[0];
 
     const RowChunk<T, CH> q = load_chunk<T, CH, LL::PSB>(Q + head_base + i * D + LL::off(s));
     FwdState<CH> st;
@@ -153,6 +154,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__res
                                                                   const T *__restrict__ V,
                                                                   const int32_t *__restrict__ idx,
                                                                   const int32_t *__restrict__ seg,
+                                                                  const int32_t *__restrict__ order,
                                                                   const T *__restrict__ O,
                                                                   const float *__restrict__ lse,
                                                                   const T *__restrict__ dO, float *__restrict__ pa,
@@ -168,13 +170,13 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_split_kernel(const T *__res
     const int k = tab.k[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPR, s = lane % LPR;
-    const int64_t iq = (int64_t)qb * (4 * RPW) + wave * RPW + grp;
-    const bool live = iq < L;
-    const int64_t i = live ? iq : L - 1;
+    const int64_t ipos = (int64_t)qb * (4 * RPW) + wave * RPW + grp;  // position in this range's row order
+    const bool live = ipos < L;
+    const int64_t i = order[((int64_t)bh * pl.S + range) * L + (live ? ipos : L - 1)];
     const int64_t head_base = (int64_t)bh * L * D;
     const int32_t *row = idx + tab.off[slot] + i * k;
     const int32_t *sp = seg + ((int64_t)bh * L + i) * (pl.S + 1) + range;
-    const int tb = sp[0], te = sp[1];
+    const int tb = sp[0], te = live ? sp[1] : sp[0];
 
     const RowChunk<T, CH> q = load_chunk<T, CH, LL::PSB>(Q + head_base + i * D + LL::off(s));
     const RowChunk<T, CH> go = load_chunk<T, CH, LL::PSB>(dO + head_base + i * D + LL::off(s));
@@ -234,8 +236,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_merge_kernel(const float *_
 // ---- backward, dkdv step -------------------------------------------------------------------------
 // Key-major: work item = (head, QUERY range, block of 16 keys); a key's ascending query list has one
 // contiguous segment per query range, whose Q / dO rows (and lse, Delta entries) stay in L2.
-// `order` (optional): keys sorted by descending list length, so that the four keys of a wave (and
-// the sixteen of a block) have segments of similar length; without it key = block position.
+// `order`: this range's keys by descending segment length (see seglen_* below).
 template <typename T, int D, int LPR>
 __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                     const T *__restrict__ V,
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
     const int64_t jpos = (int64_t)kb * (4 * RPW) + wave * RPW + grp;
     const bool live = jpos < L;
     const int64_t jp = live ? jpos : L - 1;
-    const int64_t j = order ? order[(int64_t)bh * L + jp] : jp;
+    const int64_t j = order[((int64_t)bh * pl.S + range) * L + jp];
     const int64_t head_base = (int64_t)bh * L * D;
     const int32_t *list = idxT + tab.off[slot] + col[(int64_t)bh * (L + 1) + j];
     const int32_t *sp = seg + ((int64_t)bh * L + j) * (pl.S + 1) + range;
@@ -317,21 +318,42 @@ __global__ __launch_bounds__(256) void pack_rowstat_kernel(const float *__restri
     if (e < n) out[e] = make_float2(lse[e] * kLog2e, delta[e]);
 }
 
-// ---- keys in order of descending list length (counting sort on the length) ---------------------
-// hist[bh, L - len] counts keys per length; after an exclusive scan it holds, for every length,
-// the first rank of the keys that long; the scatter hands out ranks through atomic cursors (the
-// order among keys of equal length is arbitrary and does not affect any result).
-__global__ __launch_bounds__(256) void keylen_hist_kernel(const int64_t *__restrict__ col, int L, int32_t *__restrict__ hist)
+// ---- row order per range ---------------------------------------------------------------------
+// The rows a wave works on together should have segments of the same length in the range at hand,
+// or its lanes idle until the longest one is done (uniformly random selections: 7-8 % of the sweep).
+// So every (head, range) gets its own order of the L rows, by descending segment length: a counting
+// sort on the length (at most range_len).  hist: [B*H, S, nbins] counters, nbins <= range_len + 1;
+// order: [B*H, S, L].  The order inside a length class comes from atomic cursors and may differ from
+// run to run; results do not depend on it (rows are independent).
+// Rows are handled kSeglenChunk at a time by one block per (head, range, chunk), which first counts
+// in LDS and then touches the global counters once per length class it has seen (the lengths of a
+// range cluster on ~100 values, so per-row global atomics would all hit the same few addresses).
+constexpr int kSeglenChunk = 4096;
+
+__device__ __forceinline__ int seg_len(const int32_t *__restrict__ seg, int64_t bh, int L, int S, int row, int r, int nbins)
 {
-    const int bh = blockIdx.y;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= L) return;
-    const int64_t *cp = col + (int64_t)bh * (L + 1);
-    const int len = (int)(cp[j + 1] - cp[j]);
-    atomicAdd(&hist[(int64_t)bh * (L + 1) + (L - len)], 1);
+    const int32_t *sp = seg + (bh * L + row) * (S + 1) + r;
+    return min(sp[1] - sp[0], nbins - 1);
 }
 
-__global__ __launch_bounds__(1024) void keylen_scan_kernel(int32_t *__restrict__ hist, int n)
+__global__ __launch_bounds__(256) void seglen_hist_kernel(const int32_t *__restrict__ seg, int L, int S, int nbins,
+                                                          int32_t *__restrict__ hist)
+{
+    extern __shared__ int32_t lh[];  // [nbins]
+    const int bh = blockIdx.y / S, r = blockIdx.y % S;
+    const int row0 = blockIdx.x * kSeglenChunk;
+    for (int e = threadIdx.x; e < nbins; e += 256) lh[e] = 0;
+    __syncthreads();
+    for (int row = row0 + threadIdx.x; row < min(row0 + kSeglenChunk, L); row += 256)
+        atomicAdd(&lh[nbins - 1 - seg_len(seg, bh, L, S, row, r, nbins)], 1);
+    __syncthreads();
+    int32_t *gh = hist + ((int64_t)bh * S + r) * nbins;
+    for (int e = threadIdx.x; e < nbins; e += 256)
+        if (lh[e]) atomicAdd(&gh[e], lh[e]);
+}
+
+// exclusive scan of every [n]-segment of hist (one block per segment)
+__global__ __launch_bounds__(1024) void seglen_scan_kernel(int32_t *__restrict__ hist, int n)
 {
     __shared__ int32_t part[1024];
     int32_t *h = hist + (int64_t)blockIdx.x * n;
@@ -355,16 +377,24 @@ __global__ __launch_bounds__(1024) void keylen_scan_kernel(int32_t *__restrict__
     }
 }
 
-__global__ __launch_bounds__(256) void keylen_scatter_kernel(const int64_t *__restrict__ col, int L,
+__global__ __launch_bounds__(256) void seglen_scatter_kernel(const int32_t *__restrict__ seg, int L, int S, int nbins,
                                                              int32_t *__restrict__ hist, int32_t *__restrict__ order)
 {
-    const int bh = blockIdx.y;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= L) return;
-    const int64_t *cp = col + (int64_t)bh * (L + 1);
-    const int len = (int)(cp[j + 1] - cp[j]);
-    const int rank = atomicAdd(&hist[(int64_t)bh * (L + 1) + (L - len)], 1);
-    order[(int64_t)bh * L + rank] = j;
+    extern __shared__ int32_t lh[];  // [nbins]: this chunk's count per class, then its next free slot in `order`
+    const int bh = blockIdx.y / S, r = blockIdx.y % S;
+    const int row0 = blockIdx.x * kSeglenChunk, row1 = min(row0 + kSeglenChunk, L);
+    for (int e = threadIdx.x; e < nbins; e += 256) lh[e] = 0;
+    __syncthreads();
+    for (int row = row0 + threadIdx.x; row < row1; row += 256)
+        atomicAdd(&lh[nbins - 1 - seg_len(seg, bh, L, S, row, r, nbins)], 1);
+    __syncthreads();
+    int32_t *gh = hist + ((int64_t)bh * S + r) * nbins;
+    for (int e = threadIdx.x; e < nbins; e += 256)
+        if (lh[e]) lh[e] = atomicAdd(&gh[e], lh[e]);  // reserve this chunk's slots of the class
+    __syncthreads();
+    int32_t *out = order + ((int64_t)bh * S + r) * L;
+    for (int row = row0 + threadIdx.x; row < row1; row += 256)
+        out[atomicAdd(&lh[nbins - 1 - seg_len(seg, bh, L, S, row, r, nbins)], 1)] = row;
 }
 
 __global__ __launch_bounds__(256) void zero_i32_kernel(int32_t *__restrict__ p, int64_t n)
@@ -402,12 +432,32 @@ static dsv_status launch_segments(const dsv_problem &p, const HeadTable *tabs, i
     return DSV_OK;
 }
 
+// order[bh, r, :] = the rows of head bh by descending segment length in range r (from seg).
+static dsv_status launch_row_order(const dsv_problem &p, const SplitPlan &pl, const int32_t *seg, int32_t *hist,
+                                   int32_t *order, hipStream_t st)
+{
+    const int nbh = p.B * p.H;
+    // length classes; longer segments (possible only with ranges above 8192 rows) share the last class
+    const int nbins = std::min(pl.range_len + 1, 8193);
+    const int64_t nh = (int64_t)nbh * pl.S * nbins;
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nh + 255) / 256, 4096)), dim3(256), 0, st, hist, nh);
+    if ((int64_t)nbh * pl.S > 65535) return DSV_EUNSUPPORTED;
+    dim3 grid((p.L + kSeglenChunk - 1) / kSeglenChunk, nbh * pl.S);
+    hipLaunchKernelGGL(seglen_hist_kernel, grid, dim3(256), (size_t)nbins * 4, st, seg, p.L, pl.S, nbins, hist);
+    hipLaunchKernelGGL(seglen_scan_kernel, dim3(nbh * pl.S), dim3(1024), 0, st, hist, nbins);
+    hipLaunchKernelGGL(seglen_scatter_kernel, grid, dim3(256), (size_t)nbins * 4, st, seg, p.L, pl.S, nbins, hist, order);
+    DSV_LAUNCH_CHECK();
+    return DSV_OK;
+}
+
 template <typename T, int D>
 static dsv_status fwd_split_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                               const void *V, const int32_t *idx, void *O, float *lse, const SplitPlan &pl,
                               const FwdSplitWorkspace &w, hipStream_t st)
 {
     dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idx, nullptr, w.seg, st);
+    if (rc != DSV_OK) return rc;
+    rc = launch_row_order(p, pl, w.seg, w.hist, w.order, st);
     if (rc != DSV_OK) return rc;
     {
         KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
@@ -417,7 +467,7 @@ static dsv_status fwd_split_t(const dsv_problem &p, const HeadTable *tabs, int n
             const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
             if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
             hipLaunchKernelGGL((sparse_fwd_split_kernel<T, D, kLprFwd>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
-                               (const T *)K, (const T *)V, idx, w.seg, w.pm, w.pl, w.pacc, p.L, p.scale, tabs[t], lp);
+                               (const T *)K, (const T *)V, idx, w.seg, w.order, w.pm, w.pl, w.pacc, p.L, p.scale, tabs[t], lp);
             DSV_LAUNCH_CHECK();
         }
     }
@@ -436,6 +486,8 @@ static dsv_status bwd_dq_split_t(const dsv_problem &p, const HeadTable *tabs, in
 {
     dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idx, nullptr, w.seg, st);
     if (rc != DSV_OK) return rc;
+    rc = launch_row_order(p, pl, w.seg, w.hist, w.order, st);
+    if (rc != DSV_OK) return rc;
     {
         KernelSpan span(DSV_KERNEL_DQ_SWEEP, st);
         for (int t = 0; t < n_tabs; ++t) {
@@ -444,7 +496,7 @@ static dsv_status bwd_dq_split_t(const dsv_problem &p, const HeadTable *tabs, in
             const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
             if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
             hipLaunchKernelGGL((sparse_bwd_dq_split_kernel<T, D, kLprDq>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
-                               (const T *)K, (const T *)V, idx, w.seg, (const T *)O, lse, (const T *)dO, w.pa, w.pb,
+                               (const T *)K, (const T *)V, idx, w.seg, w.order, (const T *)O, lse, (const T *)dO, w.pa, w.pb,
                                w.pdelta, p.L, p.scale, tabs[t], lp);
             DSV_LAUNCH_CHECK();
         }
@@ -468,15 +520,9 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
     const int64_t nrows = (int64_t)nbh * p.L;
     hipLaunchKernelGGL(pack_rowstat_kernel, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, st, lse, delta,
                        w.rowstat, nrows);
-    // keys by descending list length (w.hist: [B*H, L+1] counters, w.order: [B*H, L])
-    const int64_t nh = (int64_t)nbh * (p.L + 1);
-    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nh + 255) / 256, 4096)), dim3(256), 0, st,
-                       w.hist, nh);
-    dim3 kgrid((p.L + 255) / 256, nbh);
-    hipLaunchKernelGGL(keylen_hist_kernel, kgrid, dim3(256), 0, st, col, p.L, w.hist);
-    hipLaunchKernelGGL(keylen_scan_kernel, dim3(nbh), dim3(1024), 0, st, w.hist, p.L + 1);
-    hipLaunchKernelGGL(keylen_scatter_kernel, kgrid, dim3(256), 0, st, col, p.L, w.hist, w.order);
     DSV_LAUNCH_CHECK();
+    rc = launch_row_order(p, pl, w.seg, w.hist, w.order, st);
+    if (rc != DSV_OK) return rc;
     {
         KernelSpan span(DSV_KERNEL_DKDV_SWEEP, st);
         for (int t = 0; t < n_tabs; ++t) {
