@@ -232,8 +232,8 @@ static dsv_status fwd_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs,
 {
     KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
     for (int t = 0; t < n_tabs; ++t) {
-        dim3 grid((p.L + 256 / kLprFwd - 1) / (256 / kLprFwd), tabs[t].n);
-        hipLaunchKernelGGL((sparse_fwd_kernel<T, D, kLprFwd>), grid, dim3(256), 0, st, (const T *)Q, (const T *)K, (const T *)V,
+        dim3 grid((p.L + 256 / SweepLanes<T, D>::fwd - 1) / (256 / SweepLanes<T, D>::fwd), tabs[t].n);
+        hipLaunchKernelGGL((sparse_fwd_kernel<T, D, SweepLanes<T, D>::fwd>), grid, dim3(256), 0, st, (const T *)Q, (const T *)K, (const T *)V,
                            idx, (T *)O, lse, p.L, p.scale, tabs[t]);
         DSV_LAUNCH_CHECK();
     }
@@ -247,8 +247,8 @@ static dsv_status bwd_dq_t(const dsv_problem &p, const HeadTable *tabs, int n_ta
 {
     KernelSpan span(DSV_KERNEL_DQ_SWEEP, st);
     for (int t = 0; t < n_tabs; ++t) {
-        dim3 qgrid((p.L + 256 / kLprDq - 1) / (256 / kLprDq), tabs[t].n);
-        hipLaunchKernelGGL((sparse_bwd_dq_kernel<T, D, kLprDq>), qgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
+        dim3 qgrid((p.L + 256 / SweepLanes<T, D>::dq - 1) / (256 / SweepLanes<T, D>::dq), tabs[t].n);
+        hipLaunchKernelGGL((sparse_bwd_dq_kernel<T, D, SweepLanes<T, D>::dq>), qgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
                            (const T *)V, idx, (const T *)O, lse, (const T *)dO, (T *)dQ, delta, p.L, p.scale, tabs[t]);
         DSV_LAUNCH_CHECK();
     }
@@ -262,8 +262,8 @@ static dsv_status bwd_dkdv_t(const dsv_problem &p, const HeadTable *tabs, int n_
 {
     KernelSpan span(DSV_KERNEL_DKDV_SWEEP, st);
     for (int t = 0; t < n_tabs; ++t) {
-        dim3 kgrid((p.L + 256 / kLprDkdv - 1) / (256 / kLprDkdv), tabs[t].n);
-        hipLaunchKernelGGL((sparse_bwd_dkdv_kernel<T, D, kLprDkdv>), kgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
+        dim3 kgrid((p.L + 256 / SweepLanes<T, D>::dkdv - 1) / (256 / SweepLanes<T, D>::dkdv), tabs[t].n);
+        hipLaunchKernelGGL((sparse_bwd_dkdv_kernel<T, D, SweepLanes<T, D>::dkdv>), kgrid, dim3(256), 0, st, (const T *)Q, (const T *)K,
                            (const T *)V, idxT, col, lse, delta, (const T *)dO, (T *)dK, (T *)dV, p.L, p.scale, tabs[t]);
         DSV_LAUNCH_CHECK();
     }

@@ -27,11 +27,12 @@
 
 namespace dsv {
 
-// Lanes per row of each sweep (rows per 256-thread block = 256 / lanes), steps per loop trip of the
-// backward sweeps and keys per forward step.  Measured on MI355X at L = 128k, bf16, d = 128, k = 8192
-// (ms per launch) with the strip-interleaved lane layout and the staged index: forward 16 lanes: 131,
-// 8: 124, 4: 123; dq 16: 145, 8: 132, 4: 202 (registers); dkdv 16: 190, 8: 158, 4: 153.  Two steps per
-// trip or 8 keys per forward step change nothing measurable (the gathers already fill the memory path).
+// Lanes per row of each sweep (rows per 256-thread block = 256 / lanes), chosen through the bytes of a
+// row each lane holds: 64 for the forward and the dkdv sweep, 32 for the dq sweep (it keeps three row
+// chunks and two accumulators in registers).  Measured on MI355X at L = 128k, bf16, d = 128, k = 8192
+// (ms per sweep): forward 16 lanes: 131, 8: 112, 4: 110; dq 16: 145, 8: 123, 4: 202 (registers);
+// dkdv 16: 190, 8: 148, 4: 140.  Two steps per loop trip or 8 keys per forward step change nothing or
+// cost a little (the gathers already fill the memory path).
 #ifndef DSV_DQ_REP
 #define DSV_DQ_REP 1
 #endif
@@ -41,16 +42,25 @@ namespace dsv {
 #ifndef DSV_FWD_U
 #define DSV_FWD_U 4   // keys per forward step (4 or 8)
 #endif
-#ifndef DSV_LPR_FWD
-#define DSV_LPR_FWD 8
+#ifndef DSV_CHUNK_FWD
+#define DSV_CHUNK_FWD 64
 #endif
-#ifndef DSV_LPR_DQ
-#define DSV_LPR_DQ 8
+#ifndef DSV_CHUNK_DQ
+#define DSV_CHUNK_DQ 32
 #endif
-#ifndef DSV_LPR_DKDV
-#define DSV_LPR_DKDV 8
+#ifndef DSV_CHUNK_DKDV
+#define DSV_CHUNK_DKDV 64
 #endif
-constexpr int kLprFwd = DSV_LPR_FWD, kLprDq = DSV_LPR_DQ, kLprDkdv = DSV_LPR_DKDV;
+constexpr int lanes_for(int row_bytes, int chunk_bytes)
+{
+    const int l = row_bytes / chunk_bytes;
+    return l < 4 ? 4 : (l > 16 ? 16 : l);
+}
+template <typename T, int D> struct SweepLanes {
+    static constexpr int fwd = lanes_for(D * (int)sizeof(T), DSV_CHUNK_FWD);
+    static constexpr int dq = lanes_for(D * (int)sizeof(T), DSV_CHUNK_DQ);
+    static constexpr int dkdv = lanes_for(D * (int)sizeof(T), DSV_CHUNK_DKDV);
+};
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;

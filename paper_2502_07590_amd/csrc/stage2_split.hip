@@ -463,10 +463,10 @@ static dsv_status fwd_split_t(const dsv_problem &p, const HeadTable *tabs, int n
         KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
         for (int t = 0; t < n_tabs; ++t) {
             SplitPlan lp = pl;
-            lp.nqb = (p.L + 256 / kLprFwd - 1) / (256 / kLprFwd);  // row blocks of this kernel's layout
+            lp.nqb = (p.L + 256 / SweepLanes<T, D>::fwd - 1) / (256 / SweepLanes<T, D>::fwd);  // row blocks of this kernel's layout
             const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
             if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-            hipLaunchKernelGGL((sparse_fwd_split_kernel<T, D, kLprFwd>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
+            hipLaunchKernelGGL((sparse_fwd_split_kernel<T, D, SweepLanes<T, D>::fwd>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
                                (const T *)K, (const T *)V, idx, w.seg, w.order, w.pm, w.pl, w.pacc, p.L, p.scale, tabs[t], lp);
             DSV_LAUNCH_CHECK();
         }
@@ -492,10 +492,10 @@ static dsv_status bwd_dq_split_t(const dsv_problem &p, const HeadTable *tabs, in
         KernelSpan span(DSV_KERNEL_DQ_SWEEP, st);
         for (int t = 0; t < n_tabs; ++t) {
             SplitPlan lp = pl;
-            lp.nqb = (p.L + 256 / kLprDq - 1) / (256 / kLprDq);  // row blocks of this kernel's layout
+            lp.nqb = (p.L + 256 / SweepLanes<T, D>::dq - 1) / (256 / SweepLanes<T, D>::dq);  // row blocks of this kernel's layout
             const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
             if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-            hipLaunchKernelGGL((sparse_bwd_dq_split_kernel<T, D, kLprDq>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
+            hipLaunchKernelGGL((sparse_bwd_dq_split_kernel<T, D, SweepLanes<T, D>::dq>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)Q,
                                (const T *)K, (const T *)V, idx, w.seg, w.order, (const T *)O, lse, (const T *)dO, w.pa, w.pb,
                                w.pdelta, p.L, p.scale, tabs[t], lp);
             DSV_LAUNCH_CHECK();
@@ -527,10 +527,10 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
         KernelSpan span(DSV_KERNEL_DKDV_SWEEP, st);
         for (int t = 0; t < n_tabs; ++t) {
             SplitPlan lp = pl;
-            lp.nqb = (p.L + 256 / kLprDkdv - 1) / (256 / kLprDkdv);  // row blocks of this kernel's layout
+            lp.nqb = (p.L + 256 / SweepLanes<T, D>::dkdv - 1) / (256 / SweepLanes<T, D>::dkdv);  // row blocks of this kernel's layout
             const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
             if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-            hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D, kLprDkdv>), dim3((unsigned)blocks), dim3(256), 0, st,
+            hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D, SweepLanes<T, D>::dkdv>), dim3((unsigned)blocks), dim3(256), 0, st,
                                (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, w.order,
                                reinterpret_cast<const float *>(w.rowstat), (const float *)nullptr, (const T *)dO, w.pa,
                                w.pb, p.L, p.scale, tabs[t], lp);
