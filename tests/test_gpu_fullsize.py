@@ -1,8 +1,10 @@
-"""Parity at the benchmark's full size and launch configuration: config 2 (bf16, H = 6, L = 131072,
-d = 128, r = 16, k = 8192), sorted-index flag set, stage 1 emitting the transposed index, backward
-through dsv_sparse_attn_bwd_t -- exactly the calls bench.py times.
+"""Parity at the benchmark configurations' full sizes, in the launch configuration bench.py times:
+sorted-index flag set, stage 1 emitting the transposed index, backward through dsv_sparse_attn_bwd_t.
+Configs 1-4 of the benchmark list (config 0 is small enough to be checked in full elsewhere); config 2
+is the one bench.py reports.
 
-The oracle cannot do the whole problem (1e11 scores), so it computes sampled outputs one by one:
+The oracle cannot do whole problems of this size (1e11 and more scores), so it computes sampled outputs
+one by one:
   * stage 1 on the real top-k: sampled index rows against the oracle's selection applied to the
     device's own fp32 score bits (bit-exact) and against the pure fp64 oracle; properties that hold
     at any size for everything else (rows ascending and in range, exactly k per row, idx_t is the
@@ -24,13 +26,23 @@ pytestmark = pytest.mark.gpu
 
 dsv = pytest.importorskip("paper_2502_07590_amd")
 
-CFG = wl.get_config(2)
-HOST_HEADS = (0, 5)          # heads whose inputs are also kept on the host for the oracle
+CONFIGS = (1, 2, 3, 4)
 
 
-@pytest.fixture(scope="module")
-def data():
-    cfg = CFG
+def _host_heads(cfg):
+    return (0, cfg.H - 1)      # heads whose inputs are also kept on the host for the oracle
+
+
+def _row_chunks(L, k, elems=1 << 28):
+    """Row ranges of an [L, k] tensor with at most `elems` elements each (torch temporaries stay small)."""
+    step = max(1, elems // k)
+    return [(lo, min(lo + step, L)) for lo in range(0, L, step)]
+
+
+@pytest.fixture(scope="module", params=CONFIGS, ids=lambda c: f"config{c}")
+def data(request):
+    cfg = wl.get_config(request.param)
+    ks = [int(x) for x in wl.k_per_head(cfg)]
     td = torch.bfloat16
     dev = "cuda:0"
     g = {n: torch.empty((1, cfg.H, cfg.L, cfg.d), dtype=td, device=dev) for n in ("Q", "K", "V", "dO")}
@@ -44,45 +56,58 @@ def data():
         wq, wk = wl.predictor_weights(cfg, h)
         Wq[h].copy_(torch.from_numpy(wq).to(td))
         Wk[h].copy_(torch.from_numpy(wk).to(td))
-        if h in HOST_HEADS:
+        if h in _host_heads(cfg):
             host[h] = dict(t, Wq=wq, Wk=wk)
-        print(f"generated head {h}", flush=True)
-    return g, Wq, Wk, host
+    print(f"config {cfg.index}: inputs generated", flush=True)
+    yield cfg, ks, g, Wq, Wk, host
+    del g, Wq, Wk
+    torch.cuda.empty_cache()
 
 
 def test_stage1_full_size(data):
-    cfg = CFG
-    g, Wq, Wk, host = data
-    L, k = cfg.L, cfg.k
-    p = dsv.Problem(1, cfg.H, L, cfg.d, cfg.r, cfg.dtype, [k] * cfg.H, cfg.scale, sorted_index=True)
-    idx, idx_t, col = dsv.lowrank_topk_t(p, g["Q"], g["K"], Wq, Wk)
+    cfg, ks, g, Wq, Wk, host = data
+    L = cfg.L
+    off = wl.idx_offsets(1, cfg.H, L, ks)
+    p = dsv.Problem(1, cfg.H, L, cfg.d, cfg.r, cfg.dtype, ks, cfg.scale, sorted_index=True)
+    idx_flat, idx_t_flat, col = dsv.lowrank_topk_t(p, g["Q"], g["K"], Wq, Wk)
     Qlr, Klr = dsv.lowrank_project(p, g["Q"], g["K"], Wq, Wk)
     torch.cuda.synchronize()
-    idx = idx.view(cfg.H, L, k)
-    idx_t = idx_t.view(cfg.H, L * k)
+
+    def rows_of(h):
+        return idx_flat[off[h]:off[h + 1]].view(L, ks[h])
+
     # any-size properties, all heads
-    assert int(idx.min()) >= 0 and int(idx.max()) < L
     for h in range(cfg.H):
-        assert bool((idx[h, :, 1:] > idx[h, :, :-1]).all()), f"head {h}: rows not strictly ascending"
-        assert int(col[h, 0]) == 0 and int(col[h, -1]) == L * k
+        idx = rows_of(h)
+        for lo, hi in _row_chunks(L, ks[h]):
+            part = idx[lo:hi]
+            assert int(part.min()) >= 0 and int(part.max()) < L
+            if ks[h] > 1:
+                assert bool((part[:, 1:] > part[:, :-1]).all()), f"head {h}: rows not strictly ascending"
+        assert int(col[h, 0]) == 0 and int(col[h, -1]) == L * ks[h]
         assert bool((col[h, 1:] >= col[h, :-1]).all())
     # list lengths = per-key counts, one head
-    h = HOST_HEADS[1]
-    counts = torch.bincount(idx[h].reshape(-1).to(torch.int64), minlength=L)
+    h = _host_heads(cfg)[1]
+    counts = torch.zeros(L, dtype=torch.int64, device=idx_flat.device)
+    for lo, hi in _row_chunks(L, ks[h]):
+        counts += torch.bincount(rows_of(h)[lo:hi].reshape(-1), minlength=L)
     assert torch.equal(counts, col[h, 1:] - col[h, :-1])
     del counts
     rng = np.random.default_rng(0)
-    for h in HOST_HEADS:
+    for h in _host_heads(cfg):
+        idx, k = rows_of(h), ks[h]
+        idx_t = idx_t_flat[off[h]:off[h + 1]]
         # exact transpose for sampled keys
-        for j in rng.integers(0, L, size=4).tolist() + [0, L - 1]:
-            want = torch.nonzero((idx[h] == j).any(dim=1)).reshape(-1).to(torch.int32)
-            got = idx_t[h, int(col[h, j]):int(col[h, j + 1])]
+        for j in rng.integers(0, L, size=3).tolist() + [0, L - 1]:
+            hit = torch.cat([(idx[lo:hi] == j).any(dim=1) for lo, hi in _row_chunks(L, k)])
+            want = torch.nonzero(hit).reshape(-1).to(torch.int32)
+            got = idx_t[int(col[h, j]):int(col[h, j + 1])]
             assert torch.equal(want, got), f"head {h} key {j}: idx_t list is not the column of idx"
         # sampled rows against the oracle
-        rows = np.unique(np.concatenate([rng.integers(0, L, size=10), [0, L - 1]])).astype(np.int32)
+        rows = np.unique(np.concatenate([rng.integers(0, L, size=8), [0, L - 1]])).astype(np.int32)
         S_gpu = dsv.lowrank_scores_rows(p, Qlr, Klr, 0, h, torch.from_numpy(rows).cuda())
         torch.cuda.synchronize()
-        got = idx[h][torch.from_numpy(rows.astype(np.int64)).cuda()].cpu().numpy()
+        got = idx[torch.from_numpy(rows.astype(np.int64)).cuda()].cpu().numpy()
         t2 = oracle.topk_from_scores(S_gpu.cpu().numpy().astype(np.float64), k)
         assert np.array_equal(t2, got), f"head {h}: selection differs from the oracle's on the same score bits"
         t3, _, _, S_or = oracle.lowrank_topk(host[h]["Q"][rows], host[h]["K"], host[h]["Wq"], host[h]["Wk"], k, cfg.dtype,
@@ -99,68 +124,80 @@ def test_stage1_full_size(data):
             # terms) and the fp32 accumulation order differs: both are far inside 2^-6 of the largest score
             band = 2.0 ** -6 * np.abs(S_or[a]).max()
             assert np.all(np.abs(S_or[a][sym] - tau) <= band), f"head {h} row {rows[a]}: difference outside the rounding band"
-        print(f"head {h}: {same}/{len(rows)} sampled rows identical to the pure fp64 oracle", flush=True)
+        print(f"config {cfg.index} head {h}: {same}/{len(rows)} sampled rows identical to the pure fp64 oracle", flush=True)
 
 
-def _progression_on_device(L, k, head, dev):
+def _progression_on_device(L, k, head, dev, rows_out, lists_out):
+    """Fill rows_out [L, k] and lists_out [L*k] (views into the flat index tensors); return col [L+1]."""
     base, gg, ginv = wl.progression_params(L, seed=0, head=head)
     tb, tg = torch.from_numpy(base).to(dev), torch.from_numpy(gg).to(dev)
-    rows = torch.empty((L, k), dtype=torch.int32, device=dev)
     t = torch.arange(k, dtype=torch.int64, device=dev)[None, :]
-    for lo in range(0, L, 16384):
-        hi = min(lo + 16384, L)
+    step = max(1, (1 << 28) // k)                      # about 2 GB of int64 per chunk
+    for lo in range(0, L, step):
+        hi = min(lo + step, L)
         v = (tb[lo:hi, None] + t * tg[lo:hi, None]) & (L - 1)
-        rows[lo:hi] = torch.sort(v, dim=1).values.to(torch.int32)
+        rows_out[lo:hi] = torch.sort(v, dim=1).values.to(torch.int32)
     # key-major lists in closed form: query i holds key j  <=>  ((j - base_i) * ginv_i mod L) < k
     tinv = torch.from_numpy(ginv).to(dev)
-    lists, counts = [], torch.empty(L, dtype=torch.int64, device=dev)
-    for lo in range(0, L, 2048):
-        hi = min(lo + 2048, L)
+    counts = torch.empty(L, dtype=torch.int64, device=dev)
+    kstep = max(1, (1 << 28) // L)
+    pos = 0
+    for lo in range(0, L, kstep):
+        hi = min(lo + kstep, L)
         keys = torch.arange(lo, hi, dtype=torch.int64, device=dev)[:, None]
         member = (((keys - tb[None, :]) * tinv[None, :]) & (L - 1)) < k
         counts[lo:hi] = member.sum(dim=1)
-        lists.append(torch.nonzero(member)[:, 1].to(torch.int32))     # row-major nonzero: keys ascending, queries ascending
+        q = torch.nonzero(member)[:, 1].to(torch.int32)     # row-major nonzero: keys ascending, queries ascending
+        lists_out[pos:pos + q.numel()] = q
+        pos += q.numel()
+        del member, q
+    assert pos == L * k
     col = torch.zeros(L + 1, dtype=torch.int64, device=dev)
     col[1:] = torch.cumsum(counts, 0)
-    return rows, torch.cat(lists), col, (base, gg, ginv)
+    return col, (base, gg, ginv)
 
 
 def test_stage2_full_size(data):
-    cfg = CFG
-    g, _, _, host = data
-    L, k, dev = cfg.L, cfg.k, "cuda:0"
-    p = dsv.Problem(1, cfg.H, L, cfg.d, cfg.r, cfg.dtype, [k] * cfg.H, cfg.scale, sorted_index=True)
-    idx = torch.empty((cfg.H, L, k), dtype=torch.int32, device=dev)
-    idx_t = torch.empty((cfg.H, L * k), dtype=torch.int32, device=dev)
+    cfg, ks, g, _, _, host = data
+    L, dev = cfg.L, "cuda:0"
+    off = wl.idx_offsets(1, cfg.H, L, ks)
+    p = dsv.Problem(1, cfg.H, L, cfg.d, cfg.r, cfg.dtype, ks, cfg.scale, sorted_index=True)
+    idx = torch.empty(int(off[-1]), dtype=torch.int32, device=dev)
+    idx_t = torch.empty(int(off[-1]), dtype=torch.int32, device=dev)
     col = torch.empty((cfg.H, L + 1), dtype=torch.int64, device=dev)
     params = {}
     for h in range(cfg.H):
-        rows, lists, c, prm = _progression_on_device(L, k, h, dev)
-        idx[h], idx_t[h], col[h] = rows, lists, c
-        params[h] = prm
-        print(f"index sets of head {h} built", flush=True)
-    O, lse = dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx.view(-1))
-    dQ, dK, dV = dsv.sparse_attn_bwd_t(p, g["Q"], g["K"], g["V"], idx.view(-1), idx_t.view(-1), col, O, lse, g["dO"])
+        col[h], params[h] = _progression_on_device(L, ks[h], h, dev, idx[off[h]:off[h + 1]].view(L, ks[h]),
+                                                   idx_t[off[h]:off[h + 1]])
+    print(f"config {cfg.index}: index sets built", flush=True)
+    torch.cuda.empty_cache()
+    O, lse = dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx)
     torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    dQ, dK, dV = dsv.sparse_attn_bwd_t(p, g["Q"], g["K"], g["V"], idx, idx_t, col, O, lse, g["dO"])
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
     rng = np.random.default_rng(1)
-    for h in HOST_HEADS:
-        t = host[h]
+    for h in _host_heads(cfg):
+        t, k = host[h], ks[h]
         rows = np.unique(np.concatenate([rng.integers(0, L, size=6), [0, L - 1]]))
         idx_rows = wl.progression_idx_rows(L, k, rows, params[h])
-        assert np.array_equal(idx_rows, idx[h][torch.from_numpy(rows).cuda()].cpu().numpy())     # the test's own two constructions agree
+        mine = idx[off[h]:off[h + 1]].view(L, k)[torch.from_numpy(rows).cuda()].cpu().numpy()
+        assert np.array_equal(idx_rows, mine)     # the test's own two constructions agree
         O_ref, lse_ref = oracle.sparse_fwd(t["Q"][rows], t["K"], t["V"], idx_rows, cfg.scale)
         dQ_ref = oracle.sparse_bwd_dq_rows(t["Q"][rows], t["K"], t["V"], idx_rows, t["dO"][rows], cfg.scale)
         sel = torch.from_numpy(rows).cuda()
         assert_close(f"O[h={h}]", O[0, h][sel], O_ref, cfg.dtype)
         assert_close(f"lse[h={h}]", lse[0, h][sel], lse_ref, "f32")
         assert_close(f"dQ[h={h}]", dQ[0, h][sel], dQ_ref, cfg.dtype)
-    h = HOST_HEADS[0]
-    t = host[h]
+    h = _host_heads(cfg)[0]
+    t, k = host[h], ks[h]
     for j in (int(rng.integers(0, L)), L - 1):
         qs = wl.progression_queries_of_key(L, k, j, params[h])
-        assert np.array_equal(qs, idx_t[h, int(col[h, j]):int(col[h, j + 1])].cpu().numpy().astype(np.int64))
+        mine = idx_t[off[h] + int(col[h, j]):off[h] + int(col[h, j + 1])].cpu().numpy().astype(np.int64)
+        assert np.array_equal(qs, mine)
         idx_sel = wl.progression_idx_rows(L, k, qs, params[h])
         dKj, dVj = oracle.sparse_bwd_dkdv_key(j, t["Q"][qs], t["dO"][qs], idx_sel, t["K"], t["V"], cfg.scale)
         assert_close(f"dK[h={h}, j={j}]", dK[0, h, j], dKj, cfg.dtype)
         assert_close(f"dV[h={h}, j={j}]", dV[0, h, j], dVj, cfg.dtype)
-        print(f"key {j}: {len(qs)} selecting queries checked", flush=True)
+        print(f"config {cfg.index} key {j}: {len(qs)} selecting queries checked", flush=True)
