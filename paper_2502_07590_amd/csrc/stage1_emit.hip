@@ -43,68 +43,62 @@ __device__ __forceinline__ uint32_t merge_halves(uint32_t m, int half)
     return m | (uint32_t)__shfl_xor((int)m, 32);
 }
 
-// ---- output staging -------------------------------------------------------------------------------
+// ---- output: masks parked per tile, expanded in batches -------------------------------------------
 // A selected entry is 4 bytes and consecutive entries of one owner are produced ~16 tiles apart, so
-// writing them straight to memory makes every store a partial cache line (measured: 5x write
-// amplification plus read-for-ownership traffic).  Instead each owner has a ring of kRing entries in
-// LDS; entries are appended there, and whenever an owner holds 32 or more, 32 of them leave as one
-// contiguous 128-byte store issued by 32 lanes (two owners per step, one per half-wave).
-constexpr int kRing = 64;  // a tile adds at most 32 entries to an owner that holds fewer than 32
+// writing them as they appear makes every store a partial cache line (measured: 5x write
+// amplification), and appending them one by one to a per-owner buffer costs a serial loop per tile
+// that runs as long as the fullest of the 32 owners needs.  Instead the wave parks each tile's 32-bit
+// mask per owner in LDS and, every kBatch tiles, expands owner by owner: the 32 lanes of a half-wave
+// take the owner's 32 parked words (one tile each), a prefix sum of their popcounts gives every lane its
+// place in the owner's row, and the lanes write their entries side by side -- one store instruction
+// covers a contiguous stretch of the row.  Two owners are expanded at a time (one per half-wave).
+constexpr int kBatch = 32;  // tiles between two expansions (= lanes of a half-wave)
 
-// Append the set bits of `sel` (ascending = ranks 0..c-1) to the owner's ring at wpos + rank, value
-// base + bit position.  The two lanes of an owner split the work by rank: half 0 takes the lower
-// ceil(c/2) entries scanning upwards, half 1 the upper floor(c/2) scanning downwards.
-// Entries of rank >= c_ok are dropped (c_ok < c only if the row would overflow, which a correct
-// threshold rules out; the clamp keeps a wrong one from writing out of bounds).
-__device__ __forceinline__ void ring_append(int32_t *__restrict__ ring, int wpos, uint32_t sel, int c, int c_ok,
-                                            int half, int base)
+struct OwnerOut {
+    int32_t *row;   // where the owner's row / list starts
+    int32_t wpos;   // entries written so far
+    int32_t limit;  // entries the row may hold (a correct threshold fills it exactly; the clamp keeps a
+                    // wrong one from writing out of bounds)
+};
+
+struct EmitShared {
+    uint32_t mask[kBatch][33];  // [tile in batch][owner], padded: conflict-free both ways
+    OwnerOut out[32];
+};
+
+// inclusive prefix sum inside each half-wave (lanes 0..31 and lanes 32..63 separately)
+__device__ __forceinline__ int half_scan(int x)
 {
-    uint32_t work = half ? __builtin_bitreverse32(sel) : sel;
-    const int mine = half ? (c >> 1) : ((c + 1) >> 1);
-    for (int i = 0; i < mine; ++i) {
-        const int p = __ffs(work) - 1;
-        work &= work - 1;
-        const int pos = half ? 31 - p : p;
-        const int rank = half ? c - 1 - i : i;
-        if (rank < c_ok) ring[(wpos + rank) & (kRing - 1)] = base + pos;
-    }
+    int s = x;
+    s += __builtin_amdgcn_update_dpp(0, s, 0x111, 0xF, 0xF, false);  // row_shr:1 (rows of 16 lanes, zero fill)
+    s += __builtin_amdgcn_update_dpp(0, s, 0x112, 0xF, 0xF, false);  // row_shr:2
+    s += __builtin_amdgcn_update_dpp(0, s, 0x114, 0xF, 0xF, false);  // row_shr:4
+    s += __builtin_amdgcn_update_dpp(0, s, 0x118, 0xF, 0xF, false);  // row_shr:8
+    s += __builtin_amdgcn_update_dpp(0, s, 0x142, 0xA, 0xF, false);  // row_bcast15 into rows 1 and 3
+    return s;
 }
 
-// Flush 32 entries of every owner that holds at least 32.  wpos / done: entries appended / already
-// written for this lane's owner (identical in both lanes of the owner); out_base: where the owner's
-// row starts in memory (element pointer, identical in both lanes).  Returns the new `done`.
-__device__ __forceinline__ int ring_flush_full(const int32_t *__restrict__ rings, int wpos, int done,
-                                               int32_t *__restrict__ out_base, int lane)
+// Expand the parked masks of tiles tile0 .. tile0 + nfilled - 1 for all 32 owners.
+__device__ __forceinline__ void expand_batch(EmitShared &sh, int tile0, int nfilled, int lane)
 {
-    const int n = lane & 31, half = lane >> 5;
-    uint32_t pending = (uint32_t)__ballot(wpos - done >= 32);  // low half: one bit per owner
-    while (pending) {
-        const int o1 = __ffs(pending) - 1;
-        pending &= pending - 1;
-        const int o2 = pending ? __ffs(pending) - 1 : -1;
-        if (o2 >= 0) pending &= pending - 1;
-        const int o = half ? o2 : o1;  // lanes 0..31 move owner o1, lanes 32..63 owner o2
-        if (o >= 0) {
-            const int d = __shfl(done, o);
-            int32_t *dst = reinterpret_cast<int32_t *>(__shfl((long long)out_base, o));
-            dst[d + n] = rings[o * kRing + ((d + n) & (kRing - 1))];
-        }
-        if (n == o1 || n == o2) done += 32;
-    }
-    return done;
-}
-
-// Write out whatever is left (fewer than 32 entries per owner after the last ring_flush_full).
-__device__ __forceinline__ void ring_flush_rest(const int32_t *__restrict__ rings, int wpos, int done,
-                                                int32_t *__restrict__ out_base, int lane)
-{
-    const int n = lane & 31, half = lane >> 5;
+    const int t = lane & 31, half = lane >> 5;
+    const int base_val = (tile0 + t) * 32;
     for (int o0 = 0; o0 < 32; o0 += 2) {
         const int o = o0 + half;
-        const int d = __shfl(done, o);
-        const int left = __shfl(wpos, o) - d;
-        int32_t *dst = reinterpret_cast<int32_t *>(__shfl((long long)out_base, o));
-        if (n < left) dst[d + n] = rings[o * kRing + ((d + n) & (kRing - 1))];
+        uint32_t m = t < nfilled ? sh.mask[t][o] : 0u;
+        const int c = __popc(m);
+        const int incl = half_scan(c);
+        const OwnerOut oo = sh.out[o];
+        int pos = oo.wpos + incl - c;
+        while (__any(m != 0u)) {
+            if (m) {
+                const int p = __ffs(m) - 1;
+                m &= m - 1;
+                if (pos < oo.limit) oo.row[pos] = base_val + p;
+                ++pos;
+            }
+        }
+        if (t == 31) sh.out[o].wpos = min(oo.wpos + incl, oo.limit);
     }
 }
 
@@ -137,8 +131,9 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
     int32_t *row = idx + tab.off[slot] + (int64_t)qi * k;
 
     const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
-    __shared__ int32_t rings[32 * kRing];
-    int wpos = 0, done = 0, ties_taken = 0, last_tie = -1;
+    __shared__ __align__(16) EmitShared sh;
+    if (half == 0) sh.out[n] = OwnerOut{row, 0, live ? k : 0};
+    int ties_taken = 0, last_tie = -1;
     const int ntiles = (L + 31) >> 5;
     Frag<T, R> kf_next = load_frag<T, R>(Kb, 0, L, lane);
     for (int tile = 0; tile < ntiles; ++tile) {
@@ -168,13 +163,10 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
             sel = mgt | meq;
         }
         if (!live) sel = 0u;
-        const int c = __popc(sel);
-        const int c_ok = min(c, k - wpos);
-        ring_append(rings + n * kRing, wpos, sel, c, c_ok, half, j0);
-        wpos += c_ok;
-        done = ring_flush_full(rings, wpos, done, row, lane);
+        if (half == 0) sh.mask[tile % kBatch][n] = sel;
+        if (tile % kBatch == kBatch - 1) expand_batch(sh, tile - (kBatch - 1), kBatch, lane);
     }
-    ring_flush_rest(rings, wpos, done, row, lane);
+    if (ntiles % kBatch) expand_batch(sh, ntiles - ntiles % kBatch, ntiles % kBatch, lane);
     if (live && half == 0) {
         prefix[g] = __float_as_uint(tau);
         if (jcut) jcut[g] = kr < 0 ? kAllTies : last_tie;
@@ -210,15 +202,12 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
     const int j = min(j0 + n, L - 1);
 
     const Frag<T, R> kf = load_frag<T, R>(Kb, j0, L, lane);
-    __shared__ int32_t rings[WRITE ? 32 * kRing : 1];
-    int32_t *list = nullptr;
-    int limit = 0x7FFFFFFF;
-    if (WRITE) {
+    __shared__ __align__(16) EmitShared sh;
+    if (WRITE && half == 0) {
         const int64_t *cp = col + (int64_t)bh * (L + 1) + j;
-        list = idxT + tab.off[slot] + cp[0];
-        limit = (int)(cp[1] - cp[0]);
+        sh.out[n] = OwnerOut{idxT + tab.off[slot] + cp[0], 0, live ? (int)(cp[1] - cp[0]) : 0};
     }
-    int wpos = 0, done = 0;
+    int wpos = 0;  // WRITE = false: this key's list length
     // Thresholds of the queries, kTauTiles tiles at a time: one coalesced 16-byte load per lane, parked in
     // LDS, from where each lane picks the 16 values of its accumulators with broadcast reads.  (Fetching
     // them per tile straight from memory took four full-width load instructions per tile -- four times
@@ -261,18 +250,15 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
             }
             uint32_t sel = merge_halves(m, half) & valid;
             if (!live) sel = 0u;
-            const int c = __popc(sel);
             if (WRITE) {
-                const int c_ok = min(c, limit - wpos);
-                ring_append(rings + n * kRing, wpos, sel, c, c_ok, half, q0);
-                wpos += c_ok;
-                done = ring_flush_full(rings, wpos, done, list, lane);
+                if (half == 0) sh.mask[qt % kBatch][n] = sel;
+                if (qt % kBatch == kBatch - 1) expand_batch(sh, qt - (kBatch - 1), kBatch, lane);
             } else {
-                wpos += c;
+                wpos += __popc(sel);
             }
         }
     }
-    if (WRITE) ring_flush_rest(rings, wpos, done, list, lane);
+    if (WRITE && ntiles % kBatch) expand_batch(sh, ntiles - ntiles % kBatch, ntiles % kBatch, lane);
     if (!WRITE && live && half == 0) cnt[(int64_t)bh * L + j] = wpos;
 }
 
