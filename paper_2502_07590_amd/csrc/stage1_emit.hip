@@ -9,9 +9,8 @@
 // Layout of both kernels: one wave owns 32 "owners" (queries for idx, keys for idx_t) as the MFMA
 // column operand and walks the other axis in tiles of 32, ascending.  Lanes l and l+32 hold the same
 // owner; each has 16 predicate bits, which are merged into one 32-bit mask in ascending order of the
-// other axis.  The two lanes split the selected entries by rank and append them to the owner's ring in
-// LDS, from where they leave in order as 128-byte stores, so every row / list comes out ascending
-// without any sorting.
+// other axis.  The masks are parked in LDS and expanded into index entries in batches (below), in tile
+// order, so every row / list comes out ascending without any sorting.
 #include "stage1_core.h"
 
 namespace dsv {
