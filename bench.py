@@ -32,9 +32,9 @@ VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9   # 256 CUs x 64 fp32 lanes x 2.4 GHz, on
 # elementwise copy in the same run (FETCH_SIZE reads 0.5 GiB for it: factor 2.0; WRITE_SIZE reads
 # 1 GiB: factor 1.0).  See profiles/stage2_config2_pmc_traffic.md.
 PMC_TRAFFIC_CONFIG2 = {
-    "sparse_attn_fwd": int((29060808 * 2.0 + 14155845 * 1.0) * 1024),
-    "sparse_attn_bwd_dq": int((48233034 * 2.0 + 12976337 * 1.0) * 1024),
-    "sparse_attn_bwd_dkdv": int((50121155 * 2.0 + 12583050 * 1.0) * 1024),
+    "sparse_attn_fwd": int((31044477 * 2.0 + 14155840 * 1.0) * 1024),
+    "sparse_attn_bwd_dq": int((48443068 * 2.0 + 12976310 * 1.0) * 1024),
+    "sparse_attn_bwd_dkdv": int((34221672 * 2.0 + 12582937 * 1.0) * 1024),
 }
 # the gather sweep inside each stage-2 call (the kernel the roofline object is about)
 SWEEP_OF_CALL = {"sparse_attn_fwd": "fwd_sweep", "sparse_attn_bwd_dq": "dq_sweep", "sparse_attn_bwd_dkdv": "dkdv_sweep"}
