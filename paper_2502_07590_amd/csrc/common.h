@@ -123,21 +123,6 @@ __device__ __forceinline__ RowChunk<T, CH> load_chunk(const T *p)
     return c;
 }
 
-template <typename T, int CH>
-__device__ __forceinline__ void unpack_chunk(const RowChunk<T, CH> &c, float (&f)[CH])
-{
-    if constexpr (sizeof(T) == 4) {
-#pragma unroll
-        for (int i = 0; i < CH; ++i) f[i] = __uint_as_float(c.w[i]);
-    } else {
-#pragma unroll
-        for (int i = 0; i < CH / 2; ++i) {
-            f[2 * i + 0] = __uint_as_float(c.w[i] << 16);
-            f[2 * i + 1] = __uint_as_float(c.w[i] & 0xFFFF0000u);
-        }
-    }
-}
-
 template <typename T, int CH, int PSB = 16>
 __device__ __forceinline__ void store_chunk(T *p, const float (&f)[CH])
 {

@@ -2,10 +2,10 @@
 // kernels (stage2_split.hip).
 //
 // Lane layout: a group of LPR consecutive lanes (4, 8 or 16) owns one output row; lane s of the group
-// holds channels [s*CH, (s+1)*CH) of every [d]-vector, CH = d/LPR, so a gathered row is fetched by its
-// group as contiguous 16-byte pieces (every quad of lanes covers 64 contiguous bytes).  Fewer lanes per
-// row mean more channels per lane: the per-pair bookkeeping (reductions, exponentials, weights,
-// addresses) is shared by more arithmetic, at the price of more registers.
+// holds CH = d/LPR channels of every [d]-vector, as 16-byte pieces taken from the s-th slot of every
+// LPR*16-byte strip of the row (LaneLayout in common.h), so each load instruction of the group covers
+// whole strips.  Fewer lanes per row mean more channels per lane: the per-pair bookkeeping (reductions,
+// exponentials, weights, addresses) is shared by more arithmetic, at the price of more registers.
 //
 // Each sweep walks positions [tb, te) of one index row (or key-major list):
 //   fwd_sweep   online softmax over the segment: running max m (log2 domain), l, acc = sum p v
