@@ -227,7 +227,10 @@ def main():
                      "kernel_ms": round(k_ms, 3), "call_ms": round(call_ms[n], 3),
                      # the requested bytes are served by L2 and the vector L1, not by HBM (see traffic): the
                      # path that bounds the kernel is L1 -> registers, 64 B per clock per CU
-                     "l1_path": {"peak": round(L1_PEAK_GBS, 1), "unit": "GB/s", "frac": round(gbs / L1_PEAK_GBS, 4)}}
+                     "l1_path": {"peak": round(L1_PEAK_GBS, 1), "unit": "GB/s", "frac": round(gbs / L1_PEAK_GBS, 4)},
+                     "note": "achieved counts the bytes the gathers request; they are served from L2 (compare "
+                             "traffic, the bytes that crossed the fabric), so frac against the HBM peak exceeds 1; "
+                             "l1_path is the same rate against the L2 -> L1 -> register path that bounds the kernel"}
     dominant = max(pair_bytes, key=lambda n: kern_ms[SWEEP_OF_CALL[n]])
     roofline = dict(stage2[dominant])
     # stage 1 is selection work on plain VALU lanes: per score at least one subtract/compare and one
