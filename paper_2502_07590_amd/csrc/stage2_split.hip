@@ -340,8 +340,10 @@ __global__ __launch_bounds__(256) void seglen_hist_kernel(const int32_t *__restr
                                                           int32_t *__restrict__ hist)
 {
     extern __shared__ int32_t lh[];  // [nbins]
-    const int bh = blockIdx.y / S, r = blockIdx.y % S;
-    const int row0 = blockIdx.x * kSeglenChunk;
+    const int nchunks = (L + kSeglenChunk - 1) / kSeglenChunk;
+    const int unit = blockIdx.x / nchunks;  // (head, range)
+    const int bh = unit / S, r = unit % S;
+    const int row0 = (blockIdx.x % nchunks) * kSeglenChunk;
     for (int e = threadIdx.x; e < nbins; e += 256) lh[e] = 0;
     __syncthreads();
     for (int row = row0 + threadIdx.x; row < min(row0 + kSeglenChunk, L); row += 256)
@@ -381,8 +383,10 @@ __global__ __launch_bounds__(256) void seglen_scatter_kernel(const int32_t *__re
                                                              int32_t *__restrict__ hist, int32_t *__restrict__ order)
 {
     extern __shared__ int32_t lh[];  // [nbins]: this chunk's count per class, then its next free slot in `order`
-    const int bh = blockIdx.y / S, r = blockIdx.y % S;
-    const int row0 = blockIdx.x * kSeglenChunk, row1 = min(row0 + kSeglenChunk, L);
+    const int nchunks = (L + kSeglenChunk - 1) / kSeglenChunk;
+    const int unit = blockIdx.x / nchunks;  // (head, range)
+    const int bh = unit / S, r = unit % S;
+    const int row0 = (blockIdx.x % nchunks) * kSeglenChunk, row1 = min(row0 + kSeglenChunk, L);
     for (int e = threadIdx.x; e < nbins; e += 256) lh[e] = 0;
     __syncthreads();
     for (int row = row0 + threadIdx.x; row < row1; row += 256)
@@ -441,8 +445,9 @@ static dsv_status launch_row_order(const dsv_problem &p, const SplitPlan &pl, co
     const int nbins = std::min(pl.range_len + 1, 8193);
     const int64_t nh = (int64_t)nbh * pl.S * nbins;
     hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nh + 255) / 256, 4096)), dim3(256), 0, st, hist, nh);
-    if ((int64_t)nbh * pl.S > 65535) return DSV_EUNSUPPORTED;
-    dim3 grid((p.L + kSeglenChunk - 1) / kSeglenChunk, nbh * pl.S);
+    const int64_t nblocks = (int64_t)((p.L + kSeglenChunk - 1) / kSeglenChunk) * nbh * pl.S;
+    if (nblocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
+    dim3 grid((unsigned)nblocks);
     hipLaunchKernelGGL(seglen_hist_kernel, grid, dim3(256), (size_t)nbins * 4, st, seg, p.L, pl.S, nbins, hist);
     hipLaunchKernelGGL(seglen_scan_kernel, dim3(nbh * pl.S), dim3(1024), 0, st, hist, nbins);
     hipLaunchKernelGGL(seglen_scatter_kernel, grid, dim3(256), (size_t)nbins * 4, st, seg, p.L, pl.S, nbins, hist, order);
