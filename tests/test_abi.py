@@ -78,3 +78,50 @@ def test_missing_library_is_loud(dsv, monkeypatch):
     monkeypatch.setattr(b, "_LIB_PATH", os.path.join(ROOT, "no_such_dir", "libdsv.so"))
     with pytest.raises(b.DsvError):
         b.load_library()
+
+
+def test_workspace_sizes_follow_the_documented_layout(dsv):
+    """Without the sorted-index flag stage 2 needs no scratch; with it, segment pointers, the row order per
+    range and the fp32 partial results -- sizes that can be re-derived from the plan the header describes
+    (ranges of about 2 MB of K+V rows for the forward, 4 MB for the backward steps, a multiple of 8)."""
+    import workloads as wl
+    cfg = wl.get_config(2)
+    ks = [int(k) for k in wl.k_per_head(cfg)]
+    plain = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, ks, cfg.scale)
+    flagged = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, ks, cfg.scale, sorted_index=True)
+    assert dsv.sparse_attn_fwd_workspace(plain) == 0
+    assert dsv.sparse_attn_bwd_dq_workspace(plain) == 0
+    assert dsv.sparse_attn_bwd_dkdv_workspace(plain) == 0
+    rows = cfg.H * cfg.L
+
+    def ranges(target_bytes):
+        target_rows = target_bytes // (2 * cfg.d * 2)
+        return -(-cfg.L // (8 * target_rows)) * 8
+
+    s_fwd, s_bwd = ranges(2 << 20), ranges(4 << 20)
+    assert (s_fwd, s_bwd) == (32, 16)
+    fwd = dsv.sparse_attn_fwd_workspace(flagged)
+    partial = rows * s_fwd * cfg.d * 4
+    assert partial < fwd < partial + rows * (s_fwd + 1) * 4 * 5 + (1 << 20)       # + seg, m, l, order, counters
+    step = dsv.sparse_attn_bwd_dq_workspace(flagged)
+    assert step == dsv.sparse_attn_bwd_dkdv_workspace(flagged)            # the two steps share one layout
+    partial = 2 * rows * s_bwd * cfg.d * 4
+    assert partial < step < partial + rows * (s_bwd + 1) * 4 * 5 + rows * 8 + (1 << 20)   # + seg, Delta parts, order, ...
+    # whole backward with its own transpose also holds Delta, the transposed index and its column pointers
+    assert dsv.sparse_attn_bwd_workspace(flagged) >= step + flagged.nnz * 4 + cfg.H * (cfg.L + 1) * 8 + rows * 4
+    assert dsv.sparse_attn_bwd_t_workspace(flagged) >= step + rows * 4
+    # stage 1: low-rank projections plus a few words of selection state per query and key
+    s1 = dsv.lowrank_topk_t_workspace(flagged)
+    assert 2 * rows * cfg.r * 2 < s1 < 2 * rows * cfg.r * 2 + rows * 4 * 8
+
+
+def test_measurement_aid_rejects_what_has_not_run(dsv):
+    lib = dsv.load_library()
+    ms = ctypes.c_float(-1.0)
+    assert lib.dsv_kernel_timing(0) == 0                                   # switching it off touches no GPU
+    for span in range(len(dsv.KERNEL_SPANS)):
+        assert lib.dsv_kernel_ms(span, ctypes.byref(ms)) == -1            # nothing recorded
+    assert lib.dsv_kernel_ms(-1, ctypes.byref(ms)) == -1
+    assert lib.dsv_kernel_ms(len(dsv.KERNEL_SPANS), ctypes.byref(ms)) == -1
+    assert lib.dsv_kernel_ms(0, None) == -1
+    assert ms.value == -1.0
