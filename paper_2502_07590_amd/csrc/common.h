@@ -103,6 +103,25 @@ template <typename T, int D, int LPR> struct LaneLayout {
     __device__ __forceinline__ static constexpr int channel(int s, int c) { return (c / PE) * (LPR * PE) + s * PE + c % PE; }
 };
 
+// The chunks of a group's lanes must tile the row: every channel owned by exactly one (lane, element).
+template <typename T, int D, int LPR> constexpr bool lane_layout_tiles_the_row()
+{
+    typedef LaneLayout<T, D, LPR> LL;
+    bool seen[D] = {};
+    for (int s = 0; s < LPR; ++s)
+        for (int c = 0; c < LL::CH; ++c) {
+            const int ch = (c / LL::PE) * (LPR * LL::PE) + s * LL::PE + c % LL::PE;  // = LL::channel(s, c)
+            if (ch < 0 || ch >= D || seen[ch]) return false;
+            seen[ch] = true;
+        }
+    return true;
+}
+static_assert(lane_layout_tiles_the_row<uint16_t, 128, 4>() && lane_layout_tiles_the_row<uint16_t, 128, 8>() &&
+              lane_layout_tiles_the_row<uint16_t, 128, 16>() && lane_layout_tiles_the_row<uint16_t, 64, 4>() &&
+              lane_layout_tiles_the_row<uint16_t, 64, 16>() && lane_layout_tiles_the_row<float, 128, 8>() &&
+              lane_layout_tiles_the_row<float, 128, 16>() && lane_layout_tiles_the_row<float, 64, 4>() &&
+              lane_layout_tiles_the_row<float, 64, 8>(), "LaneLayout must be a permutation of the row's channels");
+
 // PSB: bytes between the chunk's consecutive 16-byte pieces (16 = contiguous).
 template <typename T, int CH, int PSB = 16>
 __device__ __forceinline__ RowChunk<T, CH> load_chunk(const T *p)
