@@ -26,7 +26,8 @@
  *   - idx contract: every value in [0, L), values distinct within a row.  dsv_lowrank_topk writes
  *     rows in ascending key index.  The stage-2 calls accept rows in any order.  Rows that break
  *     the contract give undefined results (never checked on the device).
- *   - Supported: d in {64, 128}; r in {16, 32, 64}; dtype F32 or BF16; L >= 1; B*H >= 1.
+ *   - Supported: d in {64, 128}; r in {16, 32, 64}; dtype F32 or BF16; B*H >= 1; L >= 1 with one
+ *     head's [L, d] matrix below 4 GB (L < 2^24 for bf16, d = 128); anything else: DSV_EUNSUPPORTED.
  *   - Inputs are assumed finite (no NaN / Inf).
  *
  * Paper: "DSV: Exploiting Dynamic Sparsity to Accelerate Large-Scale Video DiT Training".

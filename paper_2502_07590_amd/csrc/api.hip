@@ -32,6 +32,8 @@ dsv_status check_problem(const dsv_problem *p, bool need_r)
     if (p->flags & ~DSV_FLAG_SORTED_INDEX) return DSV_EINVAL;
     if (!supported_dtype(p->dtype) || !supported_d(p->d)) return DSV_EUNSUPPORTED;
     if (need_r && !supported_r(p->r)) return DSV_EUNSUPPORTED;
+    // the gather kernels address a head's [L, d] matrix with 32-bit byte offsets
+    if ((uint64_t)p->L * (uint64_t)p->d * esize(p->dtype) >= (1ull << 32)) return DSV_EUNSUPPORTED;
     for (int h = 0; h < p->H; ++h)
         if (p->k_per_head[h] < 1 || p->k_per_head[h] > p->L) return DSV_EINVAL;
     return DSV_OK;

@@ -58,6 +58,8 @@ def test_bad_descriptors_are_rejected_on_the_host(dsv):
     assert topk(dsv.Problem(**{**ok, "d": 80})) == -2
     assert topk(dsv.Problem(**{**ok, "r": 12})) == -2
     assert topk(dsv.Problem(**{**ok, "dtype": __import__("torch").float16})) == -2
+    assert topk(dsv.Problem(**{**ok, "L": 1 << 25, "d": 128, "k_per_head": [8, 8]})) == -2   # a head's matrix >= 4 GB
+    assert topk(dsv.Problem(**{**ok, "L": (1 << 25) - 1, "d": 64, "k_per_head": [8, 8]}), ws_bytes=0) == -3   # just below: accepted
     p = dsv.Problem(**ok)
     need = dsv.lowrank_topk_workspace(p)
     assert need > 0
