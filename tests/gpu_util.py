@@ -61,3 +61,36 @@ def assert_close(name, got: torch.Tensor, ref: np.ndarray, dtype: str):
     assert not bad.any(), (f"{name}: {bad.sum()} of {bad.size} elements out of tolerance; max abs err "
                            f"{err.max():.3e} at ref {ref.flat[err.argmax()]:.3e}")
     return float(err.max())
+
+
+def score_error_bound(Qlr_dev_rows: np.ndarray, Klr_dev: np.ndarray, S_dev_exact: np.ndarray, S_or: np.ndarray,
+                      r: int) -> np.ndarray:
+    """e[a, j] >= |S_device[a, j] - S_oracle[a, j]| for device scores accumulated in fp32:
+
+        e = r * 2^-23 * sum_t |q~_t k~_t|   +   |sum_t q~_t k~_t  -  sum_t q_t k_t|
+
+    q~, k~: the device's projections (each within one storage ulp of the oracle's q, k -- the projection
+    test asserts that); the first term bounds the fp32 accumulation of the r products, the second is the
+    exact effect of projected terms that were rounded the other way (zero where the projections agree).
+    S_dev_exact = exact scores of the device's projections, S_or = exact scores of the oracle's."""
+    absprod = np.abs(Qlr_dev_rows).astype(np.float64) @ np.abs(Klr_dev).astype(np.float64).T
+    return r * 2.0 ** -23 * absprod + np.abs(S_dev_exact - S_or) + 1e-300
+
+
+def assert_t3_valid(name: str, got_row: np.ndarray, ref_row: np.ndarray, S_or_row: np.ndarray, e_row: np.ndarray,
+                    k: int) -> bool:
+    """Tier T3: the device's index row against the pure fp64 oracle's.  Both are exact top-k sets of their
+    own score rows, which differ by at most e_row element-wise, so the k-th largest values differ by at most
+    max(e_row) and every key j in the symmetric difference satisfies
+        |S_oracle[j] - tau_oracle| <= max_j' e[j'] + e[j].
+    Returns True when the rows are identical."""
+    if np.array_equal(got_row, ref_row):
+        return True
+    L = S_or_row.shape[0]
+    tau = np.partition(S_or_row, L - k)[L - k]              # the oracle's k-th largest score
+    sym = np.setxor1d(got_row, ref_row)
+    eps = e_row.max() + e_row[sym]
+    dist = np.abs(S_or_row[sym] - tau)
+    assert np.all(dist <= eps), (f"{name}: {int((dist > eps).sum())} of {sym.size} differing keys lie outside the "
+                                 f"rounding band of the threshold (worst {dist.max():.3e} vs eps {eps.max():.3e})")
+    return False

@@ -9,10 +9,13 @@ one by one:
     device's own fp32 score bits (bit-exact) and against the pure fp64 oracle; properties that hold
     at any size for everything else (rows ascending and in range, exactly k per row, idx_t is the
     exact transpose of idx for sampled keys, list lengths = per-key counts);
+  * stage 2 on that real selection (what the benchmark runs): forward and backward_t on the device's
+    idx / idx_t; O, lse, dQ of the sampled rows -- whose index rows were just shown bit-exact -- against
+    the oracle, and dK, dV of sampled keys, among them the key with the longest list and the one with
+    the shortest, each list first checked against the column of idx by a plain device comparison;
   * stage 2 on a synthetic index tensor whose rows AND columns have a closed form (arithmetic
-    progressions modulo L, from the workload generator), so that sampled rows of O, lse, dQ and
-    sampled rows of dK, dV -- which need every query that selected the key -- can be checked
-    without the oracle ever seeing a device-made index.
+    progressions modulo L, from the workload generator): the same outputs with an index no device
+    code produced (uniform list lengths: the complement of the skewed real selection).
 """
 import numpy as np
 import pytest
@@ -20,7 +23,7 @@ import torch
 
 import oracle
 import workloads as wl
-from gpu_util import assert_close
+from gpu_util import assert_close, assert_t3_valid, score_error_bound
 
 pytestmark = pytest.mark.gpu
 
@@ -64,7 +67,20 @@ def data(request):
     torch.cuda.empty_cache()
 
 
-def test_stage1_full_size(data):
+N_ROWS = 64          # sampled query rows per checked head (plus the first and the last row)
+N_KEYS = 8           # sampled keys per config for dK / dV (longest list, shortest list, random ones)
+MAX_LIST = 100_000   # the oracle walks every selecting query's whole row: longest list checked is capped here
+
+
+def _column_of(idx_rows, j, L, k):
+    """Queries whose index row holds key j, by a plain comparison on the device (no library call)."""
+    hit = torch.cat([(idx_rows[lo:hi] == j).any(dim=1) for lo, hi in _row_chunks(L, k)])
+    return torch.nonzero(hit).reshape(-1)
+
+
+def test_real_selection_full_size(data):
+    """Stage 1 at full size, then stage 2 forward and backward on the index stage 1 wrote (the
+    benchmark's path: lowrank_topk_t -> sparse_attn_fwd -> sparse_attn_bwd_t on the device's idx / idx_t)."""
     cfg, ks, g, Wq, Wk, host = data
     L = cfg.L
     off = wl.idx_offsets(1, cfg.H, L, ks)
@@ -72,6 +88,7 @@ def test_stage1_full_size(data):
     idx_flat, idx_t_flat, col = dsv.lowrank_topk_t(p, g["Q"], g["K"], Wq, Wk)
     Qlr, Klr = dsv.lowrank_project(p, g["Q"], g["K"], Wq, Wk)
     torch.cuda.synchronize()
+    print(f"config {cfg.index}: stage 1 done", flush=True)
 
     def rows_of(h):
         return idx_flat[off[h]:off[h + 1]].view(L, ks[h])
@@ -94,37 +111,77 @@ def test_stage1_full_size(data):
     assert torch.equal(counts, col[h, 1:] - col[h, :-1])
     del counts
     rng = np.random.default_rng(0)
+    sampled = {}
     for h in _host_heads(cfg):
         idx, k = rows_of(h), ks[h]
         idx_t = idx_t_flat[off[h]:off[h + 1]]
         # exact transpose for sampled keys
         for j in rng.integers(0, L, size=3).tolist() + [0, L - 1]:
-            hit = torch.cat([(idx[lo:hi] == j).any(dim=1) for lo, hi in _row_chunks(L, k)])
-            want = torch.nonzero(hit).reshape(-1).to(torch.int32)
+            want = _column_of(idx, j, L, k).to(torch.int32)
             got = idx_t[int(col[h, j]):int(col[h, j + 1])]
             assert torch.equal(want, got), f"head {h} key {j}: idx_t list is not the column of idx"
         # sampled rows against the oracle
-        rows = np.unique(np.concatenate([rng.integers(0, L, size=8), [0, L - 1]])).astype(np.int32)
+        rows = np.unique(np.concatenate([rng.integers(0, L, size=N_ROWS), [0, L - 1]])).astype(np.int32)
         S_gpu = dsv.lowrank_scores_rows(p, Qlr, Klr, 0, h, torch.from_numpy(rows).cuda())
         torch.cuda.synchronize()
         got = idx[torch.from_numpy(rows.astype(np.int64)).cuda()].cpu().numpy()
+        # T2: the oracle's selection on the device's own fp32 score bits -> bit-exact
         t2 = oracle.topk_from_scores(S_gpu.cpu().numpy().astype(np.float64), k)
         assert np.array_equal(t2, got), f"head {h}: selection differs from the oracle's on the same score bits"
+        # T3: against the pure fp64 oracle, differences only inside the rounding band of its threshold
+        # (gpu_util.assert_t3_valid: |S_or[j] - tau_or| <= max_j' e[j'] + e[j])
         t3, _, _, S_or = oracle.lowrank_topk(host[h]["Q"][rows], host[h]["K"], host[h]["Wq"], host[h]["Wk"], k, cfg.dtype,
                                              return_intermediates=True)
-        same = 0
-        for a in range(len(rows)):
-            if np.array_equal(t3[a], got[a]):
-                same += 1
-                continue
-            # differences only where oracle scores sit within fp32 rounding of the threshold
-            tau = np.sort(S_or[a])[::-1][k - 1]
-            sym = np.setxor1d(t3[a], got[a])
-            # a projected value may round the other way on the device (one bf16 ulp = 2^-8 of one of the r
-            # terms) and the fp32 accumulation order differs: both are far inside 2^-6 of the largest score
-            band = 2.0 ** -6 * np.abs(S_or[a]).max()
-            assert np.all(np.abs(S_or[a][sym] - tau) <= band), f"head {h} row {rows[a]}: difference outside the rounding band"
+        Qd = Qlr[0, h][torch.from_numpy(rows.astype(np.int64)).cuda()].float().cpu().numpy()
+        Kd = Klr[0, h].float().cpu().numpy()
+        S_dev_exact = oracle.scores(Qd, Kd)
+        e = score_error_bound(Qd, Kd, S_dev_exact, S_or, cfg.r)
+        assert np.all(np.abs(S_gpu.cpu().numpy() - S_dev_exact) <= e)
+        same = sum(assert_t3_valid(f"config {cfg.index} head {h} row {rows[a]}", got[a], t3[a], S_or[a], e[a], k)
+                   for a in range(len(rows)))
+        del S_or, S_dev_exact, e, S_gpu
         print(f"config {cfg.index} head {h}: {same}/{len(rows)} sampled rows identical to the pure fp64 oracle", flush=True)
+        sampled[h] = (rows.astype(np.int64), got)
+    del Qlr, Klr
+    torch.cuda.empty_cache()
+
+    # ---- stage 2 on the device's own selection (rows just shown bit-exact on the device's score bits) ----
+    O, lse = dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx_flat)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    dQ, dK, dV = dsv.sparse_attn_bwd_t(p, g["Q"], g["K"], g["V"], idx_flat, idx_t_flat, col, O, lse, g["dO"])
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    print(f"config {cfg.index}: stage 2 on the real selection done", flush=True)
+    for h in _host_heads(cfg):
+        t = host[h]
+        rows, idx_rows = sampled[h]
+        O_ref, lse_ref = oracle.sparse_fwd(t["Q"][rows], t["K"], t["V"], idx_rows, cfg.scale)
+        dQ_ref = oracle.sparse_bwd_dq_rows(t["Q"][rows], t["K"], t["V"], idx_rows, t["dO"][rows], cfg.scale)
+        sel = torch.from_numpy(rows).cuda()
+        assert_close(f"O[h={h}]", O[0, h][sel], O_ref, cfg.dtype)
+        assert_close(f"lse[h={h}]", lse[0, h][sel], lse_ref, "f32")
+        assert_close(f"dQ[h={h}]", dQ[0, h][sel], dQ_ref, cfg.dtype)
+    # dK, dV of sampled keys: every selecting query is needed -- the key's list, checked against the column of idx
+    h = _host_heads(cfg)[0]
+    t, k, idx = host[h], ks[h], rows_of(h)
+    lens = (col[h, 1:] - col[h, :-1]).cpu().numpy()
+    capped = np.where(lens <= MAX_LIST, lens, -1)
+    keys = [int(capped.argmax()), int(lens.argmin())] + rng.integers(0, L, size=N_KEYS - 2).tolist()
+    print(f"config {cfg.index} head {h}: list lengths min {lens.min()} mean {lens.mean():.0f} max {lens.max()}", flush=True)
+    for j in keys:
+        qs_dev = _column_of(idx, j, L, k)
+        mine = idx_t_flat[off[h] + int(col[h, j]):off[h] + int(col[h, j + 1])]
+        assert torch.equal(qs_dev.to(torch.int32), mine), f"key {j}: idx_t list is not the column of idx"
+        qs = qs_dev.cpu().numpy()
+        idx_sel = idx[qs_dev].cpu().numpy()
+        dKj, dVj = oracle.sparse_bwd_dkdv_key(j, t["Q"][qs], t["dO"][qs], idx_sel, t["K"], t["V"], cfg.scale)
+        if len(qs) == 0:
+            assert float(dK[0, h, j].abs().max()) == 0.0 and float(dV[0, h, j].abs().max()) == 0.0
+        assert_close(f"dK[h={h}, j={j}]", dK[0, h, j], dKj, cfg.dtype)
+        assert_close(f"dV[h={h}, j={j}]", dV[0, h, j], dVj, cfg.dtype)
+        print(f"config {cfg.index} key {j}: {len(qs)} selecting queries checked", flush=True)
+        del idx_sel
 
 
 def _progression_on_device(L, k, head, dev, rows_out, lists_out):
@@ -180,7 +237,7 @@ def test_stage2_full_size(data):
     rng = np.random.default_rng(1)
     for h in _host_heads(cfg):
         t, k = host[h], ks[h]
-        rows = np.unique(np.concatenate([rng.integers(0, L, size=6), [0, L - 1]]))
+        rows = np.unique(np.concatenate([rng.integers(0, L, size=N_ROWS), [0, L - 1]]))
         idx_rows = wl.progression_idx_rows(L, k, rows, params[h])
         mine = idx[off[h]:off[h + 1]].view(L, k)[torch.from_numpy(rows).cuda()].cpu().numpy()
         assert np.array_equal(idx_rows, mine)     # the test's own two constructions agree
@@ -192,7 +249,7 @@ def test_stage2_full_size(data):
         assert_close(f"dQ[h={h}]", dQ[0, h][sel], dQ_ref, cfg.dtype)
     h = _host_heads(cfg)[0]
     t, k = host[h], ks[h]
-    for j in (int(rng.integers(0, L)), L - 1):
+    for j in rng.integers(0, L, size=N_KEYS - 1).tolist() + [L - 1]:
         qs = wl.progression_queries_of_key(L, k, j, params[h])
         mine = idx_t[off[h] + int(col[h, j]):off[h] + int(col[h, j + 1])].cpu().numpy().astype(np.int64)
         assert np.array_equal(qs, mine)
