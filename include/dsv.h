@@ -25,9 +25,11 @@
  *     found on the host before anything is launched.
  *   - idx contract: every value in [0, L), values distinct within a row.  dsv_lowrank_topk writes
  *     rows in ascending key index.  The stage-2 calls accept rows in any order.  Rows that break
- *     the contract give undefined results (never checked on the device).
- *   - Supported: d in {64, 128}; r in {16, 32, 64}; dtype F32 or BF16; B*H >= 1; L >= 1 with one
- *     head's [L, d] matrix below 4 GB (L < 2^24 for bf16, d = 128); anything else: DSV_EUNSUPPORTED.
+ *     the contract give undefined results; the stage-2 calls never check them (dsv_idx_validate does,
+ *     on request).
+ *   - Supported: d in {64, 128}; r in {16, 32, 64}; dtype F32 or BF16; 1 <= B*H <= 65535; L >= 1 with
+ *     one head's [L, d] matrix below 4 GB (L < 2^24 for bf16, d = 128); anything else: DSV_EUNSUPPORTED
+ *     (B*H out of range: DSV_EINVAL).
  *   - Inputs are assumed finite (no NaN / Inf).
  *
  * Paper: "DSV: Exploiting Dynamic Sparsity to Accelerate Large-Scale Video DiT Training".
@@ -187,6 +189,19 @@ DSV_API dsv_status dsv_sparse_attn_bwd_dkdv(const dsv_problem *p, const void *Q,
                                             const int32_t *idx_t, const int64_t *col_ptr, const float *lse,
                                             const float *delta, const void *dO, void *dK, void *dV,
                                             void *workspace, size_t ws_bytes, void *hip_stream);
+
+/* ---- Optional debug check of an index tensor ---------------------------------------------------
+ * Checks every row of idx against the idx contract above: values in [0, L), distinct within a row,
+ * and -- when dsv_problem.flags has DSV_FLAG_SORTED_INDEX -- strictly ascending (which is what the
+ * L2-blocked stage-2 kernels rely on).  Unlike every other call this one WAITS for the stream: it
+ * returns DSV_OK when all rows are valid and DSV_EINVAL when any row is not.
+ * report: HOST int64 [3], may be NULL: {number of offending rows, b*H+h of the first one, its row}
+ * (first = smallest (b*H+h, row); -1, -1 when there is none).
+ * Without the flag the duplicate check keeps a bitmap of L bits in LDS: L <= 524288, else
+ * DSV_EUNSUPPORTED.  Workspace: 256 bytes (counters). */
+DSV_API size_t dsv_idx_validate_workspace(const dsv_problem *p);
+DSV_API dsv_status dsv_idx_validate(const dsv_problem *p, const int32_t *idx, int64_t *report,
+                                    void *workspace, size_t ws_bytes, void *hip_stream);
 
 /* ---- Stage-1 internals exported for parity checks ---------------------------------------------
  * dsv_lowrank_project: only the projection step of stage 1 (Sec. "Low-Rank based Sparsity

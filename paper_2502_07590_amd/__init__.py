@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     idx_transpose,
     idx_transpose_workspace,
     sparse_attn_bwd_dkdv,
+    idx_validate,
     lowrank_project,
     lowrank_scores_rows,
     kernel_timing,

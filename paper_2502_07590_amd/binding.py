@@ -27,6 +27,7 @@ EXPORTED_SYMBOLS = (
     "dsv_sparse_attn_bwd_t_workspace", "dsv_sparse_attn_bwd_t",
     "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dq", "dsv_idx_transpose_workspace", "dsv_idx_transpose",
     "dsv_sparse_attn_bwd_dkdv_workspace", "dsv_sparse_attn_bwd_dkdv",
+    "dsv_idx_validate_workspace", "dsv_idx_validate",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
     "dsv_kernel_timing", "dsv_kernel_ms",
 )
@@ -68,7 +69,8 @@ def load_library():
     lib.dsv_idx_offsets.argtypes = [P, ctypes.POINTER(ctypes.c_int64)]
     for name in ("dsv_lowrank_topk_workspace", "dsv_sparse_attn_fwd_workspace", "dsv_sparse_attn_bwd_workspace",
                  "dsv_idx_transpose_workspace", "dsv_lowrank_topk_t_workspace", "dsv_sparse_attn_bwd_t_workspace",
-                 "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dkdv_workspace"):
+                 "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dkdv_workspace",
+                 "dsv_idx_validate_workspace"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [P]
     lib.dsv_lowrank_topk.restype = ctypes.c_int
@@ -87,6 +89,8 @@ def load_library():
     lib.dsv_idx_transpose.argtypes = [P, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_bwd_dkdv.restype = ctypes.c_int
     lib.dsv_sparse_attn_bwd_dkdv.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dsv_idx_validate.restype = ctypes.c_int
+    lib.dsv_idx_validate.argtypes = [P, vp, ctypes.POINTER(ctypes.c_int64), vp, sz, vp]
     lib.dsv_lowrank_project.restype = ctypes.c_int
     lib.dsv_lowrank_project.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
     lib.dsv_lowrank_scores_rows.restype = ctypes.c_int
@@ -156,11 +160,15 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def _workspace(nbytes: int, device, workspace):
+def _workspace(nbytes: int, device, workspace, stream=None):
     if nbytes == 0 and workspace is None:
         return None, 0
     if workspace is None:
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        if stream is not None:
+            # scratch made here dies when the wrapper returns, while the kernels may still be pending on the
+            # caller's stream: tell the caching allocator, so that it does not hand the block out under them
+            workspace.record_stream(stream)
     return workspace, workspace.numel() * workspace.element_size()
 
 
@@ -181,7 +189,7 @@ def lowrank_topk(p: Problem, Q, K, Wq, Wk, idx=None, workspace=None, stream=None
     lib = load_library()
     if idx is None:
         idx = torch.empty(p.nnz, dtype=torch.int32, device=Q.device)
-    ws, nbytes = _workspace(lowrank_topk_workspace(p), Q.device, workspace)
+    ws, nbytes = _workspace(lowrank_topk_workspace(p), Q.device, workspace, stream)
     _check(lib.dsv_lowrank_topk(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(idx), _ptr(ws), nbytes,
                                 _stream(stream)), "dsv_lowrank_topk")
     return idx
@@ -197,7 +205,7 @@ def lowrank_topk_t(p: Problem, Q, K, Wq, Wk, idx=None, idx_t=None, col_ptr=None,
     idx = torch.empty(p.nnz, dtype=torch.int32, device=Q.device) if idx is None else idx
     idx_t = torch.empty(p.nnz, dtype=torch.int32, device=Q.device) if idx_t is None else idx_t
     col_ptr = torch.empty((p.B * p.H, p.L + 1), dtype=torch.int64, device=Q.device) if col_ptr is None else col_ptr
-    ws, nbytes = _workspace(lowrank_topk_t_workspace(p), Q.device, workspace)
+    ws, nbytes = _workspace(lowrank_topk_t_workspace(p), Q.device, workspace, stream)
     _check(lib.dsv_lowrank_topk_t(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(idx), _ptr(idx_t), _ptr(col_ptr),
                                   _ptr(ws), nbytes, _stream(stream)), "dsv_lowrank_topk_t")
     return idx, idx_t, col_ptr
@@ -209,7 +217,7 @@ def sparse_attn_fwd(p: Problem, Q, K, V, idx, O=None, lse=None, workspace=None, 
         O = torch.empty_like(Q)
     if lse is None:
         lse = torch.empty((p.B, p.H, p.L), dtype=torch.float32, device=Q.device)
-    ws, nbytes = _workspace(sparse_attn_fwd_workspace(p), Q.device, workspace)
+    ws, nbytes = _workspace(sparse_attn_fwd_workspace(p), Q.device, workspace, stream)
     _check(lib.dsv_sparse_attn_fwd(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(lse), _ptr(ws), nbytes,
                                    _stream(stream)), "dsv_sparse_attn_fwd")
     return O, lse
@@ -220,7 +228,7 @@ def sparse_attn_bwd(p: Problem, Q, K, V, idx, O, lse, dO, dQ=None, dK=None, dV=N
     dQ = torch.empty_like(Q) if dQ is None else dQ
     dK = torch.empty_like(K) if dK is None else dK
     dV = torch.empty_like(V) if dV is None else dV
-    ws, nbytes = _workspace(sparse_attn_bwd_workspace(p), Q.device, workspace)
+    ws, nbytes = _workspace(sparse_attn_bwd_workspace(p), Q.device, workspace, stream)
     _check(lib.dsv_sparse_attn_bwd(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(lse), _ptr(dO),
                                    _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws), nbytes, _stream(stream)),
            "dsv_sparse_attn_bwd")
@@ -235,7 +243,7 @@ def sparse_attn_bwd_dq(p: Problem, Q, K, V, idx, O, lse, dO, dQ=None, delta=None
     lib = load_library()
     dQ = torch.empty_like(Q) if dQ is None else dQ
     delta = torch.empty((p.B, p.H, p.L), dtype=torch.float32, device=Q.device) if delta is None else delta
-    ws, nbytes = _workspace(sparse_attn_bwd_dq_workspace(p), Q.device, workspace)
+    ws, nbytes = _workspace(sparse_attn_bwd_dq_workspace(p), Q.device, workspace, stream)
     _check(lib.dsv_sparse_attn_bwd_dq(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(lse), _ptr(dO),
                                       _ptr(dQ), _ptr(delta), _ptr(ws), nbytes, _stream(stream)),
            "dsv_sparse_attn_bwd_dq")
@@ -252,7 +260,7 @@ def sparse_attn_bwd_t(p: Problem, Q, K, V, idx, idx_t, col_ptr, O, lse, dO, dQ=N
     dQ = torch.empty_like(Q) if dQ is None else dQ
     dK = torch.empty_like(K) if dK is None else dK
     dV = torch.empty_like(V) if dV is None else dV
-    ws, nbytes = _workspace(sparse_attn_bwd_t_workspace(p), Q.device, workspace)
+    ws, nbytes = _workspace(sparse_attn_bwd_t_workspace(p), Q.device, workspace, stream)
     _check(lib.dsv_sparse_attn_bwd_t(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(idx_t), _ptr(col_ptr), _ptr(O),
                                      _ptr(lse), _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(ws), nbytes,
                                      _stream(stream)), "dsv_sparse_attn_bwd_t")
@@ -267,7 +275,7 @@ def idx_transpose(p: Problem, idx, idx_t=None, col_ptr=None, workspace=None, str
     lib = load_library()
     idx_t = torch.empty_like(idx) if idx_t is None else idx_t
     col_ptr = torch.empty((p.B * p.H, p.L + 1), dtype=torch.int64, device=idx.device) if col_ptr is None else col_ptr
-    ws, nbytes = _workspace(idx_transpose_workspace(p), idx.device, workspace)
+    ws, nbytes = _workspace(idx_transpose_workspace(p), idx.device, workspace, stream)
     _check(lib.dsv_idx_transpose(p.c, _ptr(idx), _ptr(idx_t), _ptr(col_ptr), _ptr(ws), nbytes, _stream(stream)),
            "dsv_idx_transpose")
     return idx_t, col_ptr
@@ -282,11 +290,23 @@ def sparse_attn_bwd_dkdv(p: Problem, Q, K, V, idx_t, col_ptr, lse, delta, dO, dK
     lib = load_library()
     dK = torch.empty_like(K) if dK is None else dK
     dV = torch.empty_like(V) if dV is None else dV
-    ws, nbytes = _workspace(sparse_attn_bwd_dkdv_workspace(p), Q.device, workspace)
+    ws, nbytes = _workspace(sparse_attn_bwd_dkdv_workspace(p), Q.device, workspace, stream)
     _check(lib.dsv_sparse_attn_bwd_dkdv(p.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx_t), _ptr(col_ptr), _ptr(lse),
                                         _ptr(delta), _ptr(dO), _ptr(dK), _ptr(dV), _ptr(ws), nbytes, _stream(stream)),
            "dsv_sparse_attn_bwd_dkdv")
     return dK, dV
+
+
+def idx_validate(p: Problem, idx, workspace=None, stream=None):
+    """Debug check of idx against the contract (in range, distinct, ascending if p.sorted_index).  Waits for the
+    stream.  Returns (ok, (n_bad_rows, first_bad_bh, first_bad_row))."""
+    lib = load_library()
+    ws, nbytes = _workspace(int(lib.dsv_idx_validate_workspace(p.c)), idx.device, workspace, stream)
+    rep = (ctypes.c_int64 * 3)()
+    st = lib.dsv_idx_validate(p.c, _ptr(idx), rep, _ptr(ws), nbytes, _stream(stream))
+    if st not in (0, -1):
+        _check(st, "dsv_idx_validate")
+    return st == 0, tuple(int(x) for x in rep)
 
 
 def lowrank_project(p: Problem, Q, K, Wq, Wk, Qlr=None, Klr=None, stream=None):

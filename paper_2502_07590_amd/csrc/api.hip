@@ -28,7 +28,8 @@ dsv_status check_problem(const dsv_problem *p, bool need_r)
 {
     if (!p || !p->k_per_head) return DSV_EINVAL;
     if (p->B < 1 || p->H < 1 || p->L < 1) return DSV_EINVAL;
-    if ((int64_t)p->B * p->H > (1 << 20)) return DSV_EINVAL;
+    // (batch, head) pairs index grid.y / grid.x of several kernels (limit 65535)
+    if ((int64_t)p->B * p->H > 65535) return DSV_EINVAL;
     if (p->flags & ~DSV_FLAG_SORTED_INDEX) return DSV_EINVAL;
     if (!supported_dtype(p->dtype) || !supported_d(p->d)) return DSV_EUNSUPPORTED;
     if (need_r && !supported_r(p->r)) return DSV_EUNSUPPORTED;
@@ -427,6 +428,26 @@ dsv_status dsv_sparse_attn_bwd_t(const dsv_problem *p, const void *Q, const void
     if (st != DSV_OK) return st;
     return dsv_sparse_attn_bwd_dkdv(p, Q, K, V, idx_t, col_ptr, lse, delta, dO, dK, dV, ws + w.step, w.step_bytes,
                                     hip_stream);
+}
+
+// ------------------------------------------------------------------------------------ debug validator
+size_t dsv_idx_validate_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, false) != DSV_OK) return 0;
+    return 256;
+}
+
+dsv_status dsv_idx_validate(const dsv_problem *p, const int32_t *idx, int64_t *report, void *workspace,
+                            size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if (!ok_ptrs({idx})) return DSV_EINVAL;
+    st = check_workspace(workspace, ws_bytes, 256);
+    if (st != DSV_OK) return st;
+    const std::vector<HeadTable> tabs = make_tables(*p);
+    return launch_idx_validate(*p, tabs.data(), (int)tabs.size(), idx, static_cast<unsigned long long *>(workspace),
+                               report, static_cast<hipStream_t>(hip_stream));
 }
 
 // ------------------------------------------------------------------------------------ parity exports

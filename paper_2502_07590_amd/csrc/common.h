@@ -307,6 +307,9 @@ dsv_status launch_bwd_dq(const dsv_problem &p, const HeadTable *tabs, int n_tabs
 dsv_status launch_bwd_dkdv(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                            const void *V, const int32_t *idxT, const int64_t *col, const float *lse, const float *delta,
                            const void *dO, void *dK, void *dV, hipStream_t st);
+// report_dev: two 64-bit counters in device memory; report_host: optional HOST int64 [3].  Waits for the stream.
+dsv_status launch_idx_validate(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
+                               unsigned long long *report_dev, int64_t *report_host, hipStream_t st);
 // cnt: [B*H, L] int32 scratch (cnt_bytes = its size rounded up to 16); col: [B*H, L+1] int64.
 dsv_status launch_idx_transpose(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
                                 int32_t *idxT, int64_t *col, int32_t *cnt, size_t cnt_bytes, hipStream_t st);

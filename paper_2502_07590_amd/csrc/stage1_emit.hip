@@ -204,11 +204,12 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
     __shared__ __align__(16) EmitShared sh;
     if (WRITE && half == 0) {
         // col comes from the counting pass over the same predicate, so the lists fill the head's block of
-        // L * k entries exactly; the clamp only keeps an inconsistent col from sending writes out of it
+        // L * k entries exactly; the clamps (to [0, cap], b1 >= b0) only keep an inconsistent col from sending writes out of it
         const int64_t cap = (int64_t)L * tab.k[slot];
         const int64_t *cp = col + (int64_t)bh * (L + 1) + j;
-        const int64_t b0 = cp[0] < cap ? cp[0] : cap, b1 = cp[1] < cap ? cp[1] : cap;
-        sh.out[n] = OwnerOut{idxT + tab.off[slot] + b0, 0, live && b1 > b0 ? (int)(b1 - b0) : 0};
+        const int64_t b0 = cp[0] < 0 ? 0 : (cp[0] < cap ? cp[0] : cap);
+        const int64_t b1 = cp[1] < b0 ? b0 : (cp[1] < cap ? cp[1] : cap);
+        sh.out[n] = OwnerOut{idxT + tab.off[slot] + b0, 0, live ? (int)(b1 - b0) : 0};
     }
     int wpos = 0;  // WRITE = false: this key's list length
     // Thresholds of the queries, kTauTiles tiles at a time: one coalesced 16-byte load per lane, parked in

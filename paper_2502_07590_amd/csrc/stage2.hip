@@ -214,7 +214,11 @@ __global__ __launch_bounds__(256) void tindex_fill_kernel(const int32_t *__restr
         for (int t = threadIdx.x; t < k; t += 256) {
             const int j = row[t];
             const int pos = atomicAdd(&cur[j], 1);
-            out[cp[j] + pos] = (int32_t)i;
+            // col and the cursors come from the counting pass over the same idx, so dst stays inside the
+            // head's L * k entries; the bound keeps a broken idx (duplicates, changed between the passes)
+            // from sending the store anywhere else
+            const int64_t dst = cp[j] + pos;
+            if (dst >= 0 && dst < (int64_t)L * k) out[dst] = (int32_t)i;
         }
     }
 }

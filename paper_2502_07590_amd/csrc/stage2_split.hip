@@ -225,7 +225,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_merge_kernel(const float *_
     }
     const RowChunk<T, CH> go = load_chunk<T, CH>(dO + row * D + s * CH);
     const RowChunk<T, CH> o = load_chunk<T, CH>(O + row * D + s * CH);
-    const float delta0 = row16_sum(dot_chunk<T, CH>(go, o));  // same instruction sequence as in the sweep
+    const float delta0 = row16_sum(dot_chunk<T, CH>(go, o));  // the sweep reduced the same products over another lane layout: equal up to fp32 rounding (~1e-6), far below what the centring needs
     float dq[CH];
 #pragma unroll
     for (int c = 0; c < CH; ++c) dq[c] = scale * (a[c] - (delta - delta0) * b[c]);
@@ -333,7 +333,7 @@ constexpr int kSeglenChunk = 4096;
 __device__ __forceinline__ int seg_len(const int32_t *__restrict__ seg, int64_t bh, int L, int S, int row, int r, int nbins)
 {
     const int32_t *sp = seg + (bh * L + row) * (S + 1) + r;
-    return min(sp[1] - sp[0], nbins - 1);
+    return max(0, min(sp[1] - sp[0], nbins - 1));  // clamped both ways: the result indexes LDS counters
 }
 
 __global__ __launch_bounds__(256) void seglen_hist_kernel(const int32_t *__restrict__ seg, int L, int S, int nbins,
@@ -397,8 +397,12 @@ __global__ __launch_bounds__(256) void seglen_scatter_kernel(const int32_t *__re
         if (lh[e]) lh[e] = atomicAdd(&gh[e], lh[e]);  // reserve this chunk's slots of the class
     __syncthreads();
     int32_t *out = order + ((int64_t)bh * S + r) * L;
-    for (int row = row0 + threadIdx.x; row < row1; row += 256)
-        out[atomicAdd(&lh[nbins - 1 - seg_len(seg, bh, L, S, row, r, nbins)], 1)] = row;
+    for (int row = row0 + threadIdx.x; row < row1; row += 256) {
+        // slots come from the counting pass over the same seg, so they stay below L; the bound keeps an
+        // inconsistent seg from sending the store out of this (head, range)'s L entries
+        const int slot = atomicAdd(&lh[nbins - 1 - seg_len(seg, bh, L, S, row, r, nbins)], 1);
+        if (slot >= 0 && slot < L) out[slot] = row;
+    }
 }
 
 __global__ __launch_bounds__(256) void zero_i32_kernel(int32_t *__restrict__ p, int64_t n)

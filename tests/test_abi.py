@@ -72,6 +72,17 @@ def test_bad_descriptors_are_rejected_on_the_host(dsv):
     assert lib.dsv_sparse_attn_bwd(p.c, one, one, one, one, one, one, one, one, one, one, None, 0, None) == -3
     assert dsv.sparse_attn_bwd_workspace(p) >= p.nnz * 4      # holds the transposed index
     assert lib.dsv_lowrank_scores_rows(p.c, one, one, 0, 2, one, 4, one, None) == -1   # head out of range
+    # more (batch, head) pairs than a launch grid can index: an argument error, found on the host
+    assert topk(dsv.Problem(**{**ok, "B": 32768, "H": 2})) == -1
+    assert topk(dsv.Problem(**{**ok, "B": 1, "H": 65536, "k_per_head": [8] * 65536})) == -1
+    # debug validator: descriptor, pointer and workspace errors come back before anything is launched
+    lib.dsv_idx_validate_workspace.restype = ctypes.c_size_t
+    assert lib.dsv_idx_validate_workspace(p.c) == 256
+    assert lib.dsv_idx_validate(p.c, None, None, one, 256, None) == -1
+    assert lib.dsv_idx_validate(p.c, one, None, None, 0, None) == -3
+    assert lib.dsv_idx_validate(p.c, one, None, one, 255, None) == -3
+    big = dsv.Problem(**{**ok, "L": 1 << 20, "k_per_head": [8, 8]})                 # unsorted rows: bitmap of L bits
+    assert lib.dsv_idx_validate(big.c, one, None, one, 256, None) == -2
 
 
 def test_missing_library_is_loud(dsv, monkeypatch):
