@@ -17,3 +17,18 @@ def oracle_lib():
     import oracle
     oracle.build()
     return oracle
+
+
+@pytest.fixture(scope="session")
+def progress(request):
+    """say(msg): print a line straight to the terminal, past pytest's capture, so that a long GPU test shows
+    what it is doing while it runs (a run that stays silent for minutes is taken to be hung)."""
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+
+    def say(msg):
+        if capman is None:
+            print(msg, flush=True)
+            return
+        with capman.global_and_fixture_disabled():
+            print("\n    " + msg, end="", flush=True)
+    return say

@@ -43,7 +43,7 @@ def _row_chunks(L, k, elems=1 << 28):
 
 
 @pytest.fixture(scope="module", params=CONFIGS, ids=lambda c: f"config{c}")
-def data(request):
+def data(request, progress):
     cfg = wl.get_config(request.param)
     ks = [int(x) for x in wl.k_per_head(cfg)]
     td = torch.bfloat16
@@ -61,7 +61,9 @@ def data(request):
         Wk[h].copy_(torch.from_numpy(wk).to(td))
         if h in _host_heads(cfg):
             host[h] = dict(t, Wq=wq, Wk=wk)
-    print(f"config {cfg.index}: inputs generated", flush=True)
+        if cfg.L >= 1 << 18:
+            progress(f"config {cfg.index}: head {h} generated")
+    progress(f"config {cfg.index}: inputs generated")
     yield cfg, ks, g, Wq, Wk, host
     del g, Wq, Wk
     torch.cuda.empty_cache()
@@ -78,7 +80,7 @@ def _column_of(idx_rows, j, L, k):
     return torch.nonzero(hit).reshape(-1)
 
 
-def test_real_selection_full_size(data):
+def test_real_selection_full_size(data, progress):
     """Stage 1 at full size, then stage 2 forward and backward on the index stage 1 wrote (the
     benchmark's path: lowrank_topk_t -> sparse_attn_fwd -> sparse_attn_bwd_t on the device's idx / idx_t)."""
     cfg, ks, g, Wq, Wk, host = data
@@ -88,7 +90,7 @@ def test_real_selection_full_size(data):
     idx_flat, idx_t_flat, col = dsv.lowrank_topk_t(p, g["Q"], g["K"], Wq, Wk)
     Qlr, Klr = dsv.lowrank_project(p, g["Q"], g["K"], Wq, Wk)
     torch.cuda.synchronize()
-    print(f"config {cfg.index}: stage 1 done", flush=True)
+    progress(f"config {cfg.index}: stage 1 done")
 
     def rows_of(h):
         return idx_flat[off[h]:off[h + 1]].view(L, ks[h])
@@ -140,7 +142,7 @@ def test_real_selection_full_size(data):
         same = sum(assert_t3_valid(f"config {cfg.index} head {h} row {rows[a]}", got[a], t3[a], S_or[a], e[a], k)
                    for a in range(len(rows)))
         del S_or, S_dev_exact, e, S_gpu
-        print(f"config {cfg.index} head {h}: {same}/{len(rows)} sampled rows identical to the pure fp64 oracle", flush=True)
+        progress(f"config {cfg.index} head {h}: {same}/{len(rows)} sampled rows identical to the pure fp64 oracle")
         sampled[h] = (rows.astype(np.int64), got)
     del Qlr, Klr
     torch.cuda.empty_cache()
@@ -152,7 +154,7 @@ def test_real_selection_full_size(data):
     dQ, dK, dV = dsv.sparse_attn_bwd_t(p, g["Q"], g["K"], g["V"], idx_flat, idx_t_flat, col, O, lse, g["dO"])
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
-    print(f"config {cfg.index}: stage 2 on the real selection done", flush=True)
+    progress(f"config {cfg.index}: stage 2 on the real selection done")
     for h in _host_heads(cfg):
         t = host[h]
         rows, idx_rows = sampled[h]
@@ -168,20 +170,29 @@ def test_real_selection_full_size(data):
     lens = (col[h, 1:] - col[h, :-1]).cpu().numpy()
     capped = np.where(lens <= MAX_LIST, lens, -1)
     keys = [int(capped.argmax()), int(lens.argmin())] + rng.integers(0, L, size=N_KEYS - 2).tolist()
-    print(f"config {cfg.index} head {h}: list lengths min {lens.min()} mean {lens.mean():.0f} max {lens.max()}", flush=True)
+    progress(f"config {cfg.index} head {h}: list lengths min {lens.min()} mean {lens.mean():.0f} max {lens.max()}")
     for j in keys:
         qs_dev = _column_of(idx, j, L, k)
         mine = idx_t_flat[off[h] + int(col[h, j]):off[h] + int(col[h, j + 1])]
         assert torch.equal(qs_dev.to(torch.int32), mine), f"key {j}: idx_t list is not the column of idx"
         qs = qs_dev.cpu().numpy()
-        idx_sel = idx[qs_dev].cpu().numpy()
-        dKj, dVj = oracle.sparse_bwd_dkdv_key(j, t["Q"][qs], t["dO"][qs], idx_sel, t["K"], t["V"], cfg.scale)
+        # the oracle's per-key routine, a chunk of the selecting queries at a time (its terms add over queries;
+        # the chunks keep the fetched index rows small and the run talking)
+        dKj, dVj = np.zeros(cfg.d), np.zeros(cfg.d)
+        step = max(1, (1 << 27) // k)
+        for lo in range(0, len(qs), step):
+            part = qs[lo:lo + step]
+            idx_sel = idx[qs_dev[lo:lo + step]].cpu().numpy()
+            a, b = oracle.sparse_bwd_dkdv_key(j, t["Q"][part], t["dO"][part], idx_sel, t["K"], t["V"], cfg.scale)
+            dKj += a
+            dVj += b
+            if len(qs) > step:
+                progress(f"config {cfg.index} key {j}: {min(lo + step, len(qs))}/{len(qs)} selecting queries")
         if len(qs) == 0:
             assert float(dK[0, h, j].abs().max()) == 0.0 and float(dV[0, h, j].abs().max()) == 0.0
         assert_close(f"dK[h={h}, j={j}]", dK[0, h, j], dKj, cfg.dtype)
         assert_close(f"dV[h={h}, j={j}]", dV[0, h, j], dVj, cfg.dtype)
-        print(f"config {cfg.index} key {j}: {len(qs)} selecting queries checked", flush=True)
-        del idx_sel
+        progress(f"config {cfg.index} key {j}: {len(qs)} selecting queries checked")
 
 
 def _progression_on_device(L, k, head, dev, rows_out, lists_out):
@@ -214,7 +225,7 @@ def _progression_on_device(L, k, head, dev, rows_out, lists_out):
     return col, (base, gg, ginv)
 
 
-def test_stage2_full_size(data):
+def test_stage2_full_size(data, progress):
     cfg, ks, g, _, _, host = data
     L, dev = cfg.L, "cuda:0"
     off = wl.idx_offsets(1, cfg.H, L, ks)
@@ -226,7 +237,7 @@ def test_stage2_full_size(data):
     for h in range(cfg.H):
         col[h], params[h] = _progression_on_device(L, ks[h], h, dev, idx[off[h]:off[h + 1]].view(L, ks[h]),
                                                    idx_t[off[h]:off[h + 1]])
-    print(f"config {cfg.index}: index sets built", flush=True)
+    progress(f"config {cfg.index}: index sets built")
     torch.cuda.empty_cache()
     O, lse = dsv.sparse_attn_fwd(p, g["Q"], g["K"], g["V"], idx)
     torch.cuda.synchronize()
@@ -257,4 +268,4 @@ def test_stage2_full_size(data):
         dKj, dVj = oracle.sparse_bwd_dkdv_key(j, t["Q"][qs], t["dO"][qs], idx_sel, t["K"], t["V"], cfg.scale)
         assert_close(f"dK[h={h}, j={j}]", dK[0, h, j], dKj, cfg.dtype)
         assert_close(f"dV[h={h}, j={j}]", dV[0, h, j], dVj, cfg.dtype)
-        print(f"config {cfg.index} key {j}: {len(qs)} selecting queries checked", flush=True)
+        progress(f"config {cfg.index} key {j}: {len(qs)} selecting queries checked")
