@@ -203,6 +203,22 @@ DSV_API size_t dsv_idx_validate_workspace(const dsv_problem *p);
 DSV_API dsv_status dsv_idx_validate(const dsv_problem *p, const int32_t *idx, int64_t *report,
                                     void *workspace, size_t ws_bytes, void *hip_stream);
 
+/* ---- Stage 1 for callers that cannot allocate -------------------------------------------------
+ * For callers that can neither allocate device memory nor bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same result as
+ * dsv_lowrank_topk, but the scratch (projections and per-query selection state) lives in a
+ * fixed array inside the library's device image instead of a caller's workspace: the call
+ * allocates nothing and frees nothing.
+ * Limit: dsv_lowrank_topk_workspace(p) <= dsv_lowrank_topk_noalloc_max_bytes() (32 MiB: e.g.
+ * bf16, r = 16, B*H*L up to about 450 000 tokens); larger problems: DSV_EWORKSPACE, nothing launched.
+ * Every GPU the library runs on holds its own copy of the array until the process ends.  All calls
+ * on one GPU share it: calls that overlap on one GPU (two streams, two threads) race; run them
+ * one after another.  The array keeps the previous call's contents; the call itself (re)writes
+ * everything it reads. */
+DSV_API size_t dsv_lowrank_topk_noalloc_max_bytes(void);
+DSV_API dsv_status dsv_lowrank_topk_noalloc(const dsv_problem *p, const void *Q, const void *K,
+                                            const void *Wq, const void *Wk, int32_t *idx, void *hip_stream);
+
 /* ---- Stage-1 internals exported for parity checks ---------------------------------------------
  * dsv_lowrank_project: only the projection step of stage 1 (Sec. "Low-Rank based Sparsity
  * Prediction").  Qlr, Klr: [B, H, L, r] in `dtype`, no padding.  No workspace.

@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     idx_offsets,
     lowrank_topk,
     lowrank_topk_workspace,
+    lowrank_topk_noalloc,
+    lowrank_topk_noalloc_max_bytes,
     lowrank_topk_t,
     lowrank_topk_t_workspace,
     sparse_attn_fwd,

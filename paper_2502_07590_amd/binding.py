@@ -28,6 +28,7 @@ EXPORTED_SYMBOLS = (
     "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dq", "dsv_idx_transpose_workspace", "dsv_idx_transpose",
     "dsv_sparse_attn_bwd_dkdv_workspace", "dsv_sparse_attn_bwd_dkdv",
     "dsv_idx_validate_workspace", "dsv_idx_validate",
+    "dsv_lowrank_topk_noalloc_max_bytes", "dsv_lowrank_topk_noalloc",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
     "dsv_kernel_timing", "dsv_kernel_ms",
 )
@@ -89,6 +90,10 @@ def load_library():
     lib.dsv_idx_transpose.argtypes = [P, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_bwd_dkdv.restype = ctypes.c_int
     lib.dsv_sparse_attn_bwd_dkdv.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dsv_lowrank_topk_noalloc_max_bytes.restype = sz
+    lib.dsv_lowrank_topk_noalloc_max_bytes.argtypes = []
+    lib.dsv_lowrank_topk_noalloc.restype = ctypes.c_int
+    lib.dsv_lowrank_topk_noalloc.argtypes = [P, vp, vp, vp, vp, vp, vp]
     lib.dsv_idx_validate.restype = ctypes.c_int
     lib.dsv_idx_validate.argtypes = [P, vp, ctypes.POINTER(ctypes.c_int64), vp, sz, vp]
     lib.dsv_lowrank_project.restype = ctypes.c_int
@@ -192,6 +197,17 @@ def lowrank_topk(p: Problem, Q, K, Wq, Wk, idx=None, workspace=None, stream=None
     ws, nbytes = _workspace(lowrank_topk_workspace(p), Q.device, workspace, stream)
     _check(lib.dsv_lowrank_topk(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(idx), _ptr(ws), nbytes,
                                 _stream(stream)), "dsv_lowrank_topk")
+    return idx
+
+
+def lowrank_topk_noalloc_max_bytes() -> int:
+    return int(load_library().dsv_lowrank_topk_noalloc_max_bytes())
+
+
+def lowrank_topk_noalloc(p: Problem, Q, K, Wq, Wk, idx, stream=None):
+    """dsv_lowrank_topk with the scratch inside the library: the caller passes inputs and the output only."""
+    _check(load_library().dsv_lowrank_topk_noalloc(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(idx),
+                                                   _stream(stream)), "dsv_lowrank_topk_noalloc")
     return idx
 
 

@@ -2,6 +2,7 @@
 // before anything is enqueued; the library never allocates device memory.
 #include <algorithm>
 #include <initializer_list>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -195,6 +196,31 @@ BwdLayout bwd_layout(const dsv_problem &p, bool own_transpose)
 
 using namespace dsv;
 
+// ---- scratch of dsv_lowrank_topk_noalloc ---------------------------------------------------------
+// A fixed array in the library's device image: every GPU that loads the library holds its own copy at
+// its own address.  In host code the array's NAME is only a handle for hipGetSymbolAddress -- it is not
+// a device address and is never passed to a kernel, a copy or a fill; the address is looked up once
+// per device (with that device current) and kept here.
+constexpr size_t kNoallocBytes = 32u << 20;
+static __device__ __align__(256) unsigned char scratch[kNoallocBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's copy of `scratch`; nullptr (and *err set) on failure.
+static void *noalloc_scratch(dsv_status *err)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { *err = DSV_EHIP; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { *err = DSV_EHIP; return nullptr; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
 extern "C" {
 
 const char *dsv_version(void) { return "dsv 0.2 (gfx950)"; }
@@ -260,6 +286,25 @@ dsv_status dsv_lowrank_topk(const dsv_problem *p, const void *Q, const void *K, 
                             int32_t *idx, void *workspace, size_t ws_bytes, void *hip_stream)
 {
     return lowrank_topk_impl(p, Q, K, Wq, Wk, idx, nullptr, nullptr, false, workspace, ws_bytes, hip_stream);
+}
+
+size_t dsv_lowrank_topk_noalloc_max_bytes(void) { return kNoallocBytes; }
+
+dsv_status dsv_lowrank_topk_noalloc(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,
+                                    int32_t *idx, void *hip_stream)
+{
+    // everything that can be refused is refused before the scratch is looked up
+    dsv_status st = check_problem(p, true);
+    if (st != DSV_OK) return st;
+    if (!ok_ptrs({Q, K, Wq, Wk, idx})) return DSV_EINVAL;
+    const size_t need = stage1_layout(*p, false).total;
+    if (need > kNoallocBytes) return DSV_EWORKSPACE;
+    void *ws = noalloc_scratch(&st);
+    if (!ws) return st;
+    // every buffer of the layout is written by the kernels of this call before it is read (projections by
+    // project_kernel, thresholds and tie budgets by the first radix pass), so what an earlier call left in
+    // the array does not matter
+    return lowrank_topk_impl(p, Q, K, Wq, Wk, idx, nullptr, nullptr, false, ws, kNoallocBytes, hip_stream);
 }
 
 size_t dsv_lowrank_topk_t_workspace(const dsv_problem *p)
