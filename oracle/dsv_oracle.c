@@ -184,24 +184,33 @@ void dsv_oracle_sparse_fwd(const float *Q, const float *K, const float *V, const
     }
 }
 
-/* Contribution of one query row to the gradients, shared by the routines below.
- *   Delta = dO_i . O_i ;  dP_j = dO_i . v_j ;  dS_j = p_j (dP_j - Delta)
- * q, dOi, Oi [d]; writes p[t], dS[t] for the k selected keys of this row. */
+/* Per-pair terms of the backward, shared by the routines below.
+ *   Delta = dO_i . O_i ;  dP_j = dO_i . v_j ;  p_j = exp(scale q_i . k_j - lse_i) ;  dS_j = p_j (dP_j - Delta) */
+static double row_delta(const float *dOi, const double *Oi, int d)
+{
+    double delta = 0.0;
+    for (int c = 0; c < d; ++c) delta += (double)dOi[c] * Oi[c];
+    return delta;
+}
+
+static void pair_p_and_ds(const float *q, const float *dOi, double delta, double lse_i, const float *kj,
+                          const float *vj, int d, double scale, double *p, double *dS)
+{
+    double acc = 0.0, dp = 0.0;
+    for (int c = 0; c < d; ++c) acc += (double)q[c] * (double)kj[c];
+    for (int c = 0; c < d; ++c) dp += (double)dOi[c] * (double)vj[c];
+    *p = exp(scale * acc - lse_i);
+    *dS = *p * (dp - delta);
+}
+
+/* q, dOi, Oi [d]; writes p[t], dS[t] for the k selected keys of this row. */
 static void row_p_and_ds(const float *q, const float *dOi, const double *Oi, double lse_i,
                          const float *K, const float *V, const int32_t *row, int d, int64_t k,
                          double scale, double *p, double *dS)
 {
-    double delta = 0.0;
-    for (int c = 0; c < d; ++c) delta += (double)dOi[c] * Oi[c];
-    for (int64_t t = 0; t < k; ++t) {
-        const float *kj = K + (int64_t)row[t] * d;
-        const float *vj = V + (int64_t)row[t] * d;
-        double acc = 0.0, dp = 0.0;
-        for (int c = 0; c < d; ++c) acc += (double)q[c] * (double)kj[c];
-        for (int c = 0; c < d; ++c) dp += (double)dOi[c] * (double)vj[c];
-        p[t] = exp(scale * acc - lse_i);
-        dS[t] = p[t] * (dp - delta);
-    }
+    const double delta = row_delta(dOi, Oi, d);
+    for (int64_t t = 0; t < k; ++t)
+        pair_p_and_ds(q, dOi, delta, lse_i, K + (int64_t)row[t] * d, V + (int64_t)row[t] * d, d, scale, &p[t], &dS[t]);
 }
 
 /* Sparse attention backward (selection held constant) for nq query rows of one head: their dQ,
@@ -284,24 +293,20 @@ void dsv_oracle_sparse_bwd_dkdv_key(int32_t j, const float *Qs, const float *dOs
 {
     double *termK = (double *)calloc((size_t)n * d, sizeof(double));
     double *termV = (double *)calloc((size_t)n * d, sizeof(double));
-#pragma omp parallel
-    {
-        double *p = (double *)malloc((size_t)k * sizeof(double));
-        double *dS = (double *)malloc((size_t)k * sizeof(double));
-#pragma omp for schedule(static)
-        for (int64_t a = 0; a < n; ++a) {
-            const int32_t *row = idxs + a * k;
-            row_p_and_ds(Qs + a * d, dOs + a * d, Os + a * d, lses[a], K, V, row, d, k, scale, p, dS);
-            for (int64_t t = 0; t < k; ++t) {
-                if (row[t] != j) continue;
-                for (int c = 0; c < d; ++c) {
-                    termK[a * d + c] += scale * dS[t] * (double)Qs[a * d + c];
-                    termV[a * d + c] += p[t] * (double)dOs[a * d + c];
-                }
+    (void)k;
+#pragma omp parallel for schedule(static)
+    for (int64_t a = 0; a < n; ++a) {
+        const int32_t *row = idxs + a * k;
+        const double delta = row_delta(dOs + a * d, Os + a * d, d);
+        for (int64_t t = 0; t < k; ++t) {
+            if (row[t] != j) continue;   /* only the pair (query a, key j) enters dK_j and dV_j */
+            double p, dS;
+            pair_p_and_ds(Qs + a * d, dOs + a * d, delta, lses[a], K + (int64_t)j * d, V + (int64_t)j * d, d, scale, &p, &dS);
+            for (int c = 0; c < d; ++c) {
+                termK[a * d + c] += scale * dS * (double)Qs[a * d + c];
+                termV[a * d + c] += p * (double)dOs[a * d + c];
             }
         }
-        free(p);
-        free(dS);
     }
     for (int c = 0; c < d; ++c) { dKj[c] = 0.0; dVj[c] = 0.0; }
     for (int64_t a = 0; a < n; ++a)
