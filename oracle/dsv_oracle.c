@@ -14,6 +14,8 @@
  *                                                             with softmax(QK^T/sqrt(d_k))V from
  *                                                             Sec. "Various Self-Attention Paradigms"
  *   - dense attention (the k = L limit and the comparator) .. Sec. "Various Self-Attention Paradigms"
+ *   - query groups sharing one index row (3D cubes, centre query as proxy): same section as the sparse
+ *     attention, defined further down in this file
  *
  * Readings taken where the paper is silent (listed again in the design notes):
  *   - one (Wq, Wk) pair per head, applied to that head's Q and K;
@@ -372,6 +374,93 @@ void dsv_oracle_dense_bwd(const float *Q, const float *K, const float *V, const 
     free(O);
     free(lse);
     free(P);
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Query grouping (Sec. "Sparse Attention with Query Grouping"; Observation 5: neighbouring tokens of
+ * the 3D latent grid attend to similar keys).  Tokens lie on a grid of F x Hh x Ww, flattened frames
+ * first, then height, then width (Sec. "Various Self-Attention Paradigms", footnote on the token
+ * order).  The grid is tiled by cubes of gf x gh x gw voxels; the G = gf*gh*gw queries of a cube form
+ * a group, the group's centre query alone is scored against all keys, and its k best keys are the
+ * index row shared by every member.  Readings: cubes tile the grid exactly (sizes divide); the
+ * "central" voxel of a cube with an even side is the one at offset side/2 (for 2 x 2 x 2: offset
+ * (1, 1, 1)); groups are numbered in the same frames-height-width order as tokens, members likewise
+ * inside their cube.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Token index of member m of group g.  Returns -1 if the cube sizes do not divide the grid. */
+int64_t dsv_oracle_group_member(int64_t g, int m, int F, int Hh, int Ww, int gf, int gh, int gw)
+{
+    if (F % gf || Hh % gh || Ww % gw) return -1;
+    const int nh = Hh / gh, nw = Ww / gw;
+    const int64_t cf = g / ((int64_t)nh * nw), ch = (g / nw) % nh, cw = g % nw;   /* cube coordinates */
+    const int mf = m / (gh * gw), mh = (m / gw) % gh, mw = m % gw;                /* offset in the cube */
+    const int64_t f = cf * gf + mf, h = ch * gh + mh, w = cw * gw + mw;
+    return (f * Hh + h) * Ww + w;
+}
+
+/* Member number of the centre (proxy) query of every cube. */
+int dsv_oracle_group_centre(int gf, int gh, int gw)
+{
+    return ((gf / 2) * gh + gh / 2) * gw + gw / 2;
+}
+
+/* Grouped selection for one head: idx_g [n_groups, k] = the k best keys of each group's centre
+ * query (same total order and row order as the per-query selection).  Q, K [L, d], L = F*Hh*Ww. */
+void dsv_oracle_lowrank_topk_grouped(const float *Q, const float *K, const float *Wq, const float *Wk,
+                                     int F, int Hh, int Ww, int gf, int gh, int gw, int d, int r, int64_t k,
+                                     int dtype, int32_t *idx_g)
+{
+    const int64_t L = (int64_t)F * Hh * Ww;
+    const int G = gf * gh * gw;
+    const int64_t ng = L / G;
+    const int centre = dsv_oracle_group_centre(gf, gh, gw);
+    float *Qc = (float *)malloc((size_t)ng * d * sizeof(float));
+    for (int64_t g = 0; g < ng; ++g) {
+        const int64_t i = dsv_oracle_group_member(g, centre, F, Hh, Ww, gf, gh, gw);
+        memcpy(Qc + g * d, Q + i * d, (size_t)d * sizeof(float));
+    }
+    dsv_oracle_lowrank_topk(Qc, K, Wq, Wk, ng, L, d, r, k, dtype, idx_g, NULL, NULL, NULL);
+    free(Qc);
+}
+
+/* The per-query index that grouping stands for: row i = the row of i's group.  idx [L, k]. */
+void dsv_oracle_group_expand_idx(const int32_t *idx_g, int F, int Hh, int Ww, int gf, int gh, int gw, int64_t k,
+                                 int32_t *idx)
+{
+    const int64_t L = (int64_t)F * Hh * Ww;
+    const int G = gf * gh * gw;
+    for (int64_t g = 0; g < L / G; ++g)
+        for (int m = 0; m < G; ++m) {
+            const int64_t i = dsv_oracle_group_member(g, m, F, Hh, Ww, gf, gh, gw);
+            memcpy(idx + i * k, idx_g + g * k, (size_t)k * sizeof(int32_t));
+        }
+}
+
+/* Grouped sparse attention of one head: every member of a group attends over the group's shared
+ * index row -- by definition the per-query routines on the expanded index. */
+void dsv_oracle_sparse_fwd_grouped(const float *Q, const float *K, const float *V, const int32_t *idx_g,
+                                   int F, int Hh, int Ww, int gf, int gh, int gw, int d, int64_t k, double scale,
+                                   double *O, double *lse)
+{
+    const int64_t L = (int64_t)F * Hh * Ww;
+    int32_t *idx = (int32_t *)malloc((size_t)L * k * sizeof(int32_t));
+    dsv_oracle_group_expand_idx(idx_g, F, Hh, Ww, gf, gh, gw, k, idx);
+    dsv_oracle_sparse_fwd(Q, K, V, idx, L, L, d, k, scale, O, lse, NULL);
+    free(idx);
+}
+
+void dsv_oracle_sparse_bwd_grouped(const float *Q, const float *K, const float *V, const int32_t *idx_g,
+                                   const float *dO, int F, int Hh, int Ww, int gf, int gh, int gw, int d, int64_t k,
+                                   double scale, double *dQ, double *dK, double *dV)
+{
+    const int64_t L = (int64_t)F * Hh * Ww;
+    int32_t *idx = (int32_t *)malloc((size_t)L * k * sizeof(int32_t));
+    double *O = (double *)malloc((size_t)L * d * sizeof(double)), *lse = (double *)malloc((size_t)L * sizeof(double));
+    dsv_oracle_group_expand_idx(idx_g, F, Hh, Ww, gf, gh, gw, k, idx);
+    dsv_oracle_sparse_fwd(Q, K, V, idx, L, L, d, k, scale, O, lse, NULL);
+    dsv_oracle_sparse_bwd(Q, K, V, idx, O, lse, dO, L, d, k, scale, dQ, dK, dV);
+    free(idx); free(O); free(lse);
 }
 
 int dsv_oracle_max_threads(void)

@@ -20,7 +20,8 @@ DTYPES = {"f32": 0, "bf16": 1}
 
 __all__ = ["build", "lib", "round_value", "project", "scores", "topk_from_scores", "lowrank_topk",
            "sparse_fwd", "sparse_bwd", "sparse_bwd_rows", "sparse_bwd_dq_rows", "sparse_bwd_dkdv_key",
-           "dense_fwd", "dense_bwd", "max_threads", "DTYPES"]
+           "dense_fwd", "dense_bwd", "max_threads", "DTYPES", "group_member", "group_centre", "group_tokens",
+           "lowrank_topk_grouped", "group_expand_idx", "sparse_fwd_grouped", "sparse_bwd_grouped"]
 
 
 def build(force: bool = False) -> str:
@@ -209,4 +210,65 @@ def dense_bwd(Q, K, V, dO, scale: float):
     L, d = Q.shape
     dQ = np.empty((L, d)); dK = np.empty((L, d)); dV = np.empty((L, d))
     lib().dsv_oracle_dense_bwd(_p(Q), _p(K), _p(V), _p(dO), _i64(L), _int(d), _dbl(scale), _p(dQ), _p(dK), _p(dV))
+    return dQ, dK, dV
+
+
+# ---- query grouping ---------------------------------------------------------------------------
+def group_member(g: int, m: int, grid, cube) -> int:
+    """Token index of member m of group g on a (frames, height, width) grid tiled by `cube`."""
+    L = lib()
+    L.dsv_oracle_group_member.restype = ctypes.c_int64
+    return int(L.dsv_oracle_group_member(_i64(g), _int(m), *[_int(x) for x in grid], *[_int(x) for x in cube]))
+
+
+def group_centre(cube) -> int:
+    return int(lib().dsv_oracle_group_centre(*[_int(x) for x in cube]))
+
+
+def group_tokens(grid, cube) -> np.ndarray:
+    """int64 [n_groups, G]: token index of every member of every group (from the C routine)."""
+    Ltok = grid[0] * grid[1] * grid[2]
+    G = cube[0] * cube[1] * cube[2]
+    return np.array([[group_member(g, m, grid, cube) for m in range(G)] for g in range(Ltok // G)], dtype=np.int64)
+
+
+def lowrank_topk_grouped(Q, K, Wq, Wk, grid, cube, k: int, dtype: str) -> np.ndarray:
+    """idx_g [n_groups, k]: per group, the centre query's k best keys."""
+    Q, K, Wq, Wk = _f32(Q), _f32(K), _f32(Wq), _f32(Wk)
+    Ltok, d = Q.shape
+    r = Wq.shape[1]
+    G = cube[0] * cube[1] * cube[2]
+    assert Ltok == grid[0] * grid[1] * grid[2] and all(a % b == 0 for a, b in zip(grid, cube))
+    idx_g = np.empty((Ltok // G, k), dtype=np.int32)
+    lib().dsv_oracle_lowrank_topk_grouped(_p(Q), _p(K), _p(Wq), _p(Wk), *[_int(x) for x in grid], *[_int(x) for x in cube],
+                                          _int(d), _int(r), _i64(k), _int(DTYPES[dtype]), _p(idx_g))
+    return idx_g
+
+
+def group_expand_idx(idx_g, grid, cube) -> np.ndarray:
+    idx_g = _i32(idx_g)
+    Ltok = grid[0] * grid[1] * grid[2]
+    k = idx_g.shape[1]
+    idx = np.empty((Ltok, k), dtype=np.int32)
+    lib().dsv_oracle_group_expand_idx(_p(idx_g), *[_int(x) for x in grid], *[_int(x) for x in cube], _i64(k), _p(idx))
+    return idx
+
+
+def sparse_fwd_grouped(Q, K, V, idx_g, grid, cube, scale: float):
+    Q, K, V, idx_g = _f32(Q), _f32(K), _f32(V), _i32(idx_g)
+    Ltok, d = Q.shape
+    k = idx_g.shape[1]
+    O = np.empty((Ltok, d)); lse = np.empty(Ltok)
+    lib().dsv_oracle_sparse_fwd_grouped(_p(Q), _p(K), _p(V), _p(idx_g), *[_int(x) for x in grid], *[_int(x) for x in cube],
+                                        _int(d), _i64(k), _dbl(scale), _p(O), _p(lse))
+    return O, lse
+
+
+def sparse_bwd_grouped(Q, K, V, idx_g, dO, grid, cube, scale: float):
+    Q, K, V, dO, idx_g = _f32(Q), _f32(K), _f32(V), _f32(dO), _i32(idx_g)
+    Ltok, d = Q.shape
+    k = idx_g.shape[1]
+    dQ = np.empty((Ltok, d)); dK = np.empty((Ltok, d)); dV = np.empty((Ltok, d))
+    lib().dsv_oracle_sparse_bwd_grouped(_p(Q), _p(K), _p(V), _p(idx_g), _p(dO), *[_int(x) for x in grid],
+                                        *[_int(x) for x in cube], _int(d), _i64(k), _dbl(scale), _p(dQ), _p(dK), _p(dV))
     return dQ, dK, dV

@@ -18,4 +18,5 @@ from .generator import (  # noqa: F401
     progression_idx_rows,
     progression_queries_of_key,
     ternary_head_tensors,
+    head_tensors_smooth,
 )

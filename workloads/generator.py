@@ -21,7 +21,7 @@ import numpy as np
 from .configs import WorkloadConfig
 
 _TENSOR_ID = {"basis": 1, "Q": 2, "K": 3, "V": 4, "dO": 5, "Wq": 6, "Wk": 7,
-              "k_per_head": 8, "subset_idx": 9, "progression": 10, "ternary": 11}
+              "k_per_head": 8, "subset_idx": 9, "progression": 10, "ternary": 11, "tokens": 12}
 
 
 def _rng(seed: int, cfg_index: int, tensor: str, head: int = 0, extra: int = 0):
@@ -173,3 +173,43 @@ def ternary_head_tensors(L: int, d: int, r: int, seed: int = 0, head: int = 0):
     Wq = rng.integers(-1, 2, size=(d, r)).astype(np.float32)
     Wk = rng.integers(-1, 2, size=(d, r)).astype(np.float32)
     return Q, K, Wq, Wk
+
+
+# ---------------------------------------------------------------------------------------
+# Spatially smooth variant: video latents are continuous signals, so neighbouring tokens of
+# the frames x height x width grid have similar queries and keys (the i.i.d. coefficients above
+# model none of that).  The coefficient fields Cq, Ck [F, Hh, Ww, R] are white noise passed
+# through a periodic Gaussian low-pass of width `sigma` voxels along every grid axis and
+# rescaled to unit variance; everything else is the recipe of head_tensors.  The correlation
+# of two coefficient vectors at grid offset D is exp(-|D|^2 / (4 sigma^2)).
+# ---------------------------------------------------------------------------------------
+
+def _smooth_field(white: np.ndarray, sigma: float) -> np.ndarray:
+    """white [F, Hh, Ww, R] -> same shape, Gaussian low-pass over the three grid axes (periodic), unit variance."""
+    f = np.fft.rfftn(white, axes=(0, 1, 2))
+    for ax, n in enumerate(white.shape[:3]):
+        freq = np.fft.rfftfreq(n) if ax == 2 else np.fft.fftfreq(n)
+        gain = np.exp(-2.0 * (np.pi * freq * sigma) ** 2)
+        shape = [1, 1, 1, 1]
+        shape[ax] = gain.shape[0]
+        f *= gain.reshape(shape)
+    out = np.fft.irfftn(f, s=white.shape[:3], axes=(0, 1, 2))
+    return out / out.std()
+
+
+def head_tensors_smooth(cfg: WorkloadConfig, head: int, seed: int = 0, sigma: float = 5.0,
+                        names=("Q", "K", "V", "dO")) -> dict:
+    """As head_tensors, with the Q / K coefficient fields smooth over cfg.grid (V, dO unchanged)."""
+    out = {}
+    L, d, R = cfg.L, cfg.d, cfg.basis_rank
+    G = basis(cfg, seed)
+    for name in names:
+        rng = _rng(seed, cfg.index, name, head, extra=1)
+        if name in ("Q", "K"):
+            coef = _smooth_field(rng.standard_normal(tuple(cfg.grid) + (R,)), sigma).reshape(L, R)
+            noise = rng.standard_normal((L, d), dtype=np.float32)
+            x = (coef @ G).astype(np.float32) + np.float32(0.1) * noise
+        else:
+            x = rng.standard_normal((L, d), dtype=np.float32)
+        out[name] = round_to_dtype(x, cfg.dtype)
+    return out
