@@ -190,6 +190,48 @@ DSV_API dsv_status dsv_sparse_attn_bwd_dkdv(const dsv_problem *p, const void *Q,
                                             const float *delta, const void *dO, void *dK, void *dV,
                                             void *workspace, size_t ws_bytes, void *hip_stream);
 
+/* ---- Query grouping ----------------------------------------------------------------------------
+ * Sec. "Sparse Attention with Query Grouping" (with Observation 5: neighbouring tokens of the 3D latent
+ * grid attend to similar keys): the tokens lie on a grid of F x Hh x Ww (token index
+ * (f * Hh + h) * Ww + w: frames first, then height, then width); the grid is tiled by cubes of
+ * gf x gh x gw voxels; the G = gf*gh*gw queries of a cube share ONE index row, chosen by the cube's
+ * centre query alone (the voxel at offset (gf/2, gh/2, gw/2) of the cube).  Groups are numbered like
+ * tokens (cube coordinates, frames first), members likewise inside their cube.
+ * Requires F*Hh*Ww == L and gf | F, gh | Hh, gw | Ww; anything else: DSV_EINVAL.
+ *
+ * Grouped index layout: idx_g is ragged int32 like idx, the block of (b, h) holding [L/G, k_h]
+ * (one row per group, ascending keys) at element off[b*H+h] / G of dsv_idx_offsets.  idx_t_g / col_ptr:
+ * per key the ASCENDING list of GROUPS whose row holds it (col_ptr [B*H, L+1] as for idx_t).
+ *
+ * dsv_lowrank_topk_grouped: stage 1 on the centre queries only (1/G of the scoring and selection
+ *   work).  idx_t_g and col_ptr may both be NULL (no key-major lists).
+ * dsv_sparse_attn_fwd_grouped: every member of a group attends over the group's row; same O, lse as
+ *   dsv_sparse_attn_fwd on the index with that row repeated for every member.  Each selected K / V
+ *   row is gathered once per group and used by all members (scores on the matrix cores).
+ *   bf16, d = 128, G <= 8; else DSV_EUNSUPPORTED.  No workspace.
+ * dsv_sparse_attn_bwd_grouped: gradients of the above (selection held constant).  Runs the
+ *   per-query backward kernels on queries reordered group by group; the workspace holds the
+ *   reordered Q, dO, O, lse, dQ and the per-query form of both indices (2 x L*k int32 per head),
+ *   so the grouped index saves memory in the forward only.  Needs idx_t_g and col_ptr. */
+typedef struct dsv_grouping {
+    int32_t F, Hh, Ww;   /* token grid: frames, height, width */
+    int32_t gf, gh, gw;  /* cube (group) size along each axis */
+} dsv_grouping;
+
+DSV_API size_t dsv_lowrank_topk_grouped_workspace(const dsv_problem *p, const dsv_grouping *g);
+DSV_API dsv_status dsv_lowrank_topk_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
+                                            const void *Wq, const void *Wk, int32_t *idx_g, int32_t *idx_t_g,
+                                            int64_t *col_ptr, void *workspace, size_t ws_bytes, void *hip_stream);
+DSV_API dsv_status dsv_sparse_attn_fwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
+                                               const void *V, const int32_t *idx_g, void *O, float *lse,
+                                               void *hip_stream);
+DSV_API size_t dsv_sparse_attn_bwd_grouped_workspace(const dsv_problem *p, const dsv_grouping *g);
+DSV_API dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
+                                               const void *V, const int32_t *idx_g, const int32_t *idx_t_g,
+                                               const int64_t *col_ptr, const void *O, const float *lse, const void *dO,
+                                               void *dQ, void *dK, void *dV, void *workspace, size_t ws_bytes,
+                                               void *hip_stream);
+
 /* ---- Optional debug check of an index tensor ---------------------------------------------------
  * Checks every row of idx against the idx contract above: values in [0, L), distinct within a row,
  * and -- when dsv_problem.flags has DSV_FLAG_SORTED_INDEX -- strictly ascending (which is what the

@@ -28,6 +28,8 @@ EXPORTED_SYMBOLS = (
     "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dq", "dsv_idx_transpose_workspace", "dsv_idx_transpose",
     "dsv_sparse_attn_bwd_dkdv_workspace", "dsv_sparse_attn_bwd_dkdv",
     "dsv_idx_validate_workspace", "dsv_idx_validate",
+    "dsv_lowrank_topk_grouped_workspace", "dsv_lowrank_topk_grouped", "dsv_sparse_attn_fwd_grouped",
+    "dsv_sparse_attn_bwd_grouped_workspace", "dsv_sparse_attn_bwd_grouped",
     "dsv_lowrank_topk_noalloc_max_bytes", "dsv_lowrank_topk_noalloc",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
     "dsv_kernel_timing", "dsv_kernel_ms",
@@ -43,6 +45,26 @@ class _CProblem(ctypes.Structure):
                 ("r", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("k_per_head", ctypes.POINTER(ctypes.c_int32)), ("scale", ctypes.c_float),
                 ("flags", ctypes.c_uint32)]
+
+
+class _CGrouping(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("F", "Hh", "Ww", "gf", "gh", "gw")]
+
+
+class Grouping:
+    """Token grid (frames, height, width) and the cube that forms a query group (mirrors struct dsv_grouping)."""
+
+    def __init__(self, grid, cube):
+        self.grid, self.cube = tuple(int(x) for x in grid), tuple(int(x) for x in cube)
+        self._c = _CGrouping(*self.grid, *self.cube)
+
+    @property
+    def c(self):
+        return ctypes.byref(self._c)
+
+    @property
+    def G(self) -> int:
+        return self.cube[0] * self.cube[1] * self.cube[2]
 
 
 _lib = None
@@ -94,6 +116,16 @@ def load_library():
     lib.dsv_lowrank_topk_noalloc_max_bytes.argtypes = []
     lib.dsv_lowrank_topk_noalloc.restype = ctypes.c_int
     lib.dsv_lowrank_topk_noalloc.argtypes = [P, vp, vp, vp, vp, vp, vp]
+    PG = ctypes.POINTER(_CGrouping)
+    for name in ("dsv_lowrank_topk_grouped_workspace", "dsv_sparse_attn_bwd_grouped_workspace"):
+        getattr(lib, name).restype = sz
+        getattr(lib, name).argtypes = [P, PG]
+    lib.dsv_lowrank_topk_grouped.restype = ctypes.c_int
+    lib.dsv_lowrank_topk_grouped.argtypes = [P, PG, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dsv_sparse_attn_fwd_grouped.restype = ctypes.c_int
+    lib.dsv_sparse_attn_fwd_grouped.argtypes = [P, PG, vp, vp, vp, vp, vp, vp, vp]
+    lib.dsv_sparse_attn_bwd_grouped.restype = ctypes.c_int
+    lib.dsv_sparse_attn_bwd_grouped.argtypes = [P, PG] + [vp] * 12 + [vp, sz, vp]
     lib.dsv_idx_validate.restype = ctypes.c_int
     lib.dsv_idx_validate.argtypes = [P, vp, ctypes.POINTER(ctypes.c_int64), vp, sz, vp]
     lib.dsv_lowrank_project.restype = ctypes.c_int
@@ -311,6 +343,52 @@ def sparse_attn_bwd_dkdv(p: Problem, Q, K, V, idx_t, col_ptr, lse, delta, dO, dK
                                         _ptr(delta), _ptr(dO), _ptr(dK), _ptr(dV), _ptr(ws), nbytes, _stream(stream)),
            "dsv_sparse_attn_bwd_dkdv")
     return dK, dV
+
+
+# ---- query grouping -------------------------------------------------------------------------------
+def lowrank_topk_grouped_workspace(p: Problem, g: Grouping) -> int:
+    return int(load_library().dsv_lowrank_topk_grouped_workspace(p.c, g.c))
+
+
+def lowrank_topk_grouped(p: Problem, g: Grouping, Q, K, Wq, Wk, transposed=True, idx_g=None, idx_t_g=None, col_ptr=None,
+                         workspace=None, stream=None):
+    """Stage 1 on the groups' centre queries: (idx_g, idx_t_g, col_ptr); the last two None if not transposed."""
+    lib = load_library()
+    n = p.nnz // g.G
+    idx_g = torch.empty(n, dtype=torch.int32, device=Q.device) if idx_g is None else idx_g
+    if transposed:
+        idx_t_g = torch.empty(n, dtype=torch.int32, device=Q.device) if idx_t_g is None else idx_t_g
+        col_ptr = torch.empty((p.B * p.H, p.L + 1), dtype=torch.int64, device=Q.device) if col_ptr is None else col_ptr
+    ws, nbytes = _workspace(lowrank_topk_grouped_workspace(p, g), Q.device, workspace, stream)
+    _check(lib.dsv_lowrank_topk_grouped(p.c, g.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(idx_g),
+                                        _ptr(idx_t_g) if transposed else None, _ptr(col_ptr) if transposed else None,
+                                        _ptr(ws), nbytes, _stream(stream)), "dsv_lowrank_topk_grouped")
+    return idx_g, (idx_t_g if transposed else None), (col_ptr if transposed else None)
+
+
+def sparse_attn_fwd_grouped(p: Problem, g: Grouping, Q, K, V, idx_g, O=None, lse=None, stream=None):
+    O = torch.empty_like(Q) if O is None else O
+    lse = torch.empty((p.B, p.H, p.L), dtype=torch.float32, device=Q.device) if lse is None else lse
+    _check(load_library().dsv_sparse_attn_fwd_grouped(p.c, g.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx_g), _ptr(O), _ptr(lse),
+                                                      _stream(stream)), "dsv_sparse_attn_fwd_grouped")
+    return O, lse
+
+
+def sparse_attn_bwd_grouped_workspace(p: Problem, g: Grouping) -> int:
+    return int(load_library().dsv_sparse_attn_bwd_grouped_workspace(p.c, g.c))
+
+
+def sparse_attn_bwd_grouped(p: Problem, g: Grouping, Q, K, V, idx_g, idx_t_g, col_ptr, O, lse, dO, dQ=None, dK=None,
+                            dV=None, workspace=None, stream=None):
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    ws, nbytes = _workspace(sparse_attn_bwd_grouped_workspace(p, g), Q.device, workspace, stream)
+    _check(load_library().dsv_sparse_attn_bwd_grouped(p.c, g.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx_g), _ptr(idx_t_g),
+                                                      _ptr(col_ptr), _ptr(O), _ptr(lse), _ptr(dO), _ptr(dQ), _ptr(dK),
+                                                      _ptr(dV), _ptr(ws), nbytes, _stream(stream)),
+           "dsv_sparse_attn_bwd_grouped")
+    return dQ, dK, dV
 
 
 def idx_validate(p: Problem, idx, workspace=None, stream=None):

@@ -42,11 +42,13 @@ dsv_status check_problem(const dsv_problem *p, bool need_r)
 }
 
 // Launch tables: all (b, h) pairs sorted by descending k (stable), cut into groups of kMaxSlots.
-std::vector<HeadTable> make_tables(const dsv_problem &p)
+// rows: index rows per head (p.L, or the number of query groups); 0 = p.L.
+std::vector<HeadTable> make_tables(const dsv_problem &p, int rows = 0)
 {
     const int nbh = p.B * p.H;
+    if (rows == 0) rows = p.L;
     std::vector<int64_t> off(nbh + 1, 0);
-    for (int bh = 0; bh < nbh; ++bh) off[bh + 1] = off[bh] + (int64_t)p.L * p.k_per_head[bh % p.H];
+    for (int bh = 0; bh < nbh; ++bh) off[bh + 1] = off[bh] + (int64_t)rows * p.k_per_head[bh % p.H];
     std::vector<int> order(nbh);
     for (int i = 0; i < nbh; ++i) order[i] = i;
     std::stable_sort(order.begin(), order.end(),
@@ -79,26 +81,42 @@ dsv_status check_workspace(const void *ws, size_t have, size_t need)
 
 // ---- workspace layouts (byte offsets, every block aligned to 256) ------------------------------
 struct Stage1Layout {
-    size_t qlr, klr, prefix, krem, jcut, cnt, tflag, total;
+    size_t qlr, klr, prefix, krem, jcut, cnt, tflag, qc, total;
 };
 
-// transposed: also room for jcut and the per-key list lengths of the key-major emission
-Stage1Layout stage1_layout(const dsv_problem &p, bool transposed)
+// transposed: also room for jcut and the per-key list lengths of the key-major emission.
+// Lq: scored query rows per head (p.L, or one centre query per group: then also room for those rows, qc).
+Stage1Layout stage1_layout(const dsv_problem &p, bool transposed, int Lq = 0)
 {
-    const size_t tok = (size_t)p.B * p.H * p.L;
-    const size_t tokp = (size_t)p.B * p.H * ((p.L + 31) / 32 * 32);  // per-query state rows are padded to tiles
+    const bool grouped = Lq != 0;
+    if (!grouped) Lq = p.L;
+    const size_t nbh = (size_t)p.B * p.H;
+    const size_t qp = nbh * ((Lq + 31) / 32 * 32);  // per-query state rows are padded to tiles
     Stage1Layout w{};
     size_t o = 0;
-    w.qlr = o; o = align_up(o + tok * p.r * esize(p.dtype), 256);
-    w.klr = o; o = align_up(o + tok * p.r * esize(p.dtype), 256);
-    w.prefix = o; o = align_up(o + tokp * 4, 256);
-    w.krem = o; o = align_up(o + tokp * 4, 256);
-    w.jcut = o; if (transposed) o = align_up(o + tokp * 4, 256);
-    w.cnt = o; if (transposed) o = align_up(o + tok * 4, 256);
-    w.tflag = o; if (transposed) o = align_up(o + (size_t)p.B * p.H * ((p.L + 31) / 32) * 4, 256);
+    w.qlr = o; o = align_up(o + nbh * Lq * p.r * esize(p.dtype), 256);
+    w.klr = o; o = align_up(o + nbh * p.L * p.r * esize(p.dtype), 256);
+    w.prefix = o; o = align_up(o + qp * 4, 256);
+    w.krem = o; o = align_up(o + qp * 4, 256);
+    w.jcut = o; if (transposed) o = align_up(o + qp * 4, 256);
+    w.cnt = o; if (transposed) o = align_up(o + nbh * p.L * 4, 256);
+    w.tflag = o; if (transposed) o = align_up(o + nbh * ((Lq + 31) / 32) * 4, 256);
+    w.qc = o; if (grouped) o = align_up(o + nbh * Lq * p.d * esize(p.dtype), 256);
     w.total = o;
     return w;
 }
+
+// Cubes must tile the grid, and the grid must be the problem's L tokens.
+dsv_status check_grouping(const dsv_problem &p, const dsv_grouping *g)
+{
+    if (!g) return DSV_EINVAL;
+    if (g->F < 1 || g->Hh < 1 || g->Ww < 1 || g->gf < 1 || g->gh < 1 || g->gw < 1) return DSV_EINVAL;
+    if ((int64_t)g->F * g->Hh * g->Ww != (int64_t)p.L) return DSV_EINVAL;
+    if (g->F % g->gf || g->Hh % g->gh || g->Ww % g->gw) return DSV_EINVAL;
+    if ((int64_t)g->gf * g->gh * g->gw > 64) return DSV_EUNSUPPORTED;
+    return DSV_OK;
+}
+int group_size(const dsv_grouping &g) { return g.gf * g.gh * g.gw; }
 
 // Whether stage 2 runs its L2-blocked kernels: sorted indices promised and more than one range.
 bool use_split(const dsv_problem &p, const SplitPlan &pl) { return (p.flags & DSV_FLAG_SORTED_INDEX) && pl.S > 1; }
@@ -248,20 +266,30 @@ dsv_status dsv_idx_offsets(const dsv_problem *p, int64_t *off)
 }
 
 // ------------------------------------------------------------------------------------ stage 1
-static dsv_status lowrank_topk_impl(const dsv_problem *p, const void *Q, const void *K, const void *Wq,
-                                    const void *Wk, int32_t *idx, int32_t *idx_t, int64_t *col_ptr, bool transposed,
-                                    void *workspace, size_t ws_bytes, void *hip_stream)
+// grp == nullptr: every query is scored; else only the centre query of every group (idx, idx_t then hold
+// one row per group and lists of groups).
+static dsv_status lowrank_topk_impl(const dsv_problem *p, const dsv_grouping *grp, const void *Q, const void *K,
+                                    const void *Wq, const void *Wk, int32_t *idx, int32_t *idx_t, int64_t *col_ptr,
+                                    bool transposed, void *workspace, size_t ws_bytes, void *hip_stream)
 {
     dsv_status st = check_problem(p, true);
     if (st != DSV_OK) return st;
+    if (grp && (st = check_grouping(*p, grp)) != DSV_OK) return st;
     if (!ok_ptrs({Q, K, Wq, Wk, idx})) return DSV_EINVAL;
     if (transposed && !ok_ptrs({idx_t, col_ptr})) return DSV_EINVAL;
-    const Stage1Layout w = stage1_layout(*p, transposed);
+    const int Lq = grp ? p->L / group_size(*grp) : p->L;
+    const Stage1Layout w = stage1_layout(*p, transposed, grp ? Lq : 0);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
     char *ws = static_cast<char *>(workspace);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    st = launch_project(*p, Q, K, Wq, Wk, ws + w.qlr, ws + w.klr, stream);
+    const void *Qsrc = Q;
+    if (grp) {
+        st = launch_group_rows(*p, *grp, 0, Q, ws + w.qc, stream);
+        if (st != DSV_OK) return st;
+        Qsrc = ws + w.qc;
+    }
+    st = launch_project(*p, Lq, Qsrc, K, Wq, Wk, ws + w.qlr, ws + w.klr, stream);
     if (st != DSV_OK) return st;
     SelectBuffers b;
     b.prefix = reinterpret_cast<uint32_t *>(ws + w.prefix);
@@ -272,8 +300,8 @@ static dsv_status lowrank_topk_impl(const dsv_problem *p, const void *Q, const v
     b.tile_flag = transposed ? reinterpret_cast<int32_t *>(ws + w.tflag) : nullptr;
     b.col = transposed ? col_ptr : nullptr;
     b.idx_t = transposed ? idx_t : nullptr;
-    const std::vector<HeadTable> tabs = make_tables(*p);
-    return launch_select(*p, tabs.data(), (int)tabs.size(), ws + w.qlr, ws + w.klr, b, stream);
+    const std::vector<HeadTable> tabs = make_tables(*p, Lq);
+    return launch_select(*p, Lq, tabs.data(), (int)tabs.size(), ws + w.qlr, ws + w.klr, b, stream);
 }
 
 size_t dsv_lowrank_topk_workspace(const dsv_problem *p)
@@ -285,7 +313,7 @@ size_t dsv_lowrank_topk_workspace(const dsv_problem *p)
 dsv_status dsv_lowrank_topk(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,
                             int32_t *idx, void *workspace, size_t ws_bytes, void *hip_stream)
 {
-    return lowrank_topk_impl(p, Q, K, Wq, Wk, idx, nullptr, nullptr, false, workspace, ws_bytes, hip_stream);
+    return lowrank_topk_impl(p, nullptr, Q, K, Wq, Wk, idx, nullptr, nullptr, false, workspace, ws_bytes, hip_stream);
 }
 
 size_t dsv_lowrank_topk_noalloc_max_bytes(void) { return kNoallocBytes; }
@@ -304,7 +332,7 @@ dsv_status dsv_lowrank_topk_noalloc(const dsv_problem *p, const void *Q, const v
     // every buffer of the layout is written by the kernels of this call before it is read (projections by
     // project_kernel, thresholds and tie budgets by the first radix pass), so what an earlier call left in
     // the array does not matter
-    return lowrank_topk_impl(p, Q, K, Wq, Wk, idx, nullptr, nullptr, false, ws, kNoallocBytes, hip_stream);
+    return lowrank_topk_impl(p, nullptr, Q, K, Wq, Wk, idx, nullptr, nullptr, false, ws, kNoallocBytes, hip_stream);
 }
 
 size_t dsv_lowrank_topk_t_workspace(const dsv_problem *p)
@@ -317,7 +345,7 @@ dsv_status dsv_lowrank_topk_t(const dsv_problem *p, const void *Q, const void *K
                               int32_t *idx, int32_t *idx_t, int64_t *col_ptr, void *workspace, size_t ws_bytes,
                               void *hip_stream)
 {
-    return lowrank_topk_impl(p, Q, K, Wq, Wk, idx, idx_t, col_ptr, true, workspace, ws_bytes, hip_stream);
+    return lowrank_topk_impl(p, nullptr, Q, K, Wq, Wk, idx, idx_t, col_ptr, true, workspace, ws_bytes, hip_stream);
 }
 
 // ------------------------------------------------------------------------------------ stage 2 forward
@@ -475,6 +503,102 @@ dsv_status dsv_sparse_attn_bwd_t(const dsv_problem *p, const void *Q, const void
                                     hip_stream);
 }
 
+// ------------------------------------------------------------------------------------ query grouping
+size_t dsv_lowrank_topk_grouped_workspace(const dsv_problem *p, const dsv_grouping *g)
+{
+    if (check_problem(p, true) != DSV_OK || check_grouping(*p, g) != DSV_OK) return 0;
+    return stage1_layout(*p, true, p->L / group_size(*g)).total;
+}
+
+dsv_status dsv_lowrank_topk_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
+                                    const void *Wq, const void *Wk, int32_t *idx_g, int32_t *idx_t_g, int64_t *col_ptr,
+                                    void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    if (!g) return DSV_EINVAL;
+    if ((idx_t_g == nullptr) != (col_ptr == nullptr)) return DSV_EINVAL;
+    return lowrank_topk_impl(p, g, Q, K, Wq, Wk, idx_g, idx_t_g, col_ptr, idx_t_g != nullptr, workspace, ws_bytes,
+                             hip_stream);
+}
+
+dsv_status dsv_sparse_attn_fwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
+                                       const void *V, const int32_t *idx_g, void *O, float *lse, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if ((st = check_grouping(*p, g)) != DSV_OK) return st;
+    if (!ok_ptrs({Q, K, V, idx_g, O, lse})) return DSV_EINVAL;
+    const std::vector<HeadTable> tabs = make_tables(*p, p->L / group_size(*g));
+    return launch_grouped_fwd(*p, *g, tabs.data(), (int)tabs.size(), Q, K, V, idx_g, O, lse,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
+namespace {
+struct GroupedBwdLayout {
+    size_t qp, gop, op, dqp, lsep, idxx, idxtx, colx, inner, inner_bytes, total;
+};
+GroupedBwdLayout grouped_bwd_layout(const dsv_problem &p)
+{
+    const size_t nbh = (size_t)p.B * p.H;
+    const size_t rows = nbh * p.L * p.d * esize(p.dtype);
+    dsv_problem sorted = p;
+    sorted.flags |= DSV_FLAG_SORTED_INDEX;
+    GroupedBwdLayout w{};
+    size_t o = 0;
+    w.qp = o; o = align_up(o + rows, 256);
+    w.gop = o; o = align_up(o + rows, 256);
+    w.op = o; o = align_up(o + rows, 256);
+    w.dqp = o; o = align_up(o + rows, 256);
+    w.lsep = o; o = align_up(o + nbh * p.L * 4, 256);
+    w.idxx = o; o = align_up(o + total_pairs(p) * 4, 256);
+    w.idxtx = o; o = align_up(o + total_pairs(p) * 4, 256);
+    w.colx = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
+    w.inner = o; w.inner_bytes = bwd_layout(sorted, false).total; o += w.inner_bytes;
+    w.total = o;
+    return w;
+}
+}  // namespace
+
+size_t dsv_sparse_attn_bwd_grouped_workspace(const dsv_problem *p, const dsv_grouping *g)
+{
+    if (check_problem(p, false) != DSV_OK || check_grouping(*p, g) != DSV_OK) return 0;
+    return grouped_bwd_layout(*p).total;
+}
+
+dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
+                                       const void *V, const int32_t *idx_g, const int32_t *idx_t_g,
+                                       const int64_t *col_ptr, const void *O, const float *lse, const void *dO, void *dQ,
+                                       void *dK, void *dV, void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if ((st = check_grouping(*p, g)) != DSV_OK) return st;
+    if (!ok_ptrs({Q, K, V, idx_g, idx_t_g, col_ptr, O, lse, dO, dQ, dK, dV})) return DSV_EINVAL;
+    const GroupedBwdLayout w = grouped_bwd_layout(*p);
+    st = check_workspace(workspace, ws_bytes, w.total);
+    if (st != DSV_OK) return st;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // queries reordered group by group: a group's members become neighbours, and the per-query lists that
+    // the lists of groups stand for come out ascending
+    if ((st = launch_group_rows(*p, *g, 1, Q, ws + w.qp, stream)) != DSV_OK) return st;
+    if ((st = launch_group_rows(*p, *g, 1, dO, ws + w.gop, stream)) != DSV_OK) return st;
+    if ((st = launch_group_rows(*p, *g, 1, O, ws + w.op, stream)) != DSV_OK) return st;
+    if ((st = launch_group_scalar(*p, *g, lse, reinterpret_cast<float *>(ws + w.lsep), stream)) != DSV_OK) return st;
+    const std::vector<HeadTable> tabs = make_tables(*p, p->L / group_size(*g));
+    st = launch_group_expand(*p, *g, tabs.data(), (int)tabs.size(), idx_g, idx_t_g, col_ptr,
+                             reinterpret_cast<int32_t *>(ws + w.idxx), reinterpret_cast<int32_t *>(ws + w.idxtx),
+                             reinterpret_cast<int64_t *>(ws + w.colx), stream);
+    if (st != DSV_OK) return st;
+    dsv_problem sorted = *p;
+    sorted.flags |= DSV_FLAG_SORTED_INDEX;
+    st = dsv_sparse_attn_bwd_t(&sorted, ws + w.qp, K, V, reinterpret_cast<int32_t *>(ws + w.idxx),
+                               reinterpret_cast<int32_t *>(ws + w.idxtx), reinterpret_cast<int64_t *>(ws + w.colx),
+                               ws + w.op, reinterpret_cast<float *>(ws + w.lsep), ws + w.gop, ws + w.dqp, dK, dV,
+                               ws + w.inner, w.inner_bytes, hip_stream);
+    if (st != DSV_OK) return st;
+    return launch_group_rows(*p, *g, 2, ws + w.dqp, dQ, stream);
+}
+
 // ------------------------------------------------------------------------------------ debug validator
 size_t dsv_idx_validate_workspace(const dsv_problem *p)
 {
@@ -502,7 +626,7 @@ dsv_status dsv_lowrank_project(const dsv_problem *p, const void *Q, const void *
     dsv_status st = check_problem(p, true);
     if (st != DSV_OK) return st;
     if (!ok_ptrs({Q, K, Wq, Wk, Qlr, Klr})) return DSV_EINVAL;
-    return launch_project(*p, Q, K, Wq, Wk, Qlr, Klr, static_cast<hipStream_t>(hip_stream));
+    return launch_project(*p, p->L, Q, K, Wq, Wk, Qlr, Klr, static_cast<hipStream_t>(hip_stream));
 }
 
 dsv_status dsv_lowrank_scores_rows(const dsv_problem *p, const void *Qlr, const void *Klr, int32_t b, int32_t h,

@@ -233,7 +233,9 @@ struct KernelSpan {
 };
 
 // Host: entry points of the per-stage translation units (called from api.hip).
-dsv_status launch_project(const dsv_problem &p, const void *Q, const void *K, const void *Wq, const void *Wk,
+// Lq: query rows per head in Q / Qlr (p.L for per-query selection; one proxy per group with query grouping);
+// K / Klr always hold p.L rows.
+dsv_status launch_project(const dsv_problem &p, int Lq, const void *Q, const void *K, const void *Wq, const void *Wk,
                           void *Qlr, void *Klr, hipStream_t st);
 dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void *Klr, int bh,
                               const int32_t *rows, int n_rows, float *scores, hipStream_t st);
@@ -295,9 +297,11 @@ struct SelectBuffers {
     int64_t *col;      // out: [B*H, L+1]
     int32_t *idx_t;    // out: ragged key-major index
 };
-dsv_status launch_select(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
+// Lq index rows per head (state arrays are [B*H, padded_len(Lq)], tile_flag [B*H, ceil(Lq/32)], lists hold row
+// numbers below Lq); tabs[].off must be the offsets of [Lq, k] blocks.
+dsv_status launch_select(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                          const SelectBuffers &b, hipStream_t st);
-dsv_status launch_emit(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
+dsv_status launch_emit(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                        const SelectBuffers &b, hipStream_t st);
 dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                              const void *V, const int32_t *idx, void *O, float *lse, hipStream_t st);
@@ -307,6 +311,25 @@ dsv_status launch_bwd_dq(const dsv_problem &p, const HeadTable *tabs, int n_tabs
 dsv_status launch_bwd_dkdv(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,
                            const void *V, const int32_t *idxT, const int64_t *col, const float *lse, const float *delta,
                            const void *dO, void *dK, void *dV, hipStream_t st);
+// ---- query grouping (grouped.hip) -----------------------------------------------------------------------
+struct GroupGeom {
+    int F, Hh, Ww, gf, gh, gw;
+    int nh, nw;  // cubes along height and width
+    int G;       // queries per group
+};
+// mode 0: out [B*H, L/G, d] = the groups' centre query rows; 1: out [B*H, L, d] = rows in group-major order;
+// 2: the inverse of 1.
+dsv_status launch_group_rows(const dsv_problem &p, const dsv_grouping &gr, int mode, const void *in, void *out,
+                             hipStream_t st);
+dsv_status launch_group_scalar(const dsv_problem &p, const dsv_grouping &gr, const float *in, float *out, hipStream_t st);
+// tabs: built for L/G rows per head.  Writes the per-query index (group-major query order) both ways.
+dsv_status launch_group_expand(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
+                               const int32_t *idx_g, const int32_t *idx_t_g, const int64_t *col, int32_t *idx_x,
+                               int32_t *idx_t_x, int64_t *col_x, hipStream_t st);
+dsv_status launch_grouped_fwd(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
+                              const void *Q, const void *K, const void *V, const int32_t *idx_g, void *O, float *lse,
+                              hipStream_t st);
+
 // report_dev: two 64-bit counters in device memory; report_host: optional HOST int64 [3].  Waits for the stream.
 dsv_status launch_idx_validate(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
                                unsigned long long *report_dev, int64_t *report_host, hipStream_t st);

@@ -1,0 +1,347 @@
+// Query grouping (paper Sec. "Sparse Attention with Query Grouping"; Observation 5): the queries of a
+// 3D cube of the frames x height x width token grid share ONE index row, chosen by the cube's centre
+// query.  Stage 1 then scores only one query per group; stage 2 gathers every selected K / V row once per
+// group and uses it for all G members, which turns the per-query gather sweep (one K row and one V row
+// per (query, key) pair, ~1 flop per byte) into small dense tiles.
+//
+// Forward kernel (bf16, d = 128, G <= 8): one wave per group.
+//   scores   S[q, key] for 32 keys at a time on the matrix cores: A = the group's query rows (rows >= G are
+//            zero), B = the 32 gathered K rows, one v_mfma_f32_32x32x16_bf16 per 16 channels.  Lane l then
+//            holds key (l % 32) against queries 4 * (l / 32) + 0..3 (accumulators 0..3; the other twelve
+//            belong to the zero rows and are ignored).
+//   softmax  online, in the log2 domain; the tile maximum of a query is a reduction over the 32 lanes of a
+//            half-wave.  Probabilities go to LDS as bf16 [query][key].
+//   output   O[q, :] += p[q, key] * V[key, :] on the vector units with the lanes across the channels: every
+//            V row is loaded once, fully coalesced (one 256-byte row per load instruction), and multiplied
+//            into all G queries' accumulators (v_dot2_f32_bf16 on two keys at a time, the probability pairs
+//            read from LDS as broadcasts).  The matrix cores would need V with the keys contiguous per lane,
+//            i.e. a transpose of every gathered tile.
+// Bytes through the vector memory path per (query, key) pair: (256 + 256) / G + 4 / G instead of 516.
+#include <algorithm>
+
+#include "stage2_core.h"
+
+namespace dsv {
+
+// Member m of group g -> token index (frames first, then height, then width; groups and members in the
+// same order).
+__device__ __forceinline__ int64_t member_token(const GroupGeom &gm, int g, int m)
+{
+    const int cw = g % gm.nw, ch = (g / gm.nw) % gm.nh, cf = g / (gm.nw * gm.nh);
+    const int mw = m % gm.gw, mh = (m / gm.gw) % gm.gh, mf = m / (gm.gw * gm.gh);
+    return ((int64_t)(cf * gm.gf + mf) * gm.Hh + (ch * gm.gh + mh)) * gm.Ww + (cw * gm.gw + mw);
+}
+
+typedef uint16_t __attribute__((may_alias)) u16_alias;
+typedef uint32_t __attribute__((may_alias)) u32_alias;
+typedef float __attribute__((may_alias)) f32_alias;
+
+// LDS traffic between the lanes of ONE wave: keeps the compiler from moving accesses across the point.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ float half_max(float x)  // over the 32 lanes of a half-wave
+{
+    x = row16_max(x);
+    return fmaxf(x, __shfl_xor(x, 16));
+}
+__device__ __forceinline__ float half_sum(float x)
+{
+    x = row16_sum(x);
+    return x + __shfl_xor(x, 16);
+}
+
+// ---- rows of [B*H, L, D] gathered into [B*H, n_out, D]: out[bh, r] = in[bh, src(r)] --------------------
+//   MODE 0: r = group,            src = the group's centre query          (n_out = L / G)
+//   MODE 1: r = g * G + m,        src = member m of group g               (n_out = L): group-major order
+//   MODE 2: the inverse of MODE 1: out[bh, member(g, m)] = in[bh, g * G + m]
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void group_rows_kernel(const T *__restrict__ in, T *__restrict__ out, int L, int D,
+                                                         int n_out, GroupGeom gm, int centre)
+{
+    const int per_row = D * (int)sizeof(T) / 16;  // 16-byte pieces per row
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int bh = blockIdx.y;
+    if (e >= (int64_t)n_out * per_row) return;
+    const int r = (int)(e / per_row), piece = (int)(e % per_row);
+    int64_t src, dst;
+    if (MODE == 0) { src = member_token(gm, r, centre); dst = r; }
+    else if (MODE == 1) { src = member_token(gm, r / gm.G, r % gm.G); dst = r; }
+    else { src = r; dst = member_token(gm, r / gm.G, r % gm.G); }
+    const int n_in = MODE == 0 ? L : n_out;
+    const uint4 *s = reinterpret_cast<const uint4 *>(in + ((int64_t)bh * n_in + src) * D) + piece;
+    uint4 *d = reinterpret_cast<uint4 *>(out + ((int64_t)bh * n_out + dst) * D) + piece;
+    *d = *s;
+}
+
+// lse (one float per token) into group-major order.
+__global__ __launch_bounds__(256) void group_scalar_kernel(const float *__restrict__ in, float *__restrict__ out, int L,
+                                                           GroupGeom gm)
+{
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    const int bh = blockIdx.y;
+    if (r >= L) return;
+    out[(int64_t)bh * L + r] = in[(int64_t)bh * L + member_token(gm, r / gm.G, r % gm.G)];
+}
+
+// ---- the per-query index the grouped one stands for, in group-major query order ------------------------
+// idx_x[bh][g * G + m][:] = idx_g[bh][g][:]
+__global__ __launch_bounds__(256) void expand_idx_kernel(const int32_t *__restrict__ idx_g, int32_t *__restrict__ idx_x,
+                                                         int Lq, int G, HeadTable tab)
+{
+    const int slot = blockIdx.y;
+    const int k = tab.k[slot];
+    const int32_t *src = idx_g + tab.off[slot];           // [Lq, k]
+    int32_t *dst = idx_x + tab.off[slot] * G;              // [Lq * G, k]
+    for (int64_t g = blockIdx.x; g < Lq; g += gridDim.x)
+        for (int t = threadIdx.x; t < k; t += 256) {
+            const int32_t v = src[g * k + t];
+#pragma unroll 1
+            for (int m = 0; m < G; ++m) dst[(g * G + m) * k + t] = v;
+        }
+}
+
+// Key-major: entry e of a list (a group g) becomes the G entries g * G + 0 .. G - 1 at positions e * G ...;
+// lists of ascending groups stay ascending.  col_x = G * col.
+__global__ __launch_bounds__(256) void expand_idx_t_kernel(const int32_t *__restrict__ idx_t_g,
+                                                           int32_t *__restrict__ idx_t_x, int Lq, int G, HeadTable tab)
+{
+    const int slot = blockIdx.y;
+    const int64_t n = (int64_t)Lq * tab.k[slot];
+    const int32_t *src = idx_t_g + tab.off[slot];
+    int32_t *dst = idx_t_x + tab.off[slot] * G;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n * G; e += stride)
+        dst[e] = src[e / G] * G + (int32_t)(e % G);
+}
+
+__global__ __launch_bounds__(256) void scale_col_kernel(const int64_t *__restrict__ col, int64_t *__restrict__ col_x,
+                                                        int64_t n, int G)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e < n) col_x[e] = col[e] * G;
+}
+
+// ---- grouped forward ------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                          const bf16_t *__restrict__ V,
+                                                          const int32_t *__restrict__ idx_g, bf16_t *__restrict__ O,
+                                                          float *__restrict__ lse, int L, int Lq, float scale,
+                                                          HeadTable tab, GroupGeom gm)
+{
+    static_assert(D == 128, "lanes across the channels: 64 lanes x 2 channels");
+    constexpr int NM = D / 16;
+    const int slot = blockIdx.y;
+    const int bh = tab.bh[slot];
+    const int k = tab.k[slot];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, half = lane >> 5;
+    const int g = blockIdx.x * 4 + wave;
+    if (g >= Lq) return;  // the whole wave leaves; nothing below synchronises across waves
+    const int G = gm.G;
+    const bf16_t *Qh = Q + (int64_t)bh * L * D;
+    const bf16_t *Kh = K + (int64_t)bh * L * D;
+    const bf16_t *Vh = V + (int64_t)bh * L * D;
+    const int32_t *row = idx_g + tab.off[slot] + (int64_t)g * k;
+
+    __shared__ __align__(16) uint32_t lds_all[4][8 * 16 + 8];
+    u32_alias *P_s = lds_all[wave];                                      // [8 queries][16 key pairs] bf16 pairs
+    f32_alias *fac_s = reinterpret_cast<f32_alias *>(lds_all[wave] + 8 * 16);  // [8 queries]
+
+    // A operand: query row (lane % 32) of the group, zero beyond the group
+    bf16x8_t qa[NM];
+    {
+        const int64_t tq = member_token(gm, g, min(n, G - 1));
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            uint4 raw = *reinterpret_cast<const uint4 *>(Qh + tq * D + m * 16 + half * 8);
+            if (n >= G) raw = make_uint4(0u, 0u, 0u, 0u);
+            qa[m] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+    float M[4], lsum[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) { M[v] = -INFINITY; lsum[v] = 0.f; }
+    float oacc[8][2];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { oacc[q][0] = 0.f; oacc[q][1] = 0.f; }
+    const float c2 = scale * kLog2e;
+
+    for (int t0 = 0; t0 < k; t0 += 32) {
+        const int nvalid = min(32, k - t0);
+        // keys past the end of the row repeat its last entry and get probability zero
+        const int j = row[t0 + min(n, nvalid - 1)];
+        floatx16_t acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            const bf16x8_t kb = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[m], kb, acc, 0, 0, 0);
+        }
+        float p[4], corr[4];
+        bool moved = false;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const float s = n < nvalid ? acc[v] * c2 : -INFINITY;
+            const float mn = fmaxf(M[v], half_max(s));
+            corr[v] = fast_exp2(M[v] - mn);
+            moved = moved || (mn != M[v]);
+            M[v] = mn;
+            p[v] = fast_exp2(s - mn);
+            lsum[v] = fmaf(lsum[v], corr[v], p[v]);
+        }
+        moved = __any(moved);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) reinterpret_cast<u16_alias *>(P_s)[(4 * half + v) * 32 + n] = f32_to_bf16(p[v]);
+        if (moved && n == 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) fac_s[4 * half + v] = corr[v];
+        }
+        wave_sync();
+        if (moved) {  // wave-uniform
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const float f = fac_s[q];
+                oacc[q][0] *= f;
+                oacc[q][1] *= f;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {  // 8 keys = 4 key pairs at a time
+            uint32_t lo[4], hi[4];
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                const int ja = __builtin_amdgcn_readlane(j, 8 * i + 2 * pr);
+                const int jb = __builtin_amdgcn_readlane(j, 8 * i + 2 * pr + 1);
+                const uint32_t va = reinterpret_cast<const uint32_t *>(Vh + (int64_t)ja * D)[lane];
+                const uint32_t vb = reinterpret_cast<const uint32_t *>(Vh + (int64_t)jb * D)[lane];
+                lo[pr] = __builtin_amdgcn_perm(vb, va, 0x05040100u);  // (a.ch[2 lane],     b.ch[2 lane])
+                hi[pr] = __builtin_amdgcn_perm(vb, va, 0x07060302u);  // (a.ch[2 lane + 1], b.ch[2 lane + 1])
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const uint4 w = *reinterpret_cast<const uint4 *>(const_cast<const uint32_t *>(lds_all[wave]) + q * 16 + 4 * i);
+                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int pr = 0; pr < 4; ++pr) {
+                    const bf16x2_t wp = __builtin_bit_cast(bf16x2_t, ww[pr]);
+                    oacc[q][0] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, lo[pr]), wp, oacc[q][0], false);
+                    oacc[q][1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, hi[pr]), wp, oacc[q][1], false);
+                }
+            }
+        }
+        wave_sync();  // the next tile overwrites P_s
+    }
+    // normalise and write: query 4 * half + v lives in this half-wave's softmax state
+    float lt[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) lt[v] = half_sum(lsum[v]);
+    if (n == 0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int q = 4 * half + v;
+            fac_s[q] = 1.f / lt[v];
+            if (q < G) lse[(int64_t)bh * L + member_token(gm, g, q)] = (M[v] + log2f(lt[v])) * kLn2;
+        }
+    }
+    wave_sync();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        if (q < G) {
+            const float inv = fac_s[q];
+            const uint32_t packed = (uint32_t)f32_to_bf16(oacc[q][0] * inv) | ((uint32_t)f32_to_bf16(oacc[q][1] * inv) << 16);
+            reinterpret_cast<uint32_t *>(O + ((int64_t)bh * L + member_token(gm, g, q)) * D)[lane] = packed;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------ host
+GroupGeom make_group_geom(const dsv_grouping &gr)
+{
+    GroupGeom gm;
+    gm.F = gr.F; gm.Hh = gr.Hh; gm.Ww = gr.Ww;
+    gm.gf = gr.gf; gm.gh = gr.gh; gm.gw = gr.gw;
+    gm.nh = gr.Hh / gr.gh; gm.nw = gr.Ww / gr.gw;
+    gm.G = gr.gf * gr.gh * gr.gw;
+    return gm;
+}
+
+int group_centre(const dsv_grouping &gr) { return ((gr.gf / 2) * gr.gh + gr.gh / 2) * gr.gw + gr.gw / 2; }
+
+template <typename T, int MODE>
+static dsv_status group_rows_t(const dsv_problem &p, const GroupGeom &gm, int centre, const void *in, void *out, int n_out,
+                               hipStream_t st)
+{
+    const int64_t pieces = (int64_t)n_out * (p.d * (int)sizeof(T) / 16);
+    dim3 grid((unsigned)((pieces + 255) / 256), p.B * p.H);
+    hipLaunchKernelGGL((group_rows_kernel<T, MODE>), grid, dim3(256), 0, st, (const T *)in, (T *)out, p.L, p.d, n_out, gm, centre);
+    DSV_LAUNCH_CHECK();
+    return DSV_OK;
+}
+
+dsv_status launch_group_rows(const dsv_problem &p, const dsv_grouping &gr, int mode, const void *in, void *out,
+                             hipStream_t st)
+{
+    const GroupGeom gm = make_group_geom(gr);
+    const int centre = group_centre(gr);
+    const int n_out = mode == 0 ? p.L / gm.G : p.L;
+    if (p.dtype == DSV_BF16) {
+        if (mode == 0) return group_rows_t<bf16_t, 0>(p, gm, centre, in, out, n_out, st);
+        if (mode == 1) return group_rows_t<bf16_t, 1>(p, gm, centre, in, out, n_out, st);
+        return group_rows_t<bf16_t, 2>(p, gm, centre, in, out, n_out, st);
+    }
+    if (mode == 0) return group_rows_t<float, 0>(p, gm, centre, in, out, n_out, st);
+    if (mode == 1) return group_rows_t<float, 1>(p, gm, centre, in, out, n_out, st);
+    return group_rows_t<float, 2>(p, gm, centre, in, out, n_out, st);
+}
+
+dsv_status launch_group_scalar(const dsv_problem &p, const dsv_grouping &gr, const float *in, float *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(group_scalar_kernel, dim3((p.L + 255) / 256, p.B * p.H), dim3(256), 0, st, in, out, p.L,
+                       make_group_geom(gr));
+    DSV_LAUNCH_CHECK();
+    return DSV_OK;
+}
+
+dsv_status launch_group_expand(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
+                               const int32_t *idx_g, const int32_t *idx_t_g, const int64_t *col, int32_t *idx_x,
+                               int32_t *idx_t_x, int64_t *col_x, hipStream_t st)
+{
+    const GroupGeom gm = make_group_geom(gr);
+    const int Lq = p.L / gm.G;
+    for (int t = 0; t < n_tabs; ++t) {
+        hipLaunchKernelGGL(expand_idx_kernel, dim3(std::min(Lq, 8192), tabs[t].n), dim3(256), 0, st, idx_g, idx_x, Lq, gm.G, tabs[t]);
+        hipLaunchKernelGGL(expand_idx_t_kernel, dim3(8192, tabs[t].n), dim3(256), 0, st, idx_t_g, idx_t_x, Lq, gm.G, tabs[t]);
+        DSV_LAUNCH_CHECK();
+    }
+    const int64_t n = (int64_t)p.B * p.H * (p.L + 1);
+    hipLaunchKernelGGL(scale_col_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, col, col_x, n, gm.G);
+    DSV_LAUNCH_CHECK();
+    return DSV_OK;
+}
+
+dsv_status launch_grouped_fwd(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
+                              const void *Q, const void *K, const void *V, const int32_t *idx_g, void *O, float *lse,
+                              hipStream_t st)
+{
+    if (p.dtype != DSV_BF16 || p.d != 128) return DSV_EUNSUPPORTED;
+    const GroupGeom gm = make_group_geom(gr);
+    if (gm.G > 8) return DSV_EUNSUPPORTED;
+    const int Lq = p.L / gm.G;
+    KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
+    for (int t = 0; t < n_tabs; ++t) {
+        dim3 grid((Lq + 3) / 4, tabs[t].n);
+        hipLaunchKernelGGL((grouped_fwd_kernel<128>), grid, dim3(256), 0, st, (const bf16_t *)Q, (const bf16_t *)K,
+                           (const bf16_t *)V, idx_g, (bf16_t *)O, lse, p.L, Lq, p.scale, tabs[t], gm);
+        DSV_LAUNCH_CHECK();
+    }
+    return DSV_OK;
+}
+
+}  // namespace dsv

@@ -11,17 +11,20 @@
 // Scores are recomputed in every pass on the matrix cores (one 32x32 MFMA tile = 32 keys x 32
 // queries); the L x L matrix never exists in memory.  Every pass uses the same instruction
 // sequence for a score, so a score has the same bits in every pass.
+#include <algorithm>
+
 #include "stage1_core.h"
 
 namespace dsv {
 
 // ------------------------------------------------------------------------------------ projection
-// One block projects TOK token rows.  X tile and W are staged in LDS as fp32; each thread then
+// Q holds Lq rows per head and K holds Lk (equal for per-query selection; with query grouping only the
+// groups' centre queries are projected and scored).  One block projects TOK token rows.  X tile and W are staged in LDS as fp32; each thread then
 // forms a few outputs of one token with a plain ascending-c fp32 FMA chain.
 template <typename T, int D, int R>
 __global__ __launch_bounds__(256) void project_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                       const T *__restrict__ Wq, const T *__restrict__ Wk,
-                                                      T *__restrict__ Qlr, T *__restrict__ Klr, int L, int H)
+                                                      T *__restrict__ Qlr, T *__restrict__ Klr, int Lq, int Lk, int H)
 {
     constexpr int TOK = (D * R >= 128 * 64) ? 32 : 64;  // keeps the two tiles under 64 KB of LDS
     constexpr int TPT = 256 / TOK;                       // threads per token
@@ -30,6 +33,8 @@ __global__ __launch_bounds__(256) void project_kernel(const T *__restrict__ Q, c
     __shared__ float Ws[D][R];
     const int bh = blockIdx.y;
     const int h = bh % H;
+    const int L = blockIdx.z ? Lk : Lq;  // tokens on this side (the grid covers the longer side)
+    if ((int)blockIdx.x * TOK >= L) return;
     const T *X = (blockIdx.z ? K : Q) + (int64_t)bh * L * D;
     const T *W = (blockIdx.z ? Wk : Wq) + (int64_t)h * D * R;
     T *out = (blockIdx.z ? Klr : Qlr) + (int64_t)bh * L * R;
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(256) void project_kernel(const T *__restrict__ Q, c
 constexpr int kRadixWaves = DSV_RADIX_WAVES;  // waves per block; the 32 KB histogram allows 4 blocks per CU
 
 template <typename T, int R, int PASS>
-__global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
+__global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int Lq, int L,
                                                          HeadTable tab, uint32_t *__restrict__ prefix,
                                                          int32_t *__restrict__ krem)
 {
@@ -84,7 +89,7 @@ __global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_kernel(const T *_
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int q0 = blockIdx.x * 32;
-    const T *Qb = Qlr + (int64_t)bh * L * R;
+    const T *Qb = Qlr + (int64_t)bh * Lq * R;   // Lq query rows (all L tokens, or one proxy per query group)
     const T *Kb = Klr + (int64_t)bh * L * R;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, half = lane >> 5;
@@ -92,10 +97,10 @@ __global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_kernel(const T *_
     for (int e = threadIdx.x; e < 256 * 32; e += 64 * kRadixWaves) hist[e] = 0;
     __syncthreads();
 
-    const int qi = min(q0 + n, L - 1);
+    const int qi = min(q0 + n, Lq - 1);
     uint32_t pre = 0;
-    if constexpr (PASS > 0) pre = prefix[(int64_t)bh * padded_len(L) + qi];
-    const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
+    if constexpr (PASS > 0) pre = prefix[(int64_t)bh * padded_len(Lq) + qi];
+    const Frag<T, R> qf = load_frag<T, R>(Qb, q0, Lq, lane);
     const int ntiles = (L + 31) >> 5;
     const int nfull = L >> 5;  // tiles with all 32 keys in range
     uint32_t *hcol_mine = hist + n;  // counter of digit b: hcol_mine[32 * b]
@@ -173,8 +178,8 @@ __global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_kernel(const T *_
     }
     __syncthreads();
 
-    if (threadIdx.x < 32 && q0 + (int)threadIdx.x < L) {
-        const int64_t g = (int64_t)bh * padded_len(L) + q0 + threadIdx.x;
+    if (threadIdx.x < 32 && q0 + (int)threadIdx.x < Lq) {
+        const int64_t g = (int64_t)bh * padded_len(Lq) + q0 + threadIdx.x;
         const int kr = PASS == 0 ? tab.k[slot] : krem[g];
         const uint32_t *hcol = hist + threadIdx.x;
         int above = 0, digit = 0;
@@ -221,38 +226,38 @@ __global__ __launch_bounds__(64) void scores_rows_kernel(const T *__restrict__ Q
 
 // ------------------------------------------------------------------------------------ host
 template <typename T, int D, int R>
-static dsv_status project_t(const dsv_problem &p, const void *Q, const void *K, const void *Wq, const void *Wk,
+static dsv_status project_t(const dsv_problem &p, int Lq, const void *Q, const void *K, const void *Wq, const void *Wk,
                             void *Qlr, void *Klr, hipStream_t st)
 {
     constexpr int TOK = (D * R >= 128 * 64) ? 32 : 64;  // must match project_kernel
-    dim3 grid((p.L + TOK - 1) / TOK, p.B * p.H, 2);
+    dim3 grid((std::max(p.L, Lq) + TOK - 1) / TOK, p.B * p.H, 2);
     hipLaunchKernelGGL((project_kernel<T, D, R>), grid, dim3(256), 0, st, (const T *)Q, (const T *)K, (const T *)Wq,
-                       (const T *)Wk, (T *)Qlr, (T *)Klr, p.L, p.H);
+                       (const T *)Wk, (T *)Qlr, (T *)Klr, Lq, p.L, p.H);
     DSV_LAUNCH_CHECK();
     return DSV_OK;
 }
 
 template <typename T, int D>
-static dsv_status project_r(const dsv_problem &p, const void *Q, const void *K, const void *Wq, const void *Wk,
+static dsv_status project_r(const dsv_problem &p, int Lq, const void *Q, const void *K, const void *Wq, const void *Wk,
                             void *Qlr, void *Klr, hipStream_t st)
 {
     switch (p.r) {
-    case 16: return project_t<T, D, 16>(p, Q, K, Wq, Wk, Qlr, Klr, st);
-    case 32: return project_t<T, D, 32>(p, Q, K, Wq, Wk, Qlr, Klr, st);
-    case 64: return project_t<T, D, 64>(p, Q, K, Wq, Wk, Qlr, Klr, st);
+    case 16: return project_t<T, D, 16>(p, Lq, Q, K, Wq, Wk, Qlr, Klr, st);
+    case 32: return project_t<T, D, 32>(p, Lq, Q, K, Wq, Wk, Qlr, Klr, st);
+    case 64: return project_t<T, D, 64>(p, Lq, Q, K, Wq, Wk, Qlr, Klr, st);
     default: return DSV_EUNSUPPORTED;
     }
 }
 
-dsv_status launch_project(const dsv_problem &p, const void *Q, const void *K, const void *Wq, const void *Wk,
+dsv_status launch_project(const dsv_problem &p, int Lq, const void *Q, const void *K, const void *Wq, const void *Wk,
                           void *Qlr, void *Klr, hipStream_t st)
 {
     if (p.dtype == DSV_BF16) {
-        if (p.d == 64) return project_r<bf16_t, 64>(p, Q, K, Wq, Wk, Qlr, Klr, st);
-        if (p.d == 128) return project_r<bf16_t, 128>(p, Q, K, Wq, Wk, Qlr, Klr, st);
+        if (p.d == 64) return project_r<bf16_t, 64>(p, Lq, Q, K, Wq, Wk, Qlr, Klr, st);
+        if (p.d == 128) return project_r<bf16_t, 128>(p, Lq, Q, K, Wq, Wk, Qlr, Klr, st);
     } else if (p.dtype == DSV_F32) {
-        if (p.d == 64) return project_r<float, 64>(p, Q, K, Wq, Wk, Qlr, Klr, st);
-        if (p.d == 128) return project_r<float, 128>(p, Q, K, Wq, Wk, Qlr, Klr, st);
+        if (p.d == 64) return project_r<float, 64>(p, Lq, Q, K, Wq, Wk, Qlr, Klr, st);
+        if (p.d == 128) return project_r<float, 128>(p, Lq, Q, K, Wq, Wk, Qlr, Klr, st);
     }
     return DSV_EUNSUPPORTED;
 }
@@ -287,30 +292,30 @@ dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void 
 }
 
 template <typename T, int R>
-static dsv_status select_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
+static dsv_status select_t(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                            const SelectBuffers &b, hipStream_t st)
 {
     const T *Ql = (const T *)Qlr;
     const T *Kl = (const T *)Klr;
-    const int qtiles = (p.L + 31) / 32;
+    const int qtiles = (Lq + 31) / 32;
     {
         KernelSpan span(DSV_KERNEL_THRESHOLD, st);
         for (int t = 0; t < n_tabs; ++t) {
             dim3 grid(qtiles, tabs[t].n);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tabs[t], b.prefix, b.krem);
+            hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tabs[t], b.prefix, b.krem);
             DSV_LAUNCH_CHECK();
         }
     }
-    return launch_emit(p, tabs, n_tabs, Qlr, Klr, b, st);
+    return launch_emit(p, Lq, tabs, n_tabs, Qlr, Klr, b, st);
 }
 
-dsv_status launch_select(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
+dsv_status launch_select(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                          const SelectBuffers &b, hipStream_t st)
 {
-#define DSV_CASE(TT, RR) return select_t<TT, RR>(p, tabs, n_tabs, Qlr, Klr, b, st)
+#define DSV_CASE(TT, RR) return select_t<TT, RR>(p, Lq, tabs, n_tabs, Qlr, Klr, b, st)
     if (p.dtype == DSV_BF16) {
         if (p.r == 16) DSV_CASE(bf16_t, 16);
         if (p.r == 32) DSV_CASE(bf16_t, 32);

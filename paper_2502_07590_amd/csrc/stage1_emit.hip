@@ -107,7 +107,7 @@ __device__ __forceinline__ void expand_batch(EmitShared &sh, int tile0, int nfil
 // jcut (optional) and tile_flag (optional; 1 when all 32 queries of the tile take all their ties)
 // are what the key-major emission needs.
 template <typename T, int R>
-__global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
+__global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int Lq, int L,
                                                   HeadTable tab, uint32_t *__restrict__ prefix,
                                                   const int32_t *__restrict__ krem, int32_t *__restrict__ idx,
                                                   int32_t *__restrict__ jcut, int32_t *__restrict__ tile_flag)
@@ -116,20 +116,20 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
     const int q0 = blockIdx.x * 32;
-    const T *Qb = Qlr + (int64_t)bh * L * R;
+    const T *Qb = Qlr + (int64_t)bh * Lq * R;
     const T *Kb = Klr + (int64_t)bh * L * R;
     const int lane = threadIdx.x;
     const int n = lane & 31, half = lane >> 5;
-    const bool live = q0 + n < L;
-    const int qi = min(q0 + n, L - 1);
-    const int64_t g = (int64_t)bh * padded_len(L) + qi;
+    const bool live = q0 + n < Lq;
+    const int qi = min(q0 + n, Lq - 1);
+    const int64_t g = (int64_t)bh * padded_len(Lq) + qi;
     const float tau = key_score(prefix[g]);
     const int kr = krem[g];
     const int ties_wanted = kr < 0 ? -kr : kr;
     const bool all_simple = __all(kr < 0);
     int32_t *row = idx + tab.off[slot] + (int64_t)qi * k;
 
-    const Frag<T, R> qf = load_frag<T, R>(Qb, q0, L, lane);
+    const Frag<T, R> qf = load_frag<T, R>(Qb, q0, Lq, lane);
     __shared__ __align__(16) EmitShared sh;
     if (half == 0) sh.out[n] = OwnerOut{row, 0, live ? k : 0};
     int ties_taken = 0, last_tie = -1;
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(64) void emit_kernel(const T *__restrict__ Qlr, con
 // queries come from a chunk staged in LDS (state rows are padded to whole tiles).
 //   WRITE = false: list lengths -> cnt[bh, j];   WRITE = true: lists, starting at col[bh, j].
 template <typename T, int R, bool WRITE>
-__global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int L,
+__global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int Lq, int L,
                                                     HeadTable tab, const float *__restrict__ tau_f,
                                                     const int32_t *__restrict__ jcut,
                                                     const int32_t *__restrict__ tile_flag, int32_t *__restrict__ cnt,
@@ -189,11 +189,11 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int j0 = blockIdx.x * 32;
-    const T *Qb = Qlr + (int64_t)bh * L * R;
+    const T *Qb = Qlr + (int64_t)bh * Lq * R;
     const T *Kb = Klr + (int64_t)bh * L * R;
-    const float *tau_b = tau_f + (int64_t)bh * padded_len(L);
-    const int32_t *jcut_b = jcut + (int64_t)bh * padded_len(L);
-    const int ntiles = (L + 31) >> 5;
+    const float *tau_b = tau_f + (int64_t)bh * padded_len(Lq);
+    const int32_t *jcut_b = jcut + (int64_t)bh * padded_len(Lq);
+    const int ntiles = (Lq + 31) >> 5;  // query tiles: the axis this kernel walks
     const int32_t *flag_b = tile_flag + (int64_t)bh * ntiles;
     const int lane = threadIdx.x;
     const int n = lane & 31, half = lane >> 5;
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
     if (WRITE && half == 0) {
         // col comes from the counting pass over the same predicate, so the lists fill the head's block of
         // L * k entries exactly; the clamps (to [0, cap], b1 >= b0) only keep an inconsistent col from sending writes out of it
-        const int64_t cap = (int64_t)L * tab.k[slot];
+        const int64_t cap = (int64_t)Lq * tab.k[slot];
         const int64_t *cp = col + (int64_t)bh * (L + 1) + j;
         const int64_t b0 = cp[0] < 0 ? 0 : (cp[0] < cap ? cp[0] : cap);
         const int64_t b1 = cp[1] < b0 ? b0 : (cp[1] < cap ? cp[1] : cap);
@@ -218,9 +218,9 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
     // the address-path time of the tile's own fragment.)
     constexpr int kTauTiles = 8;
     __shared__ __align__(16) float tau_s[kTauTiles * 32];
-    const int npad = padded_len(L);
+    const int npad = padded_len(Lq);
     float4 tau_next = *reinterpret_cast<const float4 *>(tau_b + min(lane * 4, npad - 4));
-    Frag<T, R> qf_next = load_frag<T, R>(Qb, 0, L, lane);
+    Frag<T, R> qf_next = load_frag<T, R>(Qb, 0, Lq, lane);
     for (int qc = 0; qc < ntiles; qc += kTauTiles) {
         *reinterpret_cast<float4 *>(tau_s + lane * 4) = tau_next;
         tau_next = *reinterpret_cast<const float4 *>(tau_b + min((qc + kTauTiles) * 32 + lane * 4, npad - 4));
@@ -229,9 +229,9 @@ __global__ __launch_bounds__(64) void emit_t_kernel(const T *__restrict__ Qlr, c
             const int qt = qc + t;
             const int q0 = qt * 32;
             const Frag<T, R> qf = qf_next;
-            qf_next = load_frag<T, R>(Qb, q0 + 32, L, lane);
+            qf_next = load_frag<T, R>(Qb, q0 + 32, Lq, lane);
             const floatx16_t acc = score_tile<T, R>(qf, kf);
-            const uint32_t valid = (q0 + 32 <= L) ? 0xFFFFFFFFu : ((1u << (L - q0)) - 1u);
+            const uint32_t valid = (q0 + 32 <= Lq) ? 0xFFFFFFFFu : ((1u << (Lq - q0)) - 1u);
             // thresholds of this lane's 16 queries (tile rows 8g + 4*half + 0..3)
             float tq[16];
 #pragma unroll
@@ -296,18 +296,19 @@ __global__ __launch_bounds__(1024) void list_scan_kernel(const int32_t *__restri
 
 // ------------------------------------------------------------------------------------ host
 template <typename T, int R>
-static dsv_status emit_all_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr,
+static dsv_status emit_all_t(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr,
                              const void *Klr, const SelectBuffers &b, hipStream_t st)
 {
     const T *Ql = (const T *)Qlr;
     const T *Kl = (const T *)Klr;
-    const int tiles = (p.L + 31) / 32;
+    const int tiles = (p.L + 31) / 32;    // key tiles
+    const int qtiles = (Lq + 31) / 32;    // query (or query-group) tiles
     const float *tau_f = reinterpret_cast<const float *>(b.prefix);
     {
         KernelSpan span(DSV_KERNEL_EMIT, st);
         for (int t = 0; t < n_tabs; ++t) {
-            dim3 grid(tiles, tabs[t].n);
-            hipLaunchKernelGGL((emit_kernel<T, R>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], b.prefix, b.krem, b.idx,
+            dim3 grid(qtiles, tabs[t].n);
+            hipLaunchKernelGGL((emit_kernel<T, R>), grid, dim3(64), 0, st, Ql, Kl, Lq, p.L, tabs[t], b.prefix, b.krem, b.idx,
                                b.jcut, b.tile_flag);
             DSV_LAUNCH_CHECK();
         }
@@ -317,7 +318,7 @@ static dsv_status emit_all_t(const dsv_problem &p, const HeadTable *tabs, int n_
             KernelSpan span(DSV_KERNEL_EMIT_T_COUNT, st);
             for (int t = 0; t < n_tabs; ++t) {
                 dim3 grid(tiles, tabs[t].n);
-                hipLaunchKernelGGL((emit_t_kernel<T, R, false>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], tau_f,
+                hipLaunchKernelGGL((emit_t_kernel<T, R, false>), grid, dim3(64), 0, st, Ql, Kl, Lq, p.L, tabs[t], tau_f,
                                    b.jcut, b.tile_flag, b.cnt, (const int64_t *)nullptr, (int32_t *)nullptr);
                 DSV_LAUNCH_CHECK();
             }
@@ -327,7 +328,7 @@ static dsv_status emit_all_t(const dsv_problem &p, const HeadTable *tabs, int n_
         KernelSpan span(DSV_KERNEL_EMIT_T_WRITE, st);
         for (int t = 0; t < n_tabs; ++t) {
             dim3 grid(tiles, tabs[t].n);
-            hipLaunchKernelGGL((emit_t_kernel<T, R, true>), grid, dim3(64), 0, st, Ql, Kl, p.L, tabs[t], tau_f, b.jcut,
+            hipLaunchKernelGGL((emit_t_kernel<T, R, true>), grid, dim3(64), 0, st, Ql, Kl, Lq, p.L, tabs[t], tau_f, b.jcut,
                                b.tile_flag, (int32_t *)nullptr, b.col, b.idx_t);
             DSV_LAUNCH_CHECK();
         }
@@ -335,10 +336,10 @@ static dsv_status emit_all_t(const dsv_problem &p, const HeadTable *tabs, int n_
     return DSV_OK;
 }
 
-dsv_status launch_emit(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
+dsv_status launch_emit(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                        const SelectBuffers &b, hipStream_t st)
 {
-#define DSV_CASE(TT, RR) return emit_all_t<TT, RR>(p, tabs, n_tabs, Qlr, Klr, b, st)
+#define DSV_CASE(TT, RR) return emit_all_t<TT, RR>(p, Lq, tabs, n_tabs, Qlr, Klr, b, st)
     if (p.dtype == DSV_BF16) {
         if (p.r == 16) DSV_CASE(bf16_t, 16);
         if (p.r == 32) DSV_CASE(bf16_t, 32);
