@@ -54,6 +54,13 @@ def parse_args():
     ap.add_argument("--cpu-rows", type=int, default=0, help="query rows of the oracle sample (0 = auto)")
     ap.add_argument("--density-sweep", action="store_true",
                     help="also time the whole path at k/L = 0.5 .. 12.5 %% (same shape) and report the crossover with dense")
+    ap.add_argument("--dispatcher-table", action="store_true",
+                    help="instead of the benchmark line: the offline table a sparse/dense dispatcher consumes -- for L in "
+                         "{32k, 64k, 128k} and k/L from 0.5 to 12.5 %%, ms per stage, speedup over dense, and the bytes of "
+                         "index and workspace the sparse path needs")
+    ap.add_argument("--grouped", action="store_true",
+                    help="also time the query-grouped variant (2 x 2 x 2 cubes) at the same shape, and measure what the "
+                         "shared rows cost in accuracy on spatially smooth inputs")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the steps, run one plain elementwise copy kernel (x + 0 over this many MiB of int32) "
                          "so that a rocprofv3 --pmc run holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -141,6 +148,174 @@ class Path:
         return wall_ms, call_ms, kern_ms
 
 
+def path_memory(dsv, p):
+    """Bytes of device memory the sparse path needs beyond Q, K, V, O and the gradients, for problem p (sorted-index
+    flag as set in p): both index tensors, the column pointers, lse and Delta, and each call's workspace as the
+    library's own queries report it.  Stage 2's workspaces are never live together (one buffer of the largest size)."""
+    nbh = p.B * p.H
+    ws = {"lowrank_topk_t": dsv.lowrank_topk_t_workspace(p), "sparse_attn_fwd": dsv.sparse_attn_fwd_workspace(p),
+          "sparse_attn_bwd_dq": dsv.sparse_attn_bwd_dq_workspace(p), "sparse_attn_bwd_dkdv": dsv.sparse_attn_bwd_dkdv_workspace(p)}
+    fixed = {"idx": p.nnz * 4, "idx_t": p.nnz * 4, "col_ptr": nbh * (p.L + 1) * 8, "lse": nbh * p.L * 4, "delta": nbh * p.L * 4}
+    peak = sum(fixed.values()) + max(ws["lowrank_topk_t"], max(ws["sparse_attn_fwd"], ws["sparse_attn_bwd_dq"], ws["sparse_attn_bwd_dkdv"]))
+    return {"tensors": fixed, "workspace": ws, "peak_bytes": int(peak)}
+
+
+def dispatcher_table(dsv, torch, np, wl, args):
+    """Sec. "Two-Stage DiT Training" (stage 2): the dispatcher enables sparse attention for a block when the
+    measured speedup at the block's sparsity and token length pays and the index memory fits; this is that offline
+    measurement on this GPU."""
+    dev = torch.device("cuda:0")
+    import torch.nn.functional as F
+    rows = []
+    for ci in (1, 3, 2):                       # L = 32k (24 heads), 64k (24 heads), 128k (6 heads)
+        cfg = wl.get_config(ci)
+        g, Wq, Wk = upload_inputs(cfg, args.seed, dev, torch, wl)
+        q = g["Q"].clone().requires_grad_(True); k_ = g["K"].clone().requires_grad_(True); v = g["V"].clone().requires_grad_(True)
+        def dense():
+            o = F.scaled_dot_product_attention(q, k_, v, scale=cfg.scale)
+            o.backward(g["dO"])
+            q.grad = k_.grad = v.grad = None
+        dense_ms = _time_calls(torch, (dense,), 2, 2)[0]
+        del q, k_, v
+        torch.cuda.empty_cache()
+        for frac in (0.005, 0.01, 0.02, 0.03125, 0.0625, 0.10, 0.125):
+            kk = max(1, int(round(cfg.L * frac)))
+            pth = Path(dsv, torch, cfg, [kk] * cfg.H, g, Wq, Wk, sorted_index=True)
+            ms = _time_calls(torch, pth.calls(), 2, 1)
+            mem = path_memory(dsv, pth.p)
+            total = sum(ms)
+            rows.append({"L": cfg.L, "H": cfg.H, "r": cfg.r, "density": frac, "k": kk,
+                         "stage1_ms": round(ms[0], 2), "fwd_ms": round(ms[1], 2), "bwd_ms": round(ms[2] + ms[3], 2),
+                         "total_ms": round(total, 2), "dense_ms": round(dense_ms, 2),
+                         "speedup_over_dense": round(dense_ms / total, 3),
+                         "index_bytes": mem["tensors"]["idx"] + mem["tensors"]["idx_t"],
+                         "workspace_bytes": max(mem["workspace"].values()), "peak_extra_bytes": mem["peak_bytes"]})
+            print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+            del pth
+            torch.cuda.empty_cache()
+        del g, Wq, Wk
+        torch.cuda.empty_cache()
+    # crossover density per L: linear interpolation of total_ms between the swept densities around dense_ms
+    cross = {}
+    for L in sorted({r["L"] for r in rows}):
+        rr = sorted((r for r in rows if r["L"] == L), key=lambda r: r["density"])
+        cross[str(L)] = interpolate_crossover([(r["density"], r["total_ms"]) for r in rr], rr[0]["dense_ms"])
+    return {"table": rows, "crossover_density": cross,
+            "note": "sparse path = lowrank_topk_t + sparse_attn_fwd + sparse_attn_bwd_dq + sparse_attn_bwd_dkdv (sorted-index "
+                    "kernels), bf16, d = 128; dense = torch scaled_dot_product_attention fwd+bwd on the same GPU"}
+
+
+def interpolate_crossover(points, dense_ms):
+    """points: (density, ms) ascending in density.  Density at which the sparse path takes as long as dense
+    (linear between the two swept densities that bracket it); None if it never does inside the sweep."""
+    for (d0, m0), (d1, m1) in zip(points, points[1:]):
+        if m0 <= dense_ms < m1:
+            return round(d0 + (d1 - d0) * (dense_ms - m0) / (m1 - m0), 4)
+    return None
+
+
+def _time_calls(torch, calls, steps, warmup):
+    for _ in range(warmup):
+        for c in calls:
+            c()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(steps)]
+    for s in range(steps):
+        ev[s][0].record()
+        for i, c in enumerate(calls):
+            c()
+            ev[s][i + 1].record()
+    torch.cuda.synchronize()
+    return [sum(e[i].elapsed_time(e[i + 1]) for e in ev) / steps for i in range(len(calls))]
+
+
+def grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, steps, warmup, dense_ms, per_query_ms):
+    """The query-grouped variant at the same shape (2 x 2 x 2 cubes of the latent grid): one step =
+    dsv_lowrank_topk_grouped + dsv_sparse_attn_fwd_grouped + dsv_sparse_attn_bwd_grouped."""
+    cube = (2, 2, 2)
+    grp = dsv.Grouping(cfg.grid, cube)
+    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, [int(k) for k in ks], cfg.scale)
+    dev = g["Q"].device
+    n = p.nnz // grp.G
+    idx_g = torch.empty(n, dtype=torch.int32, device=dev)
+    idx_t_g = torch.empty(n, dtype=torch.int32, device=dev)
+    col = torch.empty((cfg.H, cfg.L + 1), dtype=torch.int64, device=dev)
+    O, dQ, dK, dV = (torch.empty_like(g["Q"]) for _ in range(4))
+    lse = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
+    ws1 = torch.empty(dsv.lowrank_topk_grouped_workspace(p, grp), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(dsv.sparse_attn_bwd_grouped_workspace(p, grp), dtype=torch.uint8, device=dev)
+    calls = (
+        lambda: dsv.lowrank_topk_grouped(p, grp, g["Q"], g["K"], Wq, Wk, idx_g=idx_g, idx_t_g=idx_t_g, col_ptr=col, workspace=ws1),
+        lambda: dsv.sparse_attn_fwd_grouped(p, grp, g["Q"], g["K"], g["V"], idx_g, O=O, lse=lse),
+        lambda: dsv.sparse_attn_bwd_grouped(p, grp, g["Q"], g["K"], g["V"], idx_g, idx_t_g, col, O, lse, g["dO"], dQ=dQ, dK=dK,
+                                            dV=dV, workspace=ws2),
+    )
+    ms = _time_calls(torch, calls, steps, warmup)
+    total = sum(ms)
+    nnz = p.nnz
+    out = {"cube": list(cube), "G": grp.G, "ms_per_step": round(total, 3),
+           "stage_ms": {"lowrank_topk_grouped": round(ms[0], 3), "sparse_attn_fwd_grouped": round(ms[1], 3),
+                        "sparse_attn_bwd_grouped": round(ms[2], 3)},
+           "speedup_over_dense": round(dense_ms / total, 3) if dense_ms else None,
+           "speedup_over_per_query_path": round(per_query_ms / total, 3),
+           "index_bytes": {"idx_g": int(n) * 4, "per_query_idx": int(nnz) * 4,
+                           "bwd_workspace": int(ws2.numel())},
+           # forward: each K / V row crosses the vector memory path once per GROUP
+           "fwd_gather_bytes_per_pair": round((2 * cfg.d * 2 + 4) / grp.G, 1),
+           "fwd_pairs_per_s": round(nnz / (ms[1] * 1e-3), 1)}
+    del ws1, ws2, idx_g, idx_t_g, col, O, dQ, dK, dV, lse
+    torch.cuda.empty_cache()
+    return out
+
+
+def grouping_accuracy(dsv, torch, np, wl, cfg, seed):
+    """What sharing the centre query's row costs, on spatially smooth inputs (neighbouring tokens alike, as in
+    video latents) and on the benchmark's i.i.d. inputs, at a reduced shape (one head, L = 32768, k = L/16):
+    mean fraction of a member's own top-k found in its group's row, and the relative RMS error of the sparse
+    outputs (per-query rows, shared rows) against dense attention."""
+    from workloads.configs import WorkloadConfig
+    grid, cube = (16, 32, 64), (2, 2, 2)
+    # predictor of rank r = basis rank: W = G^T (the basis Q and K are built on), which stands for a TRAINED
+    # predictor (Q W = Cq G G^T ~ (d/R) Cq, so Q_lr K_lr^T tracks Q K^T); the benchmark's random W selects
+    # keys that carry no particular softmax mass, and comparing outputs under it says nothing about grouping
+    c = WorkloadConfig(index=cfg.index, name="grouping_accuracy", B=1, H=1, grid=grid, d=cfg.d, r=cfg.basis_rank,
+                       k=None, k_choices=(), dtype="bf16", basis_rank=cfg.basis_rank, scale=cfg.scale)
+    L, k, G = c.L, c.L // 16, 8
+    F, H, W = grid
+    tok = np.arange(L).reshape(F // 2, 2, H // 2, 2, W // 2, 2).transpose(0, 2, 4, 1, 3, 5).reshape(-1, G)
+    group_of = np.empty(L, dtype=np.int64)
+    group_of[tok.reshape(-1)] = np.repeat(np.arange(L // G), G)
+    res = {}
+    for kind in ("smooth", "iid"):
+        t = wl.head_tensors_smooth(c, 0, seed=seed, sigma=5.0) if kind == "smooth" else wl.head_tensors(c, 0, seed=seed)
+        wq = wk = wl.round_to_dtype(wl.basis(c, seed).T, "bf16")
+        td = torch.bfloat16
+        dv = {n: torch.from_numpy(t[n]).cuda().to(td)[None, None].contiguous() for n in ("Q", "K", "V")}
+        Wq = torch.from_numpy(wq).cuda().to(td)[None].contiguous()
+        Wk = torch.from_numpy(wk).cuda().to(td)[None].contiguous()
+        p = dsv.Problem(1, 1, L, c.d, c.r, "bf16", [k], c.scale)
+        grp = dsv.Grouping(grid, cube)
+        idx_q = dsv.lowrank_topk(p, dv["Q"], dv["K"], Wq, Wk).view(L, k)
+        idx_g, _, _ = dsv.lowrank_topk_grouped(p, grp, dv["Q"], dv["K"], Wq, Wk, transposed=False)
+        idx_gx = idx_g.view(L // G, k)[torch.from_numpy(group_of).cuda()]                # [L, k]: the row each token uses
+        pos = torch.searchsorted(idx_gx, idx_q).clamp_(max=k - 1)
+        shared = (torch.gather(idx_gx, 1, pos) == idx_q).sum().item() / (L * k)
+        Oq, _ = dsv.sparse_attn_fwd(p, dv["Q"], dv["K"], dv["V"], idx_q.reshape(-1))
+        Og, _ = dsv.sparse_attn_fwd_grouped(p, grp, dv["Q"], dv["K"], dv["V"], idx_g)
+        Od = torch.nn.functional.scaled_dot_product_attention(dv["Q"], dv["K"], dv["V"], scale=c.scale)
+        torch.cuda.synchronize()
+        rms = lambda x: x.float().pow(2).mean().sqrt().item()
+        res[kind] = {"own_topk_found_in_group_row": round(shared, 4),
+                     "rel_rms_error_vs_dense": {"per_query": round(rms(Oq.float() - Od.float()) / rms(Od), 4),
+                                                "grouped": round(rms(Og.float() - Od.float()) / rms(Od), 4)}}
+        del Od
+        del dv, idx_q, idx_g, idx_gx, pos, Oq, Og
+        torch.cuda.empty_cache()
+    res["shape"] = {"L": L, "k": k, "grid": list(grid), "cube": list(cube), "predictor": f"W = basis^T, rank {c.r}",
+                    "smoothing_sigma": 5.0}
+    return res
+
+
 def cpu_baseline(cfg, ks, seed, n_rows, wl, np):
     """Time the CPU oracle (as it stands) on n_rows query rows of head 0 through the whole path and
     scale to the full problem: per-head time = t(project all keys) + (L / n_rows) * t(rows)."""
@@ -189,6 +364,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
+    if args.dispatcher_table:
+        print(json.dumps(dispatcher_table(dsv, torch, np, wl, args)))
+        return
     cfg = wl.get_config(args.config)
     ks = wl.k_per_head(cfg, seed=args.seed)
     esize = 2 if cfg.dtype == "bf16" else 4
@@ -303,8 +481,17 @@ def main():
             torch.cuda.empty_cache()
         out["density_sweep"] = sweep
         if dense_ms:
-            below = [s for s in sweep if s["ms_per_step"] <= dense_ms]
-            out["crossover_density"] = max(s["density"] for s in below) if below else None
+            out["crossover_density"] = interpolate_crossover([(s_["density"], s_["ms_per_step"]) for s_ in sweep], dense_ms)
+
+    # ---- query-grouped variant (the paper's answer to the per-query gather cost) --------------------
+    if args.grouped:
+        try:
+            del path
+        except NameError:
+            pass
+        torch.cuda.empty_cache()
+        out["grouped"] = grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, max(args.steps, 2), 1, dense_ms, ms_per_step)
+        out["grouped"]["accuracy"] = grouping_accuracy(dsv, torch, np, wl, cfg, args.seed)
 
     # ---- CPU oracle timed on a bounded sample ------------------------------------------------------
     if not args.no_cpu_baseline:
