@@ -27,18 +27,31 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9   # 256 CUs x 64 fp32 lanes x 2.4 GHz, one (unpacked) VALU op per lane per clock
 
-# L2 -> fabric traffic of the stage-2 kernels at config 2, bytes per launch, from two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE, in KiB), each scaled by what the same counter reads for a plain 1 GiB
-# elementwise copy in the same run (FETCH_SIZE reads 0.5 GiB for it: factor 2.0; WRITE_SIZE reads
-# 1 GiB: factor 1.0).  See profiles/stage2_config2_pmc_traffic.md.
-PMC_TRAFFIC_CONFIG2 = {
-    "sparse_attn_fwd": int((31044477 * 2.0 + 14155840 * 1.0) * 1024),
-    "sparse_attn_bwd_dq": int((48443068 * 2.0 + 12976310 * 1.0) * 1024),
-    "sparse_attn_bwd_dkdv": int((34221672 * 2.0 + 12582937 * 1.0) * 1024),
+# HBM traffic of the stage-2 sweeps at config 2, bytes per launch, from two rocprofv3 --pmc runs (FETCH_SIZE,
+# WRITE_SIZE, in KiB), each scaled by what the same counter reads for a plain 1 GiB elementwise copy in the same run
+# (FETCH_SIZE reads 0.5 GiB for it: factor 2.0; WRITE_SIZE reads 1 GiB: factor 1.0), and the L2 hit rate from
+# TCC_HIT_sum / (TCC_HIT_sum + TCC_MISS_sum).  Source: profiles/config2_pmc_counters.md.  The figures belong to ONE
+# build of the kernels: they are reported only while the library still names that version.
+PMC_LIBRARY_VERSION = "dsv 0.3 (gfx950)"
+PMC_CONFIG2 = {
+    "sparse_attn_fwd": {"fetch_kib": 30948725, "write_kib": 14155842, "l2_hit_rate": 0.9692},
+    "sparse_attn_bwd_dq": {"fetch_kib": 48268455, "write_kib": 12976309, "l2_hit_rate": 0.9644},
+    "sparse_attn_bwd_dkdv": {"fetch_kib": 34165752, "write_kib": 12582935, "l2_hit_rate": 0.9758},
 }
 # the gather sweep inside each stage-2 call (the kernel the roofline object is about)
 SWEEP_OF_CALL = {"sparse_attn_fwd": "fwd_sweep", "sparse_attn_bwd_dq": "dq_sweep", "sparse_attn_bwd_dkdv": "dkdv_sweep"}
-L1_PEAK_GBS = 256 * 64 * 2.4          # 256 CUs x 64 B per clock (vector L1 -> registers) x 2.4 GHz
+# Vector memory path (L2 -> vector L1 -> registers): 64 bytes per clock per CU, 256 CUs, 2.4 GHz.  The sweeps'
+# gathers are served by it (L2 hit rate 96-98 %); it is what bounds them.
+L1_PEAK_GBS = 256 * 64 * 2.4
+# What a kernel that ONLY gathers (same lane layout, index staging and block order, no arithmetic) reaches on this
+# path: bench.py --gather-ceiling, summary in profiles/gather_ceiling.md (index streamed from memory, 4 MB ranges).
+GATHER_CEILING_GBS = {"sparse_attn_fwd": 34241.5, "sparse_attn_bwd_dq": 33888.4, "sparse_attn_bwd_dkdv": 33888.4}
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def pmc_traffic_bytes(call):
+    c = PMC_CONFIG2[call]
+    return int((c["fetch_kib"] * 2.0 + c["write_kib"] * 1.0) * 1024)
 
 
 def parse_args():
@@ -54,6 +67,9 @@ def parse_args():
     ap.add_argument("--cpu-rows", type=int, default=0, help="query rows of the oracle sample (0 = auto)")
     ap.add_argument("--density-sweep", action="store_true",
                     help="also time the whole path at k/L = 0.5 .. 12.5 %% (same shape) and report the crossover with dense")
+    ap.add_argument("--gather-ceiling", action="store_true",
+                    help="instead of the benchmark line: run the library's pure-gather probe (dsv_measure_gather_ceiling) and print "
+                         "the rate the vector memory path sustains for the stage-2 access pattern")
     ap.add_argument("--dispatcher-table", action="store_true",
                     help="instead of the benchmark line: the offline table a sparse/dense dispatcher consumes -- for L in "
                          "{32k, 64k, 128k} and k/L from 0.5 to 12.5 %%, ms per stage, speedup over dense, and the bytes of "
@@ -203,6 +219,35 @@ def dispatcher_table(dsv, torch, np, wl, args):
     return {"table": rows, "crossover_density": cross,
             "note": "sparse path = lowrank_topk_t + sparse_attn_fwd + sparse_attn_bwd_dq + sparse_attn_bwd_dkdv (sorted-index "
                     "kernels), bf16, d = 128; dense = torch scaled_dot_product_attention fwd+bwd on the same GPU"}
+
+
+def gather_ceiling(dsv, torch):
+    """Rates of the pure-gather probe for the two range sizes the sweeps use (2 MB of K+V rows: forward; 4 MB:
+    backward), with the index streamed from memory (one index row per query, as in the real sweeps) and with a
+    cached index (64 shared rows).  Same selected fraction as config 2 (1/16 of a range's rows per query)."""
+    dev = torch.device("cuda:0")
+    L, nq = 131072, 32768
+    K = torch.randn((L, 128), device=dev).to(torch.bfloat16)
+    V = torch.randn((L, 128), device=dev).to(torch.bfloat16)
+    res = []
+    for range_rows in (4096, 8192):
+        n_ranges, k = L // range_rows, range_rows // 16
+        step = range_rows // k
+        for idx_rows in (nq, 64):
+            g = torch.Generator(device=dev).manual_seed(0)
+            idx = (torch.arange(k, device=dev, dtype=torch.int32)[None, None, :] * step +
+                   torch.randint(0, step, (n_ranges, idx_rows, k), device=dev, dtype=torch.int32, generator=g)).contiguous()
+            out = torch.empty((n_ranges, nq), dtype=torch.int32, device=dev)
+            ms = dsv.measure_gather_ceiling(n_ranges, range_rows, nq, k, idx_rows, K, V, idx, out, reps=5)
+            nbytes = n_ranges * nq * k * 512
+            res.append({"range_bytes": range_rows * 512, "index": "streamed" if idx_rows == nq else "cached (64 rows)",
+                        "ms": round(ms, 3), "gathered_bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                        "bytes_per_clk_per_cu": round(nbytes / (ms * 1e-3) / (256 * 2.4e9), 2),
+                        "frac_of_path_peak": round(nbytes / (ms * 1e-3) / 1e9 / L1_PEAK_GBS, 4)})
+            del idx, out
+    return {"probe": "dsv_measure_gather_ceiling: 4 lanes per row, 4 keys per step, K row + V row (2 x 256 B) per index entry, "
+                     "no arithmetic; L = 131072 rows, 32768 queries per range",
+            "path_peak_GBps": round(L1_PEAK_GBS, 1), "results": res}
 
 
 def interpolate_crossover(points, dense_ms):
@@ -367,6 +412,9 @@ def main():
     if args.dispatcher_table:
         print(json.dumps(dispatcher_table(dsv, torch, np, wl, args)))
         return
+    if args.gather_ceiling:
+        print(json.dumps(gather_ceiling(dsv, torch)))
+        return
     cfg = wl.get_config(args.config)
     ks = wl.k_per_head(cfg, seed=args.seed)
     esize = 2 if cfg.dtype == "bf16" else 4
@@ -394,31 +442,43 @@ def main():
     # (forward, dq); one Q row + one dO row + the index + lse_i + Delta_i (dkdv)
     pair_bytes = {"sparse_attn_fwd": 2 * cfg.d * esize + 4, "sparse_attn_bwd_dq": 2 * cfg.d * esize + 4,
                   "sparse_attn_bwd_dkdv": 2 * cfg.d * esize + 12}
+    pmc_ok = args.config == 2 and not args.unsorted and dsv.version() == PMC_LIBRARY_VERSION
     stage2 = {}
     for n, pb in pair_bytes.items():
         k_ms = kern_ms[SWEEP_OF_CALL[n]]          # the sweep kernel alone, by HIP events on its own stream
         gbs = pb * nnz / (k_ms * 1e-3) / 1e9
-        stage2[n] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4),
-                     "traffic": PMC_TRAFFIC_CONFIG2.get(n) if (args.config == 2 and not args.unsorted) else None,
+        traffic = pmc_traffic_bytes(n) if pmc_ok else None
+        stage2[n] = {"bound": "l1", "bound_name": "vector memory path, L2 -> vector L1 -> registers (64 B/clk/CU x 256 CUs x 2.4 GHz)",
+                     "achieved": round(gbs, 1), "peak": round(L1_PEAK_GBS, 1), "unit": "GB/s", "frac": round(gbs / L1_PEAK_GBS, 4),
+                     "traffic": traffic,
                      "algorithmic_bytes_per_launch": pb * nnz, "kernel": SWEEP_OF_CALL[n] + " kernel of " + n,
                      "kernel_ms": round(k_ms, 3), "call_ms": round(call_ms[n], 3),
-                     # the requested bytes are served by L2 and the vector L1, not by HBM (see traffic): the
-                     # path that bounds the kernel is L1 -> registers, 64 B per clock per CU
-                     "l1_path": {"peak": round(L1_PEAK_GBS, 1), "unit": "GB/s", "frac": round(gbs / L1_PEAK_GBS, 4)},
-                     "note": "achieved counts the bytes the gathers request; they are served from L2 (compare "
-                             "traffic, the bytes that crossed the fabric), so frac against the HBM peak exceeds 1; "
-                             "l1_path is the same rate against the L2 -> L1 -> register path that bounds the kernel"}
+                     # the same launch against HBM: the bytes that really crossed the fabric (traffic) per second
+                     "hbm": {"achieved": round(traffic / (k_ms * 1e-3) / 1e9, 1) if traffic else None, "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": round(traffic / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
+                             "l2_hit_rate": PMC_CONFIG2[n]["l2_hit_rate"] if pmc_ok else None},
+                     "gather_only_ceiling": {"achieved_by_pure_gather_kernel": GATHER_CEILING_GBS[n], "unit": "GB/s",
+                                             "frac_of_it": round(gbs / GATHER_CEILING_GBS[n], 4)},
+                     "note": "achieved = algorithmic gather bytes (K row + V row + index entry per pair) / kernel time; the ranges "
+                             "of the split-K plan stay in each XCD's L2, so the bytes cross the L2 -> L1 path, not HBM"}
     dominant = max(pair_bytes, key=lambda n: kern_ms[SWEEP_OF_CALL[n]])
     roofline = dict(stage2[dominant])
-    # stage 1 is selection work on plain VALU lanes: per score at least one subtract/compare and one
-    # mask update in each of its passes (4 threshold passes + emit + 2 key-major passes = 7)
-    s1_lane_ops = 2.0 * 7 * n_scores
-    s1 = {"bound": "alu", "achieved": round(s1_lane_ops / (call_ms["lowrank_topk_t"] * 1e-3) / 1e12, 3),
+    # Stage 1 is selection work on the plain vector ALUs.  Algorithmic work: per score one compare against the
+    # threshold and one update of the selection state = 2 lane-ops per score, ONCE; the implementation recomputes
+    # every score in 7 sweeps (4 threshold passes, emission, 2 key-major passes), reported separately.
+    s1_ms = call_ms["lowrank_topk_t"]
+    s1_lane_ops = 2.0 * n_scores
+    s1 = {"bound": "alu", "achieved": round(s1_lane_ops / (s1_ms * 1e-3) / 1e12, 3),
           "peak": round(VALU_LANE_OPS_PER_S / 1e12, 2), "unit": "T lane-ops/s",
-          "frac": round(s1_lane_ops / (call_ms["lowrank_topk_t"] * 1e-3) / VALU_LANE_OPS_PER_S, 4),
-          "algorithmic_lane_ops_per_launch": s1_lane_ops, "launch_ms": round(call_ms["lowrank_topk_t"], 3),
-          "mfma_tflops": round(2.0 * cfg.r * n_scores * 7 / (call_ms["lowrank_topk_t"] * 1e-3) / 1e12, 2)}
+          "frac": round(s1_lane_ops / (s1_ms * 1e-3) / VALU_LANE_OPS_PER_S, 4),
+          "algorithmic_lane_ops_per_launch": s1_lane_ops, "launch_ms": round(s1_ms, 3),
+          "frac_counting_all_seven_sweeps": round(7 * s1_lane_ops / (s1_ms * 1e-3) / VALU_LANE_OPS_PER_S, 4),
+          "mfma": {"achieved": round(2.0 * cfg.r * n_scores / (s1_ms * 1e-3) / 1e12, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                   "unit": "TFLOP/s", "frac": round(2.0 * cfg.r * n_scores / (s1_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                   "achieved_counting_recomputation": round(7 * 2.0 * cfg.r * n_scores / (s1_ms * 1e-3) / 1e12, 2)},
+          "note": "the score contraction has K = r: 2r flops per score against >= 2 vector-ALU lane-ops per score for the "
+                  "selection, so the vector ALUs bound the stage, not the matrix cores (VALU issue 95-98 % busy in the "
+                  "threshold and counting sweeps: profiles/config2_pmc_counters.md)"}
 
     out = {
         "metric": "sparse attention fwd+bwd (stage 1 + stage 2) effective TFLOP/s at L=128k" if args.config == 2

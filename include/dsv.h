@@ -300,6 +300,20 @@ typedef enum {
 DSV_API dsv_status dsv_kernel_timing(int32_t enable);
 DSV_API dsv_status dsv_kernel_ms(int32_t span, float *ms);
 
+/* Pure-gather probe: the practical ceiling of the vector memory path (L2 -> vector L1 -> registers) for the
+ * stage-2 access pattern, against which the sweeps' achieved gather rate is reported.  K, V: DEVICE bf16
+ * [n_ranges * range_rows, 128]; idx: DEVICE int32 [n_ranges, idx_rows, k], every row an ascending list of row
+ * numbers inside one range (0 .. range_rows - 1); nq query rows per range use index row (q mod idx_rows), so
+ * idx_rows = nq streams the index from memory as the real sweeps do and a small idx_rows keeps it cached.
+ * Every query gathers, per index entry, one K row and one V row of the range (2 x 256 bytes) with the forward
+ * sweep's lane layout, index staging and XCD-aware block order, and does no arithmetic on them.
+ * out: DEVICE uint32 [n_ranges, nq].  Runs the kernel once untimed, then `reps` times, and writes the mean
+ * milliseconds per launch to *ms (HOST); waits for the stream.  k must be a multiple of 4.
+ * Gathered bytes per launch = n_ranges * nq * k * 512. */
+DSV_API dsv_status dsv_measure_gather_ceiling(int32_t n_ranges, int32_t range_rows, int32_t nq, int32_t k,
+                                              int32_t idx_rows, const void *K, const void *V, const int32_t *idx,
+                                              void *out, int32_t reps, float *ms, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

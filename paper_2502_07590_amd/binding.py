@@ -32,7 +32,7 @@ EXPORTED_SYMBOLS = (
     "dsv_sparse_attn_bwd_grouped_workspace", "dsv_sparse_attn_bwd_grouped",
     "dsv_lowrank_topk_noalloc_max_bytes", "dsv_lowrank_topk_noalloc",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
-    "dsv_kernel_timing", "dsv_kernel_ms",
+    "dsv_kernel_timing", "dsv_kernel_ms", "dsv_measure_gather_ceiling",
 )
 
 
@@ -136,6 +136,8 @@ def load_library():
     lib.dsv_kernel_timing.argtypes = [i32]
     lib.dsv_kernel_ms.restype = ctypes.c_int
     lib.dsv_kernel_ms.argtypes = [i32, ctypes.POINTER(ctypes.c_float)]
+    lib.dsv_measure_gather_ceiling.restype = ctypes.c_int
+    lib.dsv_measure_gather_ceiling.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, i32, ctypes.POINTER(ctypes.c_float), vp]
     _lib = lib
     return lib
 
@@ -432,4 +434,14 @@ def kernel_timing(enable: bool):
 def kernel_ms(span: str) -> float:
     ms = ctypes.c_float(0.0)
     _check(load_library().dsv_kernel_ms(KERNEL_SPANS.index(span), ctypes.byref(ms)), "dsv_kernel_ms")
+    return float(ms.value)
+
+
+def measure_gather_ceiling(n_ranges: int, range_rows: int, nq: int, k: int, idx_rows: int, K, V, idx, out, reps: int = 3,
+                           stream=None) -> float:
+    """Mean ms per launch of the pure-gather probe (see dsv_measure_gather_ceiling)."""
+    ms = ctypes.c_float(0.0)
+    _check(load_library().dsv_measure_gather_ceiling(n_ranges, range_rows, nq, k, idx_rows, _ptr(K), _ptr(V), _ptr(idx),
+                                                     _ptr(out), reps, ctypes.byref(ms), _stream(stream)),
+           "dsv_measure_gather_ceiling")
     return float(ms.value)
