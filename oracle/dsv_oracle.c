@@ -463,6 +463,116 @@ void dsv_oracle_sparse_bwd_grouped(const float *Q, const float *K, const float *
     free(idx); free(O); free(lse);
 }
 
+/* ---------------------------------------------------------------------------------------------
+ * Predictor side (Sec. "Low-Rank based Sparsity Prediction", Sec. "Sparsity Profiling").
+ *
+ * Approximation loss of one head on a sample of n query rows (the paper samples queries at random to
+ * bound the cost): with A = Q_s K^T [n, L] and Ahat = (Q_s Wq)(K Wk)^T [n, L],
+ *     loss = 0.95 * CosLoss(Ahat, A) + 0.05 * NormLoss(Ahat, A).
+ * Readings (the paper names the two terms and their weights only):
+ *   CosLoss  = mean over the sampled queries of 1 - cos(ahat_i, a_i), the cosine between a query's
+ *              approximate and true score ROWS (what ranks that query's keys);
+ *   NormLoss = mean over all n * L entries of (ahat_ij - a_ij)^2;
+ *   scores carry no softmax scale; projections are NOT rounded to the storage type here (the loss
+ *   trains Wq, Wk in full precision; rounding belongs to the selection path).
+ * Gradients of the loss with respect to Wq and Wk, by the chain rule written out:
+ *     dAhat_ij = 0.95/n * ( -a_ij / (|ahat_i||a_i|) + <ahat_i, a_i> ahat_ij / (|ahat_i|^3 |a_i|) )
+ *              + 0.05 * 2/(n L) * (ahat_ij - a_ij)
+ *     dQlr = dAhat Klr,  dKlr = dAhat^T Qlr,  dWq = Q_s^T dQlr,  dWk = K^T dKlr.
+ * Q_s [n, d], K [L, d], Wq, Wk [d, r].  Outputs: loss_parts[3] = {loss, CosLoss, NormLoss}, dWq, dWk [d, r].
+ * ------------------------------------------------------------------------------------------- */
+void dsv_oracle_predictor_loss(const float *Qs, const float *K, const float *Wq, const float *Wk, int64_t n,
+                               int64_t L, int d, int r, double *loss_parts, double *dWq, double *dWk)
+{
+    double *Qlr = (double *)calloc((size_t)n * r, sizeof(double)), *Klr = (double *)calloc((size_t)L * r, sizeof(double));
+    double *A = (double *)malloc((size_t)n * L * sizeof(double)), *Ah = (double *)malloc((size_t)n * L * sizeof(double));
+    double *dA = (double *)malloc((size_t)n * L * sizeof(double));
+    for (int64_t i = 0; i < n; ++i)
+        for (int t = 0; t < r; ++t)
+            for (int c = 0; c < d; ++c) Qlr[i * r + t] += (double)Qs[i * d + c] * (double)Wq[(int64_t)c * r + t];
+    for (int64_t j = 0; j < L; ++j)
+        for (int t = 0; t < r; ++t)
+            for (int c = 0; c < d; ++c) Klr[j * r + t] += (double)K[j * d + c] * (double)Wk[(int64_t)c * r + t];
+    double cos_loss = 0.0, norm_loss = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : cos_loss, norm_loss)
+    for (int64_t i = 0; i < n; ++i) {
+        double aa = 0.0, hh = 0.0, ah = 0.0, sq = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            double a = 0.0, h = 0.0;
+            for (int c = 0; c < d; ++c) a += (double)Qs[i * d + c] * (double)K[j * d + c];
+            for (int t = 0; t < r; ++t) h += Qlr[i * r + t] * Klr[j * r + t];
+            A[i * L + j] = a; Ah[i * L + j] = h;
+            aa += a * a; hh += h * h; ah += a * h; sq += (h - a) * (h - a);
+        }
+        const double na = sqrt(aa), nh = sqrt(hh);
+        cos_loss += (1.0 - ah / (na * nh)) / (double)n;
+        norm_loss += sq / ((double)n * (double)L);
+        for (int64_t j = 0; j < L; ++j)
+            dA[i * L + j] = 0.95 / (double)n * (-A[i * L + j] / (nh * na) + ah * Ah[i * L + j] / (nh * nh * nh * na)) +
+                            0.05 * 2.0 / ((double)n * (double)L) * (Ah[i * L + j] - A[i * L + j]);
+    }
+    loss_parts[0] = 0.95 * cos_loss + 0.05 * norm_loss;
+    loss_parts[1] = cos_loss;
+    loss_parts[2] = norm_loss;
+    double *dQlr = (double *)calloc((size_t)n * r, sizeof(double)), *dKlr = (double *)calloc((size_t)L * r, sizeof(double));
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t j = 0; j < L; ++j)
+            for (int t = 0; t < r; ++t) {
+                dQlr[i * r + t] += dA[i * L + j] * Klr[j * r + t];
+                dKlr[j * r + t] += dA[i * L + j] * Qlr[i * r + t];
+            }
+    for (int64_t e = 0; e < (int64_t)d * r; ++e) { dWq[e] = 0.0; dWk[e] = 0.0; }
+    for (int64_t i = 0; i < n; ++i)
+        for (int c = 0; c < d; ++c)
+            for (int t = 0; t < r; ++t) dWq[(int64_t)c * r + t] += (double)Qs[i * d + c] * dQlr[i * r + t];
+    for (int64_t j = 0; j < L; ++j)
+        for (int c = 0; c < d; ++c)
+            for (int t = 0; t < r; ++t) dWk[(int64_t)c * r + t] += (double)K[j * d + c] * dKlr[j * r + t];
+    free(Qlr); free(Klr); free(A); free(Ah); free(dA); free(dQlr); free(dKlr);
+}
+
+/* Sparsity of one head measured on a sample of n query rows (Sec. "Exploiting Dynamic Sparsity": a
+ * query's critical KV are the highest-probability keys that together hold `mass` (the paper: 90 %) of
+ * its softmax; the head's sparsity is the mean fraction of NON-critical keys; Sec. "Sparsity Profiling":
+ * measured on sampled queries).  For every sampled row: p = softmax(scale * q K^T) over all L keys, sorted
+ * in descending order, c_i = the smallest count whose cumulative probability reaches `mass`.
+ * Outputs: counts [n] (c_i), and the return value mean_i (1 - c_i / L). */
+static int cmp_double_desc(const void *a, const void *b)
+{
+    const double x = *(const double *)a, y = *(const double *)b;
+    return (x < y) - (x > y);
+}
+
+double dsv_oracle_profile_sparsity(const float *Qs, const float *K, int64_t n, int64_t L, int d, double scale,
+                                   double mass, int64_t *counts)
+{
+    double total = 0.0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : total)
+    for (int64_t i = 0; i < n; ++i) {
+        double *p = (double *)malloc((size_t)L * sizeof(double));
+        double m = -INFINITY, z = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += (double)Qs[i * d + c] * (double)K[j * d + c];
+            p[j] = scale * acc;
+            if (p[j] > m) m = p[j];
+        }
+        for (int64_t j = 0; j < L; ++j) z += exp(p[j] - m);
+        for (int64_t j = 0; j < L; ++j) p[j] = exp(p[j] - m) / z;
+        qsort(p, (size_t)L, sizeof(double), cmp_double_desc);
+        double cum = 0.0;
+        int64_t c = 0;
+        while (c < L && cum < mass) cum += p[c++];
+        counts[i] = c;
+        total += 1.0 - (double)c / (double)L;
+        free(p);
+    }
+    return total / (double)n;
+}
+
+/* Exponential moving average the profiler keeps per head and block: S_i = alpha P_i + (1 - alpha) S_{i-1}. */
+double dsv_oracle_ema(double prev, double sample, double alpha) { return alpha * sample + (1.0 - alpha) * prev; }
+
 int dsv_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -21,7 +21,8 @@ DTYPES = {"f32": 0, "bf16": 1}
 __all__ = ["build", "lib", "round_value", "project", "scores", "topk_from_scores", "lowrank_topk",
            "sparse_fwd", "sparse_bwd", "sparse_bwd_rows", "sparse_bwd_dq_rows", "sparse_bwd_dkdv_key",
            "dense_fwd", "dense_bwd", "max_threads", "DTYPES", "group_member", "group_centre", "group_tokens",
-           "lowrank_topk_grouped", "group_expand_idx", "sparse_fwd_grouped", "sparse_bwd_grouped"]
+           "lowrank_topk_grouped", "group_expand_idx", "sparse_fwd_grouped", "sparse_bwd_grouped",
+           "predictor_loss", "profile_sparsity", "ema"]
 
 
 def build(force: bool = False) -> str:
@@ -272,3 +273,35 @@ def sparse_bwd_grouped(Q, K, V, idx_g, dO, grid, cube, scale: float):
     lib().dsv_oracle_sparse_bwd_grouped(_p(Q), _p(K), _p(V), _p(idx_g), _p(dO), *[_int(x) for x in grid],
                                         *[_int(x) for x in cube], _int(d), _i64(k), _dbl(scale), _p(dQ), _p(dK), _p(dV))
     return dQ, dK, dV
+
+
+# ---- predictor side ---------------------------------------------------------------------------
+def predictor_loss(Q_rows, K, Wq, Wk):
+    """0.95 CosLoss + 0.05 NormLoss of the low-rank scores of the given query rows against the true ones, and its
+    gradients: ((loss, cos, norm), dWq [d, r], dWk [d, r])."""
+    Q_rows, K, Wq, Wk = _f32(Q_rows), _f32(K), _f32(Wq), _f32(Wk)
+    n, d = Q_rows.shape
+    L = K.shape[0]
+    r = Wq.shape[1]
+    parts = np.empty(3); dWq = np.empty((d, r)); dWk = np.empty((d, r))
+    lib().dsv_oracle_predictor_loss(_p(Q_rows), _p(K), _p(Wq), _p(Wk), _i64(n), _i64(L), _int(d), _int(r), _p(parts),
+                                    _p(dWq), _p(dWk))
+    return tuple(float(x) for x in parts), dWq, dWk
+
+
+def profile_sparsity(Q_rows, K, scale: float, mass: float = 0.9):
+    """(head sparsity on the sampled rows, counts [n] of critical keys per row)."""
+    Q_rows, K = _f32(Q_rows), _f32(K)
+    n, d = Q_rows.shape
+    L = K.shape[0]
+    counts = np.empty(n, dtype=np.int64)
+    L_ = lib()
+    L_.dsv_oracle_profile_sparsity.restype = ctypes.c_double
+    s = L_.dsv_oracle_profile_sparsity(_p(Q_rows), _p(K), _i64(n), _i64(L), _int(d), _dbl(scale), _dbl(mass), _p(counts))
+    return float(s), counts
+
+
+def ema(prev: float, sample: float, alpha: float) -> float:
+    L_ = lib()
+    L_.dsv_oracle_ema.restype = ctypes.c_double
+    return float(L_.dsv_oracle_ema(_dbl(prev), _dbl(sample), _dbl(alpha)))
