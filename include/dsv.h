@@ -232,6 +232,24 @@ DSV_API dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_g
                                                void *dQ, void *dK, void *dV, void *workspace, size_t ws_bytes,
                                                void *hip_stream);
 
+/* ---- Predictor side: approximation loss and its gradients ---------------------------------------
+ * Sec. "Low-Rank based Sparsity Prediction": the predictor (Wq, Wk) of a block is trained so that
+ * Q_lr K_lr^T tracks Q K^T, with the loss 0.95 * CosLoss + 0.05 * NormLoss evaluated on a random sample of
+ * query rows, in the forward pass, without storing Q K^T.  Per (b, h), with A = Q_s K^T and
+ * Ahat = (Q_s Wq)(K Wk)^T over the n_rows sampled queries and all L keys:
+ *     CosLoss  = mean_i ( 1 - <ahat_i, a_i> / (|ahat_i| |a_i|) )      (cosine of a query's score rows)
+ *     NormLoss = mean_ij (ahat_ij - a_ij)^2
+ * (no softmax scale; projections in full precision -- rounding belongs to the selection path).
+ * rows: DEVICE int32 [n_rows], the sampled query rows (each in [0, L); the same rows for every head).
+ * loss: DEVICE float [B*H, 3] = {0.95 Cos + 0.05 Norm, CosLoss, NormLoss}; dWq, dWk: DEVICE float
+ * [B*H, d, r], the gradients of (b, h)'s loss (a caller with B > 1 sums them over b).
+ * No row of A or Ahat is formed: everything is a quadratic form in the Gram matrix K^T K, the one pass
+ * over the keys. */
+DSV_API size_t dsv_predictor_loss_workspace(const dsv_problem *p, int32_t n_rows);
+DSV_API dsv_status dsv_predictor_loss(const dsv_problem *p, const void *Q, const void *K, const void *Wq,
+                                      const void *Wk, const int32_t *rows, int32_t n_rows, float *loss, float *dWq,
+                                      float *dWk, void *workspace, size_t ws_bytes, void *hip_stream);
+
 /* ---- Optional debug check of an index tensor ---------------------------------------------------
  * Checks every row of idx against the idx contract above: values in [0, L), distinct within a row,
  * and -- when dsv_problem.flags has DSV_FLAG_SORTED_INDEX -- strictly ascending (which is what the

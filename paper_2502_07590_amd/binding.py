@@ -28,6 +28,7 @@ EXPORTED_SYMBOLS = (
     "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dq", "dsv_idx_transpose_workspace", "dsv_idx_transpose",
     "dsv_sparse_attn_bwd_dkdv_workspace", "dsv_sparse_attn_bwd_dkdv",
     "dsv_idx_validate_workspace", "dsv_idx_validate",
+    "dsv_predictor_loss_workspace", "dsv_predictor_loss",
     "dsv_lowrank_topk_grouped_workspace", "dsv_lowrank_topk_grouped", "dsv_sparse_attn_fwd_grouped",
     "dsv_sparse_attn_bwd_grouped_workspace", "dsv_sparse_attn_bwd_grouped",
     "dsv_lowrank_topk_noalloc_max_bytes", "dsv_lowrank_topk_noalloc",
@@ -126,6 +127,10 @@ def load_library():
     lib.dsv_sparse_attn_fwd_grouped.argtypes = [P, PG, vp, vp, vp, vp, vp, vp, vp]
     lib.dsv_sparse_attn_bwd_grouped.restype = ctypes.c_int
     lib.dsv_sparse_attn_bwd_grouped.argtypes = [P, PG] + [vp] * 12 + [vp, sz, vp]
+    lib.dsv_predictor_loss_workspace.restype = sz
+    lib.dsv_predictor_loss_workspace.argtypes = [P, i32]
+    lib.dsv_predictor_loss.restype = ctypes.c_int
+    lib.dsv_predictor_loss.argtypes = [P, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
     lib.dsv_idx_validate.restype = ctypes.c_int
     lib.dsv_idx_validate.argtypes = [P, vp, ctypes.POINTER(ctypes.c_int64), vp, sz, vp]
     lib.dsv_lowrank_project.restype = ctypes.c_int
@@ -391,6 +396,24 @@ def sparse_attn_bwd_grouped(p: Problem, g: Grouping, Q, K, V, idx_g, idx_t_g, co
                                                       _ptr(dV), _ptr(ws), nbytes, _stream(stream)),
            "dsv_sparse_attn_bwd_grouped")
     return dQ, dK, dV
+
+
+# ---- predictor side -------------------------------------------------------------------------------
+def predictor_loss_workspace(p: Problem, n_rows: int) -> int:
+    return int(load_library().dsv_predictor_loss_workspace(p.c, int(n_rows)))
+
+
+def predictor_loss(p: Problem, Q, K, Wq, Wk, rows, workspace=None, stream=None):
+    """(loss [B*H, 3] = {total, cos, norm}, dWq [B*H, d, r], dWk [B*H, d, r]) on the sampled query rows."""
+    n = int(rows.numel())
+    dev = Q.device
+    loss = torch.empty((p.B * p.H, 3), dtype=torch.float32, device=dev)
+    dWq = torch.empty((p.B * p.H, p.d, p.r), dtype=torch.float32, device=dev)
+    dWk = torch.empty((p.B * p.H, p.d, p.r), dtype=torch.float32, device=dev)
+    ws, nbytes = _workspace(predictor_loss_workspace(p, n), dev, workspace, stream)
+    _check(load_library().dsv_predictor_loss(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(rows), n, _ptr(loss), _ptr(dWq),
+                                             _ptr(dWk), _ptr(ws), nbytes, _stream(stream)), "dsv_predictor_loss")
+    return loss, dWq, dWk
 
 
 def idx_validate(p: Problem, idx, workspace=None, stream=None):

@@ -599,6 +599,28 @@ dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping 
     return launch_group_rows(*p, *g, 2, ws + w.dqp, dQ, stream);
 }
 
+// ------------------------------------------------------------------------------------ predictor side
+size_t dsv_predictor_loss_workspace(const dsv_problem *p, int32_t n_rows)
+{
+    if (check_problem(p, true) != DSV_OK || n_rows < 1 || n_rows > p->L) return 0;
+    return predictor_layout(*p, n_rows).total;
+}
+
+dsv_status dsv_predictor_loss(const dsv_problem *p, const void *Q, const void *K, const void *Wq, const void *Wk,
+                              const int32_t *rows, int32_t n_rows, float *loss, float *dWq, float *dWk, void *workspace,
+                              size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, true);
+    if (st != DSV_OK) return st;
+    if (n_rows < 1 || n_rows > p->L) return DSV_EINVAL;
+    if (!ok_ptrs({Q, K, Wq, Wk, loss, dWq, dWk}) || !rows) return DSV_EINVAL;
+    const PredictorLayout w = predictor_layout(*p, n_rows);
+    st = check_workspace(workspace, ws_bytes, w.total);
+    if (st != DSV_OK) return st;
+    return launch_predictor_loss(*p, Q, K, Wq, Wk, rows, n_rows, loss, dWq, dWk, static_cast<char *>(workspace), w,
+                                 static_cast<hipStream_t>(hip_stream));
+}
+
 // ------------------------------------------------------------------------------------ debug validator
 size_t dsv_idx_validate_workspace(const dsv_problem *p)
 {

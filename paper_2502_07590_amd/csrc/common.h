@@ -330,6 +330,16 @@ dsv_status launch_grouped_fwd(const dsv_problem &p, const dsv_grouping &gr, cons
                               const void *Q, const void *K, const void *V, const int32_t *idx_g, void *O, float *lse,
                               hipStream_t st);
 
+// ---- predictor side (predictor.hip) ---------------------------------------------------------------------
+struct PredictorLayout {
+    int tok_per_block, nblk;
+    size_t part, M, T1, T2, qlr, g, ca, ch, terms, dwq, n1, n2, total;
+};
+PredictorLayout predictor_layout(const dsv_problem &p, int n_rows);
+dsv_status launch_predictor_loss(const dsv_problem &p, const void *Q, const void *K, const void *Wq, const void *Wk,
+                                 const int32_t *rows, int n, float *loss, float *dWq, float *dWk, char *ws,
+                                 const PredictorLayout &w, hipStream_t st);
+
 // report_dev: two 64-bit counters in device memory; report_host: optional HOST int64 [3].  Waits for the stream.
 dsv_status launch_idx_validate(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
                                unsigned long long *report_dev, int64_t *report_host, hipStream_t st);
