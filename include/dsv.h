@@ -250,6 +250,22 @@ DSV_API dsv_status dsv_predictor_loss(const dsv_problem *p, const void *Q, const
                                       const void *Wk, const int32_t *rows, int32_t n_rows, float *loss, float *dWq,
                                       float *dWk, void *workspace, size_t ws_bytes, void *hip_stream);
 
+/* ---- Predictor side: sparsity profiler --------------------------------------------------------------
+ * Sec. "Sparsity Profiling": the sparsity of every head is measured on a sample of query rows from the softmax
+ * of the true scores (scale * Q K^T over all L keys) and kept as an exponential moving average.  Definition
+ * (Sec. "Exploiting Dynamic Sparsity"): a query's critical KV are its highest-probability keys that together
+ * hold `mass` of its softmax (the paper: 0.9); the head's sparsity is the mean fraction of NON-critical keys.
+ * rows: DEVICE int32 [n_rows] (each in [0, L); the same rows for every head); 0 < mass < 1.
+ * counts: DEVICE int32 [B*H, n_rows], the number of critical keys of every sampled query;
+ * sparsity: DEVICE float [B*H] = mean_i (1 - counts_i / L);
+ * ema: DEVICE float [B*H] or NULL: updated in place, ema = alpha * sparsity + (1 - alpha) * ema.
+ * Scores are recomputed in each of five sweeps on the matrix cores, never stored.  A count can differ by
+ * one key between runs (probability mass is summed with LDS float atomics). */
+DSV_API size_t dsv_profile_sparsity_workspace(const dsv_problem *p, int32_t n_rows);
+DSV_API dsv_status dsv_profile_sparsity(const dsv_problem *p, const void *Q, const void *K, const int32_t *rows,
+                                        int32_t n_rows, float mass, int32_t *counts, float *sparsity, float *ema,
+                                        float alpha, void *workspace, size_t ws_bytes, void *hip_stream);
+
 /* ---- Optional debug check of an index tensor ---------------------------------------------------
  * Checks every row of idx against the idx contract above: values in [0, L), distinct within a row,
  * and -- when dsv_problem.flags has DSV_FLAG_SORTED_INDEX -- strictly ascending (which is what the

@@ -28,7 +28,7 @@ EXPORTED_SYMBOLS = (
     "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dq", "dsv_idx_transpose_workspace", "dsv_idx_transpose",
     "dsv_sparse_attn_bwd_dkdv_workspace", "dsv_sparse_attn_bwd_dkdv",
     "dsv_idx_validate_workspace", "dsv_idx_validate",
-    "dsv_predictor_loss_workspace", "dsv_predictor_loss",
+    "dsv_predictor_loss_workspace", "dsv_predictor_loss", "dsv_profile_sparsity_workspace", "dsv_profile_sparsity",
     "dsv_lowrank_topk_grouped_workspace", "dsv_lowrank_topk_grouped", "dsv_sparse_attn_fwd_grouped",
     "dsv_sparse_attn_bwd_grouped_workspace", "dsv_sparse_attn_bwd_grouped",
     "dsv_lowrank_topk_noalloc_max_bytes", "dsv_lowrank_topk_noalloc",
@@ -127,6 +127,10 @@ def load_library():
     lib.dsv_sparse_attn_fwd_grouped.argtypes = [P, PG, vp, vp, vp, vp, vp, vp, vp]
     lib.dsv_sparse_attn_bwd_grouped.restype = ctypes.c_int
     lib.dsv_sparse_attn_bwd_grouped.argtypes = [P, PG] + [vp] * 12 + [vp, sz, vp]
+    lib.dsv_profile_sparsity_workspace.restype = sz
+    lib.dsv_profile_sparsity_workspace.argtypes = [P, i32]
+    lib.dsv_profile_sparsity.restype = ctypes.c_int
+    lib.dsv_profile_sparsity.argtypes = [P, vp, vp, vp, i32, ctypes.c_float, vp, vp, vp, ctypes.c_float, vp, sz, vp]
     lib.dsv_predictor_loss_workspace.restype = sz
     lib.dsv_predictor_loss_workspace.argtypes = [P, i32]
     lib.dsv_predictor_loss.restype = ctypes.c_int
@@ -414,6 +418,19 @@ def predictor_loss(p: Problem, Q, K, Wq, Wk, rows, workspace=None, stream=None):
     _check(load_library().dsv_predictor_loss(p.c, _ptr(Q), _ptr(K), _ptr(Wq), _ptr(Wk), _ptr(rows), n, _ptr(loss), _ptr(dWq),
                                              _ptr(dWk), _ptr(ws), nbytes, _stream(stream)), "dsv_predictor_loss")
     return loss, dWq, dWk
+
+
+def profile_sparsity(p: Problem, Q, K, rows, mass: float = 0.9, ema=None, alpha: float = 0.1, workspace=None, stream=None):
+    """(sparsity [B*H], counts [B*H, n_rows]) of the sampled query rows; `ema` ([B*H] float, optional) is updated in place."""
+    n = int(rows.numel())
+    dev = Q.device
+    counts = torch.empty((p.B * p.H, n), dtype=torch.int32, device=dev)
+    sparsity = torch.empty(p.B * p.H, dtype=torch.float32, device=dev)
+    lib = load_library()
+    ws, nbytes = _workspace(int(lib.dsv_profile_sparsity_workspace(p.c, n)), dev, workspace, stream)
+    _check(lib.dsv_profile_sparsity(p.c, _ptr(Q), _ptr(K), _ptr(rows), n, float(mass), _ptr(counts), _ptr(sparsity), _ptr(ema),
+                                    float(alpha), _ptr(ws), nbytes, _stream(stream)), "dsv_profile_sparsity")
+    return sparsity, counts
 
 
 def idx_validate(p: Problem, idx, workspace=None, stream=None):

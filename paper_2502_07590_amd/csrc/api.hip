@@ -621,6 +621,26 @@ dsv_status dsv_predictor_loss(const dsv_problem *p, const void *Q, const void *K
                                  static_cast<hipStream_t>(hip_stream));
 }
 
+size_t dsv_profile_sparsity_workspace(const dsv_problem *p, int32_t n_rows)
+{
+    if (check_problem(p, false) != DSV_OK || n_rows < 1 || n_rows > p->L) return 0;
+    return profile_workspace_bytes(*p, n_rows);
+}
+
+dsv_status dsv_profile_sparsity(const dsv_problem *p, const void *Q, const void *K, const int32_t *rows, int32_t n_rows,
+                                float mass, int32_t *counts, float *sparsity, float *ema, float alpha, void *workspace,
+                                size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if (n_rows < 1 || n_rows > p->L || !(mass > 0.f && mass < 1.f) || !(alpha >= 0.f && alpha <= 1.f)) return DSV_EINVAL;
+    if (!ok_ptrs({Q, K}) || !rows || !counts || !sparsity) return DSV_EINVAL;
+    st = check_workspace(workspace, ws_bytes, profile_workspace_bytes(*p, n_rows));
+    if (st != DSV_OK) return st;
+    return launch_profile_sparsity(*p, Q, K, rows, n_rows, mass, counts, sparsity, ema, alpha,
+                                   static_cast<char *>(workspace), static_cast<hipStream_t>(hip_stream));
+}
+
 // ------------------------------------------------------------------------------------ debug validator
 size_t dsv_idx_validate_workspace(const dsv_problem *p)
 {

@@ -340,6 +340,12 @@ dsv_status launch_predictor_loss(const dsv_problem &p, const void *Q, const void
                                  const int32_t *rows, int n, float *loss, float *dWq, float *dWk, char *ws,
                                  const PredictorLayout &w, hipStream_t st);
 
+// ---- sparsity profiler (profiler.hip) ----------------------------------------------------------------------
+size_t profile_workspace_bytes(const dsv_problem &p, int n_rows);
+dsv_status launch_profile_sparsity(const dsv_problem &p, const void *Q, const void *K, const int32_t *rows, int n,
+                                   float mass, int32_t *counts, float *sparsity, float *ema, float alpha, char *ws,
+                                   hipStream_t st);
+
 // report_dev: two 64-bit counters in device memory; report_host: optional HOST int64 [3].  Waits for the stream.
 dsv_status launch_idx_validate(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
                                unsigned long long *report_dev, int64_t *report_host, hipStream_t st);

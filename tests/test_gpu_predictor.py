@@ -53,3 +53,27 @@ def test_identity_predictor_has_zero_loss():
     loss, dWq, dWk = dsv.predictor_loss(p, Q, K, eye, eye, torch.arange(0, L, 16, dtype=torch.int32).cuda())
     torch.cuda.synchronize()
     assert abs(float(loss[0, 1])) < 1e-5 and abs(float(loss[0, 2])) < 1e-3 * float((Q[0, 0] @ K[0, 0].T).pow(2).mean())
+
+
+@pytest.mark.parametrize("L,d,dtype,n,scale_mul", [(1024, 64, "f32", 40, 4.0), (4096, 128, "bf16", 100, 2.0), (3001, 128, "bf16", 33, 2.0)])
+def test_profile_sparsity_matches_oracle(L, d, dtype, n, scale_mul):
+    cfg = _cfg(L, d, 16, dtype, R=64 if d == 128 else 32)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    t = [wl.head_tensors(cfg, h, names=("Q", "K")) for h in range(cfg.H)]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(td).contiguous()
+    Q, K = dev(np.stack([x["Q"] for x in t]))[None], dev(np.stack([x["K"] for x in t]))[None]
+    rows = np.sort(np.random.default_rng(5).choice(L, size=n, replace=False)).astype(np.int32)
+    scale = scale_mul / math.sqrt(d)
+    p = dsv.Problem(1, cfg.H, L, d, 16, dtype, [1] * cfg.H, scale)
+    ema = torch.full((cfg.H,), 0.5, dtype=torch.float32, device="cuda")
+    sparsity, counts = dsv.profile_sparsity(p, Q, K, torch.from_numpy(rows).cuda(), mass=0.9, ema=ema, alpha=0.25)
+    torch.cuda.synchronize()
+    sparsity, counts, ema = sparsity.cpu().numpy(), counts.cpu().numpy(), ema.cpu().numpy()
+    for h in range(cfg.H):
+        s_ref, c_ref = oracle.profile_sparsity(t[h]["Q"][rows], t[h]["K"], scale, 0.9)
+        # the device sums fp32 probabilities in another order: where the cumulative mass passes 0.9 within rounding
+        # of a key boundary the count moves by one key
+        diff = np.abs(counts[h].astype(np.int64) - c_ref)
+        assert diff.max() <= 1 and (diff == 0).mean() > 0.8, (diff.max(), (diff == 0).mean())
+        assert abs(sparsity[h] - s_ref) <= 1.0 / L + 1e-6
+        assert abs(ema[h] - oracle.ema(0.5, float(sparsity[h]), 0.25)) < 1e-6
