@@ -74,6 +74,9 @@ def parse_args():
                     help="instead of the benchmark line: the offline table a sparse/dense dispatcher consumes -- for L in "
                          "{32k, 64k, 128k} and k/L from 0.5 to 12.5 %%, ms per stage, speedup over dense, and the bytes of "
                          "index and workspace the sparse path needs")
+    ap.add_argument("--predictor", action="store_true",
+                    help="also time the predictor side at the same shape: approximation loss + gradients and the sparsity "
+                         "profiler, both on L/16 sampled query rows")
     ap.add_argument("--grouped", action="store_true",
                     help="also time the query-grouped variant (2 x 2 x 2 cubes) at the same shape, and measure what the "
                          "shared rows cost in accuracy on spatially smooth inputs")
@@ -311,6 +314,32 @@ def grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, steps, warmup, dense_
     del ws1, ws2, idx_g, idx_t_g, col, O, dQ, dK, dV, lse
     torch.cuda.empty_cache()
     return out
+
+
+def predictor_report(dsv, torch, cfg, ks, g, Wq, Wk):
+    """dsv_predictor_loss and dsv_profile_sparsity at the benchmark shape, on every 16th query row (the sampling
+    factor the paper names)."""
+    dev = g["Q"].device
+    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, [int(k) for k in ks], cfg.scale)
+    rows = torch.arange(0, cfg.L, 16, dtype=torch.int32, device=dev)
+    n = int(rows.numel())
+    ws1 = torch.empty(dsv.predictor_loss_workspace(p, n), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(max(int(dsv.load_library().dsv_profile_sparsity_workspace(p.c, n)), 256), dtype=torch.uint8, device=dev)
+    ema = torch.full((cfg.H,), 0.9, dtype=torch.float32, device=dev)
+    res = {}
+    calls = (lambda: res.__setitem__("loss", dsv.predictor_loss(p, g["Q"], g["K"], Wq, Wk, rows, workspace=ws1)),
+             lambda: res.__setitem__("prof", dsv.profile_sparsity(p, g["Q"], g["K"], rows, mass=0.9, ema=ema, alpha=0.1, workspace=ws2)))
+    ms = _time_calls(torch, calls, 3, 1)
+    esize = 2 if cfg.dtype == "bf16" else 4
+    k_bytes = cfg.H * cfg.L * cfg.d * esize
+    n_scores = cfg.H * n * cfg.L
+    return {"sampled_rows_per_head": n,
+            "predictor_loss": {"ms": round(ms[0], 3), "loss_head0": [round(float(x), 6) for x in res["loss"][0][0].tolist()],
+                               "note": "one pass over K (Gram matrix K^T K), the rest is [d, d] / [d, r] algebra in fp64",
+                               "k_bytes": k_bytes},
+            "profile_sparsity": {"ms": round(ms[1], 3), "sparsity_per_head": [round(float(x), 4) for x in res["prof"][0].tolist()],
+                                 "scores_per_sweep": n_scores, "sweeps": 5,
+                                 "mfma_tflops": round(5 * 2.0 * cfg.d * n_scores / (ms[1] * 1e-3) / 1e12, 1)}}
 
 
 def grouping_accuracy(dsv, torch, np, wl, cfg, seed):
@@ -552,6 +581,9 @@ def main():
         torch.cuda.empty_cache()
         out["grouped"] = grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, max(args.steps, 2), 1, dense_ms, ms_per_step)
         out["grouped"]["accuracy"] = grouping_accuracy(dsv, torch, np, wl, cfg, args.seed)
+
+    if args.predictor:
+        out["predictor_side"] = predictor_report(dsv, torch, cfg, ks, g, Wq, Wk)
 
     # ---- CPU oracle timed on a bounded sample ------------------------------------------------------
     if not args.no_cpu_baseline:

@@ -15,6 +15,7 @@ SOURCES = ("api.hip", "stage1.hip", "stage1_emit.hip", "stage2.hip", "stage2_spl
 # packed-fp32 instructions are disabled for device code (a requirement of the test machines).
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-munsafe-fp-atomics",                  # LDS float adds as one instruction (the profiler's mass histograms)
                "-mllvm", "-amdgpu-mfma-vgpr-form=1",   # MFMA results straight into VGPRs (no AccVGPR copies)
                "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes",
                "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -332,7 +332,7 @@ dsv_status launch_grouped_fwd(const dsv_problem &p, const dsv_grouping &gr, cons
 
 // ---- predictor side (predictor.hip) ---------------------------------------------------------------------
 struct PredictorLayout {
-    int tok_per_block, nblk;
+    int tok_per_block, nblk, nchunk;
     size_t part, M, T1, T2, qlr, g, ca, ch, terms, dwq, n1, n2, total;
 };
 PredictorLayout predictor_layout(const dsv_problem &p, int n_rows);

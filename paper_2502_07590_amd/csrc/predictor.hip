@@ -158,43 +158,80 @@ __global__ __launch_bounds__(256) void predictor_rows_kernel(const T *__restrict
     }
 }
 
-// out[bh][a][b] = sum_i X_i[a] * Y[bh][i][b], X_i = row rows[i] of Q (XQ = true) or X[bh][i][:] (doubles).
-// One thread per output element, rows walked in order (deterministic).
-template <typename T, bool XQ>
-__global__ __launch_bounds__(256) void atb_kernel(const T *__restrict__ Q, const int32_t *__restrict__ rows,
-                                                  const double *__restrict__ X, const double *__restrict__ Y, int n, int L,
-                                                  int DA, int DB, int qstride, double *__restrict__ out)
-{
-    const int bh = blockIdx.y;
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= DA * DB) return;
-    const int a = e / DB, b = e % DB;
-    double s = 0.0;
-    for (int i = 0; i < n; ++i) {
-        double x;
-        if (XQ) x = (double)to_f32<T>(Q[((int64_t)bh * L + min(max(rows[i], 0), L - 1)) * qstride + a]);
-        else x = X[((int64_t)bh * n + i) * DA + a];
-        s += x * Y[((int64_t)bh * n + i) * DB + b];
-    }
-    out[(int64_t)bh * DA * DB + e] = s;
-}
-
-// dWk = M (N1 + Wk N2); dWq copied out; loss = {0.95 cos + 0.05 norm, cos, norm}.  One block per head.
+// ---- sums over the sampled rows ---------------------------------------------------------------------------
+// dWq = Q_s^T G [D, R],  N1 = Q_s^T CA [D, R],  N2 = Qlr^T CH [R, R]: every block takes 32 sampled rows (their Q
+// rows and per-row vectors staged in LDS) and writes its partial sums; predictor_finish_kernel adds the partials
+// in block order (deterministic).
+constexpr int kAccRows = 32;
 template <typename T>
-__global__ __launch_bounds__(256) void predictor_finish_kernel(const double *__restrict__ M, const T *__restrict__ Wk,
-                                                               const double *__restrict__ N1, const double *__restrict__ N2,
-                                                               const double *__restrict__ dWq64, const double *__restrict__ terms,
-                                                               int n, int L, int H, int D, int R, float *__restrict__ loss,
-                                                               float *__restrict__ dWq, float *__restrict__ dWk)
+__global__ __launch_bounds__(256) void predictor_accum_kernel(const T *__restrict__ Q, const int32_t *__restrict__ rows,
+                                                              int n, int L, int D, int R, const double *__restrict__ qlr,
+                                                              const double *__restrict__ g, const double *__restrict__ ca,
+                                                              const double *__restrict__ ch, double *__restrict__ p_dwq,
+                                                              double *__restrict__ p_n1, double *__restrict__ p_n2)
 {
-    extern __shared__ double P[];  // [D, R]: N1 + Wk N2
-    const int bh = blockIdx.x;
-    const T *W = Wk + (int64_t)(bh % H) * D * R;
+    __shared__ float xq[kAccRows][128];
+    __shared__ double yg[kAccRows][64], yca[kAccRows][64], ych[kAccRows][64], xl[kAccRows][64];
+    const int bh = blockIdx.y, chunk = blockIdx.x;
+    const int i0 = chunk * kAccRows, ni = min(kAccRows, n - i0);
+    for (int e = threadIdx.x; e < kAccRows * D; e += 256) {
+        const int i = e / D, c = e % D;
+        xq[i][c] = i < ni ? to_f32<T>(Q[((int64_t)bh * L + min(max(rows[i0 + i], 0), L - 1)) * D + c]) : 0.f;
+    }
+    for (int e = threadIdx.x; e < kAccRows * R; e += 256) {
+        const int i = e / R, t = e % R;
+        const int64_t o = ((int64_t)bh * n + i0 + i) * R + t;
+        yg[i][t] = i < ni ? g[o] : 0.0;
+        yca[i][t] = i < ni ? ca[o] : 0.0;
+        ych[i][t] = i < ni ? ch[o] : 0.0;
+        xl[i][t] = i < ni ? qlr[o] : 0.0;
+    }
+    __syncthreads();
+    const int64_t pb = (int64_t)bh * gridDim.x + chunk;
     for (int e = threadIdx.x; e < D * R; e += 256) {
         const int c = e / R, t = e % R;
-        double s = N1[(int64_t)bh * D * R + e];
-        for (int t2 = 0; t2 < R; ++t2) s += (double)to_f32<T>(W[c * R + t2]) * N2[(int64_t)bh * R * R + t2 * R + t];
+        double s1 = 0.0, s2 = 0.0;
+        for (int i = 0; i < kAccRows; ++i) { s1 += (double)xq[i][c] * yg[i][t]; s2 += (double)xq[i][c] * yca[i][t]; }
+        p_dwq[pb * D * R + e] = s1;
+        p_n1[pb * D * R + e] = s2;
+    }
+    for (int e = threadIdx.x; e < R * R; e += 256) {
+        const int a = e / R, t = e % R;
+        double s = 0.0;
+        for (int i = 0; i < kAccRows; ++i) s += xl[i][a] * ych[i][t];
+        p_n2[pb * R * R + e] = s;
+    }
+}
+
+// dWk = M (N1 + Wk N2), dWq and N1, N2 from the blocks' partials; loss = {0.95 cos + 0.05 norm, cos, norm}.  One block per head.
+template <typename T>
+__global__ __launch_bounds__(256) void predictor_finish_kernel(const double *__restrict__ M, const T *__restrict__ Wk,
+                                                               const double *__restrict__ p_dwq, const double *__restrict__ p_n1,
+                                                               const double *__restrict__ p_n2, int nchunk,
+                                                               const double *__restrict__ terms, int n, int L, int H, int D,
+                                                               int R, float *__restrict__ loss, float *__restrict__ dWq,
+                                                               float *__restrict__ dWk)
+{
+    extern __shared__ double sh[];  // P [D, R] = N1 + Wk N2, then N2 [R, R], then 2 x 256 reduction slots
+    double *P = sh, *N2 = sh + D * R, *red = N2 + R * R;
+    const int bh = blockIdx.x;
+    const T *W = Wk + (int64_t)(bh % H) * D * R;
+    for (int e = threadIdx.x; e < R * R; e += 256) {
+        double s = 0.0;
+        for (int c = 0; c < nchunk; ++c) s += p_n2[((int64_t)bh * nchunk + c) * R * R + e];
+        N2[e] = s;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < D * R; e += 256) {
+        const int c = e / R, t = e % R;
+        double s = 0.0, q = 0.0;
+        for (int k = 0; k < nchunk; ++k) {
+            s += p_n1[((int64_t)bh * nchunk + k) * D * R + e];
+            q += p_dwq[((int64_t)bh * nchunk + k) * D * R + e];
+        }
+        for (int t2 = 0; t2 < R; ++t2) s += (double)to_f32<T>(W[c * R + t2]) * N2[t2 * R + t];
         P[e] = s;
+        dWq[(int64_t)bh * D * R + e] = (float)q;
     }
     __syncthreads();
     for (int e = threadIdx.x; e < D * R; e += 256) {
@@ -202,13 +239,19 @@ __global__ __launch_bounds__(256) void predictor_finish_kernel(const double *__r
         double s = 0.0;
         for (int c2 = 0; c2 < D; ++c2) s += M[(int64_t)bh * D * D + c * D + c2] * P[c2 * R + t];
         dWk[(int64_t)bh * D * R + e] = (float)s;
-        dWq[(int64_t)bh * D * R + e] = (float)dWq64[(int64_t)bh * D * R + e];
+    }
+    double c = 0.0, m = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) { c += terms[((int64_t)bh * n + i) * 2]; m += terms[((int64_t)bh * n + i) * 2 + 1]; }
+    red[threadIdx.x] = c;
+    red[256 + threadIdx.x] = m;
+    __syncthreads();
+    for (int step = 128; step; step >>= 1) {
+        if ((int)threadIdx.x < step) { red[threadIdx.x] += red[threadIdx.x + step]; red[256 + threadIdx.x] += red[256 + threadIdx.x + step]; }
+        __syncthreads();
     }
     if (threadIdx.x == 0) {
-        double c = 0.0, m = 0.0;
-        for (int i = 0; i < n; ++i) { c += terms[((int64_t)bh * n + i) * 2]; m += terms[((int64_t)bh * n + i) * 2 + 1]; }
-        c /= (double)n;
-        m /= (double)n * (double)L;
+        c = red[0] / (double)n;
+        m = red[256] / ((double)n * (double)L);
         loss[bh * 3 + 0] = (float)(0.95 * c + 0.05 * m);
         loss[bh * 3 + 1] = (float)c;
         loss[bh * 3 + 2] = (float)m;
@@ -232,9 +275,10 @@ PredictorLayout predictor_layout(const dsv_problem &p, int n)
     w.ca = o; o = align_up(o + nbh * n * R * 8, 256);
     w.ch = o; o = align_up(o + nbh * n * R * 8, 256);
     w.terms = o; o = align_up(o + nbh * n * 2 * 8, 256);
-    w.dwq = o; o = align_up(o + nbh * D * R * 8, 256);
-    w.n1 = o; o = align_up(o + nbh * D * R * 8, 256);
-    w.n2 = o; o = align_up(o + nbh * R * R * 8, 256);
+    w.nchunk = (n + 31) / 32;   // kAccRows sampled rows per partial sum
+    w.dwq = o; o = align_up(o + nbh * w.nchunk * D * R * 8, 256);
+    w.n1 = o; o = align_up(o + nbh * w.nchunk * D * R * 8, 256);
+    w.n2 = o; o = align_up(o + nbh * w.nchunk * R * R * 8, 256);
     w.total = o;
     return w;
 }
@@ -262,15 +306,11 @@ static dsv_status predictor_t(const dsv_problem &p, const void *Q, const void *K
     hipLaunchKernelGGL((predictor_rows_kernel<T>), dim3((n + 3) / 4, nbh), dim3(256), 0, st, (const T *)Q, (const T *)Wq, rows, n,
                        p.L, p.H, D, R, M, T1, T2, qlr, g, ca, ch, terms);
     DSV_LAUNCH_CHECK();
-    hipLaunchKernelGGL((atb_kernel<T, true>), dim3((D * R + 255) / 256, nbh), dim3(256), 0, st, (const T *)Q, rows,
-                       (const double *)nullptr, g, n, p.L, D, R, D, dwq);
-    hipLaunchKernelGGL((atb_kernel<T, true>), dim3((D * R + 255) / 256, nbh), dim3(256), 0, st, (const T *)Q, rows,
-                       (const double *)nullptr, ca, n, p.L, D, R, D, n1);
-    hipLaunchKernelGGL((atb_kernel<T, false>), dim3((R * R + 255) / 256, nbh), dim3(256), 0, st, (const T *)nullptr,
-                       (const int32_t *)nullptr, qlr, ch, n, p.L, R, R, 0, n2);
+    hipLaunchKernelGGL((predictor_accum_kernel<T>), dim3(w.nchunk, nbh), dim3(256), 0, st, (const T *)Q, rows, n, p.L, D, R, qlr, g,
+                       ca, ch, dwq, n1, n2);
     DSV_LAUNCH_CHECK();
-    hipLaunchKernelGGL((predictor_finish_kernel<T>), dim3(nbh), dim3(256), (size_t)D * R * 8, st, M, (const T *)Wk, n1, n2, dwq,
-                       terms, n, p.L, p.H, D, R, loss, dWq, dWk);
+    hipLaunchKernelGGL((predictor_finish_kernel<T>), dim3(nbh), dim3(256), (size_t)(D * R + R * R + 512) * 8, st, M, (const T *)Wk,
+                       dwq, n1, n2, w.nchunk, terms, n, p.L, p.H, D, R, loss, dWq, dWk);
     DSV_LAUNCH_CHECK();
     return DSV_OK;
 }
