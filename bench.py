@@ -282,7 +282,8 @@ def grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, steps, warmup, dense_
     dsv_lowrank_topk_grouped + dsv_sparse_attn_fwd_grouped + dsv_sparse_attn_bwd_grouped."""
     cube = (2, 2, 2)
     grp = dsv.Grouping(cfg.grid, cube)
-    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, [int(k) for k in ks], cfg.scale)
+    # stage 1 writes ascending rows and lists: the L2-blocked kernels may be used
+    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, [int(k) for k in ks], cfg.scale, sorted_index=True)
     dev = g["Q"].device
     n = p.nnz // grp.G
     idx_g = torch.empty(n, dtype=torch.int32, device=dev)
@@ -291,17 +292,23 @@ def grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, steps, warmup, dense_
     O, dQ, dK, dV = (torch.empty_like(g["Q"]) for _ in range(4))
     lse = torch.empty((1, cfg.H, cfg.L), dtype=torch.float32, device=dev)
     ws1 = torch.empty(dsv.lowrank_topk_grouped_workspace(p, grp), dtype=torch.uint8, device=dev)
-    ws2 = torch.empty(dsv.sparse_attn_bwd_grouped_workspace(p, grp), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(max(dsv.sparse_attn_bwd_grouped_workspace(p, grp), dsv.sparse_attn_fwd_grouped_workspace(p, grp)),
+                      dtype=torch.uint8, device=dev)
     calls = (
         lambda: dsv.lowrank_topk_grouped(p, grp, g["Q"], g["K"], Wq, Wk, idx_g=idx_g, idx_t_g=idx_t_g, col_ptr=col, workspace=ws1),
-        lambda: dsv.sparse_attn_fwd_grouped(p, grp, g["Q"], g["K"], g["V"], idx_g, O=O, lse=lse),
+        lambda: dsv.sparse_attn_fwd_grouped(p, grp, g["Q"], g["K"], g["V"], idx_g, O=O, lse=lse, workspace=ws2),
         lambda: dsv.sparse_attn_bwd_grouped(p, grp, g["Q"], g["K"], g["V"], idx_g, idx_t_g, col, O, lse, g["dO"], dQ=dQ, dK=dK,
                                             dV=dV, workspace=ws2),
     )
     ms = _time_calls(torch, calls, steps, warmup)
+    dsv.kernel_timing(True)
+    for c in calls:
+        c()
+    kern = {s_: round(dsv.kernel_ms(s_), 3) for s_ in ("fwd_sweep", "dq_sweep", "dkdv_sweep")}
+    dsv.kernel_timing(False)
     total = sum(ms)
     nnz = p.nnz
-    out = {"cube": list(cube), "G": grp.G, "ms_per_step": round(total, 3),
+    out = {"cube": list(cube), "G": grp.G, "ms_per_step": round(total, 3), "kernel_ms": kern,
            "stage_ms": {"lowrank_topk_grouped": round(ms[0], 3), "sparse_attn_fwd_grouped": round(ms[1], 3),
                         "sparse_attn_bwd_grouped": round(ms[2], 3)},
            "speedup_over_dense": round(dense_ms / total, 3) if dense_ms else None,

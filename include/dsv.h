@@ -208,11 +208,14 @@ DSV_API dsv_status dsv_sparse_attn_bwd_dkdv(const dsv_problem *p, const void *Q,
  * dsv_sparse_attn_fwd_grouped: every member of a group attends over the group's row; same O, lse as
  *   dsv_sparse_attn_fwd on the index with that row repeated for every member.  Each selected K / V
  *   row is gathered once per group and used by all members (scores on the matrix cores).
- *   bf16, d = 128, G <= 8; else DSV_EUNSUPPORTED.  No workspace.
- * dsv_sparse_attn_bwd_grouped: gradients of the above (selection held constant).  Runs the
- *   per-query backward kernels on queries reordered group by group; the workspace holds the
- *   reordered Q, dO, O, lse, dQ and the per-query form of both indices (2 x L*k int32 per head),
- *   so the grouped index saves memory in the forward only.  Needs idx_t_g and col_ptr. */
+ *   bf16, d = 128, G <= 8; else DSV_EUNSUPPORTED.  With DSV_FLAG_SORTED_INDEX (rows ascending, as stage 1
+ *   writes them) the L2-blocked form runs and needs workspace (segment pointers, per-range partials);
+ *   without the flag none (the query returns 0).
+ * dsv_sparse_attn_bwd_grouped: gradients of the above (selection held constant).  dQ group by group with
+ *   the forward's tiling (K and V rows gathered once per group); dK and dV with the per-query key-major
+ *   sweep on queries reordered group by group: the workspace holds the reordered Q, dO, lse, Delta and the
+ *   per-query form of the key-major index (L*k int32 per head) besides the steps' scratch.  Needs idx_t_g
+ *   and col_ptr.  The flag selects the L2-blocked dQ step as in the forward. */
 typedef struct dsv_grouping {
     int32_t F, Hh, Ww;   /* token grid: frames, height, width */
     int32_t gf, gh, gw;  /* cube (group) size along each axis */
@@ -222,9 +225,10 @@ DSV_API size_t dsv_lowrank_topk_grouped_workspace(const dsv_problem *p, const ds
 DSV_API dsv_status dsv_lowrank_topk_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
                                             const void *Wq, const void *Wk, int32_t *idx_g, int32_t *idx_t_g,
                                             int64_t *col_ptr, void *workspace, size_t ws_bytes, void *hip_stream);
+DSV_API size_t dsv_sparse_attn_fwd_grouped_workspace(const dsv_problem *p, const dsv_grouping *g);
 DSV_API dsv_status dsv_sparse_attn_fwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
                                                const void *V, const int32_t *idx_g, void *O, float *lse,
-                                               void *hip_stream);
+                                               void *workspace, size_t ws_bytes, void *hip_stream);
 DSV_API size_t dsv_sparse_attn_bwd_grouped_workspace(const dsv_problem *p, const dsv_grouping *g);
 DSV_API dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
                                                const void *V, const int32_t *idx_g, const int32_t *idx_t_g,

@@ -29,7 +29,8 @@ EXPORTED_SYMBOLS = (
     "dsv_sparse_attn_bwd_dkdv_workspace", "dsv_sparse_attn_bwd_dkdv",
     "dsv_idx_validate_workspace", "dsv_idx_validate",
     "dsv_predictor_loss_workspace", "dsv_predictor_loss", "dsv_profile_sparsity_workspace", "dsv_profile_sparsity",
-    "dsv_lowrank_topk_grouped_workspace", "dsv_lowrank_topk_grouped", "dsv_sparse_attn_fwd_grouped",
+    "dsv_lowrank_topk_grouped_workspace", "dsv_lowrank_topk_grouped", "dsv_sparse_attn_fwd_grouped_workspace",
+    "dsv_sparse_attn_fwd_grouped",
     "dsv_sparse_attn_bwd_grouped_workspace", "dsv_sparse_attn_bwd_grouped",
     "dsv_lowrank_topk_noalloc_max_bytes", "dsv_lowrank_topk_noalloc",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
@@ -118,13 +119,14 @@ def load_library():
     lib.dsv_lowrank_topk_noalloc.restype = ctypes.c_int
     lib.dsv_lowrank_topk_noalloc.argtypes = [P, vp, vp, vp, vp, vp, vp]
     PG = ctypes.POINTER(_CGrouping)
-    for name in ("dsv_lowrank_topk_grouped_workspace", "dsv_sparse_attn_bwd_grouped_workspace"):
+    for name in ("dsv_lowrank_topk_grouped_workspace", "dsv_sparse_attn_bwd_grouped_workspace",
+                 "dsv_sparse_attn_fwd_grouped_workspace"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [P, PG]
     lib.dsv_lowrank_topk_grouped.restype = ctypes.c_int
     lib.dsv_lowrank_topk_grouped.argtypes = [P, PG, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_fwd_grouped.restype = ctypes.c_int
-    lib.dsv_sparse_attn_fwd_grouped.argtypes = [P, PG, vp, vp, vp, vp, vp, vp, vp]
+    lib.dsv_sparse_attn_fwd_grouped.argtypes = [P, PG, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_bwd_grouped.restype = ctypes.c_int
     lib.dsv_sparse_attn_bwd_grouped.argtypes = [P, PG] + [vp] * 12 + [vp, sz, vp]
     lib.dsv_profile_sparsity_workspace.restype = sz
@@ -377,11 +379,16 @@ def lowrank_topk_grouped(p: Problem, g: Grouping, Q, K, Wq, Wk, transposed=True,
     return idx_g, (idx_t_g if transposed else None), (col_ptr if transposed else None)
 
 
-def sparse_attn_fwd_grouped(p: Problem, g: Grouping, Q, K, V, idx_g, O=None, lse=None, stream=None):
+def sparse_attn_fwd_grouped_workspace(p: Problem, g: Grouping) -> int:
+    return int(load_library().dsv_sparse_attn_fwd_grouped_workspace(p.c, g.c))
+
+
+def sparse_attn_fwd_grouped(p: Problem, g: Grouping, Q, K, V, idx_g, O=None, lse=None, workspace=None, stream=None):
     O = torch.empty_like(Q) if O is None else O
     lse = torch.empty((p.B, p.H, p.L), dtype=torch.float32, device=Q.device) if lse is None else lse
+    ws, nbytes = _workspace(sparse_attn_fwd_grouped_workspace(p, g), Q.device, workspace, stream)
     _check(load_library().dsv_sparse_attn_fwd_grouped(p.c, g.c, _ptr(Q), _ptr(K), _ptr(V), _ptr(idx_g), _ptr(O), _ptr(lse),
-                                                      _stream(stream)), "dsv_sparse_attn_fwd_grouped")
+                                                      _ptr(ws), nbytes, _stream(stream)), "dsv_sparse_attn_fwd_grouped")
     return O, lse
 
 

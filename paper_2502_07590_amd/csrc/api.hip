@@ -520,23 +520,50 @@ dsv_status dsv_lowrank_topk_grouped(const dsv_problem *p, const dsv_grouping *g,
                              hip_stream);
 }
 
-dsv_status dsv_sparse_attn_fwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
-                                       const void *V, const int32_t *idx_g, void *O, float *lse, void *hip_stream)
+namespace {
+// Scratch of one L2-blocked grouped kernel (forward or dq): segment pointers per group row and per-(token row,
+// range) partials.  split == false: the plain kernels (rows in any order, or a single range), no scratch.
+struct GroupedStepLayout {
+    bool split;
+    SplitPlan plan;
+    size_t seg, pa, pb, pc, total;
+};
+GroupedStepLayout grouped_step_layout(const dsv_problem &p, const dsv_grouping &g, bool dq)
 {
-    dsv_status st = check_problem(p, false);
-    if (st != DSV_OK) return st;
-    if ((st = check_grouping(*p, g)) != DSV_OK) return st;
-    if (!ok_ptrs({Q, K, V, idx_g, O, lse})) return DSV_EINVAL;
-    const std::vector<HeadTable> tabs = make_tables(*p, p->L / group_size(*g));
-    return launch_grouped_fwd(*p, *g, tabs.data(), (int)tabs.size(), Q, K, V, idx_g, O, lse,
-                              static_cast<hipStream_t>(hip_stream));
+    GroupedStepLayout w{};
+    w.plan = make_split_plan(p, kBwdRangeBytes);
+    w.split = use_split(p, w.plan);
+    if (!w.split) return w;
+    const size_t nbh = (size_t)p.B * p.H, rows = nbh * p.L, Lq = p.L / group_size(g);
+    size_t o = 0;
+    w.seg = o; o = align_up(o + nbh * Lq * (w.plan.S + 1) * 4, 256);
+    if (dq) {
+        w.pa = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
+        w.pb = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
+        w.pc = o; o = align_up(o + rows * w.plan.S * 4, 256);
+    } else {
+        w.pa = o; o = align_up(o + rows * w.plan.S * 4, 256);
+        w.pb = o; o = align_up(o + rows * w.plan.S * 4, 256);
+        w.pc = o; o = align_up(o + rows * w.plan.S * p.d * 4, 256);
+    }
+    w.total = o;
+    return w;
+}
+GroupedSplit grouped_split(char *ws, const GroupedStepLayout &w)
+{
+    GroupedSplit s;
+    s.plan = w.plan;
+    s.seg = reinterpret_cast<int32_t *>(ws + w.seg);
+    s.pa = reinterpret_cast<float *>(ws + w.pa);
+    s.pb = reinterpret_cast<float *>(ws + w.pb);
+    s.pc = reinterpret_cast<float *>(ws + w.pc);
+    return s;
 }
 
-namespace {
 struct GroupedBwdLayout {
-    size_t qp, gop, op, dqp, lsep, idxx, idxtx, colx, inner, inner_bytes, total;
+    size_t delta, qp, gop, lsep, deltap, idxtx, colx, step, step_bytes, total;
 };
-GroupedBwdLayout grouped_bwd_layout(const dsv_problem &p)
+GroupedBwdLayout grouped_bwd_layout(const dsv_problem &p, const dsv_grouping &g)
 {
     const size_t nbh = (size_t)p.B * p.H;
     const size_t rows = nbh * p.L * p.d * esize(p.dtype);
@@ -544,24 +571,49 @@ GroupedBwdLayout grouped_bwd_layout(const dsv_problem &p)
     sorted.flags |= DSV_FLAG_SORTED_INDEX;
     GroupedBwdLayout w{};
     size_t o = 0;
+    w.delta = o; o = align_up(o + nbh * p.L * 4, 256);
     w.qp = o; o = align_up(o + rows, 256);
     w.gop = o; o = align_up(o + rows, 256);
-    w.op = o; o = align_up(o + rows, 256);
-    w.dqp = o; o = align_up(o + rows, 256);
     w.lsep = o; o = align_up(o + nbh * p.L * 4, 256);
-    w.idxx = o; o = align_up(o + total_pairs(p) * 4, 256);
+    w.deltap = o; o = align_up(o + nbh * p.L * 4, 256);
     w.idxtx = o; o = align_up(o + total_pairs(p) * 4, 256);
     w.colx = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
-    w.inner = o; w.inner_bytes = bwd_layout(sorted, false).total; o += w.inner_bytes;
+    // the dq step's scratch and the dkdv step's are never live together
+    w.step = o; w.step_bytes = std::max(grouped_step_layout(p, g, true).total, step_layout(sorted).total); o += w.step_bytes;
     w.total = o;
     return w;
 }
 }  // namespace
 
+size_t dsv_sparse_attn_fwd_grouped_workspace(const dsv_problem *p, const dsv_grouping *g)
+{
+    if (check_problem(p, false) != DSV_OK || check_grouping(*p, g) != DSV_OK) return 0;
+    return grouped_step_layout(*p, *g, false).total;
+}
+
+dsv_status dsv_sparse_attn_fwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
+                                       const void *V, const int32_t *idx_g, void *O, float *lse, void *workspace,
+                                       size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if ((st = check_grouping(*p, g)) != DSV_OK) return st;
+    if (!ok_ptrs({Q, K, V, idx_g, O, lse})) return DSV_EINVAL;
+    if (p->dtype != DSV_BF16 || p->d != 128 || group_size(*g) > 8) return DSV_EUNSUPPORTED;
+    const GroupedStepLayout w = grouped_step_layout(*p, *g, false);
+    st = check_workspace(workspace, ws_bytes, w.total);
+    if (st != DSV_OK) return st;
+    const std::vector<HeadTable> tabs = make_tables(*p, p->L / group_size(*g));
+    GroupedSplit sp;
+    if (w.split) sp = grouped_split(static_cast<char *>(workspace), w);
+    return launch_grouped_fwd(*p, *g, tabs.data(), (int)tabs.size(), Q, K, V, idx_g, O, lse, w.split ? &sp : nullptr,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
 size_t dsv_sparse_attn_bwd_grouped_workspace(const dsv_problem *p, const dsv_grouping *g)
 {
     if (check_problem(p, false) != DSV_OK || check_grouping(*p, g) != DSV_OK) return 0;
-    return grouped_bwd_layout(*p).total;
+    return grouped_bwd_layout(*p, *g).total;
 }
 
 dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
@@ -573,30 +625,36 @@ dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping 
     if (st != DSV_OK) return st;
     if ((st = check_grouping(*p, g)) != DSV_OK) return st;
     if (!ok_ptrs({Q, K, V, idx_g, idx_t_g, col_ptr, O, lse, dO, dQ, dK, dV})) return DSV_EINVAL;
-    const GroupedBwdLayout w = grouped_bwd_layout(*p);
+    if (p->dtype != DSV_BF16 || p->d != 128 || group_size(*g) > 8) return DSV_EUNSUPPORTED;
+    const GroupedBwdLayout w = grouped_bwd_layout(*p, *g);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
     char *ws = static_cast<char *>(workspace);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    // queries reordered group by group: a group's members become neighbours, and the per-query lists that
-    // the lists of groups stand for come out ascending
+    const std::vector<HeadTable> tabs = make_tables(*p, p->L / group_size(*g));
+    float *delta = reinterpret_cast<float *>(ws + w.delta);
+    // dQ step, group by group (K and V rows gathered once per group)
+    const GroupedStepLayout dqw = grouped_step_layout(*p, *g, true);
+    GroupedSplit sp;
+    if (dqw.split) sp = grouped_split(ws + w.step, dqw);
+    st = launch_grouped_dq(*p, *g, tabs.data(), (int)tabs.size(), Q, K, V, idx_g, O, lse, dO, dQ, delta,
+                           dqw.split ? &sp : nullptr, stream);
+    if (st != DSV_OK) return st;
+    // dK, dV step: the per-query key-major sweep, on queries reordered group by group -- a group's members become
+    // neighbours, and the per-query lists that the lists of groups stand for come out ascending
     if ((st = launch_group_rows(*p, *g, 1, Q, ws + w.qp, stream)) != DSV_OK) return st;
     if ((st = launch_group_rows(*p, *g, 1, dO, ws + w.gop, stream)) != DSV_OK) return st;
-    if ((st = launch_group_rows(*p, *g, 1, O, ws + w.op, stream)) != DSV_OK) return st;
     if ((st = launch_group_scalar(*p, *g, lse, reinterpret_cast<float *>(ws + w.lsep), stream)) != DSV_OK) return st;
-    const std::vector<HeadTable> tabs = make_tables(*p, p->L / group_size(*g));
-    st = launch_group_expand(*p, *g, tabs.data(), (int)tabs.size(), idx_g, idx_t_g, col_ptr,
-                             reinterpret_cast<int32_t *>(ws + w.idxx), reinterpret_cast<int32_t *>(ws + w.idxtx),
-                             reinterpret_cast<int64_t *>(ws + w.colx), stream);
+    if ((st = launch_group_scalar(*p, *g, delta, reinterpret_cast<float *>(ws + w.deltap), stream)) != DSV_OK) return st;
+    st = launch_group_expand(*p, *g, tabs.data(), (int)tabs.size(), idx_g, idx_t_g, col_ptr, nullptr,
+                             reinterpret_cast<int32_t *>(ws + w.idxtx), reinterpret_cast<int64_t *>(ws + w.colx), stream);
     if (st != DSV_OK) return st;
     dsv_problem sorted = *p;
     sorted.flags |= DSV_FLAG_SORTED_INDEX;
-    st = dsv_sparse_attn_bwd_t(&sorted, ws + w.qp, K, V, reinterpret_cast<int32_t *>(ws + w.idxx),
-                               reinterpret_cast<int32_t *>(ws + w.idxtx), reinterpret_cast<int64_t *>(ws + w.colx),
-                               ws + w.op, reinterpret_cast<float *>(ws + w.lsep), ws + w.gop, ws + w.dqp, dK, dV,
-                               ws + w.inner, w.inner_bytes, hip_stream);
-    if (st != DSV_OK) return st;
-    return launch_group_rows(*p, *g, 2, ws + w.dqp, dQ, stream);
+    return dsv_sparse_attn_bwd_dkdv(&sorted, ws + w.qp, K, V, reinterpret_cast<int32_t *>(ws + w.idxtx),
+                                    reinterpret_cast<int64_t *>(ws + w.colx), reinterpret_cast<float *>(ws + w.lsep),
+                                    reinterpret_cast<float *>(ws + w.deltap), ws + w.gop, dK, dV, ws + w.step,
+                                    w.step_bytes, hip_stream);
 }
 
 // ------------------------------------------------------------------------------------ predictor side

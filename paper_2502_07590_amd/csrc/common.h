@@ -322,13 +322,32 @@ struct GroupGeom {
 dsv_status launch_group_rows(const dsv_problem &p, const dsv_grouping &gr, int mode, const void *in, void *out,
                              hipStream_t st);
 dsv_status launch_group_scalar(const dsv_problem &p, const dsv_grouping &gr, const float *in, float *out, hipStream_t st);
-// tabs: built for L/G rows per head.  Writes the per-query index (group-major query order) both ways.
+// tabs: built for L/G rows per head.  Writes the per-query form (group-major query order) of the key-major index,
+// and of the query-major index unless idx_x is null.
 dsv_status launch_group_expand(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
                                const int32_t *idx_g, const int32_t *idx_t_g, const int64_t *col, int32_t *idx_x,
                                int32_t *idx_t_x, int64_t *col_x, hipStream_t st);
+// Scratch of the L2-blocked grouped kernels (null seg: plain form, rows in any order).
+struct GroupedSplit {
+    SplitPlan plan;
+    int32_t *seg;   // [B*H, L/G, S+1]
+    float *pa;      // forward: pm [rows, S];          dq: C partials [rows, S, d]
+    float *pb;      // forward: pl [rows, S];          dq: B partials [rows, S, d]
+    float *pc;      // forward: pacc [rows, S, d];     dq: Delta partials [rows, S]
+};
 dsv_status launch_grouped_fwd(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
                               const void *Q, const void *K, const void *V, const int32_t *idx_g, void *O, float *lse,
-                              hipStream_t st);
+                              const GroupedSplit *split, hipStream_t st);
+dsv_status launch_grouped_dq(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
+                             const void *Q, const void *K, const void *V, const int32_t *idx_g, const void *O,
+                             const float *lse, const void *dO, void *dQ, float *delta, const GroupedSplit *split,
+                             hipStream_t st);
+dsv_status launch_row_segments(const dsv_problem &p, int rows, const HeadTable *tabs, int n_tabs, const SplitPlan &pl,
+                               const int32_t *index, int32_t *seg, hipStream_t st);
+dsv_status launch_fwd_merge_bf16_128(const dsv_problem &p, const float *pm, const float *pl_, const float *pacc, void *O,
+                                     float *lse, int S, hipStream_t st);
+dsv_status launch_dq_merge_bf16_128(const dsv_problem &p, const float *pa, const float *pb, const float *pdelta,
+                                    const void *O, const void *dO, void *dQ, float *delta, int S, hipStream_t st);
 
 // ---- predictor side (predictor.hip) ---------------------------------------------------------------------
 struct PredictorLayout {

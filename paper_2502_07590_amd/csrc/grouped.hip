@@ -126,28 +126,61 @@ __global__ __launch_bounds__(256) void scale_col_kernel(const int64_t *__restric
     if (e < n) col_x[e] = col[e] * G;
 }
 
+// Linear block id -> (head slot, key range, block of 4 groups), consecutive ids on consecutive XCDs, every XCD
+// walking its own ranges one after the other (the order of the per-query L2-blocked sweeps).
+__device__ __forceinline__ bool decode_group_item(const SplitPlan &pl, int64_t b, int &slot, int &range, int &gb)
+{
+    const int64_t per_head = (int64_t)pl.S_pad * pl.nqb;
+    slot = (int)(b / per_head);
+    const int64_t rem = b - (int64_t)slot * per_head;
+    const int xcd = (int)(rem & 7);
+    const int64_t local = rem >> 3;
+    const int t = (int)(local / pl.nqb);
+    gb = (int)(local - (int64_t)t * pl.nqb);
+    range = t * 8 + xcd;
+    return range < pl.S;
+}
+
 // ---- grouped forward ------------------------------------------------------------------------------------
-template <int D>
+// SPLIT: the L2-blocked form for ascending rows -- a block works on ONE key range (whose K + V rows stay in its
+// XCD's L2), walks only the segment of every group's row that falls into the range, and leaves the partial softmax
+// state (m, l, unnormalised acc) of every member for the per-query merge kernel; pm, pl_, pacc are laid out per
+// TOKEN row like the per-query partials.
+template <int D, bool SPLIT>
 __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                           const bf16_t *__restrict__ V,
                                                           const int32_t *__restrict__ idx_g, bf16_t *__restrict__ O,
-                                                          float *__restrict__ lse, int L, int Lq, float scale,
-                                                          HeadTable tab, GroupGeom gm)
+                                                          float *__restrict__ lse, const int32_t *__restrict__ seg,
+                                                          float *__restrict__ pm, float *__restrict__ pl_,
+                                                          float *__restrict__ pacc, int L, int Lq, float scale,
+                                                          HeadTable tab, GroupGeom gm, SplitPlan pl)
 {
     static_assert(D == 128, "lanes across the channels: 64 lanes x 2 channels");
     constexpr int NM = D / 16;
-    const int slot = blockIdx.y;
+    int slot, range = 0, gb;
+    if (SPLIT) {
+        if (!decode_group_item(pl, blockIdx.x, slot, range, gb)) return;
+    } else {
+        slot = blockIdx.y;
+        gb = blockIdx.x;
+    }
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, half = lane >> 5;
-    const int g = blockIdx.x * 4 + wave;
+    const int g = gb * 4 + wave;
     if (g >= Lq) return;  // the whole wave leaves; nothing below synchronises across waves
     const int G = gm.G;
     const bf16_t *Qh = Q + (int64_t)bh * L * D;
     const bf16_t *Kh = K + (int64_t)bh * L * D;
     const bf16_t *Vh = V + (int64_t)bh * L * D;
     const int32_t *row = idx_g + tab.off[slot] + (int64_t)g * k;
+    int tb = 0, te = k;
+    if (SPLIT) {
+        const int32_t *sp = seg + ((int64_t)bh * Lq + g) * (pl.S + 1) + range;
+        tb = sp[0];
+        te = sp[1];
+    }
 
     __shared__ __align__(16) uint32_t lds_all[4][8 * 16 + 8];
     u32_alias *P_s = lds_all[wave];                                      // [8 queries][16 key pairs] bf16 pairs
@@ -172,17 +205,37 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
     for (int q = 0; q < 8; ++q) { oacc[q][0] = 0.f; oacc[q][1] = 0.f; }
     const float c2 = scale * kLog2e;
 
-    for (int t0 = 0; t0 < k; t0 += 32) {
-        const int nvalid = min(32, k - t0);
-        // keys past the end of the row repeat its last entry and get probability zero
-        const int j = row[t0 + min(n, nvalid - 1)];
+    // Software pipeline: the index entries of tile t+1 and the K fragments of tile t+1 are requested while tile t is
+    // worked on, and all 32 V rows of a tile are requested before its scores are formed, so that every memory
+    // round trip overlaps arithmetic of the same wave.
+    // keys past the end of the segment repeat its last entry and get probability zero
+    auto load_j = [&](int t0) { return row[t0 + min(n, min(32, te - t0) - 1)]; };
+    int j = 0, j_next = 0;
+    bf16x8_t kb[NM];
+    if (tb < te) {
+        j = load_j(tb);
+#pragma unroll
+        for (int m = 0; m < NM; ++m) kb[m] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
+        j_next = tb + 32 < te ? load_j(tb + 32) : j;
+    }
+    for (int t0 = tb; t0 < te; t0 += 32) {
+        const int nvalid = min(32, te - t0);
+        uint32_t vw[32];  // the 32 V rows of the tile, this lane's two channels of each
+#pragma unroll
+        for (int kk = 0; kk < 32; ++kk) {
+            const int jk = __builtin_amdgcn_readlane(j, kk);
+            vw[kk] = reinterpret_cast<const uint32_t *>(Vh + (int64_t)jk * D)[lane];
+        }
         floatx16_t acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
-        for (int m = 0; m < NM; ++m) {
-            const bf16x8_t kb = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[m], kb, acc, 0, 0, 0);
+        for (int m = 0; m < NM; ++m) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[m], kb[m], acc, 0, 0, 0);
+        if (t0 + 32 < te) {  // wave-uniform: next tile's K fragments into the registers just consumed
+            j = j_next;
+#pragma unroll
+            for (int m = 0; m < NM; ++m) kb[m] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
+            if (t0 + 64 < te) j_next = load_j(t0 + 64);
         }
         float p[4], corr[4];
         bool moved = false;
@@ -217,10 +270,7 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
             uint32_t lo[4], hi[4];
 #pragma unroll
             for (int pr = 0; pr < 4; ++pr) {
-                const int ja = __builtin_amdgcn_readlane(j, 8 * i + 2 * pr);
-                const int jb = __builtin_amdgcn_readlane(j, 8 * i + 2 * pr + 1);
-                const uint32_t va = reinterpret_cast<const uint32_t *>(Vh + (int64_t)ja * D)[lane];
-                const uint32_t vb = reinterpret_cast<const uint32_t *>(Vh + (int64_t)jb * D)[lane];
+                const uint32_t va = vw[8 * i + 2 * pr], vb = vw[8 * i + 2 * pr + 1];
                 lo[pr] = __builtin_amdgcn_perm(vb, va, 0x05040100u);  // (a.ch[2 lane],     b.ch[2 lane])
                 hi[pr] = __builtin_amdgcn_perm(vb, va, 0x07060302u);  // (a.ch[2 lane + 1], b.ch[2 lane + 1])
             }
@@ -238,10 +288,32 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
         }
         wave_sync();  // the next tile overwrites P_s
     }
-    // normalise and write: query 4 * half + v lives in this half-wave's softmax state
+    // query 4 * half + v lives in this half-wave's softmax state
     float lt[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) lt[v] = half_sum(lsum[v]);
+    if (SPLIT) {
+        // partial state of this (member, range); an empty segment leaves (m = -inf, l = 0, acc = 0)
+        if (n == 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int q = 4 * half + v;
+                if (q < G) {
+                    const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range;
+                    pm[slot_id] = M[v];
+                    pl_[slot_id] = lt[v];
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (q < G) {
+                const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range;
+                reinterpret_cast<float2 *>(pacc + slot_id * D)[lane] = make_float2(oacc[q][0], oacc[q][1]);
+            }
+        }
+        return;
+    }
     if (n == 0) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -257,6 +329,200 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
             const float inv = fac_s[q];
             const uint32_t packed = (uint32_t)f32_to_bf16(oacc[q][0] * inv) | ((uint32_t)f32_to_bf16(oacc[q][1] * inv) << 16);
             reinterpret_cast<uint32_t *>(O + ((int64_t)bh * L + member_token(gm, g, q)) * D)[lane] = packed;
+        }
+    }
+}
+
+// ---- grouped backward, dQ step -------------------------------------------------------------------------------
+// Same tiling as the forward.  Per tile of 32 keys two score-shaped products on the matrix cores, S = Q_g K^T and
+// dP = dO_g V^T (K and V rows gathered once per group), then per pair p = 2^(s c2 - lse2), and the three sums of the
+// per-query dq sweep (stage2_core.h): C = sum p (dP - D0) k, B = sum p k, Delta = sum p dP, with D0 = dO . O_stored
+// as the centring value; dQ = scale (C - (Delta - D0) B).  C and B are accumulated on the vector units with the
+// lanes across the channels: every K row is loaded once more, coalesced, and multiplied into the 8 members'
+// accumulators with fp32 weights read from LDS as broadcasts.
+// SPLIT: per (member, range) partials C, B, Delta for the per-query dq merge kernel.
+template <int D, bool SPLIT>
+__global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                         const bf16_t *__restrict__ V, const int32_t *__restrict__ idx_g,
+                                                         const bf16_t *__restrict__ O, const float *__restrict__ lse,
+                                                         const bf16_t *__restrict__ dO, bf16_t *__restrict__ dQ,
+                                                         float *__restrict__ delta_out, const int32_t *__restrict__ seg,
+                                                         float *__restrict__ pa, float *__restrict__ pb,
+                                                         float *__restrict__ pdelta, int L, int Lq, float scale,
+                                                         HeadTable tab, GroupGeom gm, SplitPlan pl)
+{
+    static_assert(D == 128, "lanes across the channels: 64 lanes x 2 channels");
+    constexpr int NM = D / 16;
+    int slot, range = 0, gb;
+    if (SPLIT) {
+        if (!decode_group_item(pl, blockIdx.x, slot, range, gb)) return;
+    } else {
+        slot = blockIdx.y;
+        gb = blockIdx.x;
+    }
+    const int bh = tab.bh[slot];
+    const int k = tab.k[slot];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, half = lane >> 5;
+    const int g = gb * 4 + wave;
+    if (g >= Lq) return;  // whole wave
+    const int G = gm.G;
+    const int64_t hb = (int64_t)bh * L * D;
+    const bf16_t *Kh = K + hb, *Vh = V + hb;
+    const int32_t *row = idx_g + tab.off[slot] + (int64_t)g * k;
+    int tb = 0, te = k;
+    if (SPLIT) {
+        const int32_t *sp = seg + ((int64_t)bh * Lq + g) * (pl.S + 1) + range;
+        tb = sp[0];
+        te = sp[1];
+    }
+    constexpr int kKRow = D * 2 + 16;  // bytes from one staged K row to the next (padded: spreads the rows over the banks)
+    __shared__ __align__(16) float lds_all[4][32 * 16 + 16];
+    __shared__ __align__(16) unsigned char k_all[4][32 * kKRow];
+    // lds_all[wave]: [32 keys][16] = the weights wc of the 8 members, then p of the 8 members; then
+    f32_alias *q_s = lds_all[wave] + 32 * 16;   // [8] D0, then [8] Delta - D0
+    unsigned char *K_s = k_all[wave];           // the tile's 32 K rows, row-major: the second product reads them by row
+
+    // A operands: the members' Q and dO rows (zero beyond the group)
+    bf16x8_t qa[NM], ga[NM];
+    {
+        const int64_t tq = member_token(gm, g, min(n, G - 1));
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            uint4 rq = *reinterpret_cast<const uint4 *>(Q + hb + tq * D + m * 16 + half * 8);
+            uint4 rg = *reinterpret_cast<const uint4 *>(dO + hb + tq * D + m * 16 + half * 8);
+            if (n >= G) { rq = make_uint4(0u, 0u, 0u, 0u); rg = rq; }
+            qa[m] = __builtin_bit_cast(bf16x8_t, rq);
+            ga[m] = __builtin_bit_cast(bf16x8_t, rg);
+        }
+    }
+    // D0[q] = dO_q . O_q (stored, rounded O): lanes across the channels, then a wave reduction
+#pragma unroll 1
+    for (int q = 0; q < G; ++q) {
+        const int64_t t = member_token(gm, g, q);
+        const uint32_t go = reinterpret_cast<const uint32_t *>(dO + hb + t * D)[lane];
+        const uint32_t oo = reinterpret_cast<const uint32_t *>(O + hb + t * D)[lane];
+        float d = __uint_as_float(go << 16) * __uint_as_float(oo << 16) +
+                  __uint_as_float(go & 0xFFFF0000u) * __uint_as_float(oo & 0xFFFF0000u);
+        d = half_sum(d);
+        d += __shfl_xor(d, 32);
+        if (lane == 0) q_s[q] = d;
+    }
+    wave_sync();
+    float lse2[4], d0[4], dl[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int q = 4 * half + v;
+        lse2[v] = q < G ? lse[(int64_t)bh * L + member_token(gm, g, q)] * kLog2e : 0.f;
+        d0[v] = q < G ? q_s[q] : 0.f;
+        dl[v] = 0.f;
+    }
+    float accC[8][2], accB[8][2];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { accC[q][0] = accC[q][1] = accB[q][0] = accB[q][1] = 0.f; }
+    const float c2 = scale * kLog2e;
+
+    // Software pipeline as in the forward: index entries two tiles ahead, the next tile's K fragments requested as
+    // soon as the current ones are consumed.  The K rows are needed twice -- as matrix-core fragments (lane = key)
+    // and row by row with the lanes across the channels; the second form comes from LDS, where the fragments are
+    // parked, not from memory again.
+    auto load_j = [&](int t0) { return row[t0 + min(n, min(32, te - t0) - 1)]; };
+    int j = 0, j_next = 0;
+    bf16x8_t kb[NM];
+    if (tb < te) {
+        j = load_j(tb);
+#pragma unroll
+        for (int m = 0; m < NM; ++m) kb[m] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
+        j_next = tb + 32 < te ? load_j(tb + 32) : j;
+    }
+    for (int t0 = tb; t0 < te; t0 += 32) {
+        const int nvalid = min(32, te - t0);
+        bf16x8_t vb[NM];
+#pragma unroll
+        for (int m = 0; m < NM; ++m) vb[m] = *reinterpret_cast<const bf16x8_t *>(Vh + (int64_t)j * D + m * 16 + half * 8);
+        floatx16_t as, ap;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { as[i] = 0.f; ap[i] = 0.f; }
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            as = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[m], kb[m], as, 0, 0, 0);
+            *reinterpret_cast<uint4 *>(K_s + n * kKRow + (m * 16 + half * 8) * 2) = __builtin_bit_cast(uint4, kb[m]);
+        }
+        if (t0 + 32 < te) {  // wave-uniform
+            j = j_next;
+#pragma unroll
+            for (int m = 0; m < NM; ++m) kb[m] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
+            if (t0 + 64 < te) j_next = load_j(t0 + 64);
+        }
+#pragma unroll
+        for (int m = 0; m < NM; ++m) ap = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[m], vb[m], ap, 0, 0, 0);
+        float wc[4], pp[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            pp[v] = n < nvalid ? fast_exp2(as[v] * c2 - lse2[v]) : 0.f;
+            dl[v] = fmaf(pp[v], ap[v], dl[v]);
+            wc[v] = pp[v] * (ap[v] - d0[v]);
+        }
+        *reinterpret_cast<float4 *>(const_cast<float *>(lds_all[wave]) + n * 16 + 4 * half) = make_float4(wc[0], wc[1], wc[2], wc[3]);
+        *reinterpret_cast<float4 *>(const_cast<float *>(lds_all[wave]) + n * 16 + 8 + 4 * half) = make_float4(pp[0], pp[1], pp[2], pp[3]);
+        wave_sync();
+#pragma unroll 8
+        for (int kk = 0; kk < 32; ++kk) {
+            const uint32_t kw = *reinterpret_cast<const uint32_t *>(K_s + kk * kKRow + lane * 4);
+            const float lo = __uint_as_float(kw << 16), hi = __uint_as_float(kw & 0xFFFF0000u);
+            const float4 w0 = *reinterpret_cast<const float4 *>(const_cast<const float *>(lds_all[wave]) + kk * 16);
+            const float4 w1 = *reinterpret_cast<const float4 *>(const_cast<const float *>(lds_all[wave]) + kk * 16 + 4);
+            const float4 p0 = *reinterpret_cast<const float4 *>(const_cast<const float *>(lds_all[wave]) + kk * 16 + 8);
+            const float4 p1 = *reinterpret_cast<const float4 *>(const_cast<const float *>(lds_all[wave]) + kk * 16 + 12);
+            const float ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            const float pw[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                accC[q][0] = fmaf(ww[q], lo, accC[q][0]);
+                accC[q][1] = fmaf(ww[q], hi, accC[q][1]);
+                accB[q][0] = fmaf(pw[q], lo, accB[q][0]);
+                accB[q][1] = fmaf(pw[q], hi, accB[q][1]);
+            }
+        }
+        wave_sync();
+    }
+    float dt[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) dt[v] = half_sum(dl[v]);
+    if (SPLIT) {
+        if (n == 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int q = 4 * half + v;
+                if (q < G) pdelta[((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range] = dt[v];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (q < G) {
+                const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range;
+                reinterpret_cast<float2 *>(pa + slot_id * D)[lane] = make_float2(accC[q][0], accC[q][1]);
+                reinterpret_cast<float2 *>(pb + slot_id * D)[lane] = make_float2(accB[q][0], accB[q][1]);
+            }
+        }
+        return;
+    }
+    if (n == 0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int q = 4 * half + v;
+            q_s[8 + q] = dt[v] - d0[v];
+            if (q < G) delta_out[(int64_t)bh * L + member_token(gm, g, q)] = dt[v];
+        }
+    }
+    wave_sync();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        if (q < G) {
+            const float dd = q_s[8 + q];
+            const float x0 = scale * (accC[q][0] - dd * accB[q][0]), x1 = scale * (accC[q][1] - dd * accB[q][1]);
+            reinterpret_cast<uint32_t *>(dQ + hb + member_token(gm, g, q) * D)[lane] =
+                (uint32_t)f32_to_bf16(x0) | ((uint32_t)f32_to_bf16(x1) << 16);
         }
     }
 }
@@ -316,7 +582,8 @@ dsv_status launch_group_expand(const dsv_problem &p, const dsv_grouping &gr, con
     const GroupGeom gm = make_group_geom(gr);
     const int Lq = p.L / gm.G;
     for (int t = 0; t < n_tabs; ++t) {
-        hipLaunchKernelGGL(expand_idx_kernel, dim3(std::min(Lq, 8192), tabs[t].n), dim3(256), 0, st, idx_g, idx_x, Lq, gm.G, tabs[t]);
+        if (idx_x)
+            hipLaunchKernelGGL(expand_idx_kernel, dim3(std::min(Lq, 8192), tabs[t].n), dim3(256), 0, st, idx_g, idx_x, Lq, gm.G, tabs[t]);
         hipLaunchKernelGGL(expand_idx_t_kernel, dim3(8192, tabs[t].n), dim3(256), 0, st, idx_t_g, idx_t_x, Lq, gm.G, tabs[t]);
         DSV_LAUNCH_CHECK();
     }
@@ -328,20 +595,78 @@ dsv_status launch_group_expand(const dsv_problem &p, const dsv_grouping &gr, con
 
 dsv_status launch_grouped_fwd(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
                               const void *Q, const void *K, const void *V, const int32_t *idx_g, void *O, float *lse,
-                              hipStream_t st)
+                              const GroupedSplit *split, hipStream_t st)
 {
     if (p.dtype != DSV_BF16 || p.d != 128) return DSV_EUNSUPPORTED;
     const GroupGeom gm = make_group_geom(gr);
     if (gm.G > 8) return DSV_EUNSUPPORTED;
     const int Lq = p.L / gm.G;
-    KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
-    for (int t = 0; t < n_tabs; ++t) {
-        dim3 grid((Lq + 3) / 4, tabs[t].n);
-        hipLaunchKernelGGL((grouped_fwd_kernel<128>), grid, dim3(256), 0, st, (const bf16_t *)Q, (const bf16_t *)K,
-                           (const bf16_t *)V, idx_g, (bf16_t *)O, lse, p.L, Lq, p.scale, tabs[t], gm);
-        DSV_LAUNCH_CHECK();
+    if (!split) {
+        KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
+        for (int t = 0; t < n_tabs; ++t) {
+            dim3 grid((Lq + 3) / 4, tabs[t].n);
+            hipLaunchKernelGGL((grouped_fwd_kernel<128, false>), grid, dim3(256), 0, st, (const bf16_t *)Q, (const bf16_t *)K,
+                               (const bf16_t *)V, idx_g, (bf16_t *)O, lse, (const int32_t *)nullptr, (float *)nullptr,
+                               (float *)nullptr, (float *)nullptr, p.L, Lq, p.scale, tabs[t], gm, SplitPlan{});
+            DSV_LAUNCH_CHECK();
+        }
+        return DSV_OK;
     }
-    return DSV_OK;
+    SplitPlan pl = split->plan;
+    pl.nqb = (Lq + 3) / 4;
+    dsv_status rc = launch_row_segments(p, Lq, tabs, n_tabs, pl, idx_g, split->seg, st);
+    if (rc != DSV_OK) return rc;
+    {
+        KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
+        for (int t = 0; t < n_tabs; ++t) {
+            const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
+            if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
+            hipLaunchKernelGGL((grouped_fwd_kernel<128, true>), dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t *)Q,
+                               (const bf16_t *)K, (const bf16_t *)V, idx_g, (bf16_t *)O, lse, split->seg, split->pa, split->pb,
+                               split->pc, p.L, Lq, p.scale, tabs[t], gm, pl);
+            DSV_LAUNCH_CHECK();
+        }
+    }
+    return launch_fwd_merge_bf16_128(p, split->pa, split->pb, split->pc, O, lse, pl.S, st);
+}
+
+dsv_status launch_grouped_dq(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
+                             const void *Q, const void *K, const void *V, const int32_t *idx_g, const void *O,
+                             const float *lse, const void *dO, void *dQ, float *delta, const GroupedSplit *split,
+                             hipStream_t st)
+{
+    if (p.dtype != DSV_BF16 || p.d != 128) return DSV_EUNSUPPORTED;
+    const GroupGeom gm = make_group_geom(gr);
+    if (gm.G > 8) return DSV_EUNSUPPORTED;
+    const int Lq = p.L / gm.G;
+    if (!split) {
+        KernelSpan span(DSV_KERNEL_DQ_SWEEP, st);
+        for (int t = 0; t < n_tabs; ++t) {
+            dim3 grid((Lq + 3) / 4, tabs[t].n);
+            hipLaunchKernelGGL((grouped_dq_kernel<128, false>), grid, dim3(256), 0, st, (const bf16_t *)Q, (const bf16_t *)K,
+                               (const bf16_t *)V, idx_g, (const bf16_t *)O, lse, (const bf16_t *)dO, (bf16_t *)dQ, delta,
+                               (const int32_t *)nullptr, (float *)nullptr, (float *)nullptr, (float *)nullptr, p.L, Lq,
+                               p.scale, tabs[t], gm, SplitPlan{});
+            DSV_LAUNCH_CHECK();
+        }
+        return DSV_OK;
+    }
+    SplitPlan pl = split->plan;
+    pl.nqb = (Lq + 3) / 4;
+    dsv_status rc = launch_row_segments(p, Lq, tabs, n_tabs, pl, idx_g, split->seg, st);
+    if (rc != DSV_OK) return rc;
+    {
+        KernelSpan span(DSV_KERNEL_DQ_SWEEP, st);
+        for (int t = 0; t < n_tabs; ++t) {
+            const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
+            if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
+            hipLaunchKernelGGL((grouped_dq_kernel<128, true>), dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t *)Q,
+                               (const bf16_t *)K, (const bf16_t *)V, idx_g, (const bf16_t *)O, lse, (const bf16_t *)dO,
+                               (bf16_t *)dQ, delta, split->seg, split->pa, split->pb, split->pc, p.L, Lq, p.scale, tabs[t], gm, pl);
+            DSV_LAUNCH_CHECK();
+        }
+    }
+    return launch_dq_merge_bf16_128(p, split->pa, split->pb, split->pc, O, dO, dQ, delta, pl.S, st);
 }
 
 }  // namespace dsv

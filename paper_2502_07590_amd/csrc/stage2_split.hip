@@ -553,6 +553,41 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
     return DSV_OK;
 }
 
+// ---- pieces of the split plan used by the query-grouped kernels as well --------------------------------------
+// Segment pointers of `rows` ascending index rows per head (tabs built for that many rows).
+dsv_status launch_row_segments(const dsv_problem &p, int rows, const HeadTable *tabs, int n_tabs, const SplitPlan &pl,
+                               const int32_t *index, int32_t *seg, hipStream_t st)
+{
+    const int64_t n = (int64_t)rows * (pl.S + 1);
+    for (int t = 0; t < n_tabs; ++t) {
+        dim3 grid((unsigned)((n + 255) / 256), tabs[t].n);
+        hipLaunchKernelGGL(segment_ptr_kernel, grid, dim3(256), 0, st, index, (const int64_t *)nullptr, rows, tabs[t], pl, seg);
+        DSV_LAUNCH_CHECK();
+    }
+    return DSV_OK;
+}
+
+// Merges of per-(token row, range) partials, bf16 d = 128 (the grouped kernels' case).
+dsv_status launch_fwd_merge_bf16_128(const dsv_problem &p, const float *pm, const float *pl_, const float *pacc, void *O,
+                                     float *lse, int S, hipStream_t st)
+{
+    const int64_t n_rows = (int64_t)p.B * p.H * p.L;
+    hipLaunchKernelGGL((sparse_fwd_merge_kernel<bf16_t, 128>), dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st, pm, pl_,
+                       pacc, (bf16_t *)O, lse, n_rows, S);
+    DSV_LAUNCH_CHECK();
+    return DSV_OK;
+}
+
+dsv_status launch_dq_merge_bf16_128(const dsv_problem &p, const float *pa, const float *pb, const float *pdelta,
+                                    const void *O, const void *dO, void *dQ, float *delta, int S, hipStream_t st)
+{
+    const int64_t n_rows = (int64_t)p.B * p.H * p.L;
+    hipLaunchKernelGGL((sparse_bwd_dq_merge_kernel<bf16_t, 128>), dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, st, pa, pb,
+                       pdelta, (const bf16_t *)O, (const bf16_t *)dO, (bf16_t *)dQ, delta, n_rows, S, p.scale);
+    DSV_LAUNCH_CHECK();
+    return DSV_OK;
+}
+
 #define DSV_DISPATCH_TD(FN, ...)                                        \
     do {                                                                \
         if (p.dtype == DSV_BF16) {                                      \

@@ -102,9 +102,11 @@ def case(request):
     return cfg, cube, ks, t, g, idx_g
 
 
-def test_grouped_forward_matches_oracle(case):
+@pytest.mark.parametrize("blocked", [False, True], ids=["plain", "l2_blocked"])
+def test_grouped_forward_matches_oracle(case, blocked):
     cfg, cube, ks, t, g, idx_g = case
-    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, "bf16", ks, cfg.scale)
+    p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, "bf16", ks, cfg.scale, sorted_index=blocked)
+    assert (dsv.sparse_attn_fwd_grouped_workspace(p, dsv.Grouping(cfg.grid, cube)) > 0) == blocked
     grp = dsv.Grouping(cfg.grid, cube)
     flat = torch.from_numpy(np.concatenate([x.reshape(-1) for x in idx_g])).cuda()
     O, lse = dsv.sparse_attn_fwd_grouped(p, grp, g["Q"], g["K"], g["V"], flat)
@@ -118,10 +120,11 @@ def test_grouped_forward_matches_oracle(case):
         assert_close("O vs dense", O[0, 0], O_d, "bf16")
 
 
-def test_grouped_backward_matches_oracle(case):
+@pytest.mark.parametrize("blocked", [False, True], ids=["plain", "l2_blocked"])
+def test_grouped_backward_matches_oracle(case, blocked):
     cfg, cube, ks, t, g, idx_g = case
     L, G = cfg.L, cube[0] * cube[1] * cube[2]
-    p = dsv.Problem(1, cfg.H, L, cfg.d, cfg.r, "bf16", ks, cfg.scale)
+    p = dsv.Problem(1, cfg.H, L, cfg.d, cfg.r, "bf16", ks, cfg.scale, sorted_index=blocked)
     grp = dsv.Grouping(cfg.grid, cube)
     flat = torch.from_numpy(np.concatenate([x.reshape(-1) for x in idx_g])).cuda()
     # key-major lists of groups, ascending: a stable sort of the (group, key) pairs by key, written out here
@@ -154,9 +157,9 @@ def test_grouped_arguments_are_checked_on_the_host():
     bad_grid = dsv.Grouping((4, 8, 15), (2, 2, 1))        # 480 tokens, not L
     no_tiling = dsv.Grouping((4, 8, 16), (2, 3, 2))        # 3 does not divide 8
     for gg in (bad_grid, no_tiling):
-        assert lib.dsv_sparse_attn_fwd_grouped(p.c, gg.c, one, one, one, one, one, one, None) == -1
+        assert lib.dsv_sparse_attn_fwd_grouped(p.c, gg.c, one, one, one, one, one, one, None, 0, None) == -1
         assert dsv.lowrank_topk_grouped_workspace(p, gg) == 0
     big = dsv.Grouping((4, 8, 16), (2, 2, 4))              # G = 16: beyond the forward kernel's tile
-    assert lib.dsv_sparse_attn_fwd_grouped(p.c, big.c, one, one, one, one, one, one, None) == -2
+    assert lib.dsv_sparse_attn_fwd_grouped(p.c, big.c, one, one, one, one, one, one, None, 0, None) == -2
     f32 = dsv.Problem(1, 1, 512, 128, 16, "f32", [32], 0.1)
-    assert lib.dsv_sparse_attn_fwd_grouped(f32.c, dsv.Grouping((4, 8, 16), (2, 2, 2)).c, one, one, one, one, one, one, None) == -2
+    assert lib.dsv_sparse_attn_fwd_grouped(f32.c, dsv.Grouping((4, 8, 16), (2, 2, 2)).c, one, one, one, one, one, one, None, 0, None) == -2
