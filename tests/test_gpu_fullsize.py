@@ -15,7 +15,8 @@ one by one:
     the shortest, each list first checked against the column of idx by a plain device comparison;
   * stage 2 on a synthetic index tensor whose rows AND columns have a closed form (arithmetic
     progressions modulo L, from the workload generator): the same outputs with an index no device
-    code produced (uniform list lengths: the complement of the skewed real selection).
+    code produced (uniform list lengths: the complement of the skewed real selection);
+  * the query-grouped variant (configs 1 and 2, 2 x 2 x 2 cubes) the same way on its own real selection.
 """
 import numpy as np
 import pytest
@@ -269,3 +270,96 @@ def test_stage2_full_size(data, progress):
         assert_close(f"dK[h={h}, j={j}]", dK[0, h, j], dKj, cfg.dtype)
         assert_close(f"dV[h={h}, j={j}]", dV[0, h, j], dVj, cfg.dtype)
         progress(f"config {cfg.index} key {j}: {len(qs)} selecting queries checked")
+
+
+GROUPED_CONFIGS = (1, 2)     # config 2 is the shape bench.py --grouped times
+CUBE = (2, 2, 2)
+N_GROUPS = 24                # sampled groups per checked head (plus the first and the last)
+
+
+def test_grouped_full_size(data, progress):
+    """The query-grouped variant at full size, in the launch configuration bench.py --grouped times (sorted-index flag:
+    the L2-blocked grouped kernels): stage 1 on the groups' centre queries, grouped forward and backward on the index it
+    wrote.  Sampled groups: the group's row against the oracle's selection on the device's own score bits of the centre
+    query (bit-exact), then O, lse, dQ of all its members against the oracle with that row; sampled keys: the key's list
+    of groups against the column of the group index, then dK, dV against the oracle's per-key routine over the members
+    of the selecting groups."""
+    cfg, ks, g, Wq, Wk, host = data
+    if cfg.index not in GROUPED_CONFIGS:
+        pytest.skip("grouped full-size check runs at configs 1 and 2")
+    L, G = cfg.L, CUBE[0] * CUBE[1] * CUBE[2]
+    Lq = L // G
+    grp = dsv.Grouping(cfg.grid, CUBE)
+    p = dsv.Problem(1, cfg.H, L, cfg.d, cfg.r, cfg.dtype, ks, cfg.scale, sorted_index=True)
+    off = np.concatenate([[0], np.cumsum([Lq * k for k in ks])]).astype(np.int64)
+    idx_g, idx_t_g, col = dsv.lowrank_topk_grouped(p, grp, g["Q"], g["K"], Wq, Wk)
+    Qlr, Klr = dsv.lowrank_project(p, g["Q"], g["K"], Wq, Wk)
+    torch.cuda.synchronize()
+    progress(f"config {cfg.index} grouped: stage 1 done")
+    tokens = oracle.group_tokens(cfg.grid, CUBE)            # [Lq, G] token ids of every group's members
+    centre = tokens[:, oracle.group_centre(CUBE)]
+
+    def rows_of(h):
+        return idx_g[off[h]:off[h + 1]].view(Lq, ks[h])
+
+    for h in range(cfg.H):
+        part = rows_of(h)
+        assert int(part.min()) >= 0 and int(part.max()) < L
+        assert bool((part[:, 1:] > part[:, :-1]).all()), f"head {h}: group rows not strictly ascending"
+        assert int(col[h, 0]) == 0 and int(col[h, -1]) == Lq * ks[h]
+    rng = np.random.default_rng(1)
+    sampled = {}
+    for h in _host_heads(cfg):
+        groups = np.unique(np.concatenate([rng.integers(0, Lq, size=N_GROUPS), [0, Lq - 1]])).astype(np.int64)
+        S_gpu = dsv.lowrank_scores_rows(p, Qlr, Klr, 0, h, torch.from_numpy(centre[groups].astype(np.int32)).cuda())
+        torch.cuda.synchronize()
+        got = rows_of(h)[torch.from_numpy(groups).cuda()].cpu().numpy()
+        want = oracle.topk_from_scores(S_gpu.cpu().numpy().astype(np.float64), ks[h])
+        assert np.array_equal(want, got), f"head {h}: a group's row is not its centre query's selection"
+        sampled[h] = (groups, got)
+    del Qlr, Klr
+    torch.cuda.empty_cache()
+
+    O, lse = dsv.sparse_attn_fwd_grouped(p, grp, g["Q"], g["K"], g["V"], idx_g)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    dQ, dK, dV = dsv.sparse_attn_bwd_grouped(p, grp, g["Q"], g["K"], g["V"], idx_g, idx_t_g, col, O, lse, g["dO"])
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    progress(f"config {cfg.index} grouped: stage 2 done")
+    for h in _host_heads(cfg):
+        t = host[h]
+        groups, rows_g = sampled[h]
+        rows = tokens[groups].reshape(-1).astype(np.int64)            # all members of the sampled groups
+        idx_rows = np.repeat(rows_g, G, axis=0)                       # every member attends its group's row
+        O_ref, lse_ref = oracle.sparse_fwd(t["Q"][rows], t["K"], t["V"], idx_rows, cfg.scale)
+        dQ_ref = oracle.sparse_bwd_dq_rows(t["Q"][rows], t["K"], t["V"], idx_rows, t["dO"][rows], cfg.scale)
+        sel = torch.from_numpy(rows).cuda()
+        assert_close(f"grouped O[h={h}]", O[0, h][sel], O_ref, cfg.dtype)
+        assert_close(f"grouped lse[h={h}]", lse[0, h][sel], lse_ref, "f32")
+        assert_close(f"grouped dQ[h={h}]", dQ[0, h][sel], dQ_ref, cfg.dtype)
+    progress(f"config {cfg.index} grouped: O, lse, dQ of {len(rows)} member rows per checked head match")
+    h = _host_heads(cfg)[0]
+    t, k, rows_dev = host[h], ks[h], rows_of(h)
+    lens = (col[h, 1:] - col[h, :-1]).cpu().numpy()
+    capped = np.where(lens * G <= MAX_LIST, lens, -1)
+    keys = [int(capped.argmax()), int(lens.argmin())] + rng.integers(0, L, size=4).tolist()
+    for j in keys:
+        gs_dev = _column_of(rows_dev, j, Lq, k)
+        mine = idx_t_g[off[h] + int(col[h, j]):off[h] + int(col[h, j + 1])]
+        assert torch.equal(gs_dev.to(torch.int32), mine), f"key {j}: idx_t_g list is not the column of idx_g"
+        gs = gs_dev.cpu().numpy()
+        dKj, dVj = np.zeros(cfg.d), np.zeros(cfg.d)
+        step = max(1, (1 << 27) // (k * G))
+        for lo in range(0, len(gs), step):
+            part = gs[lo:lo + step]
+            members = tokens[part].reshape(-1).astype(np.int64)
+            idx_sel = np.repeat(rows_dev[gs_dev[lo:lo + step]].cpu().numpy(), G, axis=0)
+            a, b = oracle.sparse_bwd_dkdv_key(j, t["Q"][members], t["dO"][members], idx_sel, t["K"], t["V"], cfg.scale)
+            dKj += a
+            dVj += b
+        if len(gs) == 0:
+            assert float(dK[0, h, j].abs().max()) == 0.0 and float(dV[0, h, j].abs().max()) == 0.0
+        assert_close(f"grouped dK[h={h}, j={j}]", dK[0, h, j], dKj, cfg.dtype)
+        assert_close(f"grouped dV[h={h}, j={j}]", dV[0, h, j], dVj, cfg.dtype)
+        progress(f"config {cfg.index} grouped key {j}: {len(gs)} selecting groups checked")
