@@ -10,12 +10,9 @@
 //            holds key (l % 32) against queries 4 * (l / 32) + 0..3 (accumulators 0..3; the other twelve
 //            belong to the zero rows and are ignored).
 //   softmax  online, in the log2 domain; the tile maximum of a query is a reduction over the 32 lanes of a
-//            half-wave.  Probabilities go to LDS as bf16 [query][key].
-//   output   O[q, :] += p[q, key] * V[key, :] on the vector units with the lanes across the channels: every
-//            V row is loaded once, fully coalesced (one 256-byte row per load instruction), and multiplied
-//            into all G queries' accumulators (v_dot2_f32_bf16 on two keys at a time, the probability pairs
-//            read from LDS as broadcasts).  The matrix cores would need V with the keys contiguous per lane,
-//            i.e. a transpose of every gathered tile.
+//            half-wave.  Probabilities go to LDS as bf16 [query][key slot].
+//   output   O[q, :] += p[q, key] * V[key, :] on the matrix cores as well (v_mfma_f32_16x16x32_bf16, the
+//            contraction over the tile's 32 keys), the gathered V rows transposed on their way through LDS.
 // Bytes through the vector memory path per (query, key) pair: (256 + 256) / G + 4 / G instead of 516.
 #include <algorithm>
 
@@ -142,10 +139,35 @@ __device__ __forceinline__ bool decode_group_item(const SplitPlan &pl, int64_t b
 }
 
 // ---- grouped forward ------------------------------------------------------------------------------------
+// Both products of a tile run on the matrix cores.
+//   S = Q_g K^T   v_mfma_f32_32x32x16_bf16 per 16 channels: A = the group's query rows (rows >= G zero), B = the 32
+//                 gathered K rows (lane = key, 8 channels), read from the rows parked in LDS.
+//   O += P V      v_mfma_f32_16x16x32_bf16 per 16 channels: A = P (rows = queries, rows >= 8 zero), B = V with the
+//                 contraction over the tile's 32 keys.  A B fragment holds, per lane, 8 KEYS of one channel -- the
+//                 transpose of how a gathered row arrives -- so the tile's V rows are parked row-major in LDS and
+//                 read back as 16-bit columns.  Which keys a lane group contracts is free as long as A and B
+//                 agree: group g of 16 lanes takes keys 8 (e / 2) + 2 g + (e % 2), e = 0..7, which puts the four
+//                 groups' reads of one instruction on disjoint LDS banks (rows 2 apart, 272-byte rows); P is stored
+//                 with each group's keys contiguous, so its fragment is one 16-byte read.
 // SPLIT: the L2-blocked form for ascending rows -- a block works on ONE key range (whose K + V rows stay in its
 // XCD's L2), walks only the segment of every group's row that falls into the range, and leaves the partial softmax
 // state (m, l, unnormalised acc) of every member for the per-query merge kernel; pm, pl_, pacc are laid out per
 // TOKEN row like the per-query partials.
+constexpr int kVRow = 128 * 2 + 16;  // bytes from one parked row to the next
+
+// place of key n of a tile in a row of P: the 8 keys of lane group g are contiguous
+__device__ __forceinline__ int p_slot(int n) { return 8 * ((n & 7) >> 1) + 2 * (n >> 3) + (n & 1); }
+
+// B fragment of channel block nb (16 channels) from the parked rows: lane = (channel c, key group g)
+__device__ __forceinline__ bf16x8_t parked_frag(const unsigned char *rows, int nb, int c, int g)
+{
+    bf16x8_t f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        f[e] = *reinterpret_cast<const __bf16 *>(rows + (8 * (e / 2) + 2 * g + (e % 2)) * kVRow + (nb * 16 + c) * 2);
+    return f;
+}
+
 template <int D, bool SPLIT>
 __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                           const bf16_t *__restrict__ V,
@@ -155,7 +177,7 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
                                                           float *__restrict__ pacc, int L, int Lq, float scale,
                                                           HeadTable tab, GroupGeom gm, SplitPlan pl)
 {
-    static_assert(D == 128, "lanes across the channels: 64 lanes x 2 channels");
+    static_assert(D == 128, "8 channel blocks of 16");
     constexpr int NM = D / 16;
     int slot, range = 0, gb;
     if (SPLIT) {
@@ -168,6 +190,7 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
     const int k = tab.k[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, half = lane >> 5;
+    const int c16 = lane & 15, g4 = lane >> 4;
     const int g = gb * 4 + wave;
     if (g >= Lq) return;  // the whole wave leaves; nothing below synchronises across waves
     const int G = gm.G;
@@ -182,11 +205,16 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
         te = sp[1];
     }
 
-    __shared__ __align__(16) uint32_t lds_all[4][8 * 16 + 8];
-    u32_alias *P_s = lds_all[wave];                                      // [8 queries][16 key pairs] bf16 pairs
-    f32_alias *fac_s = reinterpret_cast<f32_alias *>(lds_all[wave] + 8 * 16);  // [8 queries]
+    __shared__ __align__(16) unsigned char k_all[4][32 * kVRow];
+    __shared__ __align__(16) unsigned char v_all[4][32 * kVRow];
+    __shared__ __align__(16) uint32_t p_all[4][16 * 16 + 8];
+    unsigned char *K_s = k_all[wave];                                        // the tile's 32 K rows, row-major
+    unsigned char *V_s = v_all[wave];                                        // the tile's 32 V rows
+    u32_alias *P_s = p_all[wave];                                            // [16 rows][32 key slots] bf16, rows 8.. zero
+    f32_alias *fac_s = reinterpret_cast<f32_alias *>(p_all[wave] + 16 * 16);  // [8 queries]
+    for (int e = lane; e < 16 * 16; e += 64) P_s[e] = 0u;
 
-    // A operand: query row (lane % 32) of the group, zero beyond the group
+    // A operand of the scores: query row (lane % 32) of the group, zero beyond the group
     bf16x8_t qa[NM];
     {
         const int64_t tq = member_token(gm, g, min(n, G - 1));
@@ -200,42 +228,56 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
     float M[4], lsum[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) { M[v] = -INFINITY; lsum[v] = 0.f; }
-    float oacc[8][2];
+    floatx4_t oacc[NM];  // oacc[nb][v]: query 4 * g4 + v (lane groups 0 and 1), channel 16 nb + c16
 #pragma unroll
-    for (int q = 0; q < 8; ++q) { oacc[q][0] = 0.f; oacc[q][1] = 0.f; }
+    for (int nb = 0; nb < NM; ++nb) oacc[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
     const float c2 = scale * kLog2e;
+    const int pslot = p_slot(n);
 
-    // Software pipeline: the index entries of tile t+1 and the K fragments of tile t+1 are requested while tile t is
-    // worked on, and all 32 V rows of a tile are requested before its scores are formed, so that every memory
-    // round trip overlaps arithmetic of the same wave.
-    // keys past the end of the segment repeat its last entry and get probability zero
-    auto load_j = [&](int t0) { return row[t0 + min(n, min(32, te - t0) - 1)]; };
-    int j = 0, j_next = 0;
-    bf16x8_t kb[NM];
-    if (tb < te) {
-        j = load_j(tb);
+    // Gathered rows come in whole: one load instruction fetches 4 rows, 16 lanes x 16 bytes each (every 64-byte
+    // sector the vector memory path moves is used in full; loading matrix-core fragments straight from memory
+    // would touch 32 rows x 32 bytes per instruction and waste half of every sector).  Rows go to LDS row-major;
+    // the score fragments (lane = key, 8 channels) and the transposed V fragments are read from there.
+    // Software pipeline: while tile t is worked on, the rows of tile t+1 are in flight and the index entries of
+    // tile t+2 are requested.  Keys past the end of the segment repeat its last entry and get probability zero.
+    int32_t jr[8];
+    bf16x8_t kr[8], vr[8];
+    auto load_idx = [&](int t0) {
 #pragma unroll
-        for (int m = 0; m < NM; ++m) kb[m] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
-        j_next = tb + 32 < te ? load_j(tb + 32) : j;
+        for (int i = 0; i < 8; ++i) jr[i] = row[min(t0 + g4 + 4 * i, te - 1)];
+    };
+    auto load_rows = [&]() {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            kr[i] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)jr[i] * D + c16 * 8);
+            vr[i] = *reinterpret_cast<const bf16x8_t *>(Vh + (int64_t)jr[i] * D + c16 * 8);
+        }
+    };
+    if (tb < te) {
+        load_idx(tb);
+        load_rows();
+        if (tb + 32 < te) load_idx(tb + 32);
     }
+    wave_sync();
     for (int t0 = tb; t0 < te; t0 += 32) {
         const int nvalid = min(32, te - t0);
-        uint32_t vw[32];  // the 32 V rows of the tile, this lane's two channels of each
 #pragma unroll
-        for (int kk = 0; kk < 32; ++kk) {
-            const int jk = __builtin_amdgcn_readlane(j, kk);
-            vw[kk] = reinterpret_cast<const uint32_t *>(Vh + (int64_t)jk * D)[lane];
+        for (int i = 0; i < 8; ++i) {
+            *reinterpret_cast<bf16x8_t *>(K_s + (g4 + 4 * i) * kVRow + c16 * 16) = kr[i];
+            *reinterpret_cast<bf16x8_t *>(V_s + (g4 + 4 * i) * kVRow + c16 * 16) = vr[i];
+        }
+        wave_sync();
+        if (t0 + 32 < te) {  // wave-uniform
+            load_rows();
+            if (t0 + 64 < te) load_idx(t0 + 64);
         }
         floatx16_t acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
-        for (int m = 0; m < NM; ++m) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[m], kb[m], acc, 0, 0, 0);
-        if (t0 + 32 < te) {  // wave-uniform: next tile's K fragments into the registers just consumed
-            j = j_next;
-#pragma unroll
-            for (int m = 0; m < NM; ++m) kb[m] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
-            if (t0 + 64 < te) j_next = load_j(t0 + 64);
+        for (int m = 0; m < NM; ++m) {
+            const bf16x8_t kb = *reinterpret_cast<const bf16x8_t *>(K_s + n * kVRow + (m * 16 + half * 8) * 2);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[m], kb, acc, 0, 0, 0);
         }
         float p[4], corr[4];
         bool moved = false;
@@ -251,44 +293,26 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
         }
         moved = __any(moved);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) reinterpret_cast<u16_alias *>(P_s)[(4 * half + v) * 32 + n] = f32_to_bf16(p[v]);
+        for (int v = 0; v < 4; ++v) reinterpret_cast<u16_alias *>(P_s)[(4 * half + v) * 32 + pslot] = f32_to_bf16(p[v]);
         if (moved && n == 0) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) fac_s[4 * half + v] = corr[v];
         }
         wave_sync();
         if (moved) {  // wave-uniform
+            const float4 f = *reinterpret_cast<const float4 *>(const_cast<const float *>(fac_s) + 4 * (g4 & 1));
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const float f = fac_s[q];
-                oacc[q][0] *= f;
-                oacc[q][1] *= f;
+            for (int nb = 0; nb < NM; ++nb) {
+                oacc[nb][0] *= f.x; oacc[nb][1] *= f.y; oacc[nb][2] *= f.z; oacc[nb][3] *= f.w;
             }
         }
+        const bf16x8_t pa = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(const_cast<const uint32_t *>(P_s) + c16 * 16 + g4 * 4));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {  // 8 keys = 4 key pairs at a time
-            uint32_t lo[4], hi[4];
-#pragma unroll
-            for (int pr = 0; pr < 4; ++pr) {
-                const uint32_t va = vw[8 * i + 2 * pr], vb = vw[8 * i + 2 * pr + 1];
-                lo[pr] = __builtin_amdgcn_perm(vb, va, 0x05040100u);  // (a.ch[2 lane],     b.ch[2 lane])
-                hi[pr] = __builtin_amdgcn_perm(vb, va, 0x07060302u);  // (a.ch[2 lane + 1], b.ch[2 lane + 1])
-            }
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const uint4 w = *reinterpret_cast<const uint4 *>(const_cast<const uint32_t *>(lds_all[wave]) + q * 16 + 4 * i);
-                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-                for (int pr = 0; pr < 4; ++pr) {
-                    const bf16x2_t wp = __builtin_bit_cast(bf16x2_t, ww[pr]);
-                    oacc[q][0] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, lo[pr]), wp, oacc[q][0], false);
-                    oacc[q][1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, hi[pr]), wp, oacc[q][1], false);
-                }
-            }
-        }
-        wave_sync();  // the next tile overwrites P_s
+        for (int nb = 0; nb < NM; ++nb)
+            oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, parked_frag(V_s, nb, c16, g4), oacc[nb], 0, 0, 0);
+        wave_sync();  // the next tile overwrites P_s and V_s
     }
-    // query 4 * half + v lives in this half-wave's softmax state
+    // query 4 * half + v lives in this half-wave's softmax state; the output rows of queries 4 * g4 + v in lane groups 0, 1
     float lt[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) lt[v] = half_sum(lsum[v]);
@@ -305,11 +329,15 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
                 }
             }
         }
+        if (g4 < 2) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            if (q < G) {
-                const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range;
-                reinterpret_cast<float2 *>(pacc + slot_id * D)[lane] = make_float2(oacc[q][0], oacc[q][1]);
+            for (int v = 0; v < 4; ++v) {
+                const int q = 4 * g4 + v;
+                if (q < G) {
+                    const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range;
+#pragma unroll
+                    for (int nb = 0; nb < NM; ++nb) pacc[slot_id * D + nb * 16 + c16] = oacc[nb][v];
+                }
             }
         }
         return;
@@ -323,12 +351,16 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
         }
     }
     wave_sync();
+    if (g4 < 2) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        if (q < G) {
-            const float inv = fac_s[q];
-            const uint32_t packed = (uint32_t)f32_to_bf16(oacc[q][0] * inv) | ((uint32_t)f32_to_bf16(oacc[q][1] * inv) << 16);
-            reinterpret_cast<uint32_t *>(O + ((int64_t)bh * L + member_token(gm, g, q)) * D)[lane] = packed;
+        for (int v = 0; v < 4; ++v) {
+            const int q = 4 * g4 + v;
+            if (q < G) {
+                const float inv = fac_s[q];
+                bf16_t *orow = O + ((int64_t)bh * L + member_token(gm, g, q)) * D;
+#pragma unroll
+                for (int nb = 0; nb < NM; ++nb) orow[nb * 16 + c16] = f32_to_bf16(oacc[nb][v] * inv);
+            }
         }
     }
 }
