@@ -366,13 +366,41 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
 }
 
 // ---- grouped backward, dQ step -------------------------------------------------------------------------------
-// Same tiling as the forward.  Per tile of 32 keys two score-shaped products on the matrix cores, S = Q_g K^T and
-// dP = dO_g V^T (K and V rows gathered once per group), then per pair p = 2^(s c2 - lse2), and the three sums of the
-// per-query dq sweep (stage2_core.h): C = sum p (dP - D0) k, B = sum p k, Delta = sum p dP, with D0 = dO . O_stored
-// as the centring value; dQ = scale (C - (Delta - D0) B).  C and B are accumulated on the vector units with the
-// lanes across the channels: every K row is loaded once more, coalesced, and multiplied into the 8 members'
-// accumulators with fp32 weights read from LDS as broadcasts.
+// Same tiling and the same row parking as the forward.  Per tile of 32 keys:
+//   S = Q_g K^T and dP = dO_g V^T   v_mfma_f32_16x16x32_bf16 (16 keys x 16 query rows, 32 channels per instruction;
+//        the A fragments of 8 real query rows cost 16 registers instead of the 32 of the 32-row form), B fragments
+//        read from the parked rows.  Lane l < 32 then holds queries 4 (l / 16) + 0..3 against keys (l % 16) and
+//        16 + (l % 16); the upper half-wave holds the zero rows.
+//   per pair  p = 2^(s c2 - lse2), and the three sums of the per-query dq sweep (stage2_core.h):
+//        C = sum p (dP - D0) k, B = sum p k, Delta = sum p dP, with D0 = dO . O_stored as the centring value;
+//        dQ = scale (C - (Delta - D0) B).
+//   C and B   one product on the matrix cores, v_mfma_f32_32x32x16_bf16 with the contraction over the keys: the 32
+//        A rows are the weights p (dP - D0) of the 8 members as bf16 head and tail (rows 0..7, 8..15) and p as head
+//        and tail (rows 16..23, 24..31) -- two bf16 terms carry 16 significant bits of every fp32 weight -- and B is
+//        K transposed, read from the parked rows as 16-bit columns.  Lane group h of a fragment takes keys
+//        16 s + 8 (e / 4) + 4 h + (e % 4) of k-step s: rows 4 apart, i.e. disjoint LDS banks for the two groups.
 // SPLIT: per (member, range) partials C, B, Delta for the per-query dq merge kernel.
+
+// place of key n of a tile in a row of the weight matrix: the 8 keys of (k-step, lane group) are contiguous
+__device__ __forceinline__ int w_slot(int n) { return (n & 16) + 8 * ((n & 7) >> 2) + 4 * ((n & 15) >> 3) + (n & 3); }
+
+// B fragment of channel block nb (32 channels), k-step s, from the parked rows: lane = (channel c, key group h)
+__device__ __forceinline__ bf16x8_t parked_frag32(const unsigned char *rows, int nb, int s, int c, int h)
+{
+    bf16x8_t f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        f[e] = *reinterpret_cast<const __bf16 *>(rows + (16 * s + 8 * (e / 4) + 4 * h + (e % 4)) * kVRow + (nb * 32 + c) * 2);
+    return f;
+}
+
+// x = head + tail as two bf16 values (head = x rounded to bf16, tail = the rounded remainder)
+__device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
+{
+    hi = f32_to_bf16(x);
+    lo = f32_to_bf16(x - __uint_as_float((uint32_t)hi << 16));
+}
+
 template <int D, bool SPLIT>
 __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                          const bf16_t *__restrict__ V, const int32_t *__restrict__ idx_g,
@@ -383,8 +411,8 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
                                                          float *__restrict__ pdelta, int L, int Lq, float scale,
                                                          HeadTable tab, GroupGeom gm, SplitPlan pl)
 {
-    static_assert(D == 128, "lanes across the channels: 64 lanes x 2 channels");
-    constexpr int NM = D / 16;
+    static_assert(D == 128, "4 channel blocks of 32");
+    constexpr int NC = D / 32;
     int slot, range = 0, gb;
     if (SPLIT) {
         if (!decode_group_item(pl, blockIdx.x, slot, range, gb)) return;
@@ -396,6 +424,7 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
     const int k = tab.k[slot];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, half = lane >> 5;
+    const int c16 = lane & 15, g4 = lane >> 4;
     const int g = gb * 4 + wave;
     if (g >= Lq) return;  // whole wave
     const int G = gm.G;
@@ -408,22 +437,24 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
         tb = sp[0];
         te = sp[1];
     }
-    constexpr int kKRow = D * 2 + 16;  // bytes from one staged K row to the next (padded: spreads the rows over the banks)
-    __shared__ __align__(16) float lds_all[4][32 * 16 + 16];
-    __shared__ __align__(16) unsigned char k_all[4][32 * kKRow];
-    // lds_all[wave]: [32 keys][16] = the weights wc of the 8 members, then p of the 8 members; then
-    f32_alias *q_s = lds_all[wave] + 32 * 16;   // [8] D0, then [8] Delta - D0
-    unsigned char *K_s = k_all[wave];           // the tile's 32 K rows, row-major: the second product reads them by row
+    __shared__ __align__(16) unsigned char k_all[4][32 * kVRow];
+    __shared__ __align__(16) unsigned char v_all[4][32 * kVRow];
+    __shared__ __align__(16) uint32_t w_all[4][32 * 16 + 16];
+    unsigned char *K_s = k_all[wave];   // the tile's 32 K rows, row-major
+    unsigned char *V_s = v_all[wave];   // the tile's 32 V rows
+    u32_alias *W_s = w_all[wave];       // [32 rows][32 key slots] bf16: weights of the second product
+    f32_alias *q_s = reinterpret_cast<f32_alias *>(w_all[wave] + 32 * 16);  // [8] D0, then [8] Delta - D0
 
-    // A operands: the members' Q and dO rows (zero beyond the group)
-    bf16x8_t qa[NM], ga[NM];
+    // A operands of the score-shaped products: the members' Q and dO rows (zero beyond the group), 16-row form:
+    // lane = (row l % 16, channels 32 m + 8 (l / 16) .. + 8)
+    bf16x8_t qa[4], ga[4];
     {
-        const int64_t tq = member_token(gm, g, min(n, G - 1));
+        const int64_t tq = member_token(gm, g, min(c16, G - 1));
 #pragma unroll
-        for (int m = 0; m < NM; ++m) {
-            uint4 rq = *reinterpret_cast<const uint4 *>(Q + hb + tq * D + m * 16 + half * 8);
-            uint4 rg = *reinterpret_cast<const uint4 *>(dO + hb + tq * D + m * 16 + half * 8);
-            if (n >= G) { rq = make_uint4(0u, 0u, 0u, 0u); rg = rq; }
+        for (int m = 0; m < 4; ++m) {
+            uint4 rq = *reinterpret_cast<const uint4 *>(Q + hb + tq * D + m * 32 + g4 * 8);
+            uint4 rg = *reinterpret_cast<const uint4 *>(dO + hb + tq * D + m * 32 + g4 * 8);
+            if (c16 >= G) { rq = make_uint4(0u, 0u, 0u, 0u); rg = rq; }
             qa[m] = __builtin_bit_cast(bf16x8_t, rq);
             ga[m] = __builtin_bit_cast(bf16x8_t, rg);
         }
@@ -441,120 +472,129 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
         if (lane == 0) q_s[q] = d;
     }
     wave_sync();
+    // softmax-side state of the lanes that hold real query rows after the 16-row products: queries 4 g4 + v, g4 < 2
     float lse2[4], d0[4], dl[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        const int q = 4 * half + v;
+        const int q = 4 * (g4 & 1) + v;
         lse2[v] = q < G ? lse[(int64_t)bh * L + member_token(gm, g, q)] * kLog2e : 0.f;
         d0[v] = q < G ? q_s[q] : 0.f;
         dl[v] = 0.f;
     }
-    float accC[8][2], accB[8][2];
+    floatx16_t acc2[NC];  // acc2[nb][4 part + i]: query 4 half + i, channel 32 nb + n; parts: C head, C tail, B head, B tail
 #pragma unroll
-    for (int q = 0; q < 8; ++q) { accC[q][0] = accC[q][1] = accB[q][0] = accB[q][1] = 0.f; }
+    for (int nb = 0; nb < NC; ++nb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc2[nb][i] = 0.f;
     const float c2 = scale * kLog2e;
 
-    // Software pipeline as in the forward: index entries two tiles ahead, the next tile's K fragments requested as
-    // soon as the current ones are consumed.  The K rows are needed twice -- as matrix-core fragments (lane = key)
-    // and row by row with the lanes across the channels; the second form comes from LDS, where the fragments are
-    // parked, not from memory again.
-    auto load_j = [&](int t0) { return row[t0 + min(n, min(32, te - t0) - 1)]; };
-    int j = 0, j_next = 0;
-    bf16x8_t kb[NM];
-    if (tb < te) {
-        j = load_j(tb);
+    // rows loaded whole and parked in LDS, software-pipelined, as in the forward
+    int32_t jr[8];
+    bf16x8_t kr[8], vr[8];
+    auto load_idx = [&](int t0) {
 #pragma unroll
-        for (int m = 0; m < NM; ++m) kb[m] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
-        j_next = tb + 32 < te ? load_j(tb + 32) : j;
+        for (int i = 0; i < 8; ++i) jr[i] = row[min(t0 + g4 + 4 * i, te - 1)];
+    };
+    auto load_rows = [&]() {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            kr[i] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)jr[i] * D + c16 * 8);
+            vr[i] = *reinterpret_cast<const bf16x8_t *>(Vh + (int64_t)jr[i] * D + c16 * 8);
+        }
+    };
+    if (tb < te) {
+        load_idx(tb);
+        load_rows();
+        if (tb + 32 < te) load_idx(tb + 32);
     }
     for (int t0 = tb; t0 < te; t0 += 32) {
         const int nvalid = min(32, te - t0);
-        bf16x8_t vb[NM];
 #pragma unroll
-        for (int m = 0; m < NM; ++m) vb[m] = *reinterpret_cast<const bf16x8_t *>(Vh + (int64_t)j * D + m * 16 + half * 8);
-        floatx16_t as, ap;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { as[i] = 0.f; ap[i] = 0.f; }
-#pragma unroll
-        for (int m = 0; m < NM; ++m) {
-            as = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[m], kb[m], as, 0, 0, 0);
-            *reinterpret_cast<uint4 *>(K_s + n * kKRow + (m * 16 + half * 8) * 2) = __builtin_bit_cast(uint4, kb[m]);
+        for (int i = 0; i < 8; ++i) {
+            *reinterpret_cast<bf16x8_t *>(K_s + (g4 + 4 * i) * kVRow + c16 * 16) = kr[i];
+            *reinterpret_cast<bf16x8_t *>(V_s + (g4 + 4 * i) * kVRow + c16 * 16) = vr[i];
         }
-        if (t0 + 32 < te) {  // wave-uniform
-            j = j_next;
-#pragma unroll
-            for (int m = 0; m < NM; ++m) kb[m] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)j * D + m * 16 + half * 8);
-            if (t0 + 64 < te) j_next = load_j(t0 + 64);
-        }
-#pragma unroll
-        for (int m = 0; m < NM; ++m) ap = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[m], vb[m], ap, 0, 0, 0);
-        float wc[4], pp[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            pp[v] = n < nvalid ? fast_exp2(as[v] * c2 - lse2[v]) : 0.f;
-            dl[v] = fmaf(pp[v], ap[v], dl[v]);
-            wc[v] = pp[v] * (ap[v] - d0[v]);
-        }
-        *reinterpret_cast<float4 *>(const_cast<float *>(lds_all[wave]) + n * 16 + 4 * half) = make_float4(wc[0], wc[1], wc[2], wc[3]);
-        *reinterpret_cast<float4 *>(const_cast<float *>(lds_all[wave]) + n * 16 + 8 + 4 * half) = make_float4(pp[0], pp[1], pp[2], pp[3]);
         wave_sync();
-#pragma unroll 8
-        for (int kk = 0; kk < 32; ++kk) {
-            const uint32_t kw = *reinterpret_cast<const uint32_t *>(K_s + kk * kKRow + lane * 4);
-            const float lo = __uint_as_float(kw << 16), hi = __uint_as_float(kw & 0xFFFF0000u);
-            const float4 w0 = *reinterpret_cast<const float4 *>(const_cast<const float *>(lds_all[wave]) + kk * 16);
-            const float4 w1 = *reinterpret_cast<const float4 *>(const_cast<const float *>(lds_all[wave]) + kk * 16 + 4);
-            const float4 p0 = *reinterpret_cast<const float4 *>(const_cast<const float *>(lds_all[wave]) + kk * 16 + 8);
-            const float4 p1 = *reinterpret_cast<const float4 *>(const_cast<const float *>(lds_all[wave]) + kk * 16 + 12);
-            const float ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-            const float pw[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        if (t0 + 32 < te) {  // wave-uniform
+            load_rows();
+            if (t0 + 64 < te) load_idx(t0 + 64);
+        }
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                accC[q][0] = fmaf(ww[q], lo, accC[q][0]);
-                accC[q][1] = fmaf(ww[q], hi, accC[q][1]);
-                accB[q][0] = fmaf(pw[q], lo, accB[q][0]);
-                accB[q][1] = fmaf(pw[q], hi, accB[q][1]);
+        for (int s = 0; s < 2; ++s) {  // keys 16 s + c16
+            floatx4_t as = {0.f, 0.f, 0.f, 0.f}, ap = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const bf16x8_t kb = *reinterpret_cast<const bf16x8_t *>(K_s + (16 * s + c16) * kVRow + (m * 32 + g4 * 8) * 2);
+                const bf16x8_t vb = *reinterpret_cast<const bf16x8_t *>(V_s + (16 * s + c16) * kVRow + (m * 32 + g4 * 8) * 2);
+                as = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[m], kb, as, 0, 0, 0);
+                ap = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ga[m], vb, ap, 0, 0, 0);
+            }
+            if (g4 < 2) {  // the half-wave with the real query rows
+                const int key = 16 * s + c16;
+                const int ws = w_slot(key);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float pp = key < nvalid ? fast_exp2(as[v] * c2 - lse2[v]) : 0.f;
+                    dl[v] = fmaf(pp, ap[v], dl[v]);
+                    const float wc = pp * (ap[v] - d0[v]);
+                    uint16_t hi, lo;
+                    const int r = 4 * g4 + v;
+                    split_bf16(wc, hi, lo);
+                    reinterpret_cast<u16_alias *>(W_s)[r * 32 + ws] = hi;
+                    reinterpret_cast<u16_alias *>(W_s)[(8 + r) * 32 + ws] = lo;
+                    split_bf16(pp, hi, lo);
+                    reinterpret_cast<u16_alias *>(W_s)[(16 + r) * 32 + ws] = hi;
+                    reinterpret_cast<u16_alias *>(W_s)[(24 + r) * 32 + ws] = lo;
+                }
             }
         }
         wave_sync();
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const bf16x8_t wa = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(const_cast<const uint32_t *>(W_s) + n * 16 + s * 8 + half * 4));
+#pragma unroll
+            for (int nb = 0; nb < NC; ++nb)
+                acc2[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, parked_frag32(K_s, nb, s, n, half), acc2[nb], 0, 0, 0);
+        }
+        wave_sync();  // the next tile overwrites the parked rows and W_s
     }
+    // Delta of query 4 g4 + v: sum over the 16 lanes of the row group (both key sub-tiles are already in dl)
     float dt[4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) dt[v] = half_sum(dl[v]);
+    for (int v = 0; v < 4; ++v) dt[v] = row16_sum(dl[v]);
+    if (g4 < 2 && c16 == 0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) q_s[8 + 4 * g4 + v] = dt[v];
+    }
+    wave_sync();
     if (SPLIT) {
-        if (n == 0) {
+        if (lane < G) pdelta[((int64_t)bh * L + member_token(gm, g, lane)) * pl.S + range] = q_s[8 + lane];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int q = 4 * half + v;
-                if (q < G) pdelta[((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range] = dt[v];
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int i = 0; i < 4; ++i) {
+            const int q = 4 * half + i;
             if (q < G) {
                 const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range;
-                reinterpret_cast<float2 *>(pa + slot_id * D)[lane] = make_float2(accC[q][0], accC[q][1]);
-                reinterpret_cast<float2 *>(pb + slot_id * D)[lane] = make_float2(accB[q][0], accB[q][1]);
+#pragma unroll
+                for (int nb = 0; nb < NC; ++nb) {
+                    pa[slot_id * D + nb * 32 + n] = acc2[nb][i] + acc2[nb][4 + i];
+                    pb[slot_id * D + nb * 32 + n] = acc2[nb][8 + i] + acc2[nb][12 + i];
+                }
             }
         }
         return;
     }
-    if (n == 0) {
+    if (lane < G) delta_out[(int64_t)bh * L + member_token(gm, g, lane)] = q_s[8 + lane];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int q = 4 * half + v;
-            q_s[8 + q] = dt[v] - d0[v];
-            if (q < G) delta_out[(int64_t)bh * L + member_token(gm, g, q)] = dt[v];
-        }
-    }
-    wave_sync();
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int i = 0; i < 4; ++i) {
+        const int q = 4 * half + i;
         if (q < G) {
-            const float dd = q_s[8 + q];
-            const float x0 = scale * (accC[q][0] - dd * accB[q][0]), x1 = scale * (accC[q][1] - dd * accB[q][1]);
-            reinterpret_cast<uint32_t *>(dQ + hb + member_token(gm, g, q) * D)[lane] =
-                (uint32_t)f32_to_bf16(x0) | ((uint32_t)f32_to_bf16(x1) << 16);
+            const float dd = q_s[8 + q] - q_s[q];
+            bf16_t *qrow = dQ + hb + member_token(gm, g, q) * D;
+#pragma unroll
+            for (int nb = 0; nb < NC; ++nb) {
+                const float cc = acc2[nb][i] + acc2[nb][4 + i], bb = acc2[nb][8 + i] + acc2[nb][12 + i];
+                qrow[nb * 32 + n] = f32_to_bf16(scale * (cc - dd * bb));
+            }
         }
     }
 }
