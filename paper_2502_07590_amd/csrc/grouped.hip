@@ -112,8 +112,20 @@ __global__ __launch_bounds__(256) void expand_idx_t_kernel(const int32_t *__rest
     const int32_t *src = idx_t_g + tab.off[slot];
     int32_t *dst = idx_t_x + tab.off[slot] * G;
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n * G; e += stride)
-        dst[e] = src[e / G] * G + (int32_t)(e % G);
+    // one thread per source entry; its G outputs are contiguous (G = 8: two 16-byte stores; tab.off is a multiple
+    // of the row length, the output stays 16-byte aligned whenever that is a multiple of 4 entries)
+    const bool wide = G == 8 && ((tab.off[slot] * G) & 3) == 0;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += stride) {
+        const int32_t b = src[e] * G;
+        if (wide) {
+            int4 *o = reinterpret_cast<int4 *>(dst + e * 8);
+            o[0] = make_int4(b, b + 1, b + 2, b + 3);
+            o[1] = make_int4(b + 4, b + 5, b + 6, b + 7);
+        } else {
+#pragma unroll 1
+            for (int m = 0; m < G; ++m) dst[e * G + m] = b + m;
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void scale_col_kernel(const int64_t *__restrict__ col, int64_t *__restrict__ col_x,
