@@ -587,6 +587,17 @@ def main():
             pass
         torch.cuda.empty_cache()
         out["grouped"] = grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, max(args.steps, 2), 1, dense_ms, ms_per_step)
+        # the grouped step at other densities (same shape, uniform k) and where it meets dense attention
+        gsweep = []
+        for frac in (0.03125, 0.0625, 0.10, 0.125, 0.1875, 0.25):
+            kk = max(1, int(round(cfg.L * frac)))
+            r = grouped_report(dsv, torch, np, wl, cfg, [kk] * cfg.H, g, Wq, Wk, 2, 1, dense_ms, ms_per_step)
+            gsweep.append({"density": frac, "k": kk, "ms_per_step": r["ms_per_step"], "stage_ms": r["stage_ms"],
+                           "speedup_over_dense": r["speedup_over_dense"]})
+            print(json.dumps(gsweep[-1]), file=sys.stderr, flush=True)
+        out["grouped"]["density_sweep"] = gsweep
+        if dense_ms:
+            out["grouped"]["crossover_density"] = interpolate_crossover([(s_["density"], s_["ms_per_step"]) for s_ in gsweep], dense_ms)
         out["grouped"]["accuracy"] = grouping_accuracy(dsv, torch, np, wl, cfg, args.seed)
 
     if args.predictor:
