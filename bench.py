@@ -80,6 +80,8 @@ def parse_args():
     ap.add_argument("--grouped", action="store_true",
                     help="also time the query-grouped variant (2 x 2 x 2 cubes) at the same shape, and measure what the "
                          "shared rows cost in accuracy on spatially smooth inputs")
+    ap.add_argument("--grouped-density-sweep", action="store_true",
+                    help="with --grouped: the grouped step at k/L = 3.1 ... 25 % and its interpolated crossover with dense")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the steps, run one plain elementwise copy kernel (x + 0 over this many MiB of int32) "
                          "so that a rocprofv3 --pmc run holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -580,7 +582,7 @@ def main():
             out["crossover_density"] = interpolate_crossover([(s_["density"], s_["ms_per_step"]) for s_ in sweep], dense_ms)
 
     # ---- query-grouped variant (the paper's answer to the per-query gather cost) --------------------
-    if args.grouped:
+    if args.grouped or args.grouped_density_sweep:
         try:
             del path
         except NameError:
@@ -589,14 +591,15 @@ def main():
         out["grouped"] = grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, max(args.steps, 2), 1, dense_ms, ms_per_step)
         # the grouped step at other densities (same shape, uniform k) and where it meets dense attention
         gsweep = []
-        for frac in (0.03125, 0.0625, 0.10, 0.125, 0.1875, 0.25):
+        for frac in ((0.03125, 0.0625, 0.10, 0.125, 0.1875, 0.25) if args.grouped_density_sweep else ()):
             kk = max(1, int(round(cfg.L * frac)))
             r = grouped_report(dsv, torch, np, wl, cfg, [kk] * cfg.H, g, Wq, Wk, 2, 1, dense_ms, ms_per_step)
             gsweep.append({"density": frac, "k": kk, "ms_per_step": r["ms_per_step"], "stage_ms": r["stage_ms"],
                            "speedup_over_dense": r["speedup_over_dense"]})
             print(json.dumps(gsweep[-1]), file=sys.stderr, flush=True)
-        out["grouped"]["density_sweep"] = gsweep
-        if dense_ms:
+        if gsweep:
+            out["grouped"]["density_sweep"] = gsweep
+        if gsweep and dense_ms:
             out["grouped"]["crossover_density"] = interpolate_crossover([(s_["density"], s_["ms_per_step"]) for s_ in gsweep], dense_ms)
         out["grouped"]["accuracy"] = grouping_accuracy(dsv, torch, np, wl, cfg, args.seed)
 
