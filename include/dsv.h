@@ -139,7 +139,12 @@ DSV_API dsv_status dsv_sparse_attn_fwd(const dsv_problem *p, const void *Q, cons
  * Delta is formed from the per-pair terms in fp32 rather than from the storage-rounded O, whose
  * rounding alone would cost more than the output tolerance; O only serves as a centring value
  * (dO . O is within rounding of Delta) that keeps the accumulated weights small.  The workspace holds Delta, the transposed index
- * (as large as idx) and its column pointers. */
+ * (as large as idx), its column pointers and the counters of dsv_idx_transpose.  The transposed index built here has
+ * ascending lists whatever the order inside the rows of idx is, so the dkdv step always runs its L2-blocked kernel
+ * and the results are identical, bit for bit, to dsv_sparse_attn_bwd_t on dsv_idx_transpose's output and from run to
+ * run.  The transposition is a scatter of 4-byte entries and costs more than either sweep on long sequences
+ * (L = 131072, k = 8192, 6 heads: 640 ms of 910); callers that run stage 1 here should take its transposed index
+ * (dsv_lowrank_topk_t) and call dsv_sparse_attn_bwd_t. */
 DSV_API size_t dsv_sparse_attn_bwd_workspace(const dsv_problem *p);
 DSV_API dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *K, const void *V,
                                const int32_t *idx, const void *O, const float *lse, const void *dO,
@@ -167,9 +172,10 @@ DSV_API dsv_status dsv_sparse_attn_bwd_t(const dsv_problem *p, const void *Q, co
  * dsv_idx_transpose: for every (b, h) and key j, the list of queries i whose idx row holds j.
  *   idx_t: int32, same ragged layout and size as idx (per head, the lists of key 0, 1, ... back to
  *   back); col_ptr: int64 [B*H, L+1], list of key j of head bh = idx_t[off[bh] + col_ptr[bh][j] ..
- *   off[bh] + col_ptr[bh][j+1]).  The order of the queries inside a list is unspecified (it comes
- *   from atomic cursors), so its output must not be combined with DSV_FLAG_SORTED_INDEX in the
- *   dkdv step.  Workspace: one int32 counter per (b, h, key).
+ *   off[bh] + col_ptr[bh][j+1]).  A stable counting sort: every list is in ascending query order whatever the
+ *   order inside the rows of idx is, and the output is the same from run to run; for rows as stage 1 writes them
+ *   it equals dsv_lowrank_topk_t's idx_t.  Workspace: int32 counters per (b, h, key) and per (b, h, chunk of
+ *   query rows, key), at most 257 per (b, h, key).
  *
  * dsv_sparse_attn_bwd_dkdv: key-major sweep over idx_t.  Writes dK, dV [B, H, L, d] (`dtype`);
  *   keys with an empty list get zeros.

@@ -200,11 +200,15 @@ BwdLayout bwd_layout(const dsv_problem &p, bool own_transpose)
     size_t o = 0;
     w.delta = o; o = align_up(o + tok * 4, 256);
     if (own_transpose) {
-        w.cnt = o; w.cnt_bytes = align_up(tok * 4, 256); o += w.cnt_bytes;
+        w.cnt = o; w.cnt_bytes = idx_transpose_bytes(p); o += w.cnt_bytes;
         w.col = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
         w.idxT = o; o = align_up(o + total_pairs(p) * 4, 256);
     }
-    w.step = o; w.step_bytes = step_layout(p).total; o += w.step_bytes;
+    // own_transpose: the lists come out ascending, so the dkdv step runs the L2-blocked kernel whatever p.flags says
+    dsv_problem sorted = p;
+    sorted.flags |= DSV_FLAG_SORTED_INDEX;
+    w.step = o; w.step_bytes = own_transpose ? std::max(step_layout(p).total, step_layout(sorted).total) : step_layout(p).total;
+    o += w.step_bytes;
     w.total = o;
     return w;
 }
@@ -405,7 +409,7 @@ dsv_status dsv_sparse_attn_bwd_dq(const dsv_problem *p, const void *Q, const voi
 size_t dsv_idx_transpose_workspace(const dsv_problem *p)
 {
     if (check_problem(p, false) != DSV_OK) return 0;
-    return align_up((size_t)p->B * p->H * p->L * 4, 256);
+    return idx_transpose_bytes(*p);
 }
 
 dsv_status dsv_idx_transpose(const dsv_problem *p, const int32_t *idx, int32_t *idx_t, int64_t *col_ptr,
@@ -472,10 +476,11 @@ dsv_status dsv_sparse_attn_bwd(const dsv_problem *p, const void *Q, const void *
     if (st != DSV_OK) return st;
     st = dsv_idx_transpose(p, idx, idx_t, col, ws + w.cnt, w.cnt_bytes, hip_stream);
     if (st != DSV_OK) return st;
-    // the lists built here are in no particular order: the dkdv step must not assume sorted lists
-    dsv_problem unsorted = *p;
-    unsorted.flags &= ~DSV_FLAG_SORTED_INDEX;
-    return dsv_sparse_attn_bwd_dkdv(&unsorted, Q, K, V, idx_t, col, lse, delta, dO, dK, dV, nullptr, 0, hip_stream);
+    // the lists built here are ascending in the query index whatever the order inside the rows of idx is: the dkdv
+    // step may run the L2-blocked kernel
+    dsv_problem sorted = *p;
+    sorted.flags |= DSV_FLAG_SORTED_INDEX;
+    return dsv_sparse_attn_bwd_dkdv(&sorted, Q, K, V, idx_t, col, lse, delta, dO, dK, dV, ws + w.step, w.step_bytes, hip_stream);
 }
 
 size_t dsv_sparse_attn_bwd_t_workspace(const dsv_problem *p)

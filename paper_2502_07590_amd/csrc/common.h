@@ -369,7 +369,9 @@ dsv_status launch_profile_sparsity(const dsv_problem &p, const void *Q, const vo
 // report_dev: two 64-bit counters in device memory; report_host: optional HOST int64 [3].  Waits for the stream.
 dsv_status launch_idx_validate(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
                                unsigned long long *report_dev, int64_t *report_host, hipStream_t st);
-// cnt: [B*H, L] int32 scratch (cnt_bytes = its size rounded up to 16); col: [B*H, L+1] int64.
+// Stable transposition: every list ascending in the query index, the same result from run to run.
+// cnt: scratch of idx_transpose_bytes(p) bytes (per-key totals, then per-(query chunk, key) counters); col: [B*H, L+1] int64.
+size_t idx_transpose_bytes(const dsv_problem &p);
 dsv_status launch_idx_transpose(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
                                 int32_t *idxT, int64_t *col, int32_t *cnt, size_t cnt_bytes, hipStream_t st);
 

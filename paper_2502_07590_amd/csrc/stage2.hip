@@ -151,30 +151,66 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_kernel(const T *__restric
 }
 
 // ---- transposed index: for every key, the list of queries whose row holds it ----------------
-// Counting sort by key.  cnt[bh, j] = number of rows holding j; col[bh, j] = exclusive prefix sum;
-// the fill pass appends each query to its keys' lists through an atomic cursor, so the order
-// inside a list is not fixed (only the fp32 summation order of dK, dV depends on it).
-__global__ __launch_bounds__(256) void tindex_count_kernel(const int32_t *__restrict__ idx, int L, HeadTable tab,
-                                                           int32_t *__restrict__ cnt)
+// A stable counting sort by key, so that every list comes out in ascending query order whatever the order inside the
+// rows is (the L2-blocked key-major sweep needs ascending lists) and the result is the same from run to run:
+//   count    the queries are cut into chunks of consecutive rows; cnt2[bh, chunk, j] = rows of the chunk holding j
+//            (integer atomics: the counts do not depend on the order of arrival);
+//   offsets  per key, an exclusive scan over the chunks (cnt2 becomes the chunk's first position inside the key's
+//            list) and the key's total; the totals are scanned into col as before;
+//   fill     one block per chunk walks its rows in ascending order, one row at a time; the entries of a row are
+//            distinct keys, so the threads bump the chunk's cursors with plain loads and stores.
+constexpr int kTransposeChunks = 256;  // at most this many query chunks per head (cnt2 holds chunks x L counters; 1024
+                                       // chunks measured no faster: both passes are bound by scattered 4-byte requests)
+
+__host__ __device__ __forceinline__ int transpose_chunk_rows(int L)
+{
+    const int r = (L + kTransposeChunks - 1) / kTransposeChunks;
+    return r < 64 ? 64 : r;
+}
+
+__global__ __launch_bounds__(256) void tindex_count_kernel(const int32_t *__restrict__ idx, int L, int n_chunks,
+                                                           HeadTable tab, int32_t *__restrict__ cnt2)
 {
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
+    const int rc = transpose_chunk_rows(L);
+    const int chunk = blockIdx.x;
     const int32_t *base = idx + tab.off[slot];
-    int32_t *c = cnt + (int64_t)bh * L;
-    for (int64_t i = blockIdx.x; i < L; i += gridDim.x) {
+    int32_t *c = cnt2 + ((int64_t)bh * n_chunks + chunk) * L;
+    const int i1 = min((chunk + 1) * rc, L);
+    for (int64_t i = (int64_t)chunk * rc; i < i1; ++i) {
         const int32_t *row = base + i * k;
-        for (int t = threadIdx.x; t < k; t += 256) atomicAdd(&c[row[t]], 1);
+        for (int t = threadIdx.x; t < k; t += 256) {
+            const int j = row[t];
+            if (j >= 0 && j < L) atomicAdd(&c[j], 1);
+        }
     }
 }
 
-// One block per (b, h): exclusive scan of cnt into col (int64, L+1 entries); cnt is reset to zero
-// so that the fill pass can reuse it as the cursor array.
-__global__ __launch_bounds__(1024) void tindex_scan_kernel(int32_t *__restrict__ cnt, int64_t *__restrict__ col, int L)
+// thread per key: cnt2[bh, c, j] <- number of rows in chunks before c holding j; tot[bh, j] <- all of them
+__global__ __launch_bounds__(256) void tindex_offsets_kernel(int32_t *__restrict__ cnt2, int32_t *__restrict__ tot, int L,
+                                                             int n_chunks)
+{
+    const int bh = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= L) return;
+    int32_t *c = cnt2 + (int64_t)bh * n_chunks * L + j;
+    int run = 0;
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const int v = c[(int64_t)ch * L];
+        c[(int64_t)ch * L] = run;
+        run += v;
+    }
+    tot[(int64_t)bh * L + j] = run;
+}
+
+// One block per (b, h): exclusive scan of cnt into col (int64, L+1 entries).
+__global__ __launch_bounds__(1024) void tindex_scan_kernel(const int32_t *__restrict__ cnt, int64_t *__restrict__ col, int L)
 {
     __shared__ int64_t part[1024];
     const int bh = blockIdx.x;
-    int32_t *c = cnt + (int64_t)bh * L;
+    const int32_t *c = cnt + (int64_t)bh * L;
     int64_t *o = col + (int64_t)bh * (L + 1);
     const int per = (L + 1023) / 1024;
     const int lo = min((int)threadIdx.x * per, L), hi = min(lo + per, L);
@@ -190,36 +226,55 @@ __global__ __launch_bounds__(1024) void tindex_scan_kernel(int32_t *__restrict__
     }
     int64_t run = part[threadIdx.x] - sum;
     for (int j = lo; j < hi; ++j) {
-        const int32_t v = c[j];
         o[j] = run;
-        run += v;
-        c[j] = 0;
+        run += c[j];
     }
     if (threadIdx.x == 1023) o[L] = part[1023];
 }
 
-__global__ __launch_bounds__(256) void tindex_fill_kernel(const int32_t *__restrict__ idx, int L, HeadTable tab,
-                                                          int32_t *__restrict__ cursor,
+__global__ __launch_bounds__(256) void tindex_fill_kernel(const int32_t *__restrict__ idx, int L, int n_chunks,
+                                                          HeadTable tab, int32_t *__restrict__ cnt2,
                                                           const int64_t *__restrict__ col, int32_t *__restrict__ idxT)
 {
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
     const int k = tab.k[slot];
+    const int rc = transpose_chunk_rows(L);
+    const int chunk = blockIdx.x;
     const int32_t *base = idx + tab.off[slot];
     int32_t *out = idxT + tab.off[slot];
-    int32_t *cur = cursor + (int64_t)bh * L;
+    int32_t *cur = cnt2 + ((int64_t)bh * n_chunks + chunk) * L;  // this chunk's next position inside every list
     const int64_t *cp = col + (int64_t)bh * (L + 1);
-    for (int64_t i = blockIdx.x; i < L; i += gridDim.x) {
+    const int i1 = min((chunk + 1) * rc, L);
+    constexpr int U = 8;  // entries a thread has in flight: the loads of all U come before the first store
+    for (int64_t i = (int64_t)chunk * rc; i < i1; ++i) {
         const int32_t *row = base + i * k;
-        for (int t = threadIdx.x; t < k; t += 256) {
-            const int j = row[t];
-            const int pos = atomicAdd(&cur[j], 1);
-            // col and the cursors come from the counting pass over the same idx, so dst stays inside the
-            // head's L * k entries; the bound keeps a broken idx (duplicates, changed between the passes)
-            // from sending the store anywhere else
-            const int64_t dst = cp[j] + pos;
-            if (dst >= 0 && dst < (int64_t)L * k) out[dst] = (int32_t)i;
+        for (int t0 = threadIdx.x; t0 < k; t0 += 256 * U) {
+            int j[U], pos[U];
+            int64_t dst[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int t = t0 + u * 256;
+                j[u] = t < k ? row[t] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool ok = j[u] >= 0 && j[u] < L;
+                pos[u] = ok ? cur[j[u]] : 0;   // no other thread touches cur[j] during this row: a row's keys are distinct
+                dst[u] = ok ? cp[j[u]] + pos[u] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (j[u] >= 0 && j[u] < L) {
+                    cur[j[u]] = pos[u] + 1;
+                    // col and the cursors come from the counting pass over the same idx, so dst stays inside the
+                    // head's L * k entries; the bound keeps a broken idx (duplicates, changed between the passes)
+                    // from sending the store anywhere else
+                    if (dst[u] >= 0 && dst[u] < (int64_t)L * k) out[dst[u]] = (int32_t)i;
+                }
+            }
         }
+        __syncthreads();  // the next row may bump the same cursors
     }
 }
 
@@ -306,24 +361,37 @@ dsv_status launch_bwd_dkdv(const dsv_problem &p, const HeadTable *tabs, int n_ta
     DSV_DISPATCH_TD(bwd_dkdv_t, p, tabs, n_tabs, Q, K, V, idxT, col, lse, delta, dO, dK, dV, st);
 }
 
+size_t idx_transpose_bytes(const dsv_problem &p)
+{
+    const size_t nbh = (size_t)p.B * p.H;
+    const int rc = transpose_chunk_rows(p.L);
+    const size_t n_chunks = (size_t)(p.L + rc - 1) / rc;
+    return align_up(nbh * p.L * 4, 256) + align_up(nbh * n_chunks * p.L * 4, 256);   // tot, cnt2
+}
+
 dsv_status launch_idx_transpose(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const int32_t *idx,
                                 int32_t *idxT, int64_t *col, int32_t *cnt, size_t cnt_bytes, hipStream_t st)
 {
     const int nbh = p.B * p.H;
-    const int64_t ncnt4 = (int64_t)(cnt_bytes / 16);
+    if (cnt_bytes < idx_transpose_bytes(p)) return DSV_EWORKSPACE;
+    const int rc = transpose_chunk_rows(p.L);
+    const int n_chunks = (p.L + rc - 1) / rc;
+    int32_t *tot = cnt;
+    int32_t *cnt2 = cnt + align_up((size_t)nbh * p.L * 4, 256) / 4;
+    const int64_t ncnt4 = (int64_t)(idx_transpose_bytes(p) / 16);
     const int zero_blocks = (int)std::min<int64_t>((ncnt4 + 255) / 256, 4096);
     hipLaunchKernelGGL(fill_zero_i32_kernel, dim3(zero_blocks), dim3(256), 0, st, (int4 *)cnt, ncnt4);
     DSV_LAUNCH_CHECK();
-    const int row_blocks = std::min(p.L, 8192);
     for (int t = 0; t < n_tabs; ++t) {
-        hipLaunchKernelGGL(tindex_count_kernel, dim3(row_blocks, tabs[t].n), dim3(256), 0, st, idx, p.L, tabs[t], cnt);
+        hipLaunchKernelGGL(tindex_count_kernel, dim3(n_chunks, tabs[t].n), dim3(256), 0, st, idx, p.L, n_chunks, tabs[t], cnt2);
         DSV_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(tindex_scan_kernel, dim3(nbh), dim3(1024), 0, st, cnt, col, p.L);
+    hipLaunchKernelGGL(tindex_offsets_kernel, dim3((p.L + 255) / 256, nbh), dim3(256), 0, st, cnt2, tot, p.L, n_chunks);
+    hipLaunchKernelGGL(tindex_scan_kernel, dim3(nbh), dim3(1024), 0, st, tot, col, p.L);
     DSV_LAUNCH_CHECK();
     for (int t = 0; t < n_tabs; ++t) {
-        hipLaunchKernelGGL(tindex_fill_kernel, dim3(row_blocks, tabs[t].n), dim3(256), 0, st, idx, p.L, tabs[t], cnt, col,
-                           idxT);
+        hipLaunchKernelGGL(tindex_fill_kernel, dim3(n_chunks, tabs[t].n), dim3(256), 0, st, idx, p.L, n_chunks, tabs[t], cnt2,
+                           col, idxT);
         DSV_LAUNCH_CHECK();
     }
     return DSV_OK;

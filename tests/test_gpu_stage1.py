@@ -138,6 +138,25 @@ def test_k_equals_L_and_k_equals_1():
 
 
 # ------------------------------------------------------------------------------ transposed index
+def test_idx_transpose_is_stable_for_any_order_inside_the_rows():
+    """dsv_idx_transpose: every list ascending in the query index and identical from run to run, also when the rows
+    themselves are in no particular order (the dkdv step of dsv_sparse_attn_bwd relies on it); several query chunks
+    per head (L > 64 * 256 would be needed for chunks above the minimum of 64 rows: L = 1500 gives 24 chunks)."""
+    L, ks = 1500, [37, 700]
+    rng = np.random.default_rng(5)
+    rows = [np.stack([rng.permutation(L)[:k] for _ in range(L)]).astype(np.int32) for k in ks]      # unsorted rows
+    p = dsv.Problem(1, len(ks), L, 64, 16, "bf16", ks, 1.0)
+    flat = torch.from_numpy(np.concatenate([r.reshape(-1) for r in rows])).cuda()
+    idx_t, col = dsv.idx_transpose(p, flat)
+    idx_t_again, col_again = dsv.idx_transpose(p, flat)
+    torch.cuda.synchronize()
+    assert torch.equal(idx_t, idx_t_again) and torch.equal(col, col_again)
+    idx_t, col = idx_t.cpu().numpy(), col.cpu().numpy()
+    off = wl.idx_offsets(1, len(ks), L, ks)
+    for h in range(len(ks)):
+        _check_transpose(rows[h], idx_t[off[h]:off[h + 1]], col[h], L, sorted_lists=True)
+
+
 def _check_transpose(idx_rows, idx_t_head, col, L, sorted_lists):
     """idx_rows [L, k]; idx_t_head: the head's block of the key-major index; col [L+1]."""
     k = idx_rows.shape[1]
@@ -182,4 +201,4 @@ def test_lowrank_topk_t_emits_the_exact_transpose(kind, dtype, L, d, r, ks):
     for h in range(H):
         rows = idx[off[h]:off[h + 1]].reshape(L, ks[h])
         _check_transpose(rows, idx_t[off[h]:off[h + 1]], col[h], L, sorted_lists=True)
-        _check_transpose(rows, idx_t2[off[h]:off[h + 1]], col2[h], L, sorted_lists=False)
+        _check_transpose(rows, idx_t2[off[h]:off[h + 1]], col2[h], L, sorted_lists=True)   # dsv_idx_transpose is stable
