@@ -149,6 +149,34 @@ def test_grouped_backward_matches_oracle(case, blocked):
             assert float(dK[0, h][torch.from_numpy(unselected).cuda()].abs().max()) == 0.0
 
 
+@pytest.mark.parametrize("grid,cube,k", [((2, 4, 6), (1, 1, 2), 31), ((3, 4, 6), (3, 1, 1), 32), ((2, 4, 8), (1, 2, 2), 33),
+                                         ((5, 2, 6), (5, 1, 1), 1), ((2, 7, 6), (1, 7, 1), 63), ((4, 4, 4), (2, 2, 2), 64),
+                                         ((2, 8, 8), (2, 2, 2), 65), ((2, 4, 8), (1, 1, 4), 64)])
+@pytest.mark.parametrize("blocked", [False, True], ids=["plain", "l2_blocked"])
+def test_every_group_size_and_tile_boundary(grid, cube, k, blocked):
+    """G = 2, 3, 4, 5, 7, 8 with k just below, at and just above whole 32-key tiles: forward and backward against the
+    grouped oracle (one head, the oracle's index)."""
+    cfg = _cfg(grid, H=1)
+    L, G = cfg.L, cube[0] * cube[1] * cube[2]
+    t = wl.head_tensors(cfg, 0)
+    g = {n: _dev(t[n][None], torch.bfloat16)[None] for n in ("Q", "K", "V", "dO")}
+    idx_g = wl.random_subset_idx(L, k, L // G, seed=11, head=0)
+    p = dsv.Problem(1, 1, L, cfg.d, cfg.r, "bf16", [k], cfg.scale, sorted_index=blocked)
+    grp = dsv.Grouping(cfg.grid, cube)
+    flat = torch.from_numpy(idx_g.reshape(-1)).cuda()
+    order = np.argsort(idx_g.reshape(-1), kind="stable")
+    idx_t_g = torch.from_numpy(np.repeat(np.arange(L // G, dtype=np.int32), k)[order]).cuda()
+    col = torch.from_numpy(np.concatenate([[0], np.cumsum(np.bincount(idx_g.reshape(-1), minlength=L))]).astype(np.int64)[None]).cuda()
+    O, lse = dsv.sparse_attn_fwd_grouped(p, grp, g["Q"], g["K"], g["V"], flat)
+    dQ, dK, dV = dsv.sparse_attn_bwd_grouped(p, grp, g["Q"], g["K"], g["V"], flat, idx_t_g, col, O, lse, g["dO"])
+    torch.cuda.synchronize()
+    O_ref, lse_ref = oracle.sparse_fwd_grouped(t["Q"], t["K"], t["V"], idx_g, cfg.grid, cube, cfg.scale)
+    dQ_ref, dK_ref, dV_ref = oracle.sparse_bwd_grouped(t["Q"], t["K"], t["V"], idx_g, t["dO"], cfg.grid, cube, cfg.scale)
+    for name, got, ref, dt in (("O", O, O_ref, "bf16"), ("lse", lse, lse_ref, "f32"), ("dQ", dQ, dQ_ref, "bf16"),
+                               ("dK", dK, dK_ref, "bf16"), ("dV", dV, dV_ref, "bf16")):
+        assert_close(f"{name} G={G} k={k}", got[0, 0], ref, dt)
+
+
 def test_grouped_arguments_are_checked_on_the_host():
     import ctypes
     lib = dsv.load_library()
