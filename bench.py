@@ -75,11 +75,13 @@ def parse_args():
                          "{32k, 64k, 128k} and k/L from 0.5 to 12.5 %%, ms per stage, speedup over dense, and the bytes of "
                          "index and workspace the sparse path needs")
     ap.add_argument("--predictor", action="store_true",
-                    help="also time the predictor side at the same shape: approximation loss + gradients and the sparsity "
-                         "profiler, both on L/16 sampled query rows")
+                    help="(default for bf16, d = 128 configs) also time the predictor side at the same shape: approximation "
+                         "loss + gradients and the sparsity profiler, both on L/16 sampled query rows")
+    ap.add_argument("--no-predictor", action="store_true", help="skip the predictor-side timings")
     ap.add_argument("--grouped", action="store_true",
-                    help="also time the query-grouped variant (2 x 2 x 2 cubes) at the same shape, and measure what the "
-                         "shared rows cost in accuracy on spatially smooth inputs")
+                    help="(default for bf16, d = 128 configs) also time the query-grouped variant (2 x 2 x 2 cubes) at the "
+                         "same shape, and measure what the shared rows cost in accuracy on spatially smooth inputs")
+    ap.add_argument("--no-grouped", action="store_true", help="skip the query-grouped variant")
     ap.add_argument("--grouped-density-sweep", action="store_true",
                     help="with --grouped: the grouped step at k/L = 3.1 ... 25 % and its interpolated crossover with dense")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -582,7 +584,15 @@ def main():
             out["crossover_density"] = interpolate_crossover([(s_["density"], s_["ms_per_step"]) for s_ in sweep], dense_ms)
 
     # ---- query-grouped variant (the paper's answer to the per-query gather cost) --------------------
-    if args.grouped or args.grouped_density_sweep:
+    # both extras are reported next to the headline; they never change `value`
+    extras_ok = cfg.dtype == "bf16" and cfg.d == 128 and all(x % 2 == 0 for x in cfg.grid)
+    if extras_ok and not args.no_grouped:   # the grouped backward's workspace must fit beside what is resident
+        p_g = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, [int(k) for k in ks], cfg.scale, sorted_index=True)
+        need = dsv.sparse_attn_bwd_grouped_workspace(p_g, dsv.Grouping(cfg.grid, (2, 2, 2))) + 3 * p_g.nnz + 8 * g["Q"].numel() * 2
+        if need > 0.8 * torch.cuda.mem_get_info()[1]:
+            args.no_grouped = True
+            out["grouped"] = {"skipped": f"needs about {need / 1e9:.0f} GB"}
+    if (extras_ok and not args.no_grouped) or args.grouped or args.grouped_density_sweep:
         try:
             del path
         except NameError:
@@ -603,7 +613,7 @@ def main():
             out["grouped"]["crossover_density"] = interpolate_crossover([(s_["density"], s_["ms_per_step"]) for s_ in gsweep], dense_ms)
         out["grouped"]["accuracy"] = grouping_accuracy(dsv, torch, np, wl, cfg, args.seed)
 
-    if args.predictor:
+    if (extras_ok and not args.no_predictor) or args.predictor:
         out["predictor_side"] = predictor_report(dsv, torch, cfg, ks, g, Wq, Wk)
 
     # ---- CPU oracle timed on a bounded sample ------------------------------------------------------
