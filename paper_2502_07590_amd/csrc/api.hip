@@ -565,13 +565,37 @@ GroupedSplit grouped_split(char *ws, const GroupedStepLayout &w)
     return s;
 }
 
+// The group kernels proper exist for bf16, d = 128 and groups of at most 8 queries.  Every other case (fp32, d = 64,
+// larger cubes) runs the per-query kernels on the queries reordered group by group, with the group index expanded to
+// one row per query: the same results, without the saving.
+bool grouped_native(const dsv_problem &p, const dsv_grouping &g) { return p.dtype == DSV_BF16 && p.d == 128 && group_size(g) <= 8; }
+
+struct GroupedFwdGeneral {
+    size_t qp, op, lsep, idxx, step, step_bytes, total;
+};
+GroupedFwdGeneral grouped_fwd_general(const dsv_problem &p)
+{
+    const size_t nbh = (size_t)p.B * p.H;
+    const size_t rows = nbh * p.L * p.d * esize(p.dtype);
+    GroupedFwdGeneral w{};
+    size_t o = 0;
+    w.qp = o; o = align_up(o + rows, 256);
+    w.op = o; o = align_up(o + rows, 256);
+    w.lsep = o; o = align_up(o + nbh * p.L * 4, 256);
+    w.idxx = o; o = align_up(o + total_pairs(p) * 4, 256);
+    w.step = o; w.step_bytes = fwd_layout(p).total; o += w.step_bytes;
+    w.total = o;
+    return w;
+}
+
 struct GroupedBwdLayout {
-    size_t delta, qp, gop, lsep, deltap, idxtx, colx, step, step_bytes, total;
+    size_t delta, qp, gop, lsep, deltap, idxtx, colx, op, dqp, idxx, step, step_bytes, total;
 };
 GroupedBwdLayout grouped_bwd_layout(const dsv_problem &p, const dsv_grouping &g)
 {
     const size_t nbh = (size_t)p.B * p.H;
     const size_t rows = nbh * p.L * p.d * esize(p.dtype);
+    const bool native = grouped_native(p, g);
     dsv_problem sorted = p;
     sorted.flags |= DSV_FLAG_SORTED_INDEX;
     GroupedBwdLayout w{};
@@ -583,8 +607,14 @@ GroupedBwdLayout grouped_bwd_layout(const dsv_problem &p, const dsv_grouping &g)
     w.deltap = o; o = align_up(o + nbh * p.L * 4, 256);
     w.idxtx = o; o = align_up(o + total_pairs(p) * 4, 256);
     w.colx = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
+    if (!native) {   // the per-query dq step on reordered queries: O and dQ in that order, one index row per query
+        w.op = o; o = align_up(o + rows, 256);
+        w.dqp = o; o = align_up(o + rows, 256);
+        w.idxx = o; o = align_up(o + total_pairs(p) * 4, 256);
+    }
     // the dq step's scratch and the dkdv step's are never live together
-    w.step = o; w.step_bytes = std::max(grouped_step_layout(p, g, true).total, step_layout(sorted).total); o += w.step_bytes;
+    const size_t dq_bytes = native ? grouped_step_layout(p, g, true).total : step_layout(p).total;
+    w.step = o; w.step_bytes = std::max(dq_bytes, step_layout(sorted).total); o += w.step_bytes;
     w.total = o;
     return w;
 }
@@ -593,7 +623,7 @@ GroupedBwdLayout grouped_bwd_layout(const dsv_problem &p, const dsv_grouping &g)
 size_t dsv_sparse_attn_fwd_grouped_workspace(const dsv_problem *p, const dsv_grouping *g)
 {
     if (check_problem(p, false) != DSV_OK || check_grouping(*p, g) != DSV_OK) return 0;
-    return grouped_step_layout(*p, *g, false).total;
+    return grouped_native(*p, *g) ? grouped_step_layout(*p, *g, false).total : grouped_fwd_general(*p).total;
 }
 
 dsv_status dsv_sparse_attn_fwd_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
@@ -604,7 +634,24 @@ dsv_status dsv_sparse_attn_fwd_grouped(const dsv_problem *p, const dsv_grouping 
     if (st != DSV_OK) return st;
     if ((st = check_grouping(*p, g)) != DSV_OK) return st;
     if (!ok_ptrs({Q, K, V, idx_g, O, lse})) return DSV_EINVAL;
-    if (p->dtype != DSV_BF16 || p->d != 128 || group_size(*g) > 8) return DSV_EUNSUPPORTED;
+    if (!grouped_native(*p, *g)) {
+        const GroupedFwdGeneral w = grouped_fwd_general(*p);
+        st = check_workspace(workspace, ws_bytes, w.total);
+        if (st != DSV_OK) return st;
+        char *ws = static_cast<char *>(workspace);
+        hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+        const std::vector<HeadTable> tabs = make_tables(*p, p->L / group_size(*g));
+        int32_t *idx_x = reinterpret_cast<int32_t *>(ws + w.idxx);
+        float *lsep = reinterpret_cast<float *>(ws + w.lsep);
+        if ((st = launch_group_rows(*p, *g, 1, Q, ws + w.qp, stream)) != DSV_OK) return st;
+        st = launch_group_expand(*p, *g, tabs.data(), (int)tabs.size(), idx_g, nullptr, nullptr, idx_x, nullptr, nullptr, stream);
+        if (st != DSV_OK) return st;
+        st = dsv_sparse_attn_fwd(p, ws + w.qp, K, V, idx_x, ws + w.op, lsep, w.step_bytes ? ws + w.step : nullptr, w.step_bytes,
+                                 hip_stream);
+        if (st != DSV_OK) return st;
+        if ((st = launch_group_rows(*p, *g, 2, ws + w.op, O, stream)) != DSV_OK) return st;
+        return launch_group_scalar(*p, *g, lsep, lse, stream, true);
+    }
     const GroupedStepLayout w = grouped_step_layout(*p, *g, false);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
@@ -630,7 +677,7 @@ dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping 
     if (st != DSV_OK) return st;
     if ((st = check_grouping(*p, g)) != DSV_OK) return st;
     if (!ok_ptrs({Q, K, V, idx_g, idx_t_g, col_ptr, O, lse, dO, dQ, dK, dV})) return DSV_EINVAL;
-    if (p->dtype != DSV_BF16 || p->d != 128 || group_size(*g) > 8) return DSV_EUNSUPPORTED;
+    const bool native = grouped_native(*p, *g);
     const GroupedBwdLayout w = grouped_bwd_layout(*p, *g);
     st = check_workspace(workspace, ws_bytes, w.total);
     if (st != DSV_OK) return st;
@@ -638,28 +685,43 @@ dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const std::vector<HeadTable> tabs = make_tables(*p, p->L / group_size(*g));
     float *delta = reinterpret_cast<float *>(ws + w.delta);
-    // dQ step, group by group (K and V rows gathered once per group)
-    const GroupedStepLayout dqw = grouped_step_layout(*p, *g, true);
-    GroupedSplit sp;
-    if (dqw.split) sp = grouped_split(ws + w.step, dqw);
-    st = launch_grouped_dq(*p, *g, tabs.data(), (int)tabs.size(), Q, K, V, idx_g, O, lse, dO, dQ, delta,
-                           dqw.split ? &sp : nullptr, stream);
-    if (st != DSV_OK) return st;
-    // dK, dV step: the per-query key-major sweep, on queries reordered group by group -- a group's members become
-    // neighbours, and the per-query lists that the lists of groups stand for come out ascending
+    float *lsep = reinterpret_cast<float *>(ws + w.lsep), *deltap = reinterpret_cast<float *>(ws + w.deltap);
+    // queries reordered group by group: a group's members become neighbours, and the per-query lists that the lists of
+    // groups stand for come out ascending
     if ((st = launch_group_rows(*p, *g, 1, Q, ws + w.qp, stream)) != DSV_OK) return st;
     if ((st = launch_group_rows(*p, *g, 1, dO, ws + w.gop, stream)) != DSV_OK) return st;
-    if ((st = launch_group_scalar(*p, *g, lse, reinterpret_cast<float *>(ws + w.lsep), stream)) != DSV_OK) return st;
-    if ((st = launch_group_scalar(*p, *g, delta, reinterpret_cast<float *>(ws + w.deltap), stream)) != DSV_OK) return st;
+    if ((st = launch_group_scalar(*p, *g, lse, lsep, stream)) != DSV_OK) return st;
+    if (native) {
+        // dQ step, group by group (K and V rows gathered once per group)
+        const GroupedStepLayout dqw = grouped_step_layout(*p, *g, true);
+        GroupedSplit sp;
+        if (dqw.split) sp = grouped_split(ws + w.step, dqw);
+        st = launch_grouped_dq(*p, *g, tabs.data(), (int)tabs.size(), Q, K, V, idx_g, O, lse, dO, dQ, delta,
+                               dqw.split ? &sp : nullptr, stream);
+        if (st != DSV_OK) return st;
+        if ((st = launch_group_scalar(*p, *g, delta, deltap, stream)) != DSV_OK) return st;
+    } else {
+        // dQ step by the per-query kernel on the reordered queries, one (expanded) index row per query
+        int32_t *idx_x = reinterpret_cast<int32_t *>(ws + w.idxx);
+        if ((st = launch_group_rows(*p, *g, 1, O, ws + w.op, stream)) != DSV_OK) return st;
+        st = launch_group_expand(*p, *g, tabs.data(), (int)tabs.size(), idx_g, nullptr, nullptr, idx_x, nullptr, nullptr, stream);
+        if (st != DSV_OK) return st;
+        const size_t dq_bytes = step_layout(*p).total;
+        st = dsv_sparse_attn_bwd_dq(p, ws + w.qp, K, V, idx_x, ws + w.op, lsep, ws + w.gop, ws + w.dqp, deltap,
+                                    dq_bytes ? ws + w.step : nullptr, dq_bytes, hip_stream);
+        if (st != DSV_OK) return st;
+        if ((st = launch_group_rows(*p, *g, 2, ws + w.dqp, dQ, stream)) != DSV_OK) return st;
+    }
+    // dK, dV step: the per-query key-major sweep on the reordered queries
     st = launch_group_expand(*p, *g, tabs.data(), (int)tabs.size(), idx_g, idx_t_g, col_ptr, nullptr,
                              reinterpret_cast<int32_t *>(ws + w.idxtx), reinterpret_cast<int64_t *>(ws + w.colx), stream);
     if (st != DSV_OK) return st;
     dsv_problem sorted = *p;
     sorted.flags |= DSV_FLAG_SORTED_INDEX;
+    const size_t dkdv_bytes = step_layout(sorted).total;
     return dsv_sparse_attn_bwd_dkdv(&sorted, ws + w.qp, K, V, reinterpret_cast<int32_t *>(ws + w.idxtx),
-                                    reinterpret_cast<int64_t *>(ws + w.colx), reinterpret_cast<float *>(ws + w.lsep),
-                                    reinterpret_cast<float *>(ws + w.deltap), ws + w.gop, dK, dV, ws + w.step,
-                                    w.step_bytes, hip_stream);
+                                    reinterpret_cast<int64_t *>(ws + w.colx), lsep, deltap, ws + w.gop, dK, dV,
+                                    dkdv_bytes ? ws + w.step : nullptr, dkdv_bytes, hip_stream);
 }
 
 // ------------------------------------------------------------------------------------ predictor side

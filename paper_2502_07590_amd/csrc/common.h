@@ -322,9 +322,10 @@ struct GroupGeom {
 // 2: the inverse of 1.
 dsv_status launch_group_rows(const dsv_problem &p, const dsv_grouping &gr, int mode, const void *in, void *out,
                              hipStream_t st);
-dsv_status launch_group_scalar(const dsv_problem &p, const dsv_grouping &gr, const float *in, float *out, hipStream_t st);
-// tabs: built for L/G rows per head.  Writes the per-query form (group-major query order) of the key-major index,
-// and of the query-major index unless idx_x is null.
+dsv_status launch_group_scalar(const dsv_problem &p, const dsv_grouping &gr, const float *in, float *out, hipStream_t st,
+                               bool inverse = false);
+// tabs: built for L/G rows per head.  Writes the per-query form (group-major query order) of the key-major index
+// (unless idx_t_x / col_x are null) and of the query-major index (unless idx_x is null).
 dsv_status launch_group_expand(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
                                const int32_t *idx_g, const int32_t *idx_t_g, const int64_t *col, int32_t *idx_x,
                                int32_t *idx_t_x, int64_t *col_x, hipStream_t st);

@@ -75,14 +75,16 @@ __global__ __launch_bounds__(256) void group_rows_kernel(const T *__restrict__ i
     *d = *s;
 }
 
-// lse (one float per token) into group-major order.
+// lse (one float per token) into group-major order, or (inverse) back into token order.
 __global__ __launch_bounds__(256) void group_scalar_kernel(const float *__restrict__ in, float *__restrict__ out, int L,
-                                                           GroupGeom gm)
+                                                           GroupGeom gm, int inverse)
 {
     const int r = blockIdx.x * 256 + threadIdx.x;
     const int bh = blockIdx.y;
     if (r >= L) return;
-    out[(int64_t)bh * L + r] = in[(int64_t)bh * L + member_token(gm, r / gm.G, r % gm.G)];
+    const int64_t tok = member_token(gm, r / gm.G, r % gm.G);
+    if (inverse) out[(int64_t)bh * L + tok] = in[(int64_t)bh * L + r];
+    else out[(int64_t)bh * L + r] = in[(int64_t)bh * L + tok];
 }
 
 // ---- the per-query index the grouped one stands for, in group-major query order ------------------------
@@ -651,10 +653,11 @@ dsv_status launch_group_rows(const dsv_problem &p, const dsv_grouping &gr, int m
     return group_rows_t<float, 2>(p, gm, centre, in, out, n_out, st);
 }
 
-dsv_status launch_group_scalar(const dsv_problem &p, const dsv_grouping &gr, const float *in, float *out, hipStream_t st)
+dsv_status launch_group_scalar(const dsv_problem &p, const dsv_grouping &gr, const float *in, float *out, hipStream_t st,
+                               bool inverse)
 {
     hipLaunchKernelGGL(group_scalar_kernel, dim3((p.L + 255) / 256, p.B * p.H), dim3(256), 0, st, in, out, p.L,
-                       make_group_geom(gr));
+                       make_group_geom(gr), inverse ? 1 : 0);
     DSV_LAUNCH_CHECK();
     return DSV_OK;
 }
@@ -668,12 +671,15 @@ dsv_status launch_group_expand(const dsv_problem &p, const dsv_grouping &gr, con
     for (int t = 0; t < n_tabs; ++t) {
         if (idx_x)
             hipLaunchKernelGGL(expand_idx_kernel, dim3(std::min(Lq, 8192), tabs[t].n), dim3(256), 0, st, idx_g, idx_x, Lq, gm.G, tabs[t]);
-        hipLaunchKernelGGL(expand_idx_t_kernel, dim3(8192, tabs[t].n), dim3(256), 0, st, idx_t_g, idx_t_x, Lq, gm.G, tabs[t]);
+        if (idx_t_x)
+            hipLaunchKernelGGL(expand_idx_t_kernel, dim3(8192, tabs[t].n), dim3(256), 0, st, idx_t_g, idx_t_x, Lq, gm.G, tabs[t]);
         DSV_LAUNCH_CHECK();
     }
-    const int64_t n = (int64_t)p.B * p.H * (p.L + 1);
-    hipLaunchKernelGGL(scale_col_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, col, col_x, n, gm.G);
-    DSV_LAUNCH_CHECK();
+    if (col_x) {
+        const int64_t n = (int64_t)p.B * p.H * (p.L + 1);
+        hipLaunchKernelGGL(scale_col_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, col, col_x, n, gm.G);
+        DSV_LAUNCH_CHECK();
+    }
     return DSV_OK;
 }
 

@@ -187,7 +187,44 @@ def test_grouped_arguments_are_checked_on_the_host():
     for gg in (bad_grid, no_tiling):
         assert lib.dsv_sparse_attn_fwd_grouped(p.c, gg.c, one, one, one, one, one, one, None, 0, None) == -1
         assert dsv.lowrank_topk_grouped_workspace(p, gg) == 0
-    big = dsv.Grouping((4, 8, 16), (2, 2, 4))              # G = 16: beyond the forward kernel's tile
-    assert lib.dsv_sparse_attn_fwd_grouped(p.c, big.c, one, one, one, one, one, one, None, 0, None) == -2
-    f32 = dsv.Problem(1, 1, 512, 128, 16, "f32", [32], 0.1)
-    assert lib.dsv_sparse_attn_fwd_grouped(f32.c, dsv.Grouping((4, 8, 16), (2, 2, 2)).c, one, one, one, one, one, one, None, 0, None) == -2
+    huge = dsv.Grouping((8, 8, 8), (8, 4, 4))              # G = 128: beyond the largest group accepted (64)
+    assert lib.dsv_sparse_attn_fwd_grouped(p.c, huge.c, one, one, one, one, one, one, None, 0, None) == -2
+    big = dsv.Grouping((4, 8, 16), (2, 2, 4))              # G = 16 runs through the per-query kernels: needs its workspace
+    assert dsv.sparse_attn_fwd_grouped_workspace(p, big) > p.nnz * 4
+    assert lib.dsv_sparse_attn_fwd_grouped(p.c, big.c, one, one, one, one, one, one, None, 0, None) == -3
+
+
+@pytest.mark.parametrize("dtype,d,grid,cube,ks", [("f32", 64, (4, 8, 8), (2, 2, 2), [40, 7]),       # fp32, d = 64
+                                                  ("bf16", 128, (4, 8, 16), (2, 2, 4), [100, 33]),  # G = 16
+                                                  ("bf16", 64, (4, 4, 8), (1, 2, 2), [128, 20]),    # d = 64; k = L
+                                                  ("f32", 128, (2, 6, 6), (2, 3, 3), [9, 72])])     # G = 18, fp32, k = L
+@pytest.mark.parametrize("sorted_index", [False, True], ids=["plain", "l2_blocked"])
+def test_general_grouped_path_matches_oracle(dtype, d, grid, cube, ks, sorted_index):
+    """dtypes, head dimensions and cube sizes the group kernels proper do not cover run the per-query kernels on
+    queries reordered group by group with the group index expanded: same contract, checked the same way."""
+    cfg = _cfg(grid, d=d, dtype=dtype, H=len(ks))
+    L, G = cfg.L, cube[0] * cube[1] * cube[2]
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    t = [wl.head_tensors(cfg, h) for h in range(cfg.H)]
+    g = {n: _dev(np.stack([x[n] for x in t]), td)[None] for n in ("Q", "K", "V", "dO")}
+    idx_g = [wl.random_subset_idx(L, k, L // G, seed=3, head=h) for h, k in enumerate(ks)]
+    p = dsv.Problem(1, cfg.H, L, d, cfg.r, dtype, ks, cfg.scale, sorted_index=sorted_index)
+    grp = dsv.Grouping(cfg.grid, cube)
+    flat = torch.from_numpy(np.concatenate([x.reshape(-1) for x in idx_g])).cuda()
+    lists, cols = [], []
+    for h, k in enumerate(ks):
+        order = np.argsort(idx_g[h].reshape(-1), kind="stable")
+        lists.append(np.repeat(np.arange(L // G, dtype=np.int32), k)[order])
+        cols.append(np.concatenate([[0], np.cumsum(np.bincount(idx_g[h].reshape(-1), minlength=L))]).astype(np.int64))
+    idx_t_g = torch.from_numpy(np.concatenate(lists)).cuda()
+    col = torch.from_numpy(np.stack(cols)).cuda()
+    O, lse = dsv.sparse_attn_fwd_grouped(p, grp, g["Q"], g["K"], g["V"], flat)
+    dQ, dK, dV = dsv.sparse_attn_bwd_grouped(p, grp, g["Q"], g["K"], g["V"], flat, idx_t_g, col, O, lse, g["dO"])
+    torch.cuda.synchronize()
+    for h in range(cfg.H):
+        O_ref, lse_ref = oracle.sparse_fwd_grouped(t[h]["Q"], t[h]["K"], t[h]["V"], idx_g[h], cfg.grid, cube, cfg.scale)
+        dQ_ref, dK_ref, dV_ref = oracle.sparse_bwd_grouped(t[h]["Q"], t[h]["K"], t[h]["V"], idx_g[h], t[h]["dO"], cfg.grid, cube,
+                                                           cfg.scale)
+        for name, got, ref, dt in (("O", O, O_ref, dtype), ("lse", lse, lse_ref, "f32"), ("dQ", dQ, dQ_ref, dtype),
+                                   ("dK", dK, dK_ref, dtype), ("dV", dV, dV_ref, dtype)):
+            assert_close(f"{name}[h={h}] {dtype} d={d} G={G}", got[0, h], ref, dt)
