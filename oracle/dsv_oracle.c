@@ -463,6 +463,34 @@ void dsv_oracle_sparse_bwd_grouped(const float *Q, const float *K, const float *
     free(idx); free(O); free(lse);
 }
 
+/* Offline profiling of the group size (Sec. "Sparse Attention with Query Grouping": the largest cube whose queries
+ * share a required ratio, e.g. 80 %, of their critical keys): for one head, given the PER-QUERY index idx [L, k]
+ * (rows = sets of distinct keys, any order), the number of (query, key) pairs whose key is also in the row of the
+ * query's group centre,
+ *     count = sum_i | row(i) intersect row(centre of i's group) |,
+ * so that count / (L k) is the mean share of a query's own selection that the shared row would keep (a centre query
+ * contributes k).  Returns -1 if the cube does not tile the grid. */
+int64_t dsv_oracle_group_overlap(const int32_t *idx, int F, int Hh, int Ww, int gf, int gh, int gw, int64_t k)
+{
+    if (F % gf || Hh % gh || Ww % gw) return -1;
+    const int64_t L = (int64_t)F * Hh * Ww;
+    const int G = gf * gh * gw;
+    const int centre = dsv_oracle_group_centre(gf, gh, gw);
+    unsigned char *in_centre = (unsigned char *)calloc((size_t)L, 1);
+    int64_t count = 0;
+    for (int64_t g = 0; g < L / G; ++g) {
+        const int32_t *crow = idx + dsv_oracle_group_member(g, centre, F, Hh, Ww, gf, gh, gw) * k;
+        for (int64_t t = 0; t < k; ++t) in_centre[crow[t]] = 1;
+        for (int m = 0; m < G; ++m) {
+            const int32_t *row = idx + dsv_oracle_group_member(g, m, F, Hh, Ww, gf, gh, gw) * k;
+            for (int64_t t = 0; t < k; ++t) count += in_centre[row[t]];
+        }
+        for (int64_t t = 0; t < k; ++t) in_centre[crow[t]] = 0;
+    }
+    free(in_centre);
+    return count;
+}
+
 /* ---------------------------------------------------------------------------------------------
  * Predictor side (Sec. "Low-Rank based Sparsity Prediction", Sec. "Sparsity Profiling").
  *

@@ -21,7 +21,7 @@ DTYPES = {"f32": 0, "bf16": 1}
 __all__ = ["build", "lib", "round_value", "project", "scores", "topk_from_scores", "lowrank_topk",
            "sparse_fwd", "sparse_bwd", "sparse_bwd_rows", "sparse_bwd_dq_rows", "sparse_bwd_dkdv_key",
            "dense_fwd", "dense_bwd", "max_threads", "DTYPES", "group_member", "group_centre", "group_tokens",
-           "lowrank_topk_grouped", "group_expand_idx", "sparse_fwd_grouped", "sparse_bwd_grouped",
+           "lowrank_topk_grouped", "group_expand_idx", "group_overlap", "sparse_fwd_grouped", "sparse_bwd_grouped",
            "predictor_loss", "profile_sparsity", "ema"]
 
 
@@ -276,6 +276,20 @@ def sparse_bwd_grouped(Q, K, V, idx_g, dO, grid, cube, scale: float):
 
 
 # ---- predictor side ---------------------------------------------------------------------------
+def group_overlap(idx, grid, cube) -> float:
+    """Mean share of a query's own selection (idx [L, k], per-query rows) that its group centre's row also holds."""
+    idx = _i32(idx)
+    L, k = idx.shape
+    F, Hh, Ww = grid
+    gf, gh, gw = cube
+    fn = lib().dsv_oracle_group_overlap
+    fn.restype = ctypes.c_int64
+    count = fn(_p(idx), _int(F), _int(Hh), _int(Ww), _int(gf), _int(gh), _int(gw), _i64(k))
+    if count < 0:
+        raise ValueError("the cube does not tile the grid")
+    return count / (L * k)
+
+
 def predictor_loss(Q_rows, K, Wq, Wk):
     """0.95 CosLoss + 0.05 NormLoss of the low-rank scores of the given query rows against the true ones, and its
     gradients: ((loss, cos, norm), dWq [d, r], dWk [d, r])."""

@@ -162,3 +162,33 @@ def test_neighbouring_queries_share_their_keys_on_smooth_inputs_only():
     ov_sm = _overlap_with_centre(oracle.lowrank_topk(t_sm["Q"], t_sm["K"], eye, eye, k, "f32"), cfg.grid, cube)
     assert ov_iid < 0.25, ov_iid          # unrelated queries share about k / L of their keys, plus the common basis
     assert ov_sm > 0.80, ov_sm            # the regime the paper reports for 2 x 2 x 2 cubes (Observation 5)
+
+
+def test_group_overlap_counts_shared_keys_with_the_centres_row():
+    """oracle.group_overlap against plain numpy set intersections, and its closed forms."""
+    grid, cube, k = (4, 6, 4), (2, 3, 2), 11
+    L = grid[0] * grid[1] * grid[2]
+    rng = np.random.default_rng(3)
+    idx = np.stack([rng.permutation(L)[:k] for _ in range(L)]).astype(np.int32)      # rows in no particular order
+    tokens = _numpy_group_tokens(grid, cube)
+    centre = tokens[:, oracle.group_centre(cube)]
+    want = sum(len(np.intersect1d(idx[i], idx[centre[g]])) for g in range(tokens.shape[0]) for i in tokens[g])
+    assert oracle.group_overlap(idx, grid, cube) == want / (L * k)
+    # closed forms: a unit cube keeps everything; identical rows keep everything; rows disjoint from their centre's
+    # keep only the centre queries' own share 1 / G
+    assert oracle.group_overlap(idx, grid, (1, 1, 1)) == 1.0
+    same = np.tile(np.arange(k, dtype=np.int32), (L, 1))
+    assert oracle.group_overlap(same, grid, cube) == 1.0
+    G = cube[0] * cube[1] * cube[2]
+    disjoint = np.tile(np.arange(k, dtype=np.int32), (L, 1))
+    disjoint[centre] += k
+    assert oracle.group_overlap(disjoint, grid, cube) == 1.0 / G
+    # and it agrees with the overlap measured on the smooth inputs above (members other than the centre: (ov G - 1) / (G - 1))
+    cfg = _cfg((8, 8, 16), d=64, r=64, R=32)
+    eye = np.eye(cfg.d, dtype=np.float32)
+    t_sm = wl.head_tensors_smooth(cfg, 0, sigma=5.0, names=("Q", "K"))
+    rows = oracle.lowrank_topk(t_sm["Q"], t_sm["K"], eye, eye, 64, "f32")
+    ov = oracle.group_overlap(rows, cfg.grid, (2, 2, 2))
+    assert abs((ov * 8 - 1) / 7 - _overlap_with_centre(rows, cfg.grid, (2, 2, 2))) < 1e-12
+    with pytest.raises(ValueError):
+        oracle.group_overlap(idx, grid, (3, 3, 2))
