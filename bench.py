@@ -367,9 +367,6 @@ def grouping_accuracy(dsv, torch, np, wl, cfg, seed):
                        k=None, k_choices=(), dtype="bf16", basis_rank=cfg.basis_rank, scale=cfg.scale)
     L, k, G = c.L, c.L // 16, 8
     F, H, W = grid
-    tok = np.arange(L).reshape(F // 2, 2, H // 2, 2, W // 2, 2).transpose(0, 2, 4, 1, 3, 5).reshape(-1, G)
-    group_of = np.empty(L, dtype=np.int64)
-    group_of[tok.reshape(-1)] = np.repeat(np.arange(L // G), G)
     res = {}
     for kind in ("smooth", "iid"):
         t = wl.head_tensors_smooth(c, 0, seed=seed, sigma=5.0) if kind == "smooth" else wl.head_tensors(c, 0, seed=seed)
@@ -382,19 +379,22 @@ def grouping_accuracy(dsv, torch, np, wl, cfg, seed):
         grp = dsv.Grouping(grid, cube)
         idx_q = dsv.lowrank_topk(p, dv["Q"], dv["K"], Wq, Wk).view(L, k)
         idx_g, _, _ = dsv.lowrank_topk_grouped(p, grp, dv["Q"], dv["K"], Wq, Wk, transposed=False)
-        idx_gx = idx_g.view(L // G, k)[torch.from_numpy(group_of).cuda()]                # [L, k]: the row each token uses
-        pos = torch.searchsorted(idx_gx, idx_q).clamp_(max=k - 1)
-        shared = (torch.gather(idx_gx, 1, pos) == idx_q).sum().item() / (L * k)
+        # the library's own group-size profiling: overlap per candidate cube, and the largest cube that keeps 80 %
+        cubes = [(1, 1, 1), (1, 2, 2), (2, 2, 2), (2, 2, 4), (2, 4, 4), (4, 4, 4)]
+        chosen, ov = dsv.choose_grouping(p, grid, cubes, idx_q.reshape(-1), min_overlap=0.8)
+        shared = ov[cubes.index(cube)][0]
         Oq, _ = dsv.sparse_attn_fwd(p, dv["Q"], dv["K"], dv["V"], idx_q.reshape(-1))
         Og, _ = dsv.sparse_attn_fwd_grouped(p, grp, dv["Q"], dv["K"], dv["V"], idx_g)
         Od = torch.nn.functional.scaled_dot_product_attention(dv["Q"], dv["K"], dv["V"], scale=c.scale)
         torch.cuda.synchronize()
         rms = lambda x: x.float().pow(2).mean().sqrt().item()
         res[kind] = {"own_topk_found_in_group_row": round(shared, 4),
+                     "overlap_by_cube": {"x".join(map(str, cb)): round(ov[i][0], 4) for i, cb in enumerate(cubes)},
+                     "largest_cube_keeping_80_percent": list(cubes[chosen]) if chosen >= 0 else None,
                      "rel_rms_error_vs_dense": {"per_query": round(rms(Oq.float() - Od.float()) / rms(Od), 4),
                                                 "grouped": round(rms(Og.float() - Od.float()) / rms(Od), 4)}}
         del Od
-        del dv, idx_q, idx_g, idx_gx, pos, Oq, Og
+        del dv, idx_q, idx_g, Oq, Og
         torch.cuda.empty_cache()
     res["shape"] = {"L": L, "k": k, "grid": list(grid), "cube": list(cube), "predictor": f"W = basis^T, rank {c.r}",
                     "smoothing_sigma": 5.0}

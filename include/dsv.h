@@ -231,6 +231,26 @@ typedef struct dsv_grouping {
     int32_t gf, gh, gw;  /* cube (group) size along each axis */
 } dsv_grouping;
 
+/* Offline profiling of the group size (same section: the largest cube whose queries share a required ratio, e.g.
+ * 80 %, of their critical keys).  Given the PER-QUERY index idx (dsv_lowrank_topk; rows in any order) and a cube,
+ *     overlap[b*H+h] = (1 / (L k_h)) sum_i | row(i) intersect row(centre query of i's group) |,
+ * the mean share of a query's own selection that the shared row would keep (a centre query counts in full).
+ * overlap: DEVICE float [B*H].  Workspace: one 64-bit counter per (b, h).  L <= 524288 (the centre's row is held as a
+ * bitmap in LDS); larger: DSV_EUNSUPPORTED.
+ *
+ * dsv_choose_grouping: evaluates n candidate cubes (cubes: HOST int32 [n][3] = gf, gh, gw; candidates that do not
+ * tile the F x Hh x Ww grid are skipped) and writes to *chosen (HOST) the index of the candidate with the most
+ * members whose overlap is at least min_overlap in EVERY (b, h) -- the first such on ties -- or -1 if none is.
+ * overlaps (HOST float [n][B*H], may be NULL) receives every candidate's figures (-1 for skipped ones).  Waits for
+ * the stream.  Workspace: dsv_group_overlap's plus one float per (b, h). */
+DSV_API size_t dsv_group_overlap_workspace(const dsv_problem *p);
+DSV_API dsv_status dsv_group_overlap(const dsv_problem *p, const dsv_grouping *g, const int32_t *idx, float *overlap,
+                                     void *workspace, size_t ws_bytes, void *hip_stream);
+DSV_API size_t dsv_choose_grouping_workspace(const dsv_problem *p);
+DSV_API dsv_status dsv_choose_grouping(const dsv_problem *p, int32_t F, int32_t Hh, int32_t Ww, const int32_t *cubes,
+                                       int32_t n, const int32_t *idx, float min_overlap, int32_t *chosen,
+                                       float *overlaps, void *workspace, size_t ws_bytes, void *hip_stream);
+
 DSV_API size_t dsv_lowrank_topk_grouped_workspace(const dsv_problem *p, const dsv_grouping *g);
 DSV_API dsv_status dsv_lowrank_topk_grouped(const dsv_problem *p, const dsv_grouping *g, const void *Q, const void *K,
                                             const void *Wq, const void *Wk, int32_t *idx_g, int32_t *idx_t_g,

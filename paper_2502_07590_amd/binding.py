@@ -32,6 +32,7 @@ EXPORTED_SYMBOLS = (
     "dsv_lowrank_topk_grouped_workspace", "dsv_lowrank_topk_grouped", "dsv_sparse_attn_fwd_grouped_workspace",
     "dsv_sparse_attn_fwd_grouped",
     "dsv_sparse_attn_bwd_grouped_workspace", "dsv_sparse_attn_bwd_grouped",
+    "dsv_group_overlap_workspace", "dsv_group_overlap", "dsv_choose_grouping_workspace", "dsv_choose_grouping",
     "dsv_lowrank_topk_noalloc_max_bytes", "dsv_lowrank_topk_noalloc",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
     "dsv_kernel_timing", "dsv_kernel_ms", "dsv_measure_gather_ceiling",
@@ -95,7 +96,7 @@ def load_library():
     for name in ("dsv_lowrank_topk_workspace", "dsv_sparse_attn_fwd_workspace", "dsv_sparse_attn_bwd_workspace",
                  "dsv_idx_transpose_workspace", "dsv_lowrank_topk_t_workspace", "dsv_sparse_attn_bwd_t_workspace",
                  "dsv_sparse_attn_bwd_dq_workspace", "dsv_sparse_attn_bwd_dkdv_workspace",
-                 "dsv_idx_validate_workspace"):
+                 "dsv_idx_validate_workspace", "dsv_group_overlap_workspace", "dsv_choose_grouping_workspace"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [P]
     lib.dsv_lowrank_topk.restype = ctypes.c_int
@@ -129,6 +130,11 @@ def load_library():
     lib.dsv_sparse_attn_fwd_grouped.argtypes = [P, PG, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dsv_sparse_attn_bwd_grouped.restype = ctypes.c_int
     lib.dsv_sparse_attn_bwd_grouped.argtypes = [P, PG] + [vp] * 12 + [vp, sz, vp]
+    lib.dsv_group_overlap.restype = ctypes.c_int
+    lib.dsv_group_overlap.argtypes = [P, PG, vp, vp, vp, sz, vp]
+    lib.dsv_choose_grouping.restype = ctypes.c_int
+    lib.dsv_choose_grouping.argtypes = [P, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), i32, vp, ctypes.c_float,
+                                        ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float), vp, sz, vp]
     lib.dsv_profile_sparsity_workspace.restype = sz
     lib.dsv_profile_sparsity_workspace.argtypes = [P, i32]
     lib.dsv_profile_sparsity.restype = ctypes.c_int
@@ -410,6 +416,30 @@ def sparse_attn_bwd_grouped(p: Problem, g: Grouping, Q, K, V, idx_g, idx_t_g, co
 
 
 # ---- predictor side -------------------------------------------------------------------------------
+def group_overlap(p: Problem, g: Grouping, idx, overlap=None, workspace=None, stream=None):
+    """Share of the queries' own selections (per-query idx) that their group centre's row holds: float [B*H]."""
+    lib = load_library()
+    overlap = torch.empty(p.B * p.H, dtype=torch.float32, device=idx.device) if overlap is None else overlap
+    ws, nbytes = _workspace(int(lib.dsv_group_overlap_workspace(p.c)), idx.device, workspace, stream)
+    _check(lib.dsv_group_overlap(p.c, g.c, _ptr(idx), _ptr(overlap), _ptr(ws), nbytes, _stream(stream)), "dsv_group_overlap")
+    return overlap
+
+
+def choose_grouping(p: Problem, grid, cubes, idx, min_overlap: float = 0.8, workspace=None, stream=None):
+    """Largest candidate cube whose overlap reaches min_overlap in every head: (index into cubes or -1, overlaps
+    [len(cubes), B*H] as nested lists; -1 rows for cubes that do not tile the grid).  Waits for the stream."""
+    lib = load_library()
+    n = len(cubes)
+    flat = (ctypes.c_int32 * (3 * n))(*[int(x) for c in cubes for x in c])
+    chosen = ctypes.c_int32(-2)
+    out = (ctypes.c_float * (n * p.B * p.H))()
+    ws, nbytes = _workspace(int(lib.dsv_choose_grouping_workspace(p.c)), idx.device, workspace, stream)
+    _check(lib.dsv_choose_grouping(p.c, int(grid[0]), int(grid[1]), int(grid[2]), flat, n, _ptr(idx), float(min_overlap),
+                                   ctypes.byref(chosen), out, _ptr(ws), nbytes, _stream(stream)), "dsv_choose_grouping")
+    nbh = p.B * p.H
+    return int(chosen.value), [[float(out[c * nbh + e]) for e in range(nbh)] for c in range(n)]
+
+
 def predictor_loss_workspace(p: Problem, n_rows: int) -> int:
     return int(load_library().dsv_predictor_loss_workspace(p.c, int(n_rows)))
 

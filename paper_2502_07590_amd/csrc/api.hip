@@ -724,6 +724,69 @@ dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping 
                                     dkdv_bytes ? ws + w.step : nullptr, dkdv_bytes, hip_stream);
 }
 
+// ------------------------------------------------------------------------------------ group-size profiling
+size_t dsv_group_overlap_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, false) != DSV_OK) return 0;
+    return align_up((size_t)p->B * p->H * 8, 256);
+}
+
+dsv_status dsv_group_overlap(const dsv_problem *p, const dsv_grouping *g, const int32_t *idx, float *overlap,
+                             void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if ((st = check_grouping(*p, g)) != DSV_OK) return st;
+    if (!ok_ptrs({idx, overlap})) return DSV_EINVAL;
+    st = check_workspace(workspace, ws_bytes, dsv_group_overlap_workspace(p));
+    if (st != DSV_OK) return st;
+    const std::vector<HeadTable> tabs = make_tables(*p);
+    return launch_group_overlap(*p, *g, tabs.data(), (int)tabs.size(), idx, static_cast<unsigned long long *>(workspace),
+                                overlap, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t dsv_choose_grouping_workspace(const dsv_problem *p)
+{
+    if (check_problem(p, false) != DSV_OK) return 0;
+    return dsv_group_overlap_workspace(p) + align_up((size_t)p->B * p->H * 4, 256);
+}
+
+dsv_status dsv_choose_grouping(const dsv_problem *p, int32_t F, int32_t Hh, int32_t Ww, const int32_t *cubes, int32_t n,
+                               const int32_t *idx, float min_overlap, int32_t *chosen, float *overlaps, void *workspace,
+                               size_t ws_bytes, void *hip_stream)
+{
+    dsv_status st = check_problem(p, false);
+    if (st != DSV_OK) return st;
+    if (!cubes || !chosen || n < 1 || !ok_ptrs({idx})) return DSV_EINVAL;
+    st = check_workspace(workspace, ws_bytes, dsv_choose_grouping_workspace(p));
+    if (st != DSV_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int nbh = p->B * p->H;
+    float *dev = reinterpret_cast<float *>(static_cast<char *>(workspace) + dsv_group_overlap_workspace(p));
+    std::vector<float> host(nbh);
+    int best = -1, best_members = 0;
+    for (int c = 0; c < n; ++c) {
+        const dsv_grouping g{F, Hh, Ww, cubes[3 * c], cubes[3 * c + 1], cubes[3 * c + 2]};
+        const dsv_status ok = check_grouping(*p, &g);
+        if (ok != DSV_OK) {   // does not tile the grid (or is too large): not a candidate
+            if (overlaps) for (int e = 0; e < nbh; ++e) overlaps[(size_t)c * nbh + e] = -1.f;
+            continue;
+        }
+        st = dsv_group_overlap(p, &g, idx, dev, workspace, dsv_group_overlap_workspace(p), hip_stream);
+        if (st != DSV_OK) return st;
+        DSV_HIP_CHECK(hipMemcpyAsync(host.data(), dev, (size_t)nbh * 4, hipMemcpyDeviceToHost, stream));
+        DSV_HIP_CHECK(hipStreamSynchronize(stream));
+        bool all = true;
+        for (int e = 0; e < nbh; ++e) {
+            if (overlaps) overlaps[(size_t)c * nbh + e] = host[e];
+            all = all && host[e] >= min_overlap;
+        }
+        if (all && group_size(g) > best_members) { best = c; best_members = group_size(g); }
+    }
+    *chosen = best;
+    return DSV_OK;
+}
+
 // ------------------------------------------------------------------------------------ predictor side
 size_t dsv_predictor_loss_workspace(const dsv_problem *p, int32_t n_rows)
 {

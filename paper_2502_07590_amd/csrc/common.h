@@ -329,6 +329,10 @@ dsv_status launch_group_scalar(const dsv_problem &p, const dsv_grouping &gr, con
 dsv_status launch_group_expand(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
                                const int32_t *idx_g, const int32_t *idx_t_g, const int64_t *col, int32_t *idx_x,
                                int32_t *idx_t_x, int64_t *col_x, hipStream_t st);
+// Group-size profiling: overlap[bh] = share of the members' own rows (per-query idx, tabs for L rows per head) that the
+// centre's row holds.  count: one 64-bit counter per (b, h).
+dsv_status launch_group_overlap(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
+                                const int32_t *idx, unsigned long long *count, float *overlap, hipStream_t st);
 // Scratch of the L2-blocked grouped kernels (null seg: plain form, rows in any order).
 struct GroupedSplit {
     SplitPlan plan;

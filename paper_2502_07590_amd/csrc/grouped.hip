@@ -137,6 +137,64 @@ __global__ __launch_bounds__(256) void scale_col_kernel(const int64_t *__restric
     if (e < n) col_x[e] = col[e] * G;
 }
 
+// ---- share of the members' own selections that the centre's row holds (group-size profiling) -------------------
+// One block walks groups blockIdx.x, blockIdx.x + gridDim.x, ... of one head: the centre query's row goes into a
+// bitmap of L bits in LDS, every member's row is tested against it, and the row's own words are cleared again.
+// count[bh] += number of (member, key) pairs found; integer sums, so the result does not depend on the order.
+__global__ __launch_bounds__(256) void group_overlap_kernel(const int32_t *__restrict__ idx, int L, HeadTable tab,
+                                                            GroupGeom gm, int centre,
+                                                            unsigned long long *__restrict__ count)
+{
+    extern __shared__ uint32_t bitmap[];  // [(L + 31) / 32]
+    __shared__ unsigned long long part[4];
+    const int slot = blockIdx.y;
+    const int bh = tab.bh[slot];
+    const int k = tab.k[slot];
+    const int32_t *base = idx + tab.off[slot];
+    const int Lq = L / gm.G;
+    for (int w = threadIdx.x; w < (L + 31) / 32; w += 256) bitmap[w] = 0u;
+    __syncthreads();
+    unsigned long long mine = 0;
+    for (int g = blockIdx.x; g < Lq; g += gridDim.x) {
+        const int32_t *crow = base + member_token(gm, g, centre) * k;
+        for (int t = threadIdx.x; t < k; t += 256) {
+            const int v = crow[t];
+            if (v >= 0 && v < L) atomicOr(&bitmap[v >> 5], 1u << (v & 31));
+        }
+        __syncthreads();
+        for (int m = 0; m < gm.G; ++m) {
+            const int32_t *row = base + member_token(gm, g, m) * k;
+            for (int t = threadIdx.x; t < k; t += 256) {
+                const int v = row[t];
+                if (v >= 0 && v < L) mine += (bitmap[v >> 5] >> (v & 31)) & 1u;
+            }
+        }
+        __syncthreads();
+        for (int t = threadIdx.x; t < k; t += 256) {
+            const int v = crow[t];
+            if (v >= 0 && v < L) bitmap[v >> 5] = 0u;
+        }
+        __syncthreads();
+    }
+    for (int o = 32; o; o >>= 1) mine += __shfl_xor(mine, o);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicAdd(&count[bh], part[0] + part[1] + part[2] + part[3]);
+}
+
+__global__ void group_overlap_reset_kernel(unsigned long long *count, int n)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e < n) count[e] = 0ull;
+}
+
+__global__ void group_overlap_finish_kernel(const unsigned long long *__restrict__ count, float *__restrict__ overlap,
+                                            int L, HeadTable tab)
+{
+    const int slot = threadIdx.x;
+    if (slot < tab.n) overlap[tab.bh[slot]] = (float)((double)count[tab.bh[slot]] / ((double)L * tab.k[slot]));
+}
+
 // Linear block id -> (head slot, key range, block of 4 groups), consecutive ids on consecutive XCDs, every XCD
 // walking its own ranges one after the other (the order of the per-query L2-blocked sweeps).
 __device__ __forceinline__ bool decode_group_item(const SplitPlan &pl, int64_t b, int &slot, int &range, int &gb)
@@ -678,6 +736,26 @@ dsv_status launch_group_expand(const dsv_problem &p, const dsv_grouping &gr, con
     if (col_x) {
         const int64_t n = (int64_t)p.B * p.H * (p.L + 1);
         hipLaunchKernelGGL(scale_col_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, col, col_x, n, gm.G);
+        DSV_LAUNCH_CHECK();
+    }
+    return DSV_OK;
+}
+
+// tabs: built for L rows per head (the per-query index).
+dsv_status launch_group_overlap(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
+                                const int32_t *idx, unsigned long long *count, float *overlap, hipStream_t st)
+{
+    const size_t lds = (size_t)((p.L + 31) / 32) * 4;
+    if (lds > (64u << 10)) return DSV_EUNSUPPORTED;
+    const GroupGeom gm = make_group_geom(gr);
+    const int nbh = p.B * p.H;
+    hipLaunchKernelGGL(group_overlap_reset_kernel, dim3((nbh + 255) / 256), dim3(256), 0, st, count, nbh);
+    DSV_LAUNCH_CHECK();
+    const int Lq = p.L / gm.G;
+    for (int t = 0; t < n_tabs; ++t) {
+        hipLaunchKernelGGL(group_overlap_kernel, dim3(std::min(Lq, 2048), tabs[t].n), dim3(256), lds, st, idx, p.L, tabs[t], gm,
+                           group_centre(gr), count);
+        hipLaunchKernelGGL(group_overlap_finish_kernel, dim3(1), dim3(kMaxSlots), 0, st, count, overlap, p.L, tabs[t]);
         DSV_LAUNCH_CHECK();
     }
     return DSV_OK;

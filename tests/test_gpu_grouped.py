@@ -228,3 +228,41 @@ def test_general_grouped_path_matches_oracle(dtype, d, grid, cube, ks, sorted_in
         for name, got, ref, dt in (("O", O, O_ref, dtype), ("lse", lse, lse_ref, "f32"), ("dQ", dQ, dQ_ref, dtype),
                                    ("dK", dK, dK_ref, dtype), ("dV", dV, dV_ref, dtype)):
             assert_close(f"{name}[h={h}] {dtype} d={d} G={G}", got[0, h], ref, dt)
+
+
+def test_group_overlap_and_the_choice_of_the_group_size():
+    """dsv_group_overlap against the oracle (the counts behind both are integers: equal up to the final float
+    division) on rows in no particular order and on a real selection of smooth inputs; dsv_choose_grouping picks the
+    largest cube that keeps the required share in every head."""
+    grid, ks = (4, 8, 8), [37, 200]
+    L = grid[0] * grid[1] * grid[2]
+    rng = np.random.default_rng(9)
+    rows = [np.stack([rng.permutation(L)[:k] for _ in range(L)]).astype(np.int32) for k in ks]
+    p = dsv.Problem(1, len(ks), L, 128, 16, "bf16", ks, 1.0)
+    flat = torch.from_numpy(np.concatenate([r.reshape(-1) for r in rows])).cuda()
+    for cube in ((2, 2, 2), (1, 1, 1), (4, 2, 1), (2, 4, 8)):
+        got = dsv.group_overlap(p, dsv.Grouping(grid, cube), flat).cpu().numpy()
+        want = np.array([oracle.group_overlap(r, grid, cube) for r in rows])
+        assert np.allclose(got, want, rtol=0, atol=1e-6), (cube, got, want)
+        assert np.array_equal(np.rint(got.astype(np.float64) * L * np.array(ks)), np.rint(want * L * np.array(ks)))
+    # a real selection: smooth inputs, identity-like predictor (W = basis^T): neighbouring queries share most keys
+    cfg = _cfg((8, 8, 16), d=128, r=32, R=32, H=1)
+    t = wl.head_tensors_smooth(cfg, 0, sigma=5.0, names=("Q", "K"))
+    W = wl.basis(cfg, 0).T.astype(np.float32).copy()
+    k = cfg.L // 16
+    ps = dsv.Problem(1, 1, cfg.L, cfg.d, cfg.r, "bf16", [k], cfg.scale)
+    dev = lambda a: _dev(a, torch.bfloat16)
+    idx = dsv.lowrank_topk(ps, dev(t["Q"][None])[None], dev(t["K"][None])[None], dev(W[None]), dev(W[None]))
+    torch.cuda.synchronize()
+    rows_s = idx.view(cfg.L, k).cpu().numpy()
+    cubes = [(1, 1, 1), (2, 2, 2), (1, 2, 2), (4, 4, 4), (3, 2, 2), (8, 8, 16)]       # (3, 2, 2) does not tile; the last has G > 64
+    chosen, ov = dsv.choose_grouping(ps, cfg.grid, cubes, idx, min_overlap=0.8)
+    for c, cube in enumerate(cubes):
+        if cfg.grid[0] % cube[0] or cube[0] * cube[1] * cube[2] > 64:
+            assert ov[c][0] == -1.0
+        else:
+            assert abs(ov[c][0] - oracle.group_overlap(rows_s, cfg.grid, cube)) < 1e-6
+    ok = [c for c, cube in enumerate(cubes) if ov[c][0] >= 0.8]
+    assert chosen == max(ok, key=lambda c: cubes[c][0] * cubes[c][1] * cubes[c][2])
+    assert ov[0][0] == 1.0 and chosen != 0            # the unit cube always qualifies; on smooth inputs a larger one does too
+    assert dsv.choose_grouping(ps, cfg.grid, cubes[1:2], idx, min_overlap=1.01)[0] == -1
