@@ -363,8 +363,9 @@ def grouping_accuracy(dsv, torch, np, wl, cfg, seed):
     # predictor of rank r = basis rank: W = G^T (the basis Q and K are built on), which stands for a TRAINED
     # predictor (Q W = Cq G G^T ~ (d/R) Cq, so Q_lr K_lr^T tracks Q K^T); the benchmark's random W selects
     # keys that carry no particular softmax mass, and comparing outputs under it says nothing about grouping
-    c = WorkloadConfig(index=cfg.index, name="grouping_accuracy", B=1, H=1, grid=grid, d=cfg.d, r=cfg.basis_rank,
-                       k=None, k_choices=(), dtype="bf16", basis_rank=cfg.basis_rank, scale=cfg.scale)
+    R = min(cfg.basis_rank, 64)            # the predictor's rank here (the library takes r <= 64)
+    c = WorkloadConfig(index=cfg.index, name="grouping_accuracy", B=1, H=1, grid=grid, d=cfg.d, r=R,
+                       k=None, k_choices=(), dtype="bf16", basis_rank=R, scale=cfg.scale)
     L, k, G = c.L, c.L // 16, 8
     F, H, W = grid
     res = {}
