@@ -65,6 +65,42 @@ int main()
     CHECK(dsv_status_string(DSV_EHIP) != nullptr && dsv_version() != nullptr);
     float ms = 0.f;
     CHECK(dsv_kernel_ms(99, &ms) == DSV_EINVAL && dsv_kernel_ms(0, nullptr) == DSV_EINVAL);
+    // query grouping: layouts of the group kernels and of the general path, argument checks
+    {
+        void *one = reinterpret_cast<void *>(256);
+        std::vector<int32_t> k6(6, 8192);
+        for (uint32_t fl : flags) {
+            dsv_problem p = make(1, 6, 131072, 128, 16, DSV_BF16, k6, fl);
+            const dsv_grouping g8{32, 64, 64, 2, 2, 2}, g32{32, 64, 64, 2, 4, 4}, g128{32, 64, 64, 8, 4, 4}, bad{32, 64, 64, 3, 2, 2};
+            CHECK(dsv_lowrank_topk_grouped_workspace(&p, &g8) > 0 && dsv_lowrank_topk_grouped_workspace(&p, &bad) == 0);
+            CHECK((dsv_sparse_attn_fwd_grouped_workspace(&p, &g8) > 0) == (fl != 0));
+            CHECK(dsv_sparse_attn_fwd_grouped_workspace(&p, &g32) > (size_t)6 * 131072 * 8192 * 4);   // holds the expanded index
+            CHECK(dsv_sparse_attn_bwd_grouped_workspace(&p, &g32) > dsv_sparse_attn_bwd_grouped_workspace(&p, &g8));
+            CHECK(dsv_sparse_attn_fwd_grouped(&p, &g128, one, one, one, static_cast<int32_t *>(one), one, static_cast<float *>(one),
+                                              nullptr, 0, nullptr) == DSV_EUNSUPPORTED);
+            CHECK(dsv_sparse_attn_fwd_grouped(&p, &bad, one, one, one, static_cast<int32_t *>(one), one, static_cast<float *>(one),
+                                              nullptr, 0, nullptr) == DSV_EINVAL);
+            CHECK(dsv_sparse_attn_bwd_grouped(&p, &g32, one, one, one, static_cast<int32_t *>(one), static_cast<int32_t *>(one),
+                                              static_cast<int64_t *>(one), one, static_cast<float *>(one), one, one, one, one, one,
+                                              16, nullptr) == DSV_EWORKSPACE);
+            CHECK(dsv_group_overlap_workspace(&p) >= 48 && dsv_choose_grouping_workspace(&p) > dsv_group_overlap_workspace(&p));
+            CHECK(dsv_group_overlap(&p, &g8, static_cast<int32_t *>(one), static_cast<float *>(one), nullptr, 0, nullptr) == DSV_EWORKSPACE);
+            int32_t chosen = 7;
+            const int32_t cubes[6] = {2, 2, 2, 1, 1, 1};
+            CHECK(dsv_choose_grouping(&p, 32, 64, 64, nullptr, 2, static_cast<int32_t *>(one), 0.8f, &chosen, nullptr, one, 1 << 20,
+                                      nullptr) == DSV_EINVAL);
+            CHECK(dsv_choose_grouping(&p, 32, 64, 64, cubes, 0, static_cast<int32_t *>(one), 0.8f, &chosen, nullptr, one, 1 << 20,
+                                      nullptr) == DSV_EINVAL);
+            CHECK(dsv_choose_grouping(&p, 32, 64, 64, cubes, 2, static_cast<int32_t *>(one), 0.8f, &chosen, nullptr, one, 8,
+                                      nullptr) == DSV_EWORKSPACE && chosen == 7);
+        }
+        std::vector<int32_t> k128 = {128, 128};
+        dsv_problem f32p = make(1, 2, 1024, 64, 16, DSV_F32, k128, 0);
+        const dsv_grouping g{8, 8, 16, 2, 2, 2};
+        CHECK(dsv_sparse_attn_fwd_grouped_workspace(&f32p, &g) > 0);    // fp32 runs the general path
+        CHECK(dsv_predictor_loss_workspace(&f32p, 64) > 0 && dsv_predictor_loss_workspace(&f32p, 0) == 0);
+        CHECK(dsv_profile_sparsity_workspace(&f32p, 2000) == 0);        // more rows than tokens
+    }
     std::printf("host checks sanitizer run ok\n");
     return 0;
 }
