@@ -82,6 +82,8 @@ def parse_args():
                     help="(default for bf16, d = 128 configs) also time the query-grouped variant (2 x 2 x 2 cubes) at the "
                          "same shape, and measure what the shared rows cost in accuracy on spatially smooth inputs")
     ap.add_argument("--no-grouped", action="store_true", help="skip the query-grouped variant")
+    ap.add_argument("--grouped-cubes", action="store_true",
+                    help="with the grouped report: the grouped step also for 2 x 2 x 4 and 2 x 4 x 4 cubes (16 and 32 queries per group)")
     ap.add_argument("--grouped-density-sweep", action="store_true",
                     help="with --grouped: the grouped step at k/L = 3.1 ... 25 % and its interpolated crossover with dense")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -281,10 +283,9 @@ def _time_calls(torch, calls, steps, warmup):
     return [sum(e[i].elapsed_time(e[i + 1]) for e in ev) / steps for i in range(len(calls))]
 
 
-def grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, steps, warmup, dense_ms, per_query_ms):
+def grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, steps, warmup, dense_ms, per_query_ms, cube=(2, 2, 2)):
     """The query-grouped variant at the same shape (2 x 2 x 2 cubes of the latent grid): one step =
     dsv_lowrank_topk_grouped + dsv_sparse_attn_fwd_grouped + dsv_sparse_attn_bwd_grouped."""
-    cube = (2, 2, 2)
     grp = dsv.Grouping(cfg.grid, cube)
     # stage 1 writes ascending rows and lists: the L2-blocked kernels may be used
     p = dsv.Problem(1, cfg.H, cfg.L, cfg.d, cfg.r, cfg.dtype, [int(k) for k in ks], cfg.scale, sorted_index=True)
@@ -608,6 +609,13 @@ def main():
             gsweep.append({"density": frac, "k": kk, "ms_per_step": r["ms_per_step"], "stage_ms": r["stage_ms"],
                            "speedup_over_dense": r["speedup_over_dense"]})
             print(json.dumps(gsweep[-1]), file=sys.stderr, flush=True)
+        if args.grouped_cubes:
+            out["grouped"]["other_cubes"] = []
+            for cube in ((2, 2, 4), (2, 4, 4)):
+                r = grouped_report(dsv, torch, np, wl, cfg, ks, g, Wq, Wk, 2, 1, dense_ms, ms_per_step, cube=cube)
+                out["grouped"]["other_cubes"].append({k_: r[k_] for k_ in ("cube", "G", "ms_per_step", "kernel_ms", "stage_ms",
+                                                                           "speedup_over_dense")})
+                print(json.dumps(out["grouped"]["other_cubes"][-1]), file=sys.stderr, flush=True)
         if gsweep:
             out["grouped"]["density_sweep"] = gsweep
         if gsweep and dense_ms:

@@ -565,10 +565,10 @@ GroupedSplit grouped_split(char *ws, const GroupedStepLayout &w)
     return s;
 }
 
-// The group kernels proper exist for bf16, d = 128 and groups of at most 8 queries.  Every other case (fp32, d = 64,
+// The group kernels proper exist for bf16, d = 128 and groups of at most 32 queries.  Every other case (fp32, d = 64,
 // larger cubes) runs the per-query kernels on the queries reordered group by group, with the group index expanded to
 // one row per query: the same results, without the saving.
-bool grouped_native(const dsv_problem &p, const dsv_grouping &g) { return p.dtype == DSV_BF16 && p.d == 128 && group_size(g) <= 8; }
+bool grouped_native(const dsv_problem &p, const dsv_grouping &g) { return p.dtype == DSV_BF16 && p.d == 128 && group_size(g) <= 32; }
 
 struct GroupedFwdGeneral {
     size_t qp, op, lsep, idxx, step, step_bytes, total;

@@ -114,15 +114,14 @@ __global__ __launch_bounds__(256) void expand_idx_t_kernel(const int32_t *__rest
     const int32_t *src = idx_t_g + tab.off[slot];
     int32_t *dst = idx_t_x + tab.off[slot] * G;
     const int64_t stride = (int64_t)gridDim.x * 256;
-    // one thread per source entry; its G outputs are contiguous (G = 8: two 16-byte stores; tab.off is a multiple
+    // one thread per source entry; its G outputs are contiguous (G a multiple of 4: 16-byte stores; tab.off is a multiple
     // of the row length, the output stays 16-byte aligned whenever that is a multiple of 4 entries)
-    const bool wide = G == 8 && ((tab.off[slot] * G) & 3) == 0;
+    const bool wide = (G & 3) == 0 && ((tab.off[slot] * G) & 3) == 0;
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += stride) {
         const int32_t b = src[e] * G;
         if (wide) {
-            int4 *o = reinterpret_cast<int4 *>(dst + e * 8);
-            o[0] = make_int4(b, b + 1, b + 2, b + 3);
-            o[1] = make_int4(b + 4, b + 5, b + 6, b + 7);
+            int4 *o = reinterpret_cast<int4 *>(dst + e * G);
+            for (int m = 0; m < G; m += 4) o[m >> 2] = make_int4(b + m, b + m + 1, b + m + 2, b + m + 3);
         } else {
 #pragma unroll 1
             for (int m = 0; m < G; ++m) dst[e * G + m] = b + m;
@@ -240,7 +239,11 @@ __device__ __forceinline__ bf16x8_t parked_frag(const unsigned char *rows, int n
     return f;
 }
 
-template <int D, bool SPLIT>
+// NSUB = 1: the four waves of a block take four groups of at most 8 queries.  NSUB = 2 / 4: ONE group of up to 16 / 32
+// queries per block of NSUB waves, wave w taking members 8 w .. 8 w + 7; the waves gather the tile's rows together (two load instructions
+// each instead of eight), park them once, and every wave forms its own 8 members' scores and outputs from the shared
+// rows -- each K / V row crosses the vector memory path once per 32 queries.
+template <int D, bool SPLIT, int NSUB>
 __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                           const bf16_t *__restrict__ V,
                                                           const int32_t *__restrict__ idx_g, bf16_t *__restrict__ O,
@@ -263,9 +266,13 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, half = lane >> 5;
     const int c16 = lane & 15, g4 = lane >> 4;
-    const int g = gb * 4 + wave;
-    if (g >= Lq) return;  // the whole wave leaves; nothing below synchronises across waves
+    const int g = NSUB == 1 ? gb * 4 + wave : gb;
+    if (g >= Lq) return;  // NSUB = 1: the whole wave leaves, nothing below synchronises across waves; else the whole block
     const int G = gm.G;
+    const int mb = NSUB == 1 ? 0 : 8 * wave;     // first member this wave works for
+    const bool active = mb < G;                  // NSUB = 4: waves beyond the group still load and synchronise
+    const int Gw = min(G - mb, 8);               // members of this wave (<= 0: none)
+    auto block_sync = [&]() { if constexpr (NSUB == 1) wave_sync(); else __syncthreads(); };
     const bf16_t *Qh = Q + (int64_t)bh * L * D;
     const bf16_t *Kh = K + (int64_t)bh * L * D;
     const bf16_t *Vh = V + (int64_t)bh * L * D;
@@ -277,11 +284,11 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
         te = sp[1];
     }
 
-    __shared__ __align__(16) unsigned char k_all[4][32 * kVRow];
-    __shared__ __align__(16) unsigned char v_all[4][32 * kVRow];
+    __shared__ __align__(16) unsigned char k_all[NSUB == 1 ? 4 : 1][32 * kVRow];   // per wave, or one for the block
+    __shared__ __align__(16) unsigned char v_all[NSUB == 1 ? 4 : 1][32 * kVRow];
     __shared__ __align__(16) uint32_t p_all[4][16 * 16 + 8];
-    unsigned char *K_s = k_all[wave];                                        // the tile's 32 K rows, row-major
-    unsigned char *V_s = v_all[wave];                                        // the tile's 32 V rows
+    unsigned char *K_s = k_all[NSUB == 1 ? wave : 0];                        // the tile's 32 K rows, row-major
+    unsigned char *V_s = v_all[NSUB == 1 ? wave : 0];                        // the tile's 32 V rows
     u32_alias *P_s = p_all[wave];                                            // [16 rows][32 key slots] bf16, rows 8.. zero
     f32_alias *fac_s = reinterpret_cast<f32_alias *>(p_all[wave] + 16 * 16);  // [8 queries]
     for (int e = lane; e < 16 * 16; e += 64) P_s[e] = 0u;
@@ -289,11 +296,11 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
     // A operand of the scores: query row (lane % 32) of the group, zero beyond the group
     bf16x8_t qa[NM];
     {
-        const int64_t tq = member_token(gm, g, min(n, G - 1));
+        const int64_t tq = member_token(gm, g, min(mb + n, G - 1));
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
             uint4 raw = *reinterpret_cast<const uint4 *>(Qh + tq * D + m * 16 + half * 8);
-            if (n >= G) raw = make_uint4(0u, 0u, 0u, 0u);
+            if (n >= Gw) raw = make_uint4(0u, 0u, 0u, 0u);
             qa[m] = __builtin_bit_cast(bf16x8_t, raw);
         }
     }
@@ -312,15 +319,17 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
     // the score fragments (lane = key, 8 channels) and the transposed V fragments are read from there.
     // Software pipeline: while tile t is worked on, the rows of tile t+1 are in flight and the index entries of
     // tile t+2 are requested.  Keys past the end of the segment repeat its last entry and get probability zero.
-    int32_t jr[8];
-    bf16x8_t kr[8], vr[8];
+    constexpr int NI = 8 / NSUB;                 // load instructions (4 rows each) of this wave per tile and matrix
+    const int i0 = NSUB == 1 ? 0 : NI * wave;    // the first of them
+    int32_t jr[NI];
+    bf16x8_t kr[NI], vr[NI];
     auto load_idx = [&](int t0) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) jr[i] = row[min(t0 + g4 + 4 * i, te - 1)];
+        for (int i = 0; i < NI; ++i) jr[i] = row[min(t0 + g4 + 4 * (i0 + i), te - 1)];
     };
     auto load_rows = [&]() {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < NI; ++i) {
             kr[i] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)jr[i] * D + c16 * 8);
             vr[i] = *reinterpret_cast<const bf16x8_t *>(Vh + (int64_t)jr[i] * D + c16 * 8);
         }
@@ -334,11 +343,11 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
     for (int t0 = tb; t0 < te; t0 += 32) {
         const int nvalid = min(32, te - t0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            *reinterpret_cast<bf16x8_t *>(K_s + (g4 + 4 * i) * kVRow + c16 * 16) = kr[i];
-            *reinterpret_cast<bf16x8_t *>(V_s + (g4 + 4 * i) * kVRow + c16 * 16) = vr[i];
+        for (int i = 0; i < NI; ++i) {
+            *reinterpret_cast<bf16x8_t *>(K_s + (g4 + 4 * (i0 + i)) * kVRow + c16 * 16) = kr[i];
+            *reinterpret_cast<bf16x8_t *>(V_s + (g4 + 4 * (i0 + i)) * kVRow + c16 * 16) = vr[i];
         }
-        wave_sync();
+        block_sync();
         if (t0 + 32 < te) {  // wave-uniform
             load_rows();
             if (t0 + 64 < te) load_idx(t0 + 64);
@@ -382,8 +391,9 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
 #pragma unroll
         for (int nb = 0; nb < NM; ++nb)
             oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, parked_frag(V_s, nb, c16, g4), oacc[nb], 0, 0, 0);
-        wave_sync();  // the next tile overwrites P_s and V_s
+        block_sync();  // the next tile overwrites P_s and the parked rows
     }
+    if (!active) return;
     // query 4 * half + v lives in this half-wave's softmax state; the output rows of queries 4 * g4 + v in lane groups 0, 1
     float lt[4];
 #pragma unroll
@@ -394,8 +404,8 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int q = 4 * half + v;
-                if (q < G) {
-                    const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range;
+                if (q < Gw) {
+                    const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, mb + q)) * pl.S + range;
                     pm[slot_id] = M[v];
                     pl_[slot_id] = lt[v];
                 }
@@ -405,8 +415,8 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int q = 4 * g4 + v;
-                if (q < G) {
-                    const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range;
+                if (q < Gw) {
+                    const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, mb + q)) * pl.S + range;
 #pragma unroll
                     for (int nb = 0; nb < NM; ++nb) pacc[slot_id * D + nb * 16 + c16] = oacc[nb][v];
                 }
@@ -419,7 +429,7 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
         for (int v = 0; v < 4; ++v) {
             const int q = 4 * half + v;
             fac_s[q] = 1.f / lt[v];
-            if (q < G) lse[(int64_t)bh * L + member_token(gm, g, q)] = (M[v] + log2f(lt[v])) * kLn2;
+            if (q < Gw) lse[(int64_t)bh * L + member_token(gm, g, mb + q)] = (M[v] + log2f(lt[v])) * kLn2;
         }
     }
     wave_sync();
@@ -427,9 +437,9 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int q = 4 * g4 + v;
-            if (q < G) {
+            if (q < Gw) {
                 const float inv = fac_s[q];
-                bf16_t *orow = O + ((int64_t)bh * L + member_token(gm, g, q)) * D;
+                bf16_t *orow = O + ((int64_t)bh * L + member_token(gm, g, mb + q)) * D;
 #pragma unroll
                 for (int nb = 0; nb < NM; ++nb) orow[nb * 16 + c16] = f32_to_bf16(oacc[nb][v] * inv);
             }
@@ -473,7 +483,8 @@ __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
     lo = f32_to_bf16(x - __uint_as_float((uint32_t)hi << 16));
 }
 
-template <int D, bool SPLIT>
+// NSUB as in the forward: 4 = one group of up to 32 queries per block, the rows gathered and parked once per block.
+template <int D, bool SPLIT, int NSUB>
 __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                          const bf16_t *__restrict__ V, const int32_t *__restrict__ idx_g,
                                                          const bf16_t *__restrict__ O, const float *__restrict__ lse,
@@ -497,9 +508,13 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, half = lane >> 5;
     const int c16 = lane & 15, g4 = lane >> 4;
-    const int g = gb * 4 + wave;
-    if (g >= Lq) return;  // whole wave
+    const int g = NSUB == 1 ? gb * 4 + wave : gb;
+    if (g >= Lq) return;  // NSUB = 1: whole wave; else whole block
     const int G = gm.G;
+    const int mb = NSUB == 1 ? 0 : 8 * wave;     // first member this wave works for
+    const bool active = mb < G;
+    const int Gw = min(G - mb, 8);               // members of this wave (<= 0: none; the wave still loads and synchronises)
+    auto block_sync = [&]() { if constexpr (NSUB == 1) wave_sync(); else __syncthreads(); };
     const int64_t hb = (int64_t)bh * L * D;
     const bf16_t *Kh = K + hb, *Vh = V + hb;
     const int32_t *row = idx_g + tab.off[slot] + (int64_t)g * k;
@@ -509,11 +524,11 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
         tb = sp[0];
         te = sp[1];
     }
-    __shared__ __align__(16) unsigned char k_all[4][32 * kVRow];
-    __shared__ __align__(16) unsigned char v_all[4][32 * kVRow];
+    __shared__ __align__(16) unsigned char k_all[NSUB == 1 ? 4 : 1][32 * kVRow];   // per wave, or one for the block
+    __shared__ __align__(16) unsigned char v_all[NSUB == 1 ? 4 : 1][32 * kVRow];
     __shared__ __align__(16) uint32_t w_all[4][32 * 16 + 16];
-    unsigned char *K_s = k_all[wave];   // the tile's 32 K rows, row-major
-    unsigned char *V_s = v_all[wave];   // the tile's 32 V rows
+    unsigned char *K_s = k_all[NSUB == 1 ? wave : 0];   // the tile's 32 K rows, row-major
+    unsigned char *V_s = v_all[NSUB == 1 ? wave : 0];   // the tile's 32 V rows
     u32_alias *W_s = w_all[wave];       // [32 rows][32 key slots] bf16: weights of the second product
     f32_alias *q_s = reinterpret_cast<f32_alias *>(w_all[wave] + 32 * 16);  // [8] D0, then [8] Delta - D0
 
@@ -521,20 +536,20 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
     // lane = (row l % 16, channels 32 m + 8 (l / 16) .. + 8)
     bf16x8_t qa[4], ga[4];
     {
-        const int64_t tq = member_token(gm, g, min(c16, G - 1));
+        const int64_t tq = member_token(gm, g, min(mb + c16, G - 1));
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             uint4 rq = *reinterpret_cast<const uint4 *>(Q + hb + tq * D + m * 32 + g4 * 8);
             uint4 rg = *reinterpret_cast<const uint4 *>(dO + hb + tq * D + m * 32 + g4 * 8);
-            if (c16 >= G) { rq = make_uint4(0u, 0u, 0u, 0u); rg = rq; }
+            if (c16 >= Gw) { rq = make_uint4(0u, 0u, 0u, 0u); rg = rq; }
             qa[m] = __builtin_bit_cast(bf16x8_t, rq);
             ga[m] = __builtin_bit_cast(bf16x8_t, rg);
         }
     }
     // D0[q] = dO_q . O_q (stored, rounded O): lanes across the channels, then a wave reduction
 #pragma unroll 1
-    for (int q = 0; q < G; ++q) {
-        const int64_t t = member_token(gm, g, q);
+    for (int q = 0; q < Gw; ++q) {
+        const int64_t t = member_token(gm, g, mb + q);
         const uint32_t go = reinterpret_cast<const uint32_t *>(dO + hb + t * D)[lane];
         const uint32_t oo = reinterpret_cast<const uint32_t *>(O + hb + t * D)[lane];
         float d = __uint_as_float(go << 16) * __uint_as_float(oo << 16) +
@@ -549,8 +564,8 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int q = 4 * (g4 & 1) + v;
-        lse2[v] = q < G ? lse[(int64_t)bh * L + member_token(gm, g, q)] * kLog2e : 0.f;
-        d0[v] = q < G ? q_s[q] : 0.f;
+        lse2[v] = q < Gw ? lse[(int64_t)bh * L + member_token(gm, g, mb + q)] * kLog2e : 0.f;
+        d0[v] = q < Gw ? q_s[q] : 0.f;
         dl[v] = 0.f;
     }
     floatx16_t acc2[NC];  // acc2[nb][4 part + i]: query 4 half + i, channel 32 nb + n; parts: C head, C tail, B head, B tail
@@ -561,15 +576,17 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
     const float c2 = scale * kLog2e;
 
     // rows loaded whole and parked in LDS, software-pipelined, as in the forward
-    int32_t jr[8];
-    bf16x8_t kr[8], vr[8];
+    constexpr int NI = 8 / NSUB;                 // load instructions (4 rows each) of this wave per tile and matrix
+    const int i0 = NSUB == 1 ? 0 : NI * wave;
+    int32_t jr[NI];
+    bf16x8_t kr[NI], vr[NI];
     auto load_idx = [&](int t0) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) jr[i] = row[min(t0 + g4 + 4 * i, te - 1)];
+        for (int i = 0; i < NI; ++i) jr[i] = row[min(t0 + g4 + 4 * (i0 + i), te - 1)];
     };
     auto load_rows = [&]() {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < NI; ++i) {
             kr[i] = *reinterpret_cast<const bf16x8_t *>(Kh + (int64_t)jr[i] * D + c16 * 8);
             vr[i] = *reinterpret_cast<const bf16x8_t *>(Vh + (int64_t)jr[i] * D + c16 * 8);
         }
@@ -582,11 +599,11 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
     for (int t0 = tb; t0 < te; t0 += 32) {
         const int nvalid = min(32, te - t0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            *reinterpret_cast<bf16x8_t *>(K_s + (g4 + 4 * i) * kVRow + c16 * 16) = kr[i];
-            *reinterpret_cast<bf16x8_t *>(V_s + (g4 + 4 * i) * kVRow + c16 * 16) = vr[i];
+        for (int i = 0; i < NI; ++i) {
+            *reinterpret_cast<bf16x8_t *>(K_s + (g4 + 4 * (i0 + i)) * kVRow + c16 * 16) = kr[i];
+            *reinterpret_cast<bf16x8_t *>(V_s + (g4 + 4 * (i0 + i)) * kVRow + c16 * 16) = vr[i];
         }
-        wave_sync();
+        block_sync();
         if (t0 + 32 < te) {  // wave-uniform
             load_rows();
             if (t0 + 64 < te) load_idx(t0 + 64);
@@ -628,8 +645,9 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
             for (int nb = 0; nb < NC; ++nb)
                 acc2[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, parked_frag32(K_s, nb, s, n, half), acc2[nb], 0, 0, 0);
         }
-        wave_sync();  // the next tile overwrites the parked rows and W_s
+        block_sync();  // the next tile overwrites the parked rows and W_s
     }
+    if (!active) return;
     // Delta of query 4 g4 + v: sum over the 16 lanes of the row group (both key sub-tiles are already in dl)
     float dt[4];
 #pragma unroll
@@ -640,12 +658,12 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
     }
     wave_sync();
     if (SPLIT) {
-        if (lane < G) pdelta[((int64_t)bh * L + member_token(gm, g, lane)) * pl.S + range] = q_s[8 + lane];
+        if (lane < Gw) pdelta[((int64_t)bh * L + member_token(gm, g, mb + lane)) * pl.S + range] = q_s[8 + lane];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int q = 4 * half + i;
-            if (q < G) {
-                const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, q)) * pl.S + range;
+            if (q < Gw) {
+                const int64_t slot_id = ((int64_t)bh * L + member_token(gm, g, mb + q)) * pl.S + range;
 #pragma unroll
                 for (int nb = 0; nb < NC; ++nb) {
                     pa[slot_id * D + nb * 32 + n] = acc2[nb][i] + acc2[nb][4 + i];
@@ -655,13 +673,13 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
         }
         return;
     }
-    if (lane < G) delta_out[(int64_t)bh * L + member_token(gm, g, lane)] = q_s[8 + lane];
+    if (lane < Gw) delta_out[(int64_t)bh * L + member_token(gm, g, mb + lane)] = q_s[8 + lane];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int q = 4 * half + i;
-        if (q < G) {
+        if (q < Gw) {
             const float dd = q_s[8 + q] - q_s[q];
-            bf16_t *qrow = dQ + hb + member_token(gm, g, q) * D;
+            bf16_t *qrow = dQ + hb + member_token(gm, g, mb + q) * D;
 #pragma unroll
             for (int nb = 0; nb < NC; ++nb) {
                 const float cc = acc2[nb][i] + acc2[nb][4 + i], bb = acc2[nb][8 + i] + acc2[nb][12 + i];
@@ -761,27 +779,49 @@ dsv_status launch_group_overlap(const dsv_problem &p, const dsv_grouping &gr, co
     return DSV_OK;
 }
 
+// Launch shapes of the group kernels: groups of at most 8 queries, four to a block (one wave each); groups of up to 16
+// (32), one to a block of two (four) waves that share the parked rows.
+static int groups_per_block(int G) { return G <= 8 ? 4 : 1; }
+static int waves_per_group(int G) { return G <= 8 ? 1 : (G <= 16 ? 2 : 4); }
+
+template <bool SPLIT, typename... Args>
+static void launch_fwd_variant(int nsub, dim3 grid, hipStream_t st, Args... args)
+{
+    if (nsub == 1) hipLaunchKernelGGL((grouped_fwd_kernel<128, SPLIT, 1>), grid, dim3(256), 0, st, args...);
+    else if (nsub == 2) hipLaunchKernelGGL((grouped_fwd_kernel<128, SPLIT, 2>), grid, dim3(128), 0, st, args...);
+    else hipLaunchKernelGGL((grouped_fwd_kernel<128, SPLIT, 4>), grid, dim3(256), 0, st, args...);
+}
+template <bool SPLIT, typename... Args>
+static void launch_dq_variant(int nsub, dim3 grid, hipStream_t st, Args... args)
+{
+    if (nsub == 1) hipLaunchKernelGGL((grouped_dq_kernel<128, SPLIT, 1>), grid, dim3(256), 0, st, args...);
+    else if (nsub == 2) hipLaunchKernelGGL((grouped_dq_kernel<128, SPLIT, 2>), grid, dim3(128), 0, st, args...);
+    else hipLaunchKernelGGL((grouped_dq_kernel<128, SPLIT, 4>), grid, dim3(256), 0, st, args...);
+}
+
 dsv_status launch_grouped_fwd(const dsv_problem &p, const dsv_grouping &gr, const HeadTable *tabs, int n_tabs,
                               const void *Q, const void *K, const void *V, const int32_t *idx_g, void *O, float *lse,
                               const GroupedSplit *split, hipStream_t st)
 {
     if (p.dtype != DSV_BF16 || p.d != 128) return DSV_EUNSUPPORTED;
     const GroupGeom gm = make_group_geom(gr);
-    if (gm.G > 8) return DSV_EUNSUPPORTED;
+    if (gm.G > 32) return DSV_EUNSUPPORTED;
     const int Lq = p.L / gm.G;
+    const int gpb = groups_per_block(gm.G), nsub = waves_per_group(gm.G);
+    const int nqb = (Lq + gpb - 1) / gpb;
     if (!split) {
         KernelSpan span(DSV_KERNEL_FWD_SWEEP, st);
         for (int t = 0; t < n_tabs; ++t) {
-            dim3 grid((Lq + 3) / 4, tabs[t].n);
-            hipLaunchKernelGGL((grouped_fwd_kernel<128, false>), grid, dim3(256), 0, st, (const bf16_t *)Q, (const bf16_t *)K,
-                               (const bf16_t *)V, idx_g, (bf16_t *)O, lse, (const int32_t *)nullptr, (float *)nullptr,
-                               (float *)nullptr, (float *)nullptr, p.L, Lq, p.scale, tabs[t], gm, SplitPlan{});
+            dim3 grid(nqb, tabs[t].n);
+            launch_fwd_variant<false>(nsub, grid, st, (const bf16_t *)Q, (const bf16_t *)K, (const bf16_t *)V, idx_g, (bf16_t *)O, lse,
+                                      (const int32_t *)nullptr, (float *)nullptr, (float *)nullptr, (float *)nullptr, p.L, Lq,
+                                      p.scale, tabs[t], gm, SplitPlan{});
             DSV_LAUNCH_CHECK();
         }
         return DSV_OK;
     }
     SplitPlan pl = split->plan;
-    pl.nqb = (Lq + 3) / 4;
+    pl.nqb = nqb;
     dsv_status rc = launch_row_segments(p, Lq, tabs, n_tabs, pl, idx_g, split->seg, st);
     if (rc != DSV_OK) return rc;
     {
@@ -789,9 +829,10 @@ dsv_status launch_grouped_fwd(const dsv_problem &p, const dsv_grouping &gr, cons
         for (int t = 0; t < n_tabs; ++t) {
             const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
             if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-            hipLaunchKernelGGL((grouped_fwd_kernel<128, true>), dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t *)Q,
-                               (const bf16_t *)K, (const bf16_t *)V, idx_g, (bf16_t *)O, lse, split->seg, split->pa, split->pb,
-                               split->pc, p.L, Lq, p.scale, tabs[t], gm, pl);
+            dim3 grid((unsigned)blocks);
+            launch_fwd_variant<true>(nsub, grid, st, (const bf16_t *)Q, (const bf16_t *)K, (const bf16_t *)V, idx_g, (bf16_t *)O, lse,
+                                     (const int32_t *)split->seg, split->pa, split->pb, split->pc, p.L, Lq, p.scale, tabs[t], gm,
+                                     pl);
             DSV_LAUNCH_CHECK();
         }
     }
@@ -805,22 +846,23 @@ dsv_status launch_grouped_dq(const dsv_problem &p, const dsv_grouping &gr, const
 {
     if (p.dtype != DSV_BF16 || p.d != 128) return DSV_EUNSUPPORTED;
     const GroupGeom gm = make_group_geom(gr);
-    if (gm.G > 8) return DSV_EUNSUPPORTED;
+    if (gm.G > 32) return DSV_EUNSUPPORTED;
     const int Lq = p.L / gm.G;
+    const int gpb = groups_per_block(gm.G), nsub = waves_per_group(gm.G);
+    const int nqb = (Lq + gpb - 1) / gpb;
     if (!split) {
         KernelSpan span(DSV_KERNEL_DQ_SWEEP, st);
         for (int t = 0; t < n_tabs; ++t) {
-            dim3 grid((Lq + 3) / 4, tabs[t].n);
-            hipLaunchKernelGGL((grouped_dq_kernel<128, false>), grid, dim3(256), 0, st, (const bf16_t *)Q, (const bf16_t *)K,
-                               (const bf16_t *)V, idx_g, (const bf16_t *)O, lse, (const bf16_t *)dO, (bf16_t *)dQ, delta,
-                               (const int32_t *)nullptr, (float *)nullptr, (float *)nullptr, (float *)nullptr, p.L, Lq,
-                               p.scale, tabs[t], gm, SplitPlan{});
+            dim3 grid(nqb, tabs[t].n);
+            launch_dq_variant<false>(nsub, grid, st, (const bf16_t *)Q, (const bf16_t *)K, (const bf16_t *)V, idx_g, (const bf16_t *)O, lse,
+                                     (const bf16_t *)dO, (bf16_t *)dQ, delta, (const int32_t *)nullptr, (float *)nullptr,
+                                     (float *)nullptr, (float *)nullptr, p.L, Lq, p.scale, tabs[t], gm, SplitPlan{});
             DSV_LAUNCH_CHECK();
         }
         return DSV_OK;
     }
     SplitPlan pl = split->plan;
-    pl.nqb = (Lq + 3) / 4;
+    pl.nqb = nqb;
     dsv_status rc = launch_row_segments(p, Lq, tabs, n_tabs, pl, idx_g, split->seg, st);
     if (rc != DSV_OK) return rc;
     {
@@ -828,9 +870,10 @@ dsv_status launch_grouped_dq(const dsv_problem &p, const dsv_grouping &gr, const
         for (int t = 0; t < n_tabs; ++t) {
             const int64_t blocks = (int64_t)tabs[t].n * pl.S_pad * pl.nqb;
             if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-            hipLaunchKernelGGL((grouped_dq_kernel<128, true>), dim3((unsigned)blocks), dim3(256), 0, st, (const bf16_t *)Q,
-                               (const bf16_t *)K, (const bf16_t *)V, idx_g, (const bf16_t *)O, lse, (const bf16_t *)dO,
-                               (bf16_t *)dQ, delta, split->seg, split->pa, split->pb, split->pc, p.L, Lq, p.scale, tabs[t], gm, pl);
+            dim3 grid((unsigned)blocks);
+            launch_dq_variant<true>(nsub, grid, st, (const bf16_t *)Q, (const bf16_t *)K, (const bf16_t *)V, idx_g, (const bf16_t *)O, lse,
+                                    (const bf16_t *)dO, (bf16_t *)dQ, delta, (const int32_t *)split->seg, split->pa, split->pb,
+                                    split->pc, p.L, Lq, p.scale, tabs[t], gm, pl);
             DSV_LAUNCH_CHECK();
         }
     }

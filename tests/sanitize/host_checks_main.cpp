@@ -71,7 +71,7 @@ int main()
         std::vector<int32_t> k6(6, 8192);
         for (uint32_t fl : flags) {
             dsv_problem p = make(1, 6, 131072, 128, 16, DSV_BF16, k6, fl);
-            const dsv_grouping g8{32, 64, 64, 2, 2, 2}, g32{32, 64, 64, 2, 4, 4}, g128{32, 64, 64, 8, 4, 4}, bad{32, 64, 64, 3, 2, 2};
+            const dsv_grouping g8{32, 64, 64, 2, 2, 2}, g32{32, 64, 64, 4, 4, 4}, g128{32, 64, 64, 8, 4, 4}, bad{32, 64, 64, 3, 2, 2};   // g32: 64 members, the general path
             CHECK(dsv_lowrank_topk_grouped_workspace(&p, &g8) > 0 && dsv_lowrank_topk_grouped_workspace(&p, &bad) == 0);
             CHECK((dsv_sparse_attn_fwd_grouped_workspace(&p, &g8) > 0) == (fl != 0));
             CHECK(dsv_sparse_attn_fwd_grouped_workspace(&p, &g32) > (size_t)6 * 131072 * 8192 * 4);   // holds the expanded index

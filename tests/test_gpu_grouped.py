@@ -151,11 +151,14 @@ def test_grouped_backward_matches_oracle(case, blocked):
 
 @pytest.mark.parametrize("grid,cube,k", [((2, 4, 6), (1, 1, 2), 31), ((3, 4, 6), (3, 1, 1), 32), ((2, 4, 8), (1, 2, 2), 33),
                                          ((5, 2, 6), (5, 1, 1), 1), ((2, 7, 6), (1, 7, 1), 63), ((4, 4, 4), (2, 2, 2), 64),
-                                         ((2, 8, 8), (2, 2, 2), 65), ((2, 4, 8), (1, 1, 4), 64)])
+                                         ((2, 8, 8), (2, 2, 2), 65), ((2, 4, 8), (1, 1, 4), 64),
+                                         ((4, 8, 8), (2, 4, 4), 40), ((2, 4, 6), (2, 2, 3), 33), ((4, 4, 8), (4, 2, 2), 128),
+                                         ((2, 6, 10), (1, 3, 5), 31), ((8, 8, 8), (2, 4, 4), 200)])
 @pytest.mark.parametrize("blocked", [False, True], ids=["plain", "l2_blocked"])
 def test_every_group_size_and_tile_boundary(grid, cube, k, blocked):
-    """G = 2, 3, 4, 5, 7, 8 with k just below, at and just above whole 32-key tiles: forward and backward against the
-    grouped oracle (one head, the oracle's index)."""
+    """G = 2, 3, 4, 5, 7, 8 (four groups per block) and 12, 15, 16, 32 (one group per block, its waves sharing the
+    gathered rows) with k just below, at and just above whole 32-key tiles: forward and backward against the grouped
+    oracle (one head, the oracle's index)."""
     cfg = _cfg(grid, H=1)
     L, G = cfg.L, cube[0] * cube[1] * cube[2]
     t = wl.head_tensors(cfg, 0)
@@ -189,13 +192,13 @@ def test_grouped_arguments_are_checked_on_the_host():
         assert dsv.lowrank_topk_grouped_workspace(p, gg) == 0
     huge = dsv.Grouping((8, 8, 8), (8, 4, 4))              # G = 128: beyond the largest group accepted (64)
     assert lib.dsv_sparse_attn_fwd_grouped(p.c, huge.c, one, one, one, one, one, one, None, 0, None) == -2
-    big = dsv.Grouping((4, 8, 16), (2, 2, 4))              # G = 16 runs through the per-query kernels: needs its workspace
+    big = dsv.Grouping((4, 8, 16), (2, 4, 8))              # G = 64 runs through the per-query kernels: needs its workspace
     assert dsv.sparse_attn_fwd_grouped_workspace(p, big) > p.nnz * 4
     assert lib.dsv_sparse_attn_fwd_grouped(p.c, big.c, one, one, one, one, one, one, None, 0, None) == -3
 
 
 @pytest.mark.parametrize("dtype,d,grid,cube,ks", [("f32", 64, (4, 8, 8), (2, 2, 2), [40, 7]),       # fp32, d = 64
-                                                  ("bf16", 128, (4, 8, 16), (2, 2, 4), [100, 33]),  # G = 16
+                                                  ("bf16", 128, (4, 8, 16), (2, 4, 8), [100, 33]),  # G = 64
                                                   ("bf16", 64, (4, 4, 8), (1, 2, 2), [128, 20]),    # d = 64; k = L
                                                   ("f32", 128, (2, 6, 6), (2, 3, 3), [9, 72])])     # G = 18, fp32, k = L
 @pytest.mark.parametrize("sorted_index", [False, True], ids=["plain", "l2_blocked"])
