@@ -214,8 +214,8 @@ DSV_API dsv_status dsv_sparse_attn_bwd_dkdv(const dsv_problem *p, const void *Q,
  * dsv_sparse_attn_fwd_grouped: every member of a group attends over the group's row; same O, lse as
  *   dsv_sparse_attn_fwd on the index with that row repeated for every member.  Each selected K / V
  *   row is gathered once per group and used by all members (both products of a tile on the matrix cores)
- *   for bf16, d = 128, G <= 32 (up to 8 members: one wave per group; up to 32: one block per group, its four waves
- *   sharing the gathered rows).  Every other dtype, head dimension or cube (G <= 64; larger: DSV_EUNSUPPORTED)
+ *   for bf16, d = 128, G <= 32 (up to 8 members: one wave per group; up to 16 / 32: one block of two / four waves per
+ *   group, sharing the gathered rows).  Every other dtype, head dimension or cube (G <= 64; larger: DSV_EUNSUPPORTED)
  *   gives the same results through the per-query kernels on queries reordered group by group, with the
  *   index expanded to one row per query in the workspace -- the contract without the saving.  With
  *   DSV_FLAG_SORTED_INDEX (rows ascending, as stage 1 writes them) the L2-blocked form runs and needs

@@ -4,7 +4,8 @@
 // group and uses it for all G members, which turns the per-query gather sweep (one K row and one V row
 // per (query, key) pair, ~1 flop per byte) into small dense tiles.
 //
-// Forward kernel (bf16, d = 128, G <= 8): one wave per group.
+// Forward kernel (bf16, d = 128): one wave per 8 queries of a group (groups of up to 32 queries: up to four waves that
+// share the gathered rows).
 //   scores   S[q, key] for 32 keys at a time on the matrix cores: A = the group's query rows (rows >= G are
 //            zero), B = the 32 gathered K rows, one v_mfma_f32_32x32x16_bf16 per 16 channels.  Lane l then
 //            holds key (l % 32) against queries 4 * (l / 32) + 0..3 (accumulators 0..3; the other twelve
