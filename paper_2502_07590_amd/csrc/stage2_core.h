@@ -349,12 +349,14 @@ template <int CH> struct DkdvState {
     float dk[CH], dv[CH];
 };
 
-template <typename T, int D, int LPR, bool TAIL>
+// stat_s (optional): the packed {lse * log2(e), Delta} entries of the queries from stat_base on, parked in
+// LDS by the caller (every query of the list segment lies in that stretch); then lse_h / delta_h are unused.
+template <typename T, int D, int LPR, bool TAIL, bool LDS_STAT>
 __device__ __forceinline__ void dkdv_step(DkdvState<D / LPR> &st, const RowChunk<T, D / LPR> &kc,
                                           const RowChunk<T, D / LPR> &vc, const T *__restrict__ Qh,
                                           const T *__restrict__ Gh, const float *__restrict__ lse_h,
-                                          const float *__restrict__ delta_h, uint32_t lane_off,
-                                          const int32_t *jsrc, int nvalid, float c2)
+                                          const float *__restrict__ delta_h, const float2 *stat_s, int stat_base,
+                                          uint32_t lane_off, const int32_t *jsrc, int nvalid, float c2)
 {
     constexpr int CH = D / LPR;
     constexpr int U = 2;
@@ -368,7 +370,11 @@ __device__ __forceinline__ void dkdv_step(DkdvState<D / LPR> &st, const RowChunk
     for (int u = 0; u < U; ++u) {
         qc[u] = gather_chunk<T, D, LPR>(Qh, (uint32_t)iq[u], lane_off);
         gc[u] = gather_chunk<T, D, LPR>(Gh, (uint32_t)iq[u], lane_off);
-        if (delta_h) {
+        if constexpr (LDS_STAT) {
+            const float2 rs = stat_s[iq[u] - stat_base];
+            l2[u] = rs.x;
+            dl[u] = rs.y;
+        } else if (delta_h) {
             l2[u] = lse_h[iq[u]] * kLog2e;
             dl[u] = delta_h[iq[u]];
         } else {  // lse_h is a packed array {lse * log2(e), Delta} per query: one 8-byte load
@@ -391,13 +397,13 @@ __device__ __forceinline__ void dkdv_step(DkdvState<D / LPR> &st, const RowChunk
     axpy_pair_precise<T, CH>(st.dv, gc[0], gc[1], p[0], p[1]);
 }
 
-template <typename T, int D, int LPR>
+template <typename T, int D, int LPR, bool LDS_STAT = false>
 __device__ __forceinline__ void dkdv_sweep(DkdvState<D / LPR> &st, const RowChunk<T, D / LPR> &kc,
                                            const RowChunk<T, D / LPR> &vc, const T *__restrict__ Qh,
                                            const T *__restrict__ Gh, const float *__restrict__ lse_h,
                                            const float *__restrict__ delta_h, uint32_t lane_off,
                                            const int32_t *__restrict__ list, int tb, int te, float c2, int32_t *stage,
-                                           int s)
+                                           int s, const float2 *stat_s = nullptr, int stat_base = 0)
 {
     if (tb >= te) return;
     StagedIndex<LPR> si;
@@ -409,12 +415,12 @@ __device__ __forceinline__ void dkdv_sweep(DkdvState<D / LPR> &st, const RowChun
         int it = 0;
 #if DSV_DKDV_REP == 2
         for (; it + 4 <= n; it += 4) {
-            dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it, 2, c2);
-            dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it + 2, 2, c2);
+            dkdv_step<T, D, LPR, false, LDS_STAT>(st, kc, vc, Qh, Gh, lse_h, delta_h, stat_s, stat_base, lane_off, stage + it, 2, c2);
+            dkdv_step<T, D, LPR, false, LDS_STAT>(st, kc, vc, Qh, Gh, lse_h, delta_h, stat_s, stat_base, lane_off, stage + it + 2, 2, c2);
         }
 #endif
-        for (; it + 2 <= n; it += 2) dkdv_step<T, D, LPR, false>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it, 2, c2);
-        if (it < n) dkdv_step<T, D, LPR, true>(st, kc, vc, Qh, Gh, lse_h, delta_h, lane_off, stage + it, n - it, c2);
+        for (; it + 2 <= n; it += 2) dkdv_step<T, D, LPR, false, LDS_STAT>(st, kc, vc, Qh, Gh, lse_h, delta_h, stat_s, stat_base, lane_off, stage + it, 2, c2);
+        if (it < n) dkdv_step<T, D, LPR, true, LDS_STAT>(st, kc, vc, Qh, Gh, lse_h, delta_h, stat_s, stat_base, lane_off, stage + it, n - it, c2);
     }
 }
 
