@@ -360,7 +360,7 @@ typedef enum {
   DSV_KERNEL_FWD_SWEEP = 0,   /* sparse forward gather sweep */
   DSV_KERNEL_DQ_SWEEP = 1,    /* backward, query-major sweep */
   DSV_KERNEL_DKDV_SWEEP = 2,  /* backward, key-major sweep */
-  DSV_KERNEL_THRESHOLD = 3,   /* stage 1: the four threshold-search passes together */
+  DSV_KERNEL_THRESHOLD = 3,   /* stage 1: all kernels of the threshold search together */
   DSV_KERNEL_EMIT = 4,        /* stage 1: query-major emission */
   DSV_KERNEL_EMIT_T_COUNT = 5,/* stage 1: key-major counting pass */
   DSV_KERNEL_EMIT_T_WRITE = 6,/* stage 1: key-major emission */
@@ -368,6 +368,17 @@ typedef enum {
 } dsv_kernel_span;
 DSV_API dsv_status dsv_kernel_timing(int32_t enable);
 DSV_API dsv_status dsv_kernel_ms(int32_t span, float *ms);
+
+/* How stage 1 finds every query's threshold score (the k-th largest; paper Sec. "Critical KV Estimation with
+ * Kernel Fusion").  Both methods are exact and give identical results; the choice only affects speed.
+ *   0  automatic (default): the windowed search -- a key sample brackets the threshold, then two sweeps over
+ *      the keys -- for heads with L >= 16384 and k <= L/4, else the radix search (four sweeps, 8 bits each);
+ *   1  always the radix search;
+ *   2  the windowed search wherever its sample fits (L >= 4096).
+ * Query tiles the windowed search cannot settle (threshold outside the bracket, massive ties) go through the
+ * radix search afterwards, inside the same call.  Process-wide; for tests and measurements.  Returns the
+ * previous mode; a mode outside 0..2 changes nothing and returns -1. */
+DSV_API int32_t dsv_threshold_search(int32_t mode);
 
 /* Pure-gather probe: the practical ceiling of the vector memory path (L2 -> vector L1 -> registers) for the
  * stage-2 access pattern, against which the sweeps' achieved gather rate is reported.  K, V: DEVICE bf16

@@ -35,7 +35,7 @@ EXPORTED_SYMBOLS = (
     "dsv_group_overlap_workspace", "dsv_group_overlap", "dsv_choose_grouping_workspace", "dsv_choose_grouping",
     "dsv_lowrank_topk_noalloc_max_bytes", "dsv_lowrank_topk_noalloc",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
-    "dsv_kernel_timing", "dsv_kernel_ms", "dsv_measure_gather_ceiling",
+    "dsv_kernel_timing", "dsv_kernel_ms", "dsv_threshold_search", "dsv_measure_gather_ceiling",
 )
 
 
@@ -149,6 +149,8 @@ def load_library():
     lib.dsv_lowrank_project.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
     lib.dsv_lowrank_scores_rows.restype = ctypes.c_int
     lib.dsv_lowrank_scores_rows.argtypes = [P, vp, vp, i32, i32, vp, i32, vp, vp]
+    lib.dsv_threshold_search.restype = ctypes.c_int32
+    lib.dsv_threshold_search.argtypes = [i32]
     lib.dsv_kernel_timing.restype = ctypes.c_int
     lib.dsv_kernel_timing.argtypes = [i32]
     lib.dsv_kernel_ms.restype = ctypes.c_int
@@ -502,6 +504,14 @@ def lowrank_scores_rows(p: Problem, Qlr, Klr, b: int, h: int, rows, scores=None,
 
 
 KERNEL_SPANS = ("fwd_sweep", "dq_sweep", "dkdv_sweep", "threshold", "emit", "emit_t_count", "emit_t_write")
+
+
+def threshold_search(mode: int) -> int:
+    """dsv_threshold_search: 0 automatic, 1 radix search, 2 windowed search wherever it fits; returns the old mode."""
+    old = load_library().dsv_threshold_search(int(mode))
+    if old < 0:
+        raise ValueError(f"dsv_threshold_search: mode {mode} is not 0, 1 or 2")
+    return old
 
 
 def kernel_timing(enable: bool):

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libdsv.so")
-SOURCES = ("api.hip", "stage1.hip", "stage1_emit.hip", "stage2.hip", "stage2_split.hip", "validate.hip", "grouped.hip", "measure.hip", "predictor.hip", "profiler.hip")
+SOURCES = ("api.hip", "stage1.hip", "stage1_emit.hip", "stage1_window.hip", "stage2.hip", "stage2_split.hip", "validate.hip", "grouped.hip", "measure.hip", "predictor.hip", "profiler.hip")
 
 # packed-fp32 instructions are disabled for device code (a requirement of the test machines).
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

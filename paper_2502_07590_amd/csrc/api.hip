@@ -81,7 +81,7 @@ dsv_status check_workspace(const void *ws, size_t have, size_t need)
 
 // ---- workspace layouts (byte offsets, every block aligned to 256) ------------------------------
 struct Stage1Layout {
-    size_t qlr, klr, prefix, krem, jcut, cnt, tflag, qc, total;
+    size_t qlr, klr, prefix, krem, win, todo, jcut, cnt, tflag, qc, total;
 };
 
 // transposed: also room for jcut and the per-key list lengths of the key-major emission.
@@ -98,6 +98,8 @@ Stage1Layout stage1_layout(const dsv_problem &p, bool transposed, int Lq = 0)
     w.klr = o; o = align_up(o + nbh * p.L * p.r * esize(p.dtype), 256);
     w.prefix = o; o = align_up(o + qp * 4, 256);
     w.krem = o; o = align_up(o + qp * 4, 256);
+    w.win = o; o = align_up(o + qp * 4, 256);
+    w.todo = o; o = align_up(o + (1 + nbh * ((Lq + 31) / 32)) * 4, 256);
     w.jcut = o; if (transposed) o = align_up(o + qp * 4, 256);
     w.cnt = o; if (transposed) o = align_up(o + nbh * p.L * 4, 256);
     w.tflag = o; if (transposed) o = align_up(o + nbh * ((Lq + 31) / 32) * 4, 256);
@@ -298,6 +300,8 @@ static dsv_status lowrank_topk_impl(const dsv_problem *p, const dsv_grouping *gr
     SelectBuffers b;
     b.prefix = reinterpret_cast<uint32_t *>(ws + w.prefix);
     b.krem = reinterpret_cast<int32_t *>(ws + w.krem);
+    b.win = reinterpret_cast<uint32_t *>(ws + w.win);
+    b.todo = reinterpret_cast<int32_t *>(ws + w.todo);
     b.idx = idx;
     b.jcut = transposed ? reinterpret_cast<int32_t *>(ws + w.jcut) : nullptr;
     b.cnt = transposed ? reinterpret_cast<int32_t *>(ws + w.cnt) : nullptr;
@@ -882,6 +886,12 @@ dsv_status dsv_kernel_timing(int32_t enable)
     for (int i = 0; i < DSV_KERNEL_COUNT; ++i) t.recorded[i] = false;
     t.on = enable != 0;
     return DSV_OK;
+}
+
+int32_t dsv_threshold_search(int32_t mode)
+{
+    if (mode < 0 || mode > 2) return -1;
+    return dsv::set_threshold_search(mode);
 }
 
 dsv_status dsv_kernel_ms(int32_t span, float *ms)

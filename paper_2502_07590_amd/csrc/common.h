@@ -297,11 +297,20 @@ struct SelectBuffers {
     int32_t *cnt;      // [B*H, L]   list length of every key
     int64_t *col;      // out: [B*H, L+1]
     int32_t *idx_t;    // out: ragged key-major index
+    uint32_t *win;     // [B*H, L]   windowed threshold search: upper end of the bracket, then the bin width
+    int32_t *todo;     // [1 + B*H * ceil(L/32)]  windowed search: number and ids of the query tiles left to the radix search
 };
 // Lq index rows per head (state arrays are [B*H, padded_len(Lq)], tile_flag [B*H, ceil(Lq/32)], lists hold row
 // numbers below Lq); tabs[].off must be the offsets of [Lq, k] blocks.
 dsv_status launch_select(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                          const SelectBuffers &b, hipStream_t st);
+// Threshold search in two sweeps (stage1_window.hip) for the head slots of one table; the tiles it lists in
+// b.todo still need the radix passes.  window_search_fits: the problem is large enough for its key sample.
+dsv_status launch_window_search(const dsv_problem &p, int Lq, const HeadTable &tab, const void *Qlr, const void *Klr,
+                                const SelectBuffers &b, hipStream_t st);
+bool window_search_fits(const dsv_problem &p);
+// 0: automatic; 1: always the four-pass radix search; 2: the windowed search wherever it fits.  Returns the old mode.
+int set_threshold_search(int mode);
 dsv_status launch_emit(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                        const SelectBuffers &b, hipStream_t st);
 dsv_status launch_sparse_fwd(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q, const void *K,

@@ -12,6 +12,7 @@
 // queries); the L x L matrix never exists in memory.  Every pass uses the same instruction
 // sequence for a score, so a score has the same bits in every pass.
 #include <algorithm>
+#include <atomic>
 
 #include "stage1_core.h"
 
@@ -74,21 +75,15 @@ __global__ __launch_bounds__(256) void project_kernel(const T *__restrict__ Q, c
 //   remaining key is appended to the prefix and k_rem is reduced by the keys in higher buckets.
 // After pass 3 the prefix is the full key of the k-th largest score and |k_rem| is the number of
 // keys equal to it that belong to the top-k (at least 1); k_rem < 0 marks "all of them".
-#ifndef DSV_RADIX_WAVES
-#define DSV_RADIX_WAVES 8
-#endif
-constexpr int kRadixWaves = DSV_RADIX_WAVES;  // waves per block; the 32 KB histogram allows 4 blocks per CU
 
+// One 32-query tile (queries q0 .. q0+31 of head slot `slot`); hist: the block's 256 x 32 counters.
 template <typename T, int R, int PASS>
-__global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int Lq, int L,
-                                                         HeadTable tab, uint32_t *__restrict__ prefix,
-                                                         int32_t *__restrict__ krem)
+__device__ __forceinline__ void radix_pass_tile(uint32_t *hist, const T *__restrict__ Qlr, const T *__restrict__ Klr, int Lq,
+                                                int L, const HeadTable &tab, int slot, int q0, uint32_t *__restrict__ prefix,
+                                                int32_t *__restrict__ krem)
 {
     constexpr int SHIFT = 24 - 8 * PASS;
-    __shared__ uint32_t hist[256 * 32];
-    const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
-    const int q0 = blockIdx.x * 32;
     const T *Qb = Qlr + (int64_t)bh * Lq * R;   // Lq query rows (all L tokens, or one proxy per query group)
     const T *Kb = Klr + (int64_t)bh * L * R;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -200,6 +195,35 @@ __global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_kernel(const T *_
     }
 }
 
+template <typename T, int R, int PASS>
+__global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int Lq, int L,
+                                                         HeadTable tab, uint32_t *__restrict__ prefix,
+                                                         int32_t *__restrict__ krem)
+{
+    __shared__ uint32_t hist[256 * 32];
+    radix_pass_tile<T, R, PASS>(hist, Qlr, Klr, Lq, L, tab, blockIdx.y, blockIdx.x * 32, prefix, krem);
+}
+
+// The same digit pass for the query tiles on a list (todo[0] = their number, todo[1 + i] = slot * qtiles +
+// tile): the tiles the windowed search (stage1_window.hip) could not settle.  The grid is fixed; an empty
+// list costs a launch.
+template <typename T, int R, int PASS>
+__global__ __launch_bounds__(64 * kRadixWaves) void radix_pass_list_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr,
+                                                              int Lq, int L, HeadTable tab, uint32_t *__restrict__ prefix,
+                                                              int32_t *__restrict__ krem, const int32_t *__restrict__ todo,
+                                                              int qtiles)
+{
+    __shared__ uint32_t hist[256 * 32];
+    const int n = min(todo[0], tab.n * qtiles);
+    for (int i = blockIdx.x; i < n; i += gridDim.x) {
+        const int id = todo[1 + i];
+        const int slot = id / qtiles;
+        if (slot >= 0 && slot < tab.n)  // an id outside the table can only come from a corrupted list
+            radix_pass_tile<T, R, PASS>(hist, Qlr, Klr, Lq, L, tab, slot, (id - slot * qtiles) * 32, prefix, krem);
+        __syncthreads();  // the tile's last readers of hist are done before the next tile clears it
+    }
+}
+
 // ------------------------------------------------------------------------------------ debug scores
 // fp32 scores of chosen query rows against every key, through the same tile routine.
 template <typename T, int R>
@@ -291,6 +315,19 @@ dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void 
     return DSV_EUNSUPPORTED;
 }
 
+static std::atomic<int> g_threshold_search{0};
+int set_threshold_search(int mode) { return g_threshold_search.exchange(mode); }
+
+// Which head slots take the windowed search.  It pays when the bracket from the sample is narrow in the
+// key space: a threshold well inside the positive scores (k <= L/4; around zero the float keys spread a
+// narrow band of values over most of the key space) and enough keys for the sample to be a small part.
+static bool slot_takes_window(const dsv_problem &p, int k, int mode)
+{
+    if (mode == 1 || !window_search_fits(p)) return false;
+    if (mode == 2) return true;
+    return p.L >= 16384 && (int64_t)k * 4 <= p.L;
+}
+
 template <typename T, int R>
 static dsv_status select_t(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                            const SelectBuffers &b, hipStream_t st)
@@ -298,15 +335,38 @@ static dsv_status select_t(const dsv_problem &p, int Lq, const HeadTable *tabs, 
     const T *Ql = (const T *)Qlr;
     const T *Kl = (const T *)Klr;
     const int qtiles = (Lq + 31) / 32;
+    const int mode = b.win && b.todo ? g_threshold_search.load() : 1;
     {
         KernelSpan span(DSV_KERNEL_THRESHOLD, st);
         for (int t = 0; t < n_tabs; ++t) {
-            dim3 grid(qtiles, tabs[t].n);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tabs[t], b.prefix, b.krem);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tabs[t], b.prefix, b.krem);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tabs[t], b.prefix, b.krem);
-            hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tabs[t], b.prefix, b.krem);
-            DSV_LAUNCH_CHECK();
+            HeadTable radix{}, window{};  // the table's slots by search method
+            for (int s = 0; s < tabs[t].n; ++s) {
+                HeadTable &dst = slot_takes_window(p, tabs[t].k[s], mode) ? window : radix;
+                dst.bh[dst.n] = tabs[t].bh[s];
+                dst.k[dst.n] = tabs[t].k[s];
+                dst.off[dst.n] = tabs[t].off[s];
+                ++dst.n;
+            }
+            const dim3 block(64 * kRadixWaves);
+            if (radix.n) {
+                dim3 grid(qtiles, radix.n);
+                hipLaunchKernelGGL((radix_pass_kernel<T, R, 0>), grid, block, 0, st, Ql, Kl, Lq, p.L, radix, b.prefix, b.krem);
+                hipLaunchKernelGGL((radix_pass_kernel<T, R, 1>), grid, block, 0, st, Ql, Kl, Lq, p.L, radix, b.prefix, b.krem);
+                hipLaunchKernelGGL((radix_pass_kernel<T, R, 2>), grid, block, 0, st, Ql, Kl, Lq, p.L, radix, b.prefix, b.krem);
+                hipLaunchKernelGGL((radix_pass_kernel<T, R, 3>), grid, block, 0, st, Ql, Kl, Lq, p.L, radix, b.prefix, b.krem);
+                DSV_LAUNCH_CHECK();
+            }
+            if (window.n) {
+                const dsv_status rc = launch_window_search(p, Lq, window, Qlr, Klr, b, st);
+                if (rc != DSV_OK) return rc;
+                // the tiles it listed (normally none): the grid is fixed, the blocks walk the list
+                const dim3 grid((unsigned)std::min<int64_t>((int64_t)qtiles * window.n, 2048));
+                hipLaunchKernelGGL((radix_pass_list_kernel<T, R, 0>), grid, block, 0, st, Ql, Kl, Lq, p.L, window, b.prefix, b.krem, (const int32_t *)b.todo, qtiles);
+                hipLaunchKernelGGL((radix_pass_list_kernel<T, R, 1>), grid, block, 0, st, Ql, Kl, Lq, p.L, window, b.prefix, b.krem, (const int32_t *)b.todo, qtiles);
+                hipLaunchKernelGGL((radix_pass_list_kernel<T, R, 2>), grid, block, 0, st, Ql, Kl, Lq, p.L, window, b.prefix, b.krem, (const int32_t *)b.todo, qtiles);
+                hipLaunchKernelGGL((radix_pass_list_kernel<T, R, 3>), grid, block, 0, st, Ql, Kl, Lq, p.L, window, b.prefix, b.krem, (const int32_t *)b.todo, qtiles);
+                DSV_LAUNCH_CHECK();
+            }
         }
     }
     return launch_emit(p, Lq, tabs, n_tabs, Qlr, Klr, b, st);

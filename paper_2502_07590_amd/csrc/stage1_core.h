@@ -75,6 +75,13 @@ __device__ __forceinline__ float key_score(uint32_t key)
     return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
 }
 
+// Waves per block of the threshold-search kernels (one block = 32 queries, the waves stride over the key
+// tiles); their 32 KB histogram allows 4 blocks per CU.
+#ifndef DSV_RADIX_WAVES
+#define DSV_RADIX_WAVES 8
+#endif
+constexpr int kRadixWaves = DSV_RADIX_WAVES;
+
 // Per-query selection state (threshold, tie budget, jcut) is stored [B*H, padded_len(L)]: rows padded
 // to whole 32-query tiles, so that a tile's 32 values can be fetched with aligned vector loads.
 __host__ __device__ __forceinline__ constexpr int padded_len(int L) { return (L + 31) & ~31; }

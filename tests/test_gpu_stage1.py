@@ -202,3 +202,85 @@ def test_lowrank_topk_t_emits_the_exact_transpose(kind, dtype, L, d, r, ks):
         rows = idx[off[h]:off[h + 1]].reshape(L, ks[h])
         _check_transpose(rows, idx_t[off[h]:off[h + 1]], col[h], L, sorted_lists=True)
         _check_transpose(rows, idx_t2[off[h]:off[h + 1]], col2[h], L, sorted_lists=True)   # dsv_idx_transpose is stable
+
+
+# ------------------------------------------------------------------------------ windowed threshold search
+@pytest.fixture
+def search_mode():
+    """Switch the threshold search and put the automatic choice back afterwards."""
+    yield dsv.threshold_search
+    dsv.threshold_search(0)
+
+
+def _both_searches(p, Q, K, Wq, Wk):
+    dsv.threshold_search(1)
+    radix = _run_topk(p, Q, K, Wq, Wk)
+    dsv.threshold_search(2)
+    window = _run_topk(p, Q, K, Wq, Wk)
+    return radix, window
+
+
+@pytest.mark.parametrize("dtype,L,d,r,ks", [("bf16", 16384, 128, 16, [1024, 64, 4096]), ("bf16", 5000, 64, 32, [313, 2500, 1]),
+                                            ("f32", 4100, 64, 16, [4100, 4099, 256]), ("bf16", 8192, 128, 64, [512, 7])])
+def test_windowed_search_gives_the_radix_search_result(search_mode, dtype, L, d, r, ks):
+    """Gaussian inputs: every row of the index identical under both searches (dense, sparse, k = 1, k = L, k = L - 1,
+    ragged last key tile), and sampled rows equal to the oracle's selection on the device's own score bits."""
+    case = Case(make_cfg(L, d, r, len(ks), dtype, basis_rank=32, scale_num=2.0), ks, names=("Q", "K"))
+    p = case.problem(dsv)
+    radix, window = _both_searches(p, case.dev["Q"], case.dev["K"], case.dWq, case.dWk)
+    assert np.array_equal(radix, window)
+    Qlr, Klr = dsv.lowrank_project(p, case.dev["Q"], case.dev["K"], case.dWq, case.dWk)
+    rows = np.unique(np.concatenate([np.arange(0, L, L // 23), [L - 1, 31, 32]])).astype(np.int32)
+    for h in range(len(ks)):
+        S_gpu = dsv.lowrank_scores_rows(p, Qlr, Klr, 0, h, torch.from_numpy(rows).cuda())
+        torch.cuda.synchronize()
+        ref = oracle.topk_from_scores(S_gpu.cpu().numpy().astype(np.float64), ks[h])
+        assert np.array_equal(ref, case.idx_rows(window, h)[rows]), f"head {h}"
+
+
+def test_windowed_search_hands_ties_and_bad_samples_to_the_radix_search(search_mode):
+    """Inputs the windowed search cannot settle by itself: scores with massive ties (ternary inputs: bins overflow),
+    all scores equal, and keys whose sampled rows say nothing about the rest (the bracket misses the threshold)."""
+    L, d, r, ks = 4096, 64, 16, [300, 77]
+    H = len(ks)
+    Qs, Ks, Wqs, Wks = zip(*(wl.ternary_head_tensors(L, d, r, seed=3, head=h) for h in range(H)))
+    dev = lambda a: torch.from_numpy(np.stack(a)).cuda().to(torch.bfloat16).contiguous()
+    p = dsv.Problem(1, H, L, d, r, "bf16", ks, 1.0)
+    dsv.threshold_search(2)
+    idx = _run_topk(p, dev(Qs)[None], dev(Ks)[None], dev(Wqs), dev(Wks))
+    off = wl.idx_offsets(1, H, L, ks)
+    for h in range(H):
+        ref = oracle.lowrank_topk(Qs[h], Ks[h], Wqs[h], Wks[h], ks[h], "bf16")
+        assert np.array_equal(idx[off[h]:off[h + 1]].reshape(L, ks[h]), ref), f"ternary head {h}"
+
+    case = Case(make_cfg(L, d, r, 1, "bf16"), [37], names=("Q", "K"))
+    p1 = case.problem(dsv)
+    idx = _run_topk(p1, torch.zeros_like(case.dev["Q"]), case.dev["K"], case.dWq, case.dWk)
+    assert np.array_equal(idx.reshape(L, 37), np.tile(np.arange(37, dtype=np.int32), (L, 1)))
+
+    # the sample takes key rows i * stride + stride / 2 (stride = L / 2048): shrink exactly those rows
+    case = Case(make_cfg(L, d, r, 2, "bf16", basis_rank=32, scale_num=2.0), [256, 1000], names=("Q", "K"))
+    p2 = case.problem(dsv)
+    K = case.dev["K"].clone()
+    stride = L // 2048
+    K[:, :, stride // 2::stride, :] *= 1.0 / 64
+    radix, window = _both_searches(p2, case.dev["Q"], K, case.dWq, case.dWk)
+    assert np.array_equal(radix, window)
+
+
+def test_windowed_search_with_transposed_and_grouped_emission(search_mode):
+    """The transposed index and the query-grouped call (fewer query rows than keys) on top of the windowed search."""
+    grid, cube, ks = (4, 32, 32), (2, 2, 2), [256, 100]
+    L = grid[0] * grid[1] * grid[2]
+    case = Case(make_cfg(L, 128, 16, len(ks), "bf16", basis_rank=32, scale_num=2.0), ks, names=("Q", "K"))
+    p = case.problem(dsv)
+    grp = dsv.Grouping(grid, cube)
+    out = {}
+    for mode in (1, 2):
+        dsv.threshold_search(mode)
+        idx, idx_t, col = dsv.lowrank_topk_t(p, case.dev["Q"], case.dev["K"], case.dWq, case.dWk)
+        idx_g, idx_t_g, col_g = dsv.lowrank_topk_grouped(p, grp, case.dev["Q"], case.dev["K"], case.dWq, case.dWk)
+        torch.cuda.synchronize()
+        out[mode] = [x.cpu().numpy() for x in (idx, idx_t, col, idx_g, idx_t_g, col_g)]
+    for a, b in zip(out[1], out[2]):
+        assert np.array_equal(a, b)
