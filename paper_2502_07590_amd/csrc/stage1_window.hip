@@ -24,7 +24,7 @@
 namespace dsv {
 
 constexpr int kSampleKeys = 2048;  // keys in the sample (64 tiles)
-constexpr int kWindowCap = 128;    // scores of the chosen bin that fit the LDS slots of a query
+constexpr int kWindowCap = 256;    // scores of the chosen bin that fit the LDS slots of a query
 
 // Ranks (1 = largest) of the two sample order statistics of every head slot: hi bounds the threshold from
 // above, lo from below.  hi < 1 or lo > kSampleKeys: no bound on that side.
