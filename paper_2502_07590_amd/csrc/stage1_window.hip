@@ -35,7 +35,7 @@ struct WindowRanks {
 
 // ------------------------------------------------------------------------------------ sample
 template <typename T, int R>
-__global__ __launch_bounds__(256) void window_sample_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int Lq, int L,
+__global__ __launch_bounds__(64 * kRadixWaves) void window_sample_kernel(const T *__restrict__ Qlr, const T *__restrict__ Klr, int Lq, int L,
                                                             HeadTable tab, WindowRanks wr, uint32_t *__restrict__ lo_out,
                                                             uint32_t *__restrict__ hi_out, int32_t *__restrict__ todo)
 {
@@ -53,9 +53,9 @@ __global__ __launch_bounds__(256) void window_sample_kernel(const T *__restrict_
     const int rank[2] = {wr.hi[slot], wr.lo[slot]};
     constexpr int kTiles = kSampleKeys / 32;
 
-    for (int e = threadIdx.x; e < 256 * 32; e += 256) hA[e] = 0;
+    for (int e = threadIdx.x; e < 256 * 32; e += 64 * kRadixWaves) hA[e] = 0;
     __syncthreads();
-    for (int tile = wave; tile < kTiles; tile += 4) {
+    for (int tile = wave; tile < kTiles; tile += kRadixWaves) {
         const int64_t row = (int64_t)(tile * 32 + n) * wr.stride + wr.stride / 2;
         const floatx16_t acc = score_tile<T, R>(load_frag_row<T, R>(Kb, row, lane), qf);
 #pragma unroll
@@ -76,10 +76,10 @@ __global__ __launch_bounds__(256) void window_sample_kernel(const T *__restrict_
         abv[w][q] = above;
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < 256 * 32; e += 256) { hA[e] = 0; hB[e] = 0; }
+    for (int e = threadIdx.x; e < 256 * 32; e += 64 * kRadixWaves) { hA[e] = 0; hB[e] = 0; }
     __syncthreads();
     const uint32_t d_hi = (uint32_t)dig[0][n], d_lo = (uint32_t)dig[1][n];  // -1 matches no top byte
-    for (int tile = wave; tile < kTiles; tile += 4) {
+    for (int tile = wave; tile < kTiles; tile += kRadixWaves) {
         const int64_t row = (int64_t)(tile * 32 + n) * wr.stride + wr.stride / 2;
         const floatx16_t acc = score_tile<T, R>(load_frag_row<T, R>(Kb, row, lane), qf);
 #pragma unroll
@@ -156,7 +156,8 @@ __global__ __launch_bounds__(64 * kRadixWaves) void window_hist_kernel(const T *
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int32_t bits = (int32_t)__float_as_uint(acc[v]);
-                if (bits >= raw_lo) atomicAdd(&hcol_mine[min((uint32_t)(bits - raw_lo) >> s, 255u) * 32], 1u);
+                // some lane of the wave nearly always has a hit: keep the update on the straight path
+                if (__builtin_expect(bits >= raw_lo, 1)) atomicAdd(&hcol_mine[min((uint32_t)(bits - raw_lo) >> s, 255u) * 32], 1u);
             }
         }
     } else {
@@ -344,7 +345,7 @@ static dsv_status window_search_t(const dsv_problem &p, int Lq, const HeadTable 
         wr.lo[s] = (int32_t)std::ceil(ks + m);
     }
     dim3 grid(qtiles, tab.n);
-    hipLaunchKernelGGL((window_sample_kernel<T, R>), grid, dim3(256), 0, st, Ql, Kl, Lq, p.L, tab, wr, b.prefix, b.win, b.todo);
+    hipLaunchKernelGGL((window_sample_kernel<T, R>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tab, wr, b.prefix, b.win, b.todo);
     hipLaunchKernelGGL((window_hist_kernel<T, R>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tab, b.prefix, b.win,
                        b.krem, b.todo, qtiles);
     hipLaunchKernelGGL((window_collect_kernel<T, R>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tab, b.prefix,
