@@ -372,9 +372,10 @@ DSV_API dsv_status dsv_kernel_ms(int32_t span, float *ms);
 /* How stage 1 finds every query's threshold score (the k-th largest; paper Sec. "Critical KV Estimation with
  * Kernel Fusion").  Both methods are exact and give identical results; the choice only affects speed.
  *   0  automatic (default): the windowed search -- a key sample brackets the threshold, then two sweeps over
- *      the keys -- for heads with L >= 16384 and k <= L/4, else the radix search (four sweeps, 8 bits each);
+ *      the keys -- for heads with L >= 16384 and k <= L/4 whose sample (2048 to 16384 keys, at most L/8) holds
+ *      enough keys on both sides of the threshold; else the radix search (four sweeps, 8 bits each);
  *   1  always the radix search;
- *   2  the windowed search wherever its sample fits (L >= 4096).
+ *   2  the windowed search for every head it can serve at all (L >= 4096, sample up to L/2 keys).
  * Query tiles the windowed search cannot settle (threshold outside the bracket, massive ties) go through the
  * radix search afterwards, inside the same call.  Process-wide; for tests and measurements.  Returns the
  * previous mode; a mode outside 0..2 changes nothing and returns -1. */

@@ -305,10 +305,12 @@ struct SelectBuffers {
 dsv_status launch_select(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                          const SelectBuffers &b, hipStream_t st);
 // Threshold search in two sweeps (stage1_window.hip) for the head slots of one table; the tiles it lists in
-// b.todo still need the radix passes.  window_search_fits: the problem is large enough for its key sample.
+// b.todo still need the radix passes.
 dsv_status launch_window_search(const dsv_problem &p, int Lq, const HeadTable &tab, const void *Qlr, const void *Klr,
                                 const SelectBuffers &b, hipStream_t st);
-bool window_search_fits(const dsv_problem &p);
+// Keys the search would sample for a head keeping k of L keys, 0 if it does not fit that head (forced: leave
+// out the checks that only decide whether it pays).
+int window_sample_keys(int L, int k, bool forced);
 // 0: automatic; 1: always the four-pass radix search; 2: the windowed search wherever it fits.  Returns the old mode.
 int set_threshold_search(int mode);
 dsv_status launch_emit(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,

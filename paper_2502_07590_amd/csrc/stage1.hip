@@ -318,14 +318,10 @@ dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void 
 static std::atomic<int> g_threshold_search{0};
 int set_threshold_search(int mode) { return g_threshold_search.exchange(mode); }
 
-// Which head slots take the windowed search.  It pays when the bracket from the sample is narrow in the
-// key space: a threshold well inside the positive scores (k <= L/4; around zero the float keys spread a
-// narrow band of values over most of the key space) and enough keys for the sample to be a small part.
+// Which head slots take the windowed search (mode: see set_threshold_search).
 static bool slot_takes_window(const dsv_problem &p, int k, int mode)
 {
-    if (mode == 1 || !window_search_fits(p)) return false;
-    if (mode == 2) return true;
-    return p.L >= 16384 && (int64_t)k * 4 <= p.L;
+    return mode != 1 && window_sample_keys(p.L, k, mode == 2) > 0;
 }
 
 template <typename T, int R>

@@ -3,7 +3,7 @@
 //
 // The radix search of stage1.hip resolves the 32 bits of the k-th largest score 8 bits per sweep.  Here
 // a sample of the keys first brackets that score for every query:
-//   sample   scores of kSampleKeys evenly spaced keys; two order statistics of the sample, a few standard
+//   sample   scores of a few thousand evenly spaced keys; two order statistics of the sample, a few standard
 //            deviations of the sampling error to either side of rank k * (sample / L), resolved to their
 //            top 16 bits: [lo, hi] in the order-preserving key space;
 //   window   one sweep over all keys: 255 equal bins from lo upward (bin width a power of two, chosen so
@@ -23,15 +23,46 @@
 
 namespace dsv {
 
-constexpr int kSampleKeys = 2048;  // keys in the sample (64 tiles)
-constexpr int kWindowCap = 256;    // scores of the chosen bin that fit the LDS slots of a query
+constexpr int kMinSampleKeys = 2048;  // smallest key sample (64 tiles)
+constexpr int kWindowCap = 256;       // scores of the chosen bin that fit the LDS slots of a query
 
-// Ranks (1 = largest) of the two sample order statistics of every head slot: hi bounds the threshold from
-// above, lo from below.  hi < 1 or lo > kSampleKeys: no bound on that side.
+// Per head slot: the sample (tiles of 32 keys; sample key i is row i * stride + stride / 2) and the ranks
+// (1 = largest) of its two order statistics: hi bounds the threshold from above, lo from below.
 struct WindowRanks {
     int32_t hi[kMaxSlots], lo[kMaxSlots];
-    int32_t stride;  // sample key i is row i * stride + stride / 2
+    int32_t tiles[kMaxSlots], stride[kMaxSlots];
 };
+
+// Rank of the threshold in a sample of n keys and six standard deviations of its sampling error either way.
+static void sample_ranks(int L, int k, int n, int &hi, int &lo)
+{
+    const double frac = (double)k / (double)L;
+    const double ks = frac * n;
+    const double m = 6.0 * std::sqrt(std::max(ks * (1.0 - frac), 0.0)) + 2.0;
+    hi = (int)std::floor(ks - m);
+    lo = (int)std::ceil(ks + m);
+}
+
+// Keys to sample for a head that keeps k of L keys; 0: the windowed search does not fit that head.
+// The sample must be large enough that (a) both order statistics exist in it -- about 64 sample keys above
+// the threshold -- and (b) the bracket, whose width in ranks shrinks with the square root of the sample,
+// leaves a few dozen scores per bin; and small enough to stay a minor part of the work.  Unless forced,
+// the search is also left to the radix passes where it would not pay: short sequences, and thresholds near
+// zero (k > L/4), where the float keys spread a narrow band of values over most of the key space.
+int window_sample_keys(int L, int k, bool forced)
+{
+    if (L < 2 * kMinSampleKeys || k < 1 || k >= L) return 0;
+    if (!forced && (L < 16384 || (int64_t)k * 4 > L)) return 0;
+    const double frac = (double)k / (double)L;
+    const double per_bin = (double)L * std::sqrt(frac * (1.0 - frac)) / 700.0;
+    const double want = std::max({(double)kMinSampleKeys, 64.0 / frac, per_bin * per_bin});
+    const int cap = (forced ? L / 2 : std::min(L / 8, 16384)) / 32 * 32;
+    const int n = (int)std::min((double)cap, std::ceil(want / 32.0) * 32.0);
+    if (n < kMinSampleKeys) return 0;
+    int hi, lo;
+    sample_ranks(L, k, n, hi, lo);
+    return hi >= 1 && lo <= n ? n : 0;
+}
 
 // ------------------------------------------------------------------------------------ sample
 template <typename T, int R>
@@ -51,12 +82,13 @@ __global__ __launch_bounds__(64 * kRadixWaves) void window_sample_kernel(const T
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) todo[0] = 0;  // the list of unsettled tiles starts empty
     const Frag<T, R> qf = load_frag<T, R>(Qb, q0, Lq, lane);
     const int rank[2] = {wr.hi[slot], wr.lo[slot]};
-    constexpr int kTiles = kSampleKeys / 32;
+    const int kTiles = wr.tiles[slot], stride = wr.stride[slot];
+    const int n_keys = kTiles * 32;
 
     for (int e = threadIdx.x; e < 256 * 32; e += 64 * kRadixWaves) hA[e] = 0;
     __syncthreads();
     for (int tile = wave; tile < kTiles; tile += kRadixWaves) {
-        const int64_t row = (int64_t)(tile * 32 + n) * wr.stride + wr.stride / 2;
+        const int64_t row = (int64_t)(tile * 32 + n) * stride + stride / 2;
         const floatx16_t acc = score_tile<T, R>(load_frag_row<T, R>(Kb, row, lane), qf);
 #pragma unroll
         for (int v = 0; v < 16; ++v) atomicAdd(&hA[(score_key(acc[v]) >> 24) * 32 + n], 1u);
@@ -65,7 +97,7 @@ __global__ __launch_bounds__(64 * kRadixWaves) void window_sample_kernel(const T
     if (threadIdx.x < 64) {
         const int q = threadIdx.x & 31, w = threadIdx.x >> 5;
         int d = -1, above = 0;
-        if (rank[w] >= 1 && rank[w] <= kSampleKeys) {
+        if (rank[w] >= 1 && rank[w] <= n_keys) {
             for (int b = 255; b >= 0; --b) {
                 const int c = (int)hA[b * 32 + q];
                 if (above + c >= rank[w]) { d = b; break; }
@@ -80,7 +112,7 @@ __global__ __launch_bounds__(64 * kRadixWaves) void window_sample_kernel(const T
     __syncthreads();
     const uint32_t d_hi = (uint32_t)dig[0][n], d_lo = (uint32_t)dig[1][n];  // -1 matches no top byte
     for (int tile = wave; tile < kTiles; tile += kRadixWaves) {
-        const int64_t row = (int64_t)(tile * 32 + n) * wr.stride + wr.stride / 2;
+        const int64_t row = (int64_t)(tile * 32 + n) * stride + stride / 2;
         const floatx16_t acc = score_tile<T, R>(load_frag_row<T, R>(Kb, row, lane), qf);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -325,7 +357,6 @@ __global__ __launch_bounds__(64 * kRadixWaves) void window_collect_kernel(const 
 }
 
 // ------------------------------------------------------------------------------------ host
-bool window_search_fits(const dsv_problem &p) { return p.L >= 2 * kSampleKeys; }
 
 template <typename T, int R>
 static dsv_status window_search_t(const dsv_problem &p, int Lq, const HeadTable &tab, const void *Qlr, const void *Klr,
@@ -335,14 +366,12 @@ static dsv_status window_search_t(const dsv_problem &p, int Lq, const HeadTable 
     const T *Kl = (const T *)Klr;
     const int qtiles = (Lq + 31) / 32;
     WindowRanks wr{};
-    wr.stride = p.L / kSampleKeys;
     for (int s = 0; s < tab.n; ++s) {
-        // rank of the threshold in the sample, and six standard deviations of its sampling error either way
-        const double frac = (double)tab.k[s] / (double)p.L;
-        const double ks = frac * kSampleKeys;
-        const double m = 6.0 * std::sqrt(std::max(ks * (1.0 - frac), 0.0)) + 2.0;
-        wr.hi[s] = (int32_t)std::floor(ks - m);
-        wr.lo[s] = (int32_t)std::ceil(ks + m);
+        const int n = window_sample_keys(p.L, tab.k[s], true);
+        if (n == 0) return DSV_EINVAL;  // the caller only passes heads the search fits
+        wr.tiles[s] = n / 32;
+        wr.stride[s] = p.L / n;
+        sample_ranks(p.L, tab.k[s], n, wr.hi[s], wr.lo[s]);
     }
     dim3 grid(qtiles, tab.n);
     hipLaunchKernelGGL((window_sample_kernel<T, R>), grid, dim3(64 * kRadixWaves), 0, st, Ql, Kl, Lq, p.L, tab, wr, b.prefix, b.win, b.todo);
