@@ -227,18 +227,27 @@ __device__ __forceinline__ bool decode_group_item(const SplitPlan &pl, int64_t b
 // TOKEN row like the per-query partials.
 constexpr int kVRow = 128 * 2 + 16;  // bytes from one parked row to the next
 
-// place of key n of a tile in a row of P: the 8 keys of lane group g are contiguous
-__device__ __forceinline__ int p_slot(int n) { return 8 * ((n & 7) >> 1) + 2 * (n >> 3) + (n & 1); }
-
-// B fragment of channel block nb (16 channels) from the parked rows: lane = (channel c, key group g)
-__device__ __forceinline__ bf16x8_t parked_frag(const unsigned char *rows, int nb, int c, int g)
+// Transposing LDS read (ds_read_b64_tr_b16): inside every block of 16 lanes, lane i receives four halfwords, the
+// e-th being halfword (i % 4) at the address passed by lane 4 e + i / 4 of the block.  So when lane 4 e + q
+// passes the address of channels c0 + 4 q .. + 3 of parked row key(e), lane i ends up with channel c0 + i of rows
+// key(0..3): a quarter of a matrix-core B fragment whose contraction runs over the parked rows.  Two reads
+// (rows key(0..3), key(4..7)) make the 8-element fragment.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+__device__ __forceinline__ bf16x8_t tr_frag(const unsigned char *a0, const unsigned char *a1)
 {
-    bf16x8_t f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-        f[e] = *reinterpret_cast<const __bf16 *>(rows + (8 * (e / 2) + 2 * g + (e % 2)) * kVRow + (nb * 16 + c) * 2);
-    return f;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)a0);
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)a1);
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x8_t f = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, f);
 }
+
+// Forward, O += P V: lane group g (16 lanes) contracts, in this order, keys fwd_key(g, 0..7); the 32 lanes that
+// one pass of a read serves (two lane groups) then touch 8 rows 2 apart, i.e. 8 disjoint stretches of LDS banks
+// (272-byte rows).  p_slot: place of key n in a row of P, where the 8 keys of a lane group are contiguous.
+__device__ __forceinline__ int fwd_key(int g, int e) { return 16 * (e >> 2) + 2 * (4 * (g & 1) + (e & 3)) + (g >> 1); }
+__device__ __forceinline__ int p_slot(int n) { return 16 * (n & 1) + 8 * ((n >> 3) & 1) + 4 * (n >> 4) + ((n >> 1) & 3); }
 
 // NSUB = 1: the four waves of a block take four groups of at most 8 queries.  NSUB = 2 / 4: ONE group of up to 16 / 32
 // queries per block of NSUB waves, wave w taking members 8 w .. 8 w + 7; the waves gather the tile's rows together (two load instructions
@@ -313,6 +322,10 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
     for (int nb = 0; nb < NM; ++nb) oacc[nb] = floatx4_t{0.f, 0.f, 0.f, 0.f};
     const float c2 = scale * kLog2e;
     const int pslot = p_slot(n);
+    // this lane's addresses for the transposing reads of V: rows fwd_key(g4, c16 / 4) and fwd_key(g4, 4 + c16 / 4),
+    // channels 4 (c16 % 4) .. + 3 of a 16-channel block
+    const int vt0 = fwd_key(g4, c16 >> 2) * kVRow + (c16 & 3) * 8;
+    const int vt1 = fwd_key(g4, 4 + (c16 >> 2)) * kVRow + (c16 & 3) * 8;
 
     // Gathered rows come in whole: one load instruction fetches 4 rows, 16 lanes x 16 bytes each (every 64-byte
     // sector the vector memory path moves is used in full; loading matrix-core fragments straight from memory
@@ -391,7 +404,7 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
         const bf16x8_t pa = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(const_cast<const uint32_t *>(P_s) + c16 * 16 + g4 * 4));
 #pragma unroll
         for (int nb = 0; nb < NM; ++nb)
-            oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, parked_frag(V_s, nb, c16, g4), oacc[nb], 0, 0, 0);
+            oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, tr_frag(V_s + vt0 + nb * 32, V_s + vt1 + nb * 32), oacc[nb], 0, 0, 0);
         block_sync();  // the next tile overwrites P_s and the parked rows
     }
     if (!active) return;
@@ -464,18 +477,11 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
 //        16 s + 8 (e / 4) + 4 h + (e % 4) of k-step s: rows 4 apart, i.e. disjoint LDS banks for the two groups.
 // SPLIT: per (member, range) partials C, B, Delta for the per-query dq merge kernel.
 
-// place of key n of a tile in a row of the weight matrix: the 8 keys of (k-step, lane group) are contiguous
-__device__ __forceinline__ int w_slot(int n) { return (n & 16) + 8 * ((n & 7) >> 2) + 4 * ((n & 15) >> 3) + (n & 3); }
-
-// B fragment of channel block nb (32 channels), k-step s, from the parked rows: lane = (channel c, key group h)
-__device__ __forceinline__ bf16x8_t parked_frag32(const unsigned char *rows, int nb, int s, int c, int h)
-{
-    bf16x8_t f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-        f[e] = *reinterpret_cast<const __bf16 *>(rows + (16 * s + 8 * (e / 4) + 4 * h + (e % 4)) * kVRow + (nb * 32 + c) * 2);
-    return f;
-}
+// dQ step, second product: lane group h (32 lanes) of k-step s contracts, in this order, keys dq_key(s, h, 0..7);
+// one pass of a transposing read then touches 4 rows 4 apart, 64 bytes each: disjoint LDS banks.  w_slot: place
+// of key n in a row of the weight matrix, where the 8 keys of (k-step, lane group) are contiguous.
+__device__ __forceinline__ int dq_key(int s, int h, int e) { return 16 * s + 4 * (e & 3) + 2 * h + (e >> 2); }
+__device__ __forceinline__ int w_slot(int n) { return (n & 16) + 8 * ((n >> 1) & 1) + 4 * (n & 1) + ((n >> 2) & 3); }
 
 // x = head + tail as two bf16 values (head = x rounded to bf16, tail = the rounded remainder)
 __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
@@ -575,6 +581,13 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc2[nb][i] = 0.f;
     const float c2 = scale * kLog2e;
+    // this lane's addresses for the transposing reads of K (second product): rows dq_key(s, half, c16 / 4) and
+    // dq_key(s, half, 4 + c16 / 4), channels 16 (g4 % 2) + 4 (c16 % 4) .. + 3 of a 32-channel block
+    int kt[2][2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int r = 0; r < 2; ++r) kt[s][r] = dq_key(s, half, 4 * r + (c16 >> 2)) * kVRow + (g4 & 1) * 32 + (c16 & 3) * 8;
 
     // rows loaded whole and parked in LDS, software-pipelined, as in the forward
     constexpr int NI = 8 / NSUB;                 // load instructions (4 rows each) of this wave per tile and matrix
@@ -644,7 +657,7 @@ __global__ __launch_bounds__(256) void grouped_dq_kernel(const bf16_t *__restric
             const bf16x8_t wa = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(const_cast<const uint32_t *>(W_s) + n * 16 + s * 8 + half * 4));
 #pragma unroll
             for (int nb = 0; nb < NC; ++nb)
-                acc2[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, parked_frag32(K_s, nb, s, n, half), acc2[nb], 0, 0, 0);
+                acc2[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, tr_frag(K_s + kt[s][0] + nb * 64, K_s + kt[s][1] + nb * 64), acc2[nb], 0, 0, 0);
         }
         block_sync();  // the next tile overwrites the parked rows and W_s
     }
