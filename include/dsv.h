@@ -380,6 +380,9 @@ DSV_API dsv_status dsv_kernel_ms(int32_t span, float *ms);
  * radix search afterwards, inside the same call.  Process-wide; for tests and measurements.  Returns the
  * previous mode; a mode outside 0..2 changes nothing and returns -1. */
 DSV_API int32_t dsv_threshold_search(int32_t mode);
+/* Which search a head that keeps k of L keys gets under the current mode: the number of keys the windowed
+ * search samples for it (a multiple of 32), or 0 when the head takes the radix search.  Host arithmetic only. */
+DSV_API int32_t dsv_threshold_sample_keys(int32_t L, int32_t k);
 
 /* Pure-gather probe: the practical ceiling of the vector memory path (L2 -> vector L1 -> registers) for the
  * stage-2 access pattern, against which the sweeps' achieved gather rate is reported.  K, V: DEVICE bf16

@@ -35,7 +35,7 @@ EXPORTED_SYMBOLS = (
     "dsv_group_overlap_workspace", "dsv_group_overlap", "dsv_choose_grouping_workspace", "dsv_choose_grouping",
     "dsv_lowrank_topk_noalloc_max_bytes", "dsv_lowrank_topk_noalloc",
     "dsv_lowrank_project", "dsv_lowrank_scores_rows",
-    "dsv_kernel_timing", "dsv_kernel_ms", "dsv_threshold_search", "dsv_measure_gather_ceiling",
+    "dsv_kernel_timing", "dsv_kernel_ms", "dsv_threshold_search", "dsv_threshold_sample_keys", "dsv_measure_gather_ceiling",
 )
 
 
@@ -149,6 +149,8 @@ def load_library():
     lib.dsv_lowrank_project.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
     lib.dsv_lowrank_scores_rows.restype = ctypes.c_int
     lib.dsv_lowrank_scores_rows.argtypes = [P, vp, vp, i32, i32, vp, i32, vp, vp]
+    lib.dsv_threshold_sample_keys.restype = ctypes.c_int32
+    lib.dsv_threshold_sample_keys.argtypes = [i32, i32]
     lib.dsv_threshold_search.restype = ctypes.c_int32
     lib.dsv_threshold_search.argtypes = [i32]
     lib.dsv_kernel_timing.restype = ctypes.c_int
@@ -512,6 +514,11 @@ def threshold_search(mode: int) -> int:
     if old < 0:
         raise ValueError(f"dsv_threshold_search: mode {mode} is not 0, 1 or 2")
     return old
+
+
+def threshold_sample_keys(L: int, k: int) -> int:
+    """dsv_threshold_sample_keys: keys the windowed threshold search samples for a head keeping k of L (0: radix search)."""
+    return int(load_library().dsv_threshold_sample_keys(int(L), int(k)))
 
 
 def kernel_timing(enable: bool):

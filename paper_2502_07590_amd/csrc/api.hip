@@ -894,6 +894,12 @@ int32_t dsv_threshold_search(int32_t mode)
     return dsv::set_threshold_search(mode);
 }
 
+int32_t dsv_threshold_sample_keys(int32_t L, int32_t k)
+{
+    const int mode = dsv::set_threshold_search(-1);
+    return mode == 1 ? 0 : dsv::window_sample_keys(L, k, mode == 2);
+}
+
 dsv_status dsv_kernel_ms(int32_t span, float *ms)
 {
     dsv::KernelTimer &t = dsv::g_kernel_timer;

@@ -311,7 +311,8 @@ dsv_status launch_window_search(const dsv_problem &p, int Lq, const HeadTable &t
 // Keys the search would sample for a head keeping k of L keys, 0 if it does not fit that head (forced: leave
 // out the checks that only decide whether it pays).
 int window_sample_keys(int L, int k, bool forced);
-// 0: automatic; 1: always the four-pass radix search; 2: the windowed search wherever it fits.  Returns the old mode.
+// 0: automatic; 1: always the four-pass radix search; 2: the windowed search wherever it fits.  Returns the old mode
+// (mode < 0: only that).
 int set_threshold_search(int mode);
 dsv_status launch_emit(const dsv_problem &p, int Lq, const HeadTable *tabs, int n_tabs, const void *Qlr, const void *Klr,
                        const SelectBuffers &b, hipStream_t st);

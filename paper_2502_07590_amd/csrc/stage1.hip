@@ -316,7 +316,7 @@ dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void 
 }
 
 static std::atomic<int> g_threshold_search{0};
-int set_threshold_search(int mode) { return g_threshold_search.exchange(mode); }
+int set_threshold_search(int mode) { return mode < 0 ? g_threshold_search.load() : g_threshold_search.exchange(mode); }
 
 // Which head slots take the windowed search (mode: see set_threshold_search).
 static bool slot_takes_window(const dsv_problem &p, int k, int mode)

@@ -65,6 +65,16 @@ int main()
     CHECK(dsv_status_string(DSV_EHIP) != nullptr && dsv_version() != nullptr);
     float ms = 0.f;
     CHECK(dsv_kernel_ms(99, &ms) == DSV_EINVAL && dsv_kernel_ms(0, nullptr) == DSV_EINVAL);
+    // threshold search: the choice per head and the sample size are host arithmetic, for any (L, k) and mode
+    for (int mode = 0; mode < 3; ++mode) {
+        CHECK(dsv_threshold_search(mode) >= 0);
+        for (int L : {1, 31, 4095, 4096, 5000, 16384, 131072, 524288, 1 << 24, 0x7FFFFFF0})
+            for (int k : {-1, 0, 1, 7, 64, 1000, 4096, L / 16, L / 4, L / 2, L - 1, L, L + 1}) {
+                const int n = dsv_threshold_sample_keys(L, k);
+                CHECK(n == 0 || (mode != 1 && n % 32 == 0 && n >= 2048 && n <= L / 2 && k >= 1 && k < L));
+            }
+    }
+    CHECK(dsv_threshold_search(7) == -1 && dsv_threshold_search(0) == 2);
     // query grouping: layouts of the group kernels and of the general path, argument checks
     {
         void *one = reinterpret_cast<void *>(256);

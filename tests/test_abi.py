@@ -138,3 +138,34 @@ def test_measurement_aid_rejects_what_has_not_run(dsv):
     assert lib.dsv_kernel_ms(len(dsv.KERNEL_SPANS), ctypes.byref(ms)) == -1
     assert lib.dsv_kernel_ms(0, None) == -1
     assert ms.value == -1.0
+
+
+def test_threshold_search_choice_is_host_arithmetic(dsv):
+    """dsv_threshold_search / dsv_threshold_sample_keys: which heads the windowed threshold search takes, and with how
+    large a key sample (no GPU involved)."""
+    try:
+        assert dsv.threshold_search(0) in (0, 1, 2)
+        n = dsv.threshold_sample_keys(131072, 8192)
+        assert n == 2080                                   # (L sqrt(f (1 - f)) / 700)^2 = 2054.4, up to a multiple of 32
+        assert dsv.threshold_sample_keys(524288, 16384) == 16384             # capped: min(L / 8, 16384)
+        assert dsv.threshold_sample_keys(65536, 512) == 8192                 # 64 sample keys above the threshold: 64 L / k
+        assert dsv.threshold_sample_keys(8192, 512) == 0                     # short sequence
+        assert dsv.threshold_sample_keys(131072, 32769) == 0                 # k > L / 4: threshold too close to zero
+        assert dsv.threshold_sample_keys(131072, 64) == 0                    # no sample of <= L / 8 keys holds the upper bound
+        assert dsv.threshold_sample_keys(131072, 131072) == 0 and dsv.threshold_sample_keys(131072, 0) == 0
+        for L, k in ((131072, 8192), (65536, 1024), (32768, 8192), (1 << 20, 4096)):
+            n = dsv.threshold_sample_keys(L, k)
+            assert n % 32 == 0 and 2048 <= n <= min(L // 8, 16384)
+        assert dsv.threshold_search(2) == 0
+        assert dsv.threshold_sample_keys(4096, 256) == 2048                  # forced: up to L / 2 keys
+        assert dsv.threshold_sample_keys(4000, 256) == 0                     # below twice the smallest sample
+        assert dsv.threshold_sample_keys(8192, 4096) == 2048                 # forced: any density the sample can bracket
+        assert dsv.threshold_sample_keys(8192, 1) == 0
+        assert dsv.threshold_search(1) == 2
+        assert dsv.threshold_sample_keys(131072, 8192) == 0
+        with pytest.raises(ValueError):
+            dsv.threshold_search(3)
+        assert dsv.load_library().dsv_threshold_search(-1) == -1
+        assert dsv.threshold_search(1) == 1                                  # the refused calls changed nothing
+    finally:
+        dsv.threshold_search(0)
