@@ -32,11 +32,11 @@ VALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9   # 256 CUs x 64 fp32 lanes x 2.4 GHz, on
 # (FETCH_SIZE reads 0.5 GiB for it: factor 2.0; WRITE_SIZE reads 1 GiB: factor 1.0), and the L2 hit rate from
 # TCC_HIT_sum / (TCC_HIT_sum + TCC_MISS_sum).  Source: profiles/config2_pmc_counters.md.  The figures belong to ONE
 # build of the kernels: they are reported only while the library still names that version.
-PMC_LIBRARY_VERSION = "dsv 0.3 (gfx950)"
+PMC_LIBRARY_VERSION = "dsv 0.4 (gfx950)"
 PMC_CONFIG2 = {
-    "sparse_attn_fwd": {"fetch_kib": 30948725, "write_kib": 14155842, "l2_hit_rate": 0.9692},
-    "sparse_attn_bwd_dq": {"fetch_kib": 48268455, "write_kib": 12976309, "l2_hit_rate": 0.9644},
-    "sparse_attn_bwd_dkdv": {"fetch_kib": 34165752, "write_kib": 12582935, "l2_hit_rate": 0.9758},
+    "sparse_attn_fwd": {"fetch_kib": 31042322, "write_kib": 14155844, "l2_hit_rate": 0.9693},
+    "sparse_attn_bwd_dq": {"fetch_kib": 48468979, "write_kib": 12976401, "l2_hit_rate": 0.9644},
+    "sparse_attn_bwd_dkdv": {"fetch_kib": 33568648, "write_kib": 12582918, "l2_hit_rate": 0.9739},
 }
 # the gather sweep inside each stage-2 call (the kernel the roofline object is about)
 SWEEP_OF_CALL = {"sparse_attn_fwd": "fwd_sweep", "sparse_attn_bwd_dq": "dq_sweep", "sparse_attn_bwd_dkdv": "dkdv_sweep"}

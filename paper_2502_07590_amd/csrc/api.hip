@@ -247,7 +247,7 @@ static void *noalloc_scratch(dsv_status *err)
 
 extern "C" {
 
-const char *dsv_version(void) { return "dsv 0.3 (gfx950)"; }
+const char *dsv_version(void) { return "dsv 0.4 (gfx950)"; }
 
 const char *dsv_status_string(dsv_status s)
 {
