@@ -593,6 +593,7 @@ GroupedFwdGeneral grouped_fwd_general(const dsv_problem &p)
 }
 
 struct GroupedBwdLayout {
+    bool lists_of_groups;  // the dkdv sweep reads the lists of groups as they are (no per-query copy of them)
     size_t delta, qp, gop, lsep, deltap, idxtx, colx, op, dqp, idxx, step, step_bytes, total;
 };
 GroupedBwdLayout grouped_bwd_layout(const dsv_problem &p, const dsv_grouping &g)
@@ -603,14 +604,19 @@ GroupedBwdLayout grouped_bwd_layout(const dsv_problem &p, const dsv_grouping &g)
     dsv_problem sorted = p;
     sorted.flags |= DSV_FLAG_SORTED_INDEX;
     GroupedBwdLayout w{};
+    // the L2-blocked sweep expands a list of groups while it stages it; the plain sweep (a single range) and the
+    // general path take the per-query form written out
+    w.lists_of_groups = native && step_layout(sorted).split && (uint64_t)p.L * (uint64_t)group_size(g) < (1ull << 32);
     size_t o = 0;
     w.delta = o; o = align_up(o + nbh * p.L * 4, 256);
     w.qp = o; o = align_up(o + rows, 256);
     w.gop = o; o = align_up(o + rows, 256);
     w.lsep = o; o = align_up(o + nbh * p.L * 4, 256);
     w.deltap = o; o = align_up(o + nbh * p.L * 4, 256);
-    w.idxtx = o; o = align_up(o + total_pairs(p) * 4, 256);
-    w.colx = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
+    if (!w.lists_of_groups) {
+        w.idxtx = o; o = align_up(o + total_pairs(p) * 4, 256);
+        w.colx = o; o = align_up(o + nbh * ((size_t)p.L + 1) * 8, 256);
+    }
     if (!native) {   // the per-query dq step on reordered queries: O and dQ in that order, one index row per query
         w.op = o; o = align_up(o + rows, 256);
         w.dqp = o; o = align_up(o + rows, 256);
@@ -717,6 +723,13 @@ dsv_status dsv_sparse_attn_bwd_grouped(const dsv_problem *p, const dsv_grouping 
         if ((st = launch_group_rows(*p, *g, 2, ws + w.dqp, dQ, stream)) != DSV_OK) return st;
     }
     // dK, dV step: the per-query key-major sweep on the reordered queries
+    if (w.lists_of_groups) {
+        dsv_problem sorted = *p;
+        sorted.flags |= DSV_FLAG_SORTED_INDEX;
+        const StepLayout kw = step_layout(sorted);
+        return launch_bwd_dkdv_split(sorted, tabs.data(), (int)tabs.size(), ws + w.qp, K, V, idx_t_g, col_ptr, lsep, deltap,
+                                     ws + w.gop, dK, dV, kw.plan, step_buffers(ws + w.step, kw), stream, group_size(*g));
+    }
     st = launch_group_expand(*p, *g, tabs.data(), (int)tabs.size(), idx_g, idx_t_g, col_ptr, nullptr,
                              reinterpret_cast<int32_t *>(ws + w.idxtx), reinterpret_cast<int64_t *>(ws + w.colx), stream);
     if (st != DSV_OK) return st;

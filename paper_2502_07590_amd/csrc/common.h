@@ -248,6 +248,22 @@ dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void 
 constexpr size_t kFwdRangeBytes = 2u << 20;
 constexpr size_t kBwdRangeBytes = 4u << 20;
 
+// A key-major list of GROUPS standing for the per-query list it expands to (queries in group-major order: group g
+// holds queries g G .. g G + G - 1): position pos of the expanded list is entry pos / G of the stored one, times G,
+// plus pos % G.  G = 1: a plain list.  magic = floor(2^32 / G) + 1 divides positions below 2^32 / G exactly.
+struct GroupExpand {
+    int32_t G;
+    uint32_t magic;
+};
+__host__ __device__ __forceinline__ GroupExpand no_expand() { return GroupExpand{1, 0u}; }
+__host__ __forceinline__ GroupExpand make_expand(int G) { return GroupExpand{G, (uint32_t)((1ull << 32) / (uint64_t)G) + 1u}; }
+__device__ __forceinline__ int32_t expanded_entry(const int32_t *__restrict__ list, int pos, const GroupExpand &ge)
+{
+    if (ge.G == 1) return list[pos];
+    const int q = (int)__umulhi((uint32_t)pos, ge.magic);
+    return list[q] * ge.G + (pos - q * ge.G);
+}
+
 struct SplitPlan {
     int range_len;  // keys (queries) per range
     int S;          // ranges
@@ -284,7 +300,9 @@ dsv_status launch_bwd_dq_split(const dsv_problem &p, const HeadTable *tabs, int 
 dsv_status launch_bwd_dkdv_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
                                  const void *K, const void *V, const int32_t *idxT, const int64_t *col,
                                  const float *lse, const float *delta, const void *dO, void *dK, void *dV,
-                                 const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st);
+                                 const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st, int expand_G = 1);
+// expand_G > 1: idxT / col hold lists of groups of expand_G queries (tabs[].off the offsets of those lists); the sweep
+// runs on the per-query lists they stand for.  Needs p.L < 2^32 / expand_G.
 
 // Device buffers of the selection.  idx_t == nullptr skips the key-major emission (then jcut, cnt,
 // col may be null as well).

@@ -255,6 +255,12 @@ template <int LPR> struct StagedIndex {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) a[e] = row[min(c0 + e * LPR + s, te - 1)];
     }
+    // the same on the per-query list that a list of groups stands for
+    __device__ __forceinline__ void request(const int32_t *__restrict__ row, int c0, int te, int s, const GroupExpand &ge)
+    {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) a[e] = expanded_entry(row, min(c0 + e * LPR + s, te - 1), ge);
+    }
     __device__ __forceinline__ void park(int32_t *stage, int s) const
     {
 #pragma unroll
@@ -403,14 +409,15 @@ __device__ __forceinline__ void dkdv_sweep(DkdvState<D / LPR> &st, const RowChun
                                            const T *__restrict__ Gh, const float *__restrict__ lse_h,
                                            const float *__restrict__ delta_h, uint32_t lane_off,
                                            const int32_t *__restrict__ list, int tb, int te, float c2, int32_t *stage,
-                                           int s, const float2 *stat_s = nullptr, int stat_base = 0)
+                                           int s, const float2 *stat_s = nullptr, int stat_base = 0,
+                                           GroupExpand ge = no_expand())
 {
     if (tb >= te) return;
     StagedIndex<LPR> si;
-    si.request(list, tb, te, s);
+    si.request(list, tb, te, s, ge);
     for (int c0 = tb; c0 < te; c0 += kStage) {
         si.park(stage, s);
-        if (c0 + kStage < te) si.request(list, c0 + kStage, te, s);
+        if (c0 + kStage < te) si.request(list, c0 + kStage, te, s, ge);
         const int n = min(kStage, te - c0);
         int it = 0;
 #if DSV_DKDV_REP == 2

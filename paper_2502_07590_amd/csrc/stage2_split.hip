@@ -40,7 +40,7 @@ __device__ __forceinline__ bool decode_item(const SplitPlan &pl, int64_t b, int 
 // from col_ptr), cut by QUERY ranges.
 __global__ __launch_bounds__(256) void segment_ptr_kernel(const int32_t *__restrict__ index,
                                                           const int64_t *__restrict__ col, int L, HeadTable tab,
-                                                          SplitPlan pl, int32_t *__restrict__ seg)
+                                                          SplitPlan pl, int32_t *__restrict__ seg, GroupExpand ge)
 {
     const int slot = blockIdx.y;
     const int bh = tab.bh[slot];
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void segment_ptr_kernel(const int32_t *__restr
     if (col) {
         const int64_t *cp = col + (int64_t)bh * (L + 1);
         base = index + tab.off[slot] + cp[row];
-        len = (int)(cp[row + 1] - cp[row]);
+        len = (int)(cp[row + 1] - cp[row]) * ge.G;  // lists of groups: positions of the expanded list
     } else {
         len = tab.k[slot];
         base = index + tab.off[slot] + (int64_t)row * len;
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void segment_ptr_kernel(const int32_t *__restr
     int lo = 0, hi = len;  // first position with value >= target
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
-        if ((int64_t)base[mid] < target) lo = mid + 1; else hi = mid;
+        if ((int64_t)expanded_entry(base, mid, ge) < target) lo = mid + 1; else hi = mid;
     }
     seg[((int64_t)bh * L + row) * np + s] = lo;
 }
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
                                                                     const float *__restrict__ delta,
                                                                     const T *__restrict__ dO, float *__restrict__ pdk,
                                                                     float *__restrict__ pdv, int L, float scale,
-                                                                    HeadTable tab, SplitPlan pl)
+                                                                    HeadTable tab, SplitPlan pl, GroupExpand ge)
 {
     typedef LaneLayout<T, D, LPR> LL;
     constexpr int CH = D / LPR;
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
     }
     dkdv_sweep<T, D, LPR, LDS_STAT>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L * (delta ? 1 : 2),
                                     delta ? delta + (int64_t)bh * L : nullptr, (uint32_t)LL::off(s), list, tb, te,
-                                    scale * kLog2e, stage, s, stat_s, q_first);
+                                    scale * kLog2e, stage, s, stat_s, q_first, ge);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + j) * pl.S + range;
         store_acc<T, D, LPR>(pdk + slot_id * D, s, st.dk);
@@ -440,12 +440,13 @@ SplitPlan make_split_plan(const dsv_problem &p, size_t range_bytes)
 }
 
 static dsv_status launch_segments(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const SplitPlan &pl,
-                                  const int32_t *index, const int64_t *col, int32_t *seg, hipStream_t st)
+                                  const int32_t *index, const int64_t *col, int32_t *seg, hipStream_t st,
+                                  GroupExpand ge = no_expand())
 {
     const int64_t n = (int64_t)p.L * (pl.S + 1);
     for (int t = 0; t < n_tabs; ++t) {
         dim3 grid((unsigned)((n + 255) / 256), tabs[t].n);
-        hipLaunchKernelGGL(segment_ptr_kernel, grid, dim3(256), 0, st, index, col, p.L, tabs[t], pl, seg);
+        hipLaunchKernelGGL(segment_ptr_kernel, grid, dim3(256), 0, st, index, col, p.L, tabs[t], pl, seg, ge);
         DSV_LAUNCH_CHECK();
     }
     return DSV_OK;
@@ -534,10 +535,12 @@ template <typename T, int D>
 static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
                                    const void *K, const void *V, const int32_t *idxT, const int64_t *col,
                                    const float *lse, const float *delta, const void *dO, void *dK, void *dV,
-                                   const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st)
+                                   const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st, int expand_G)
 {
     const int nbh = p.B * p.H;
-    dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idxT, col, w.seg, st);
+    if (expand_G < 1 || (uint64_t)p.L * (uint64_t)expand_G >= (1ull << 32)) return DSV_EUNSUPPORTED;
+    const GroupExpand ge = expand_G > 1 ? make_expand(expand_G) : no_expand();
+    dsv_status rc = launch_segments(p, tabs, n_tabs, pl, idxT, col, w.seg, st, ge);
     if (rc != DSV_OK) return rc;
     const int64_t nrows = (int64_t)nbh * p.L;
     hipLaunchKernelGGL(pack_rowstat_kernel, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, st, lse, delta,
@@ -560,12 +563,12 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
                                                   (int)kDkdvStatLdsBytes));
                 hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), stat_bytes, st, (const T *)Q, (const T *)K,
                                    (const T *)V, idxT, col, w.seg, w.order, reinterpret_cast<const float *>(w.rowstat),
-                                   (const float *)nullptr, (const T *)dO, w.pa, w.pb, p.L, p.scale, tabs[t], lp);
+                                   (const float *)nullptr, (const T *)dO, w.pa, w.pb, p.L, p.scale, tabs[t], lp, ge);
             } else {
                 hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D, SweepLanes<T, D>::dkdv, false>), dim3((unsigned)blocks),
                                    dim3(256), 0, st, (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, w.order,
                                    reinterpret_cast<const float *>(w.rowstat), (const float *)nullptr, (const T *)dO, w.pa,
-                                   w.pb, p.L, p.scale, tabs[t], lp);
+                                   w.pb, p.L, p.scale, tabs[t], lp, ge);
             }
             DSV_LAUNCH_CHECK();
         }
@@ -585,7 +588,7 @@ dsv_status launch_row_segments(const dsv_problem &p, int rows, const HeadTable *
     const int64_t n = (int64_t)rows * (pl.S + 1);
     for (int t = 0; t < n_tabs; ++t) {
         dim3 grid((unsigned)((n + 255) / 256), tabs[t].n);
-        hipLaunchKernelGGL(segment_ptr_kernel, grid, dim3(256), 0, st, index, (const int64_t *)nullptr, rows, tabs[t], pl, seg);
+        hipLaunchKernelGGL(segment_ptr_kernel, grid, dim3(256), 0, st, index, (const int64_t *)nullptr, rows, tabs[t], pl, seg, no_expand());
         DSV_LAUNCH_CHECK();
     }
     return DSV_OK;
@@ -641,9 +644,9 @@ dsv_status launch_bwd_dq_split(const dsv_problem &p, const HeadTable *tabs, int 
 dsv_status launch_bwd_dkdv_split(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
                                  const void *K, const void *V, const int32_t *idxT, const int64_t *col,
                                  const float *lse, const float *delta, const void *dO, void *dK, void *dV,
-                                 const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st)
+                                 const SplitPlan &pl, const BwdSplitWorkspace &w, hipStream_t st, int expand_G)
 {
-    DSV_DISPATCH_TD(bwd_dkdv_split_t, p, tabs, n_tabs, Q, K, V, idxT, col, lse, delta, dO, dK, dV, pl, w, st);
+    DSV_DISPATCH_TD(bwd_dkdv_split_t, p, tabs, n_tabs, Q, K, V, idxT, col, lse, delta, dO, dK, dV, pl, w, st, expand_G);
 }
 
 }  // namespace dsv
