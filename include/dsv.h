@@ -223,8 +223,9 @@ DSV_API dsv_status dsv_sparse_attn_bwd_dkdv(const dsv_problem *p, const void *Q,
  *   query returns 0).
  * dsv_sparse_attn_bwd_grouped: gradients of the above (selection held constant).  dQ group by group with
  *   the forward's tiling (K and V rows gathered once per group); dK and dV with the per-query key-major
- *   sweep on queries reordered group by group: the workspace holds the reordered Q, dO, lse, Delta and the
- *   per-query form of the key-major index (L*k int32 per head) besides the steps' scratch.  Needs idx_t_g
+ *   sweep on queries reordered group by group: the workspace holds the reordered Q, dO, lse, Delta besides
+ *   the steps' scratch, and -- unless the group kernels run with the flag set, where the sweep reads the lists
+ *   of groups as they are -- the per-query form of the key-major index (L*k int32 per head).  Needs idx_t_g
  *   and col_ptr.  The flag selects the L2-blocked dQ step as in the forward.  Cases outside bf16, d = 128,
  *   G <= 32: dQ by the per-query kernel as described for the forward. */
 typedef struct dsv_grouping {
