@@ -247,6 +247,7 @@ dsv_status launch_scores_rows(const dsv_problem &p, const void *Qlr, const void 
 // (dq 132 / 131 / 135 ms and dkdv 158 / 162 / 164 ms at 4 / 3 / 2 MB); 8 ranges per head are 20 % slower.
 constexpr size_t kFwdRangeBytes = 2u << 20;
 constexpr size_t kBwdRangeBytes = 4u << 20;
+constexpr size_t kMaxRangeRows = 8192;  // rows of a range: 8 bytes of row statistics each fit 64 KB of LDS
 
 // A key-major list of GROUPS standing for the per-query list it expands to (queries in group-major order: group g
 // holds queries g G .. g G + G - 1): position pos of the expanded list is entry pos / G of the stored one, times G,

@@ -237,17 +237,17 @@ __global__ __launch_bounds__(256) void sparse_bwd_dq_merge_kernel(const float *_
 // Key-major: work item = (head, QUERY range, block of 16 keys); a key's ascending query list has one
 // contiguous segment per query range, whose Q / dO rows (and lse, Delta entries) stay in L2.
 // `order`: this range's keys by descending segment length (see seglen_* below).
-// LDS_STAT: the block first parks the range's {lse * log2(e), Delta} entries (8 bytes per query, dynamic LDS
-// of range_len entries) and the sweep reads them from there: one vector-memory access less per pair.
-template <typename T, int D, int LPR, bool LDS_STAT>
+// The block first parks the range's {lse * log2(e), Delta} entries (8 bytes per query, dynamic LDS of range_len
+// entries: at most 64 KB, two blocks per CU, which is what the registers allow anyway) and the sweep reads them
+// from there: one vector-memory access less per pair.
+template <typename T, int D, int LPR>
 __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                                     const T *__restrict__ V,
                                                                     const int32_t *__restrict__ idxT,
                                                                     const int64_t *__restrict__ col,
                                                                     const int32_t *__restrict__ seg,
                                                                     const int32_t *__restrict__ order,
-                                                                    const float *__restrict__ lse,
-                                                                    const float *__restrict__ delta,
+                                                                    const float2 *__restrict__ rowstat,
                                                                     const T *__restrict__ dO, float *__restrict__ pdk,
                                                                     float *__restrict__ pdv, int L, float scale,
                                                                     HeadTable tab, SplitPlan pl, GroupExpand ge)
@@ -274,20 +274,18 @@ __global__ __launch_bounds__(256) void sparse_bwd_dkdv_split_kernel(const T *__r
     DkdvState<CH> st;
 #pragma unroll
     for (int c = 0; c < CH; ++c) { st.dk[c] = 0.f; st.dv[c] = 0.f; }
-    // delta == nullptr: lse is the packed {lse * log2(e), Delta} array (two floats per query)
     __shared__ __align__(16) int32_t stage_all[256 / LPR][kStage];  // one index staging slot per row group
     int32_t *stage = stage_all[threadIdx.x / LPR];
-    extern __shared__ __align__(16) float2 stat_s[];  // LDS_STAT: [range_len]
+    extern __shared__ __align__(16) float2 stat_s[];  // [range_len]
     const int q_first = range * pl.range_len;          // first query of this range
-    if constexpr (LDS_STAT) {
-        const float2 *src = reinterpret_cast<const float2 *>(lse) + (int64_t)bh * L + q_first;
+    {
+        const float2 *src = rowstat + (int64_t)bh * L + q_first;
         const int nq = min(pl.range_len, L - q_first);
         for (int e = threadIdx.x; e < nq; e += 256) stat_s[e] = src[e];
         __syncthreads();
     }
-    dkdv_sweep<T, D, LPR, LDS_STAT>(st, kc, vc, Q + head_base, dO + head_base, lse + (int64_t)bh * L * (delta ? 1 : 2),
-                                    delta ? delta + (int64_t)bh * L : nullptr, (uint32_t)LL::off(s), list, tb, te,
-                                    scale * kLog2e, stage, s, stat_s, q_first, ge);
+    dkdv_sweep<T, D, LPR, true>(st, kc, vc, Q + head_base, dO + head_base, nullptr, nullptr, (uint32_t)LL::off(s), list, tb,
+                                te, scale * kLog2e, stage, s, stat_s, q_first, ge);
     if (live) {
         const int64_t slot_id = ((int64_t)bh * L + j) * pl.S + range;
         store_acc<T, D, LPR>(pdk + slot_id * D, s, st.dk);
@@ -430,7 +428,8 @@ SplitPlan make_split_plan(const dsv_problem &p, size_t range_bytes)
     SplitPlan pl;
     // ranges of about range_bytes, their number a multiple of 8 so that every XCD gets the same
     // number of ranges (a 6-5 split of ranges over XCDs costs ~10 %)
-    const size_t target = std::max<size_t>(256, range_bytes / row_pair_bytes);
+    // at most kMaxRangeRows rows per range: the dkdv sweep parks the range's row statistics in LDS
+    const size_t target = std::min<size_t>(kMaxRangeRows, std::max<size_t>(256, range_bytes / row_pair_bytes));
     int S = (int)((p.L + 8 * target - 1) / (8 * target)) * 8;
     pl.range_len = (p.L + S - 1) / S;
     pl.S = (p.L + pl.range_len - 1) / pl.range_len;
@@ -529,8 +528,6 @@ static dsv_status bwd_dq_split_t(const dsv_problem &p, const HeadTable *tabs, in
     return DSV_OK;
 }
 
-constexpr size_t kDkdvStatLdsBytes = 64u << 10;  // row statistics of one query range parked in LDS (dkdv sweep)
-
 template <typename T, int D>
 static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, int n_tabs, const void *Q,
                                    const void *K, const void *V, const int32_t *idxT, const int64_t *col,
@@ -555,21 +552,13 @@ static dsv_status bwd_dkdv_split_t(const dsv_problem &p, const HeadTable *tabs, 
             lp.nqb = (p.L + 256 / SweepLanes<T, D>::dkdv - 1) / (256 / SweepLanes<T, D>::dkdv);  // row blocks of this kernel's layout
             const int64_t blocks = (int64_t)tabs[t].n * lp.S_pad * lp.nqb;
             if (blocks > 0x7FFFFFFF) return DSV_EUNSUPPORTED;
-            // the range's row statistics go to LDS when they leave room for two blocks per CU (the registers allow no more)
-            const size_t stat_bytes = (size_t)lp.range_len * sizeof(float2);
-            if (stat_bytes <= kDkdvStatLdsBytes) {
-                auto kern = &sparse_bwd_dkdv_split_kernel<T, D, SweepLanes<T, D>::dkdv, true>;
-                DSV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                  (int)kDkdvStatLdsBytes));
-                hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), stat_bytes, st, (const T *)Q, (const T *)K,
-                                   (const T *)V, idxT, col, w.seg, w.order, reinterpret_cast<const float *>(w.rowstat),
-                                   (const float *)nullptr, (const T *)dO, w.pa, w.pb, p.L, p.scale, tabs[t], lp, ge);
-            } else {
-                hipLaunchKernelGGL((sparse_bwd_dkdv_split_kernel<T, D, SweepLanes<T, D>::dkdv, false>), dim3((unsigned)blocks),
-                                   dim3(256), 0, st, (const T *)Q, (const T *)K, (const T *)V, idxT, col, w.seg, w.order,
-                                   reinterpret_cast<const float *>(w.rowstat), (const float *)nullptr, (const T *)dO, w.pa,
-                                   w.pb, p.L, p.scale, tabs[t], lp, ge);
-            }
+            const size_t stat_bytes = (size_t)lp.range_len * sizeof(float2);  // <= kMaxRangeRows * 8
+            auto kern = &sparse_bwd_dkdv_split_kernel<T, D, SweepLanes<T, D>::dkdv>;
+            DSV_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                              (int)(kMaxRangeRows * sizeof(float2))));
+            hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), stat_bytes, st, (const T *)Q, (const T *)K,
+                               (const T *)V, idxT, col, w.seg, w.order, (const float2 *)w.rowstat, (const T *)dO, w.pa, w.pb,
+                               p.L, p.scale, tabs[t], lp, ge);
             DSV_LAUNCH_CHECK();
         }
     }
