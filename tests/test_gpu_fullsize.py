@@ -6,7 +6,8 @@ is the one bench.py reports.
 The oracle cannot do whole problems of this size (1e11 and more scores), so it computes sampled outputs
 one by one:
   * stage 1 on the real top-k: sampled index rows against the oracle's selection applied to the
-    device's own fp32 score bits (bit-exact) and against the pure fp64 oracle; properties that hold
+    device's own fp32 score bits (bit-exact) and against the pure fp64 oracle; the whole index identical
+    under both threshold searches; properties that hold
     at any size for everything else (rows ascending and in range, exactly k per row, idx_t is the
     exact transpose of idx for sampled keys, list lengths = per-key counts);
   * stage 2 on that real selection (what the benchmark runs): forward and backward_t on the device's
@@ -92,6 +93,19 @@ def test_real_selection_full_size(data, progress):
     Qlr, Klr = dsv.lowrank_project(p, g["Q"], g["K"], Wq, Wk)
     torch.cuda.synchronize()
     progress(f"config {cfg.index}: stage 1 done")
+    # the two threshold searches are both exact: every row of the index identical whichever one ran
+    # (automatic choice above: the windowed search for the heads it fits; here the radix search for all)
+    try:
+        dsv.threshold_search(1)
+        idx_radix = dsv.lowrank_topk(p, g["Q"], g["K"], Wq, Wk)
+        torch.cuda.synchronize()
+    finally:
+        dsv.threshold_search(0)
+    for lo in range(0, idx_flat.numel(), 1 << 30):
+        assert torch.equal(idx_flat[lo:lo + (1 << 30)], idx_radix[lo:lo + (1 << 30)]), "windowed and radix search differ"
+    del idx_radix
+    torch.cuda.empty_cache()
+    progress(f"config {cfg.index}: windowed = radix on all {idx_flat.numel()} index entries")
 
     def rows_of(h):
         return idx_flat[off[h]:off[h + 1]].view(L, ks[h])
