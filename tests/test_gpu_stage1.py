@@ -284,3 +284,19 @@ def test_windowed_search_with_transposed_and_grouped_emission(search_mode):
         out[mode] = [x.cpu().numpy() for x in (idx, idx_t, col, idx_g, idx_t_g, col_g)]
     for a, b in zip(out[1], out[2]):
         assert np.array_equal(a, b)
+
+
+def test_windowed_search_over_more_heads_than_one_launch_table_holds(search_mode):
+    """70 heads: the (batch, head) pairs go through the kernels 64 at a time, each table with its own list of
+    unsettled tiles; ternary inputs in some heads put tiles on those lists."""
+    L, d, r, H = 4096, 64, 16, 70
+    ks = [256 if h % 3 else 100 for h in range(H)]
+    case = Case(make_cfg(L, d, r, H, "bf16", basis_rank=32, scale_num=2.0), ks, names=("Q", "K"))
+    Q, K = case.dev["Q"].clone(), case.dev["K"].clone()
+    for h in (5, 64, 69):                      # massive ties in heads of both tables
+        tq, tk, _, _ = wl.ternary_head_tensors(L, d, r, seed=4, head=h)
+        Q[0, h] = torch.from_numpy(tq).to(Q.dtype)
+        K[0, h] = torch.from_numpy(tk).to(K.dtype)
+    p = case.problem(dsv)
+    radix, window = _both_searches(p, Q, K, case.dWq, case.dWk)
+    assert np.array_equal(radix, window)
