@@ -217,10 +217,9 @@ __device__ __forceinline__ bool decode_group_item(const SplitPlan &pl, int64_t b
 //   O += P V      v_mfma_f32_16x16x32_bf16 per 16 channels: A = P (rows = queries, rows >= 8 zero), B = V with the
 //                 contraction over the tile's 32 keys.  A B fragment holds, per lane, 8 KEYS of one channel -- the
 //                 transpose of how a gathered row arrives -- so the tile's V rows are parked row-major in LDS and
-//                 read back as 16-bit columns.  Which keys a lane group contracts is free as long as A and B
-//                 agree: group g of 16 lanes takes keys 8 (e / 2) + 2 g + (e % 2), e = 0..7, which puts the four
-//                 groups' reads of one instruction on disjoint LDS banks (rows 2 apart, 272-byte rows); P is stored
-//                 with each group's keys contiguous, so its fragment is one 16-byte read.
+//                 read back with transposing LDS reads (tr_frag below).  Which keys a lane group contracts is
+//                 free as long as A and B agree (fwd_key below); P is stored with each group's keys contiguous,
+//                 so its fragment is one 16-byte read.
 // SPLIT: the L2-blocked form for ascending rows -- a block works on ONE key range (whose K + V rows stay in its
 // XCD's L2), walks only the segment of every group's row that falls into the range, and leaves the partial softmax
 // state (m, l, unnormalised acc) of every member for the per-query merge kernel; pm, pl_, pacc are laid out per
@@ -473,8 +472,8 @@ __global__ __launch_bounds__(256) void grouped_fwd_kernel(const bf16_t *__restri
 //   C and B   one product on the matrix cores, v_mfma_f32_32x32x16_bf16 with the contraction over the keys: the 32
 //        A rows are the weights p (dP - D0) of the 8 members as bf16 head and tail (rows 0..7, 8..15) and p as head
 //        and tail (rows 16..23, 24..31) -- two bf16 terms carry 16 significant bits of every fp32 weight -- and B is
-//        K transposed, read from the parked rows as 16-bit columns.  Lane group h of a fragment takes keys
-//        16 s + 8 (e / 4) + 4 h + (e % 4) of k-step s: rows 4 apart, i.e. disjoint LDS banks for the two groups.
+//        K transposed, read from the parked rows with transposing LDS reads (tr_frag; which keys a lane group
+//        takes: dq_key below).
 // SPLIT: per (member, range) partials C, B, Delta for the per-query dq merge kernel.
 
 // dQ step, second product: lane group h (32 lanes) of k-step s contracts, in this order, keys dq_key(s, h, 0..7);
